@@ -1,0 +1,254 @@
+/*
+ * CPU oracle for replicated-share linear layers over the ring Z_{2^64}.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the yardstick the GPU library is
+ * compared against; it is never part of the product path.  Only the tests,
+ * the smoke check and the benchmark's cpu_baseline leg may load it.  It shares
+ * no code, header, table or helper with the HIP kernels.
+ *
+ * Everything here is the plain definition written out with C unsigned
+ * 64-bit arithmetic, whose wraparound IS arithmetic mod 2^64 (paper Sec. III-B,
+ * "Secret sharing": ring Z_n with n = 2^k, k = 64).  No blocking, no limb
+ * splitting, no reordering of the three-term share product.  The only
+ * concession to wall-clock time is an OpenMP "parallel for" over independent
+ * output rows; integer sums mod 2^64 are exact in any order, so threading
+ * cannot change a single bit.
+ *
+ * Pins (tests/test_oracle_*.py, run without a GPU): Python big-integer brute
+ * force on tiny shapes, closed forms (identity, all-(-1), 2^32 squares to 0),
+ * linearity, direct convolution == explicit patch matrix times weights,
+ * 1x1 convolution == matmul, delta-kernel shift, output sizes printed in the
+ * paper's AlexNet/VGG tables, share/reconstruct identity, sum of the three
+ * parties' local products == product of the plaintext encodings, and the
+ * decoded fixed-point product against an fp64 product.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef uint64_t u64;
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---- fixed-point encoding (Sec. III-B "Fixed point representation") -------
+ * A real x with t fractional bits is the integer nearest to x*2^t, embedded in
+ * the ring as a two's-complement 64-bit word.  Ties go to even (the paper does
+ * not fix the tie rule; this is the IEEE default of rint). */
+void oracle_encode(const double *x, u64 *out, size_t n, int t)
+{
+    const double scale = ldexp(1.0, t);
+    for (size_t i = 0; i < n; ++i)
+        out[i] = (u64)(int64_t)rint(x[i] * scale);
+}
+
+/* Inverse map for a word at scale 2^bits: read it as signed, divide by 2^bits.
+ * A product of two t-bit encodings is at scale 2^(2t) because the tensor
+ * product is not truncated inside the linear layer (Sec. III-B,
+ * "Convolutions and matrix multiplication", last paragraph). */
+void oracle_decode(const u64 *z, double *out, size_t n, int bits)
+{
+    const double inv = ldexp(1.0, -bits);
+    for (size_t i = 0; i < n; ++i)
+        out[i] = (double)(int64_t)z[i] * inv;
+}
+
+/* ---- sharing (Sec. III-B "Secret sharing") --------------------------------
+ * x = s0 + s1 + s2 in the ring.  Two words r0, r1 of caller-supplied
+ * randomness fix s0 and s1; s2 is what is left.  Party i then holds the pair
+ * (s_i, s_{(i+1) mod 3}). */
+void oracle_share(const u64 *x, const u64 *r0, const u64 *r1,
+                  u64 *s0, u64 *s1, u64 *s2, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        s0[i] = r0[i];
+        s1[i] = r1[i];
+        s2[i] = x[i] - r0[i] - r1[i];
+    }
+}
+
+void oracle_reconstruct(const u64 *s0, const u64 *s1, const u64 *s2, u64 *out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        out[i] = s0[i] + s1[i] + s2[i];
+}
+
+/* ---- local linear operations (Sec. III-B "Linear operations") -------------
+ * [[alpha*x + beta*y + gamma]] = (alpha*x1 + beta*y1 + gamma, alpha*x2 + beta*y2,
+ * alpha*x3 + beta*y3): component-wise on every share, the public constant goes
+ * into the first share only. */
+void oracle_share_add(const u64 *xa, const u64 *xb, const u64 *ya, const u64 *yb,
+                      u64 *za, u64 *zb, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        za[i] = xa[i] + ya[i];
+        zb[i] = xb[i] + yb[i];
+    }
+}
+
+void oracle_share_mul_public(const u64 *xa, const u64 *xb, u64 alpha,
+                             u64 *za, u64 *zb, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        za[i] = alpha * xa[i];
+        zb[i] = alpha * xb[i];
+    }
+}
+
+/* Party `party` (0,1,2) holds (s_party, s_{party+1}).  The constant gamma is
+ * added to share index 0 (the paper's x_1) only: that is the first component
+ * of party 0 and the second component of party 2; party 1 holds neither. */
+void oracle_share_add_public(const u64 *xa, const u64 *xb, u64 gamma, int party,
+                             u64 *za, u64 *zb, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        za[i] = xa[i] + (party == 0 ? gamma : 0);
+        zb[i] = xb[i] + (party == 2 ? gamma : 0);
+    }
+}
+
+/* ---- ring matrix product ---------------------------------------------------
+ * C[m][n] = sum_k A[m][k] * Y[n][k]  (mod 2^64).
+ * A is [M,K] row-major; the right operand is stored as Y = [N,K] row-major
+ * (K fastest, the usual weight layout of a fully connected layer), i.e. the
+ * mathematical right factor is Y transposed. */
+void oracle_matmul_u64(const u64 *A, const u64 *Y, u64 *C,
+                       int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            u64 acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += A[m * K + k] * Y[n * K + k];
+            C[m * N + n] = acc;
+        }
+}
+
+/* ---- ring convolution ------------------------------------------------------
+ * Cross-correlation with zero padding, as deep-learning layers define it:
+ * Z[b][ho][wo][co] = sum_{r,s,c} X[b][ho*sh - ph + r][wo*sw - pw + s][c] * W[co][r][s][c]
+ * with X read as 0 outside [0,H)x[0,W).  X is NHWC, W is [Cout,kh,kw,Cin],
+ * Z is NHWC [B,Ho,Wo,Cout], Ho = floor((H + 2ph - kh)/sh) + 1 and likewise Wo.
+ * Seven nested loops, no patch matrix. */
+int64_t oracle_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
+{
+    int64_t span = in + 2 * pad - k;
+    if (span < 0) return 0;
+    return span / stride + 1;
+}
+
+void oracle_conv2d_u64(const u64 *X, const u64 *W, u64 *Z,
+                       int64_t B, int64_t H, int64_t Wd, int64_t Cin, int64_t Cout,
+                       int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    const int64_t Ho = oracle_conv_out_dim(H, kh, sh, ph);
+    const int64_t Wo = oracle_conv_out_dim(Wd, kw, sw, pw);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    u64 acc = 0;
+                    for (int64_t r = 0; r < kh; ++r) {
+                        const int64_t hi = ho * sh - ph + r;
+                        if (hi < 0 || hi >= H) continue;
+                        for (int64_t s = 0; s < kw; ++s) {
+                            const int64_t wi = wo * sw - pw + s;
+                            if (wi < 0 || wi >= Wd) continue;
+                            for (int64_t c = 0; c < Cin; ++c)
+                                acc += X[((b * H + hi) * Wd + wi) * Cin + c] *
+                                       W[((co * kh + r) * kw + s) * Cin + c];
+                        }
+                    }
+                    Z[((b * Ho + ho) * Wo + wo) * Cout + co] = acc;
+                }
+}
+
+/* ---- one party's local product (Sec. III-B "Multiplication" and
+ * "Convolutions and matrix multiplication") ---------------------------------
+ * z_i = x_i*y_i + x_{i+1}*y_i + x_i*y_{i+1}: three separate products, the
+ * activation always on the left, then two ring additions.  The result is one
+ * component of a 3-out-of-3 additive sharing of x*y: not re-shared, not
+ * truncated.  Returns 0, or -1 if scratch memory could not be obtained. */
+int oracle_party_matmul(const u64 *x_i, const u64 *x_ip1, const u64 *y_i, const u64 *y_ip1,
+                        u64 *z_i, int64_t M, int64_t N, int64_t K)
+{
+    const size_t n = (size_t)M * (size_t)N;
+    u64 *t1 = (u64 *)malloc(n * sizeof(u64)), *t2 = (u64 *)malloc(n * sizeof(u64));
+    if (!t1 || !t2) { free(t1); free(t2); return -1; }
+    oracle_matmul_u64(x_i,   y_i,   z_i, M, N, K);
+    oracle_matmul_u64(x_ip1, y_i,   t1,  M, N, K);
+    oracle_matmul_u64(x_i,   y_ip1, t2,  M, N, K);
+    for (size_t j = 0; j < n; ++j) z_i[j] = z_i[j] + t1[j] + t2[j];
+    free(t1); free(t2);
+    return 0;
+}
+
+int oracle_party_conv2d(const u64 *x_i, const u64 *x_ip1, const u64 *w_i, const u64 *w_ip1,
+                        u64 *z_i,
+                        int64_t B, int64_t H, int64_t Wd, int64_t Cin, int64_t Cout,
+                        int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    const int64_t Ho = oracle_conv_out_dim(H, kh, sh, ph);
+    const int64_t Wo = oracle_conv_out_dim(Wd, kw, sw, pw);
+    const size_t n = (size_t)B * (size_t)Ho * (size_t)Wo * (size_t)Cout;
+    u64 *t1 = (u64 *)malloc(n * sizeof(u64)), *t2 = (u64 *)malloc(n * sizeof(u64));
+    if (!t1 || !t2) { free(t1); free(t2); return -1; }
+    oracle_conv2d_u64(x_i,   w_i,   z_i, B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    oracle_conv2d_u64(x_ip1, w_i,   t1,  B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    oracle_conv2d_u64(x_i,   w_ip1, t2,  B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    for (size_t j = 0; j < n; ++j) z_i[j] = z_i[j] + t1[j] + t2[j];
+    free(t1); free(t2);
+    return 0;
+}
+
+/* Single output element of one party's local matmul / conv, for spot checks on
+ * shapes too large to compute in full.  Same three literal products. */
+u64 oracle_party_matmul_at(const u64 *x_i, const u64 *x_ip1, const u64 *y_i, const u64 *y_ip1,
+                           int64_t m, int64_t n, int64_t K)
+{
+    u64 p0 = 0, p1 = 0, p2 = 0;
+    for (int64_t k = 0; k < K; ++k) p0 += x_i[m * K + k]   * y_i[n * K + k];
+    for (int64_t k = 0; k < K; ++k) p1 += x_ip1[m * K + k] * y_i[n * K + k];
+    for (int64_t k = 0; k < K; ++k) p2 += x_i[m * K + k]   * y_ip1[n * K + k];
+    return p0 + p1 + p2;
+}
+
+static u64 conv_at(const u64 *X, const u64 *W, int64_t b, int64_t ho, int64_t wo, int64_t co,
+                   int64_t H, int64_t Wd, int64_t Cin,
+                   int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    u64 acc = 0;
+    for (int64_t r = 0; r < kh; ++r) {
+        const int64_t hi = ho * sh - ph + r;
+        if (hi < 0 || hi >= H) continue;
+        for (int64_t s = 0; s < kw; ++s) {
+            const int64_t wi = wo * sw - pw + s;
+            if (wi < 0 || wi >= Wd) continue;
+            for (int64_t c = 0; c < Cin; ++c)
+                acc += X[((b * H + hi) * Wd + wi) * Cin + c] * W[((co * kh + r) * kw + s) * Cin + c];
+        }
+    }
+    return acc;
+}
+
+u64 oracle_party_conv2d_at(const u64 *x_i, const u64 *x_ip1, const u64 *w_i, const u64 *w_ip1,
+                           int64_t b, int64_t ho, int64_t wo, int64_t co,
+                           int64_t H, int64_t Wd, int64_t Cin,
+                           int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    return conv_at(x_i,   w_i,   b, ho, wo, co, H, Wd, Cin, kh, kw, sh, sw, ph, pw)
+         + conv_at(x_ip1, w_i,   b, ho, wo, co, H, Wd, Cin, kh, kw, sh, sw, ph, pw)
+         + conv_at(x_i,   w_ip1, b, ho, wo, co, H, Wd, Cin, kh, kw, sh, sw, ph, pw);
+}

@@ -1,0 +1,211 @@
+"""ctypes front end of the C oracle in ``ring_oracle.c``.
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this module; the product package never does.
+
+All functions take and return numpy arrays of dtype uint64 (ring elements of
+Z_{2^64}) or float64 (reals before encoding / after decoding).  No function
+here does arithmetic of its own: each one forwards to the C routine of the
+same name, which writes the paper's definition out as plain loops.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ring_oracle.c")
+_LIB = os.path.join(_HERE, "libring_oracle.so")
+
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i64 = ctypes.c_int64
+_sz = ctypes.c_size_t
+
+
+def build(force: bool = False) -> str:
+    """Compile ``ring_oracle.c`` with gcc into ``libring_oracle.so`` beside it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-march=native", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_encode.argtypes = [_f64p, _u64p, _sz, ctypes.c_int]
+        L.oracle_decode.argtypes = [_u64p, _f64p, _sz, ctypes.c_int]
+        L.oracle_share.argtypes = [_u64p] * 6 + [_sz]
+        L.oracle_reconstruct.argtypes = [_u64p] * 4 + [_sz]
+        L.oracle_share_add.argtypes = [_u64p] * 6 + [_sz]
+        L.oracle_share_mul_public.argtypes = [_u64p, _u64p, ctypes.c_uint64, _u64p, _u64p, _sz]
+        L.oracle_share_add_public.argtypes = [_u64p, _u64p, ctypes.c_uint64, ctypes.c_int, _u64p, _u64p, _sz]
+        L.oracle_matmul_u64.argtypes = [_u64p, _u64p, _u64p, _i64, _i64, _i64]
+        L.oracle_conv_out_dim.argtypes = [_i64] * 4
+        L.oracle_conv_out_dim.restype = _i64
+        L.oracle_conv2d_u64.argtypes = [_u64p, _u64p, _u64p] + [_i64] * 11
+        L.oracle_party_matmul.argtypes = [_u64p] * 5 + [_i64] * 3
+        L.oracle_party_matmul.restype = ctypes.c_int
+        L.oracle_party_conv2d.argtypes = [_u64p] * 5 + [_i64] * 11
+        L.oracle_party_conv2d.restype = ctypes.c_int
+        L.oracle_party_matmul_at.argtypes = [_u64p] * 4 + [_i64] * 3
+        L.oracle_party_matmul_at.restype = ctypes.c_uint64
+        L.oracle_party_conv2d_at.argtypes = [_u64p] * 4 + [_i64] * 13
+        L.oracle_party_conv2d_at.restype = ctypes.c_uint64
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def _u(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint64:
+        raise TypeError(f"ring tensors are uint64, got {a.dtype}")
+    return a
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(_u64p)
+
+
+def encode(x, t: int = 16) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = np.empty(x.shape, dtype=np.uint64)
+    lib().oracle_encode(x.ctypes.data_as(_f64p), _p(out), x.size, int(t))
+    return out
+
+
+def decode(z, bits: int) -> np.ndarray:
+    z = _u(z)
+    out = np.empty(z.shape, dtype=np.float64)
+    lib().oracle_decode(_p(z), out.ctypes.data_as(_f64p), z.size, int(bits))
+    return out
+
+
+def share(x, r0, r1):
+    """Split x into (s0, s1, s2) with s0 = r0, s1 = r1, s2 = x - r0 - r1."""
+    x, r0, r1 = _u(x), _u(r0), _u(r1)
+    assert x.shape == r0.shape == r1.shape
+    s = [np.empty(x.shape, dtype=np.uint64) for _ in range(3)]
+    lib().oracle_share(_p(x), _p(r0), _p(r1), _p(s[0]), _p(s[1]), _p(s[2]), x.size)
+    return tuple(s)
+
+
+def party_pair(shares, i: int):
+    """Party i's replicated pair (s_i, s_{i+1 mod 3})."""
+    return shares[i % 3], shares[(i + 1) % 3]
+
+
+def reconstruct(s0, s1, s2) -> np.ndarray:
+    s0, s1, s2 = _u(s0), _u(s1), _u(s2)
+    assert s0.shape == s1.shape == s2.shape
+    out = np.empty(s0.shape, dtype=np.uint64)
+    lib().oracle_reconstruct(_p(s0), _p(s1), _p(s2), _p(out), s0.size)
+    return out
+
+
+def share_add(xa, xb, ya, yb):
+    xa, xb, ya, yb = _u(xa), _u(xb), _u(ya), _u(yb)
+    za, zb = np.empty_like(xa), np.empty_like(xb)
+    lib().oracle_share_add(_p(xa), _p(xb), _p(ya), _p(yb), _p(za), _p(zb), xa.size)
+    return za, zb
+
+
+def share_mul_public(xa, xb, alpha: int):
+    xa, xb = _u(xa), _u(xb)
+    za, zb = np.empty_like(xa), np.empty_like(xb)
+    lib().oracle_share_mul_public(_p(xa), _p(xb), ctypes.c_uint64(alpha % (1 << 64)), _p(za), _p(zb), xa.size)
+    return za, zb
+
+
+def share_add_public(xa, xb, gamma: int, party: int):
+    xa, xb = _u(xa), _u(xb)
+    za, zb = np.empty_like(xa), np.empty_like(xb)
+    lib().oracle_share_add_public(_p(xa), _p(xb), ctypes.c_uint64(gamma % (1 << 64)), int(party),
+                                  _p(za), _p(zb), xa.size)
+    return za, zb
+
+
+def matmul(A, Y) -> np.ndarray:
+    """C[m,n] = sum_k A[m,k] * Y[n,k] mod 2^64; A is [M,K], Y is [N,K]."""
+    A, Y = _u(A), _u(Y)
+    M, K = A.shape
+    N, K2 = Y.shape
+    assert K == K2
+    C = np.empty((M, N), dtype=np.uint64)
+    lib().oracle_matmul_u64(_p(A), _p(Y), _p(C), M, N, K)
+    return C
+
+
+def conv_out_dim(n: int, k: int, stride: int, pad: int) -> int:
+    return int(lib().oracle_conv_out_dim(n, k, stride, pad))
+
+
+def conv2d(X, W, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    """X NHWC [B,H,W,Cin], W [Cout,kh,kw,Cin] -> Z NHWC [B,Ho,Wo,Cout]."""
+    X, W = _u(X), _u(W)
+    B, H, Wd, Cin = X.shape
+    Cout, kh, kw, Cin2 = W.shape
+    assert Cin == Cin2
+    sh, sw = stride
+    ph, pw = pad
+    Ho, Wo = conv_out_dim(H, kh, sh, ph), conv_out_dim(Wd, kw, sw, pw)
+    Z = np.empty((B, Ho, Wo, Cout), dtype=np.uint64)
+    lib().oracle_conv2d_u64(_p(X), _p(W), _p(Z), B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw)
+    return Z
+
+
+def party_matmul(x_i, x_ip1, y_i, y_ip1) -> np.ndarray:
+    x_i, x_ip1, y_i, y_ip1 = _u(x_i), _u(x_ip1), _u(y_i), _u(y_ip1)
+    M, K = x_i.shape
+    N, _ = y_i.shape
+    assert x_ip1.shape == (M, K) and y_i.shape == (N, K) and y_ip1.shape == (N, K)
+    z = np.empty((M, N), dtype=np.uint64)
+    rc = lib().oracle_party_matmul(_p(x_i), _p(x_ip1), _p(y_i), _p(y_ip1), _p(z), M, N, K)
+    if rc != 0:
+        raise MemoryError("oracle_party_matmul")
+    return z
+
+
+def party_conv2d(x_i, x_ip1, w_i, w_ip1, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    x_i, x_ip1, w_i, w_ip1 = _u(x_i), _u(x_ip1), _u(w_i), _u(w_ip1)
+    B, H, Wd, Cin = x_i.shape
+    Cout, kh, kw, _ = w_i.shape
+    assert x_ip1.shape == x_i.shape and w_ip1.shape == w_i.shape and w_i.shape[3] == Cin
+    sh, sw = stride
+    ph, pw = pad
+    Ho, Wo = conv_out_dim(H, kh, sh, ph), conv_out_dim(Wd, kw, sw, pw)
+    z = np.empty((B, Ho, Wo, Cout), dtype=np.uint64)
+    rc = lib().oracle_party_conv2d(_p(x_i), _p(x_ip1), _p(w_i), _p(w_ip1), _p(z),
+                                   B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw)
+    if rc != 0:
+        raise MemoryError("oracle_party_conv2d")
+    return z
+
+
+def party_matmul_at(x_i, x_ip1, y_i, y_ip1, m: int, n: int) -> int:
+    x_i, x_ip1, y_i, y_ip1 = _u(x_i), _u(x_ip1), _u(y_i), _u(y_ip1)
+    K = x_i.shape[1]
+    return int(lib().oracle_party_matmul_at(_p(x_i), _p(x_ip1), _p(y_i), _p(y_ip1), m, n, K))
+
+
+def party_conv2d_at(x_i, x_ip1, w_i, w_ip1, b, ho, wo, co, stride=(1, 1), pad=(0, 0)) -> int:
+    x_i, x_ip1, w_i, w_ip1 = _u(x_i), _u(x_ip1), _u(w_i), _u(w_ip1)
+    _, H, Wd, Cin = x_i.shape
+    _, kh, kw, _ = w_i.shape
+    return int(lib().oracle_party_conv2d_at(_p(x_i), _p(x_ip1), _p(w_i), _p(w_ip1), b, ho, wo, co,
+                                            H, Wd, Cin, kh, kw, stride[0], stride[1], pad[0], pad[1]))
