@@ -1,0 +1,144 @@
+/*
+ * cg.h -- replicated-share linear layers over the ring Z_{2^64} on one AMD MI355X.
+ *
+ * The library computes what ONE party of the three-party protocol computes
+ * locally, between two communication steps, for a linear layer on 2-out-of-3
+ * replicated secret shares (CryptGPU, Sec. III-B).  A secret x is split as
+ * x = s_0 + s_1 + s_2 (mod 2^64); party i holds the pair (s_i, s_{i+1 mod 3}).
+ * Ring elements are uint64_t; every operation is exact arithmetic mod 2^64.
+ *
+ * Conventions shared by all entry points
+ *   - Every data pointer is DEVICE memory owned by the caller (8-byte aligned
+ *     at least; 16-byte alignment lets the kernels use their widest loads).
+ *     The library never allocates, frees or retains device memory and keeps
+ *     no state between calls.
+ *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *     Calls only enqueue work: on CG_OK the kernels have been launched, not
+ *     finished.  Synchronise the stream before reading results on the host.
+ *   - Arguments are validated on the host BEFORE any HIP call.  A failed
+ *     validation returns a status other than CG_OK and launches nothing.
+ *   - Outputs of cg_share_matmul / cg_share_conv2d must not overlap their
+ *     inputs.  The element-wise calls may run in place (an output pointer equal
+ *     to the input pointer of the same position); partial overlap is rejected.
+ */
+#ifndef CG_H
+#define CG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CG_API __attribute__((visibility("default")))
+
+typedef enum {
+    CG_OK = 0,
+    CG_ERR_NULL = 1,        /* a required pointer is NULL */
+    CG_ERR_SHAPE = 2,       /* a dimension is < 1, a product of dimensions overflows, or the
+                               convolution has an empty output */
+    CG_ERR_ALIGN = 3,       /* a pointer is not 8-byte aligned */
+    CG_ERR_ALIAS = 4,       /* an output overlaps an input where that is not allowed */
+    CG_ERR_UNSUPPORTED = 5, /* valid mathematics, but outside what the kernels address
+                               (see each call) */
+    CG_ERR_DEVICE = 6       /* the HIP runtime reported an error at launch */
+} cg_status;
+
+/* Human-readable name of a status; static storage, never freed. */
+CG_API const char *cg_status_string(cg_status s);
+
+/* Library version, major*10000 + minor*100 + patch. */
+CG_API int cg_version(void);
+
+/*
+ * One party's local step of the share multiplication protocol, for a matrix
+ * product (Sec. III-B, "Multiplication" and "Convolutions and matrix
+ * multiplication"):
+ *
+ *     z_i = x_i * y_i  +  x_{i+1} * y_i  +  x_i * y_{i+1}      (mod 2^64)
+ *
+ * where "*" is the matrix product with the activation on the left.  Over the
+ * three parties z_0 + z_1 + z_2 = x*y, so z_i is one component of a
+ * 3-out-of-3 additive sharing.  It is NOT re-shared and NOT truncated: for
+ * fixed-point operands with t fractional bits the result carries 2t.
+ *
+ *   x_i, x_ip1 : [M,K] row-major, the party's two shares of the left operand
+ *   y_i, y_ip1 : [N,K] row-major (K fastest: the weight layout of a fully
+ *                connected layer), the party's two shares of the right operand;
+ *                the mathematical right factor is its transpose
+ *   z_i        : [M,N] row-major, written in full
+ *   M, N, K    : >= 1
+ *
+ * CG_ERR_UNSUPPORTED if K exceeds 2^20 or M or N exceeds 2^31-1.
+ */
+CG_API cg_status cg_share_matmul(const uint64_t *x_i, const uint64_t *x_ip1,
+                          const uint64_t *y_i, const uint64_t *y_ip1,
+                          uint64_t *z_i, int64_t M, int64_t N, int64_t K, void *stream);
+
+/*
+ * Same local step for a 2-D convolution (Sec. III-B, "Convolutions and matrix
+ * multiplication"), evaluated as an implicit matrix product: no patch matrix
+ * is ever written to memory.  Convolution means cross-correlation with zero
+ * padding, as neural-network layers define it:
+ *
+ *   Z[b][ho][wo][co] = sum_{r,s,c} X[b][ho*stride_h - pad_h + r][wo*stride_w - pad_w + s][c]
+ *                                  * W[co][r][s][c]
+ *
+ * with X read as zero outside the image.  A zero in every share is a share of
+ * zero, so padding each share with zeros pads the secret with zeros.
+ *
+ *   x_i, x_ip1 : NHWC [B,H,W,Cin]
+ *   w_i, w_ip1 : [Cout,kh,kw,Cin]
+ *   z_i        : NHWC [B,Ho,Wo,Cout], Ho = floor((H + 2*pad_h - kh)/stride_h) + 1, same for Wo
+ *
+ * No dilation, no groups.  CG_ERR_SHAPE if Ho or Wo would be < 1, a stride is
+ * < 1 or a padding is negative.  CG_ERR_UNSUPPORTED if kh*kw*Cin exceeds 2^20,
+ * if B*Ho*Wo or Cout exceeds 2^31-1, if a stride or padding exceeds 32767, or if
+ * the images one 256-row block of outputs can touch ((255 / (Ho*Wo) + 2 of them,
+ * at most B) exceed 2^31-1 bytes together.
+ */
+typedef struct {
+    int64_t B, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w;
+} cg_conv2d_desc;
+
+CG_API cg_status cg_share_conv2d(const uint64_t *x_i, const uint64_t *x_ip1,
+                          const uint64_t *w_i, const uint64_t *w_ip1,
+                          uint64_t *z_i, const cg_conv2d_desc *desc, void *stream);
+
+/*
+ * Local linear operations on a replicated pair (a = s_i, b = s_{i+1}), over n
+ * elements (Sec. III-B, "Linear operations": shares of alpha*x + beta*y are
+ * the same combination of the shares, component by component).
+ *
+ *   cg_share_add        : (za, zb) = (xa + ya, xb + yb)
+ *   cg_share_mul_public : (za, zb) = (alpha*xa, alpha*xb), alpha a public ring element
+ *   cg_share_add_public : adds the public ring element gamma to share index 0 only,
+ *                         i.e. to the first component of party 0 and to the second
+ *                         component of party 2; party 1's pair is copied unchanged.
+ *                         party must be 0, 1 or 2 (CG_ERR_SHAPE otherwise).
+ * n == 0 is allowed: the call returns CG_OK without looking at the pointers.
+ */
+CG_API cg_status cg_share_add(const uint64_t *xa, const uint64_t *xb,
+                       const uint64_t *ya, const uint64_t *yb,
+                       uint64_t *za, uint64_t *zb, size_t n, void *stream);
+
+CG_API cg_status cg_share_mul_public(const uint64_t *xa, const uint64_t *xb, uint64_t alpha,
+                              uint64_t *za, uint64_t *zb, size_t n, void *stream);
+
+CG_API cg_status cg_share_add_public(const uint64_t *xa, const uint64_t *xb, uint64_t gamma, int party,
+                              uint64_t *za, uint64_t *zb, size_t n, void *stream);
+
+/*
+ * out = s0 + s1 + s2 (mod 2^64), element-wise over n (Sec. III-B, "Secret
+ * sharing").  Opens a replicated sharing (pass its three distinct shares) and
+ * equally the three parties' additive outputs z_0, z_1, z_2 of
+ * cg_share_matmul / cg_share_conv2d.  n == 0 is allowed (CG_OK, pointers not looked at).
+ */
+CG_API cg_status cg_reconstruct(const uint64_t *s0, const uint64_t *s1, const uint64_t *s2,
+                         uint64_t *out, size_t n, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CG_H */

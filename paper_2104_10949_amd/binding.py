@@ -1,0 +1,187 @@
+"""Thin Python front end of libcg.so (the C-ABI declared in include/cg.h).
+
+Argument marshalling only: tensors are torch int64 tensors on the GPU whose
+bits are the uint64 ring elements; every function forwards pointers and sizes
+to the C entry point of the same name and raises on a non-zero status.  There
+is no fallback: if the library has not been built, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcg.so")
+
+CG_OK, CG_ERR_NULL, CG_ERR_SHAPE, CG_ERR_ALIGN, CG_ERR_ALIAS, CG_ERR_UNSUPPORTED, CG_ERR_DEVICE = range(7)
+
+EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d", "cg_share_add",
+           "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct")
+
+
+class ConvDesc(ctypes.Structure):
+    """Mirror of cg_conv2d_desc."""
+    _fields_ = [(n, ctypes.c_int64) for n in
+                ("B", "H", "W", "Cin", "Cout", "kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w")]
+
+
+class CgError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcg.so (built by paper_2104_10949_amd.build.build()); no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2104_10949_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, u64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_size_t
+        L.cg_status_string.argtypes = [ctypes.c_int]
+        L.cg_status_string.restype = ctypes.c_char_p
+        L.cg_version.argtypes = []
+        L.cg_version.restype = ctypes.c_int
+        L.cg_share_matmul.argtypes = [vp] * 5 + [i64] * 3 + [vp]
+        L.cg_share_conv2d.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
+        L.cg_share_add.argtypes = [vp] * 6 + [sz, vp]
+        L.cg_share_mul_public.argtypes = [vp, vp, u64, vp, vp, sz, vp]
+        L.cg_share_add_public.argtypes = [vp, vp, u64, ctypes.c_int, vp, vp, sz, vp]
+        L.cg_reconstruct.argtypes = [vp] * 4 + [sz, vp]
+        for name in EXPORTS[2:]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().cg_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().cg_version())
+
+
+def _ptr(t: torch.Tensor) -> int:
+    if t.dtype != torch.int64:
+        raise TypeError(f"ring tensors are torch.int64 (uint64 bit patterns), got {t.dtype}")
+    if not t.is_cuda:
+        raise ValueError("ring tensors must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("ring tensors must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(status: int, where: str) -> None:
+    if status != CG_OK:
+        raise CgError(status, where)
+
+
+def cg_share_matmul(x_i, x_ip1, y_i, y_ip1, z_i=None, stream=None) -> torch.Tensor:
+    """z_i = x_i y_i^T + x_ip1 y_i^T + x_i y_ip1^T mod 2^64; x [M,K], y [N,K], z [M,N]."""
+    M, K = x_i.shape
+    N = y_i.shape[0]
+    if x_ip1.shape != x_i.shape or y_ip1.shape != y_i.shape or y_i.shape[1] != K:
+        raise ValueError("operand shapes do not match")
+    if z_i is None:
+        z_i = torch.empty((M, N), dtype=torch.int64, device=x_i.device)
+    elif tuple(z_i.shape) != (M, N):
+        raise ValueError("output shape does not match")
+    _check(lib().cg_share_matmul(_ptr(x_i), _ptr(x_ip1), _ptr(y_i), _ptr(y_ip1), _ptr(z_i),
+                                 M, N, K, _stream(stream)), "cg_share_matmul")
+    return z_i
+
+
+def conv_out_shape(x_shape: Sequence[int], w_shape: Sequence[int], stride: Tuple[int, int],
+                   pad: Tuple[int, int]) -> Tuple[int, int, int, int]:
+    B, H, W, _ = x_shape
+    Cout, kh, kw, _ = w_shape
+    return (B, (H + 2 * pad[0] - kh) // stride[0] + 1, (W + 2 * pad[1] - kw) // stride[1] + 1, Cout)
+
+
+def cg_share_conv2d(x_i, x_ip1, w_i, w_ip1, stride=(1, 1), pad=(0, 0), z_i=None, stream=None) -> torch.Tensor:
+    """Party-local convolution on shares; x NHWC [B,H,W,Cin], w [Cout,kh,kw,Cin], z NHWC."""
+    B, H, W, Cin = x_i.shape
+    Cout, kh, kw, Cin2 = w_i.shape
+    if x_ip1.shape != x_i.shape or w_ip1.shape != w_i.shape or Cin2 != Cin:
+        raise ValueError("operand shapes do not match")
+    d = ConvDesc(B, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    zs = conv_out_shape(x_i.shape, w_i.shape, stride, pad)
+    if z_i is None:
+        if zs[1] < 1 or zs[2] < 1:
+            _check(CG_ERR_SHAPE, "cg_share_conv2d")
+        z_i = torch.empty(zs, dtype=torch.int64, device=x_i.device)
+    elif tuple(z_i.shape) != zs:
+        raise ValueError("output shape does not match")
+    _check(lib().cg_share_conv2d(_ptr(x_i), _ptr(x_ip1), _ptr(w_i), _ptr(w_ip1), _ptr(z_i),
+                                 ctypes.byref(d), _stream(stream)), "cg_share_conv2d")
+    return z_i
+
+
+def cg_share_add(xa, xb, ya, yb, za=None, zb=None, stream=None):
+    za = torch.empty_like(xa) if za is None else za
+    zb = torch.empty_like(xb) if zb is None else zb
+    if not (xa.shape == xb.shape == ya.shape == yb.shape == za.shape == zb.shape):
+        raise ValueError("operand shapes do not match")
+    _check(lib().cg_share_add(_ptr(xa), _ptr(xb), _ptr(ya), _ptr(yb), _ptr(za), _ptr(zb),
+                              xa.numel(), _stream(stream)), "cg_share_add")
+    return za, zb
+
+
+def cg_share_mul_public(xa, xb, alpha: int, za=None, zb=None, stream=None):
+    za = torch.empty_like(xa) if za is None else za
+    zb = torch.empty_like(xb) if zb is None else zb
+    if not (xa.shape == xb.shape == za.shape == zb.shape):
+        raise ValueError("operand shapes do not match")
+    _check(lib().cg_share_mul_public(_ptr(xa), _ptr(xb), int(alpha) % (1 << 64), _ptr(za), _ptr(zb),
+                                     xa.numel(), _stream(stream)), "cg_share_mul_public")
+    return za, zb
+
+
+def cg_share_add_public(xa, xb, gamma: int, party: int, za=None, zb=None, stream=None):
+    za = torch.empty_like(xa) if za is None else za
+    zb = torch.empty_like(xb) if zb is None else zb
+    if not (xa.shape == xb.shape == za.shape == zb.shape):
+        raise ValueError("operand shapes do not match")
+    _check(lib().cg_share_add_public(_ptr(xa), _ptr(xb), int(gamma) % (1 << 64), int(party), _ptr(za), _ptr(zb),
+                                     xa.numel(), _stream(stream)), "cg_share_add_public")
+    return za, zb
+
+
+def cg_reconstruct(s0, s1, s2, out=None, stream=None) -> torch.Tensor:
+    out = torch.empty_like(s0) if out is None else out
+    if not (s0.shape == s1.shape == s2.shape == out.shape):
+        raise ValueError("operand shapes do not match")
+    _check(lib().cg_reconstruct(_ptr(s0), _ptr(s1), _ptr(s2), _ptr(out), s0.numel(), _stream(stream)),
+           "cg_reconstruct")
+    return out
+
+
+def to_device(a) -> torch.Tensor:
+    """numpy uint64 array -> int64 GPU tensor with the same bits."""
+    import numpy as np
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint64:
+        raise TypeError("expected uint64")
+    return torch.from_numpy(a.view(np.int64)).cuda()
+
+
+def to_host(t: torch.Tensor):
+    """int64 GPU tensor -> numpy uint64 array with the same bits."""
+    import numpy as np
+    return t.cpu().numpy().view(np.uint64)

@@ -1,0 +1,307 @@
+// C-ABI entry points declared in include/cg.h: host-side validation, choice of
+// the address generator, and the element-wise share operations.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cg.h"
+#include "share_gemm.h"
+
+namespace {
+
+typedef uint64_t u64;
+
+const int64_t MAX_DIM = 0x7FFFFFFF;      // M, N as 32-bit ints in the kernel
+const int64_t MAX_ROW_WORDS = 1 << 20;   // K: MAX_TILE_ROWS rows of K words stay below 2^31 bytes
+const int64_t MAX_VIEW_BYTES = 0x7FFFFFFF;
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// do [a, a+na) and [b, b+nb) (bytes) intersect?
+bool overlap(const void* a, u64 na, const void* b, u64 nb) {
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return pa < pb + nb && pb < pa + na;
+}
+
+// element-wise calls: identical pointers are fine (in place), partial overlap is not
+bool bad_overlap(const void* out, const void* in, u64 bytes) {
+    return out != in && overlap(out, bytes, in, bytes);
+}
+
+bool mul_overflows(int64_t a, int64_t b, int64_t* out) { return __builtin_mul_overflow(a, b, out); }
+
+// ---- element-wise kernels: pure streaming, 16 bytes per lane per access ------
+typedef unsigned long long ull2 __attribute__((ext_vector_type(2)));
+
+const int EW_THREADS = 256;
+
+template <class F>
+__global__ __launch_bounds__(EW_THREADS) void ew_kernel(size_t n, F f) {
+    const size_t n2 = n >> 1;
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n2; i += stride) f.pair(i);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (n & 1)) f.one(n - 1);
+}
+
+template <class F>
+__global__ __launch_bounds__(EW_THREADS) void ew_kernel_scalar(size_t n, F f) {
+    const size_t stride = (size_t)gridDim.x * EW_THREADS;
+    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) f.one(i);
+}
+
+#define LD2(p, i) (reinterpret_cast<const ull2*>(p)[i])
+#define ST2(p, i) (reinterpret_cast<ull2*>(p)[i])
+
+struct AddOp {  // (za, zb) = (xa + ya, xb + yb)
+    const u64 *xa, *xb, *ya, *yb;
+    u64 *za, *zb;
+    __device__ void pair(size_t i) const {
+        const ull2 a = LD2(xa, i) + LD2(ya, i), b = LD2(xb, i) + LD2(yb, i);
+        ST2(za, i) = a;
+        ST2(zb, i) = b;
+    }
+    __device__ void one(size_t i) const {
+        const u64 a = xa[i] + ya[i], b = xb[i] + yb[i];
+        za[i] = a;
+        zb[i] = b;
+    }
+};
+
+struct MulPublicOp {  // (za, zb) = (alpha xa, alpha xb)
+    const u64 *xa, *xb;
+    u64 alpha;
+    u64 *za, *zb;
+    __device__ void pair(size_t i) const {
+        const ull2 a = LD2(xa, i) * alpha, b = LD2(xb, i) * alpha;
+        ST2(za, i) = a;
+        ST2(zb, i) = b;
+    }
+    __device__ void one(size_t i) const {
+        const u64 a = xa[i] * alpha, b = xb[i] * alpha;
+        za[i] = a;
+        zb[i] = b;
+    }
+};
+
+struct AddPublicOp {  // (za, zb) = (xa + ga, xb + gb)
+    const u64 *xa, *xb;
+    u64 ga, gb;
+    u64 *za, *zb;
+    __device__ void pair(size_t i) const {
+        const ull2 a = LD2(xa, i) + ga, b = LD2(xb, i) + gb;
+        ST2(za, i) = a;
+        ST2(zb, i) = b;
+    }
+    __device__ void one(size_t i) const {
+        const u64 a = xa[i] + ga, b = xb[i] + gb;
+        za[i] = a;
+        zb[i] = b;
+    }
+};
+
+struct ReconstructOp {  // out = s0 + s1 + s2
+    const u64 *s0, *s1, *s2;
+    u64* out;
+    __device__ void pair(size_t i) const { ST2(out, i) = LD2(s0, i) + LD2(s1, i) + LD2(s2, i); }
+    __device__ void one(size_t i) const { out[i] = s0[i] + s1[i] + s2[i]; }
+};
+
+template <class F>
+cg_status launch_ew(size_t n, bool vec, const F& f, void* stream) {
+    if (n == 0) return CG_OK;
+    const size_t work = vec ? (n + 1) / 2 : n;
+    size_t blocks = (work + EW_THREADS - 1) / EW_THREADS;
+    const size_t cap = 256 * 16;  // 16 resident blocks per compute unit, grid-stride beyond that
+    if (blocks > cap) blocks = cap;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vec) hipLaunchKernelGGL(ew_kernel<F>, dim3((unsigned)blocks), dim3(EW_THREADS), 0, s, n, f);
+    else hipLaunchKernelGGL(ew_kernel_scalar<F>, dim3((unsigned)blocks), dim3(EW_THREADS), 0, s, n, f);
+    return hipGetLastError() == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+cg_status check_ptrs(const void* const* ptrs, int count) {
+    for (int i = 0; i < count; ++i)
+        if (!ptrs[i]) return CG_ERR_NULL;
+    for (int i = 0; i < count; ++i)
+        if (!aligned(ptrs[i], 8)) return CG_ERR_ALIGN;
+    return CG_OK;
+}
+
+bool all_aligned16(const void* const* ptrs, int count) {
+    for (int i = 0; i < count; ++i)
+        if (!aligned(ptrs[i], 16)) return false;
+    return true;
+}
+
+cg_status check_product_ptrs(const u64* x_i, const u64* x_ip1, const u64* y_i, const u64* y_ip1, u64* z_i,
+                             u64 x_bytes, u64 y_bytes, u64 z_bytes) {
+    const void* ptrs[5] = {x_i, x_ip1, y_i, y_ip1, z_i};
+    if (cg_status st = check_ptrs(ptrs, 5)) return st;
+    if (overlap(z_i, z_bytes, x_i, x_bytes) || overlap(z_i, z_bytes, x_ip1, x_bytes) ||
+        overlap(z_i, z_bytes, y_i, y_bytes) || overlap(z_i, z_bytes, y_ip1, y_bytes))
+        return CG_ERR_ALIAS;
+    return CG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* cg_status_string(cg_status s) {
+    switch (s) {
+        case CG_OK: return "CG_OK";
+        case CG_ERR_NULL: return "CG_ERR_NULL: a required pointer is NULL";
+        case CG_ERR_SHAPE: return "CG_ERR_SHAPE: bad or overflowing dimensions";
+        case CG_ERR_ALIGN: return "CG_ERR_ALIGN: pointer not 8-byte aligned";
+        case CG_ERR_ALIAS: return "CG_ERR_ALIAS: output overlaps an input";
+        case CG_ERR_UNSUPPORTED: return "CG_ERR_UNSUPPORTED: shape outside the kernels' addressing range";
+        case CG_ERR_DEVICE: return "CG_ERR_DEVICE: HIP launch error";
+    }
+    return "unknown cg_status";
+}
+
+int cg_version(void) { return 100; }
+
+cg_status cg_share_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
+                          const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
+                          void* stream) {
+    if (!x_i || !x_ip1 || !y_i || !y_ip1 || !z_i) return CG_ERR_NULL;
+    if (M < 1 || N < 1 || K < 1) return CG_ERR_SHAPE;
+    int64_t mk, nk, mn, tmp;
+    if (mul_overflows(M, K, &mk) || mul_overflows(N, K, &nk) || mul_overflows(M, N, &mn) ||
+        mul_overflows(mk, 8, &tmp) || mul_overflows(nk, 8, &tmp) || mul_overflows(mn, 8, &tmp))
+        return CG_ERR_SHAPE;
+    if (cg_status st = check_product_ptrs(x_i, x_ip1, y_i, y_ip1, z_i, (u64)mk * 8, (u64)nk * 8, (u64)mn * 8))
+        return st;
+    if (M > MAX_DIM || N > MAX_DIM || K > MAX_ROW_WORDS) return CG_ERR_UNSUPPORTED;
+
+    cg::GemmParams p = {};
+    p.x_a = x_i; p.x_b = x_ip1; p.w_a = y_i; p.w_b = y_ip1; p.z = z_i;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K; p.lda = (int)K;
+    p.x_elems = (u64)mk;
+    p.Ho = p.Wo = 1;
+    const void* in[4] = {x_i, x_ip1, y_i, y_ip1};
+    const bool vec = (K % 2 == 0) && all_aligned16(in, 4);
+    const hipError_t e = cg::launch_share_gemm(p, vec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR, vec,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+cg_status cg_share_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i,
+                          const uint64_t* w_ip1, uint64_t* z_i, const cg_conv2d_desc* d, void* stream) {
+    if (!x_i || !x_ip1 || !w_i || !w_ip1 || !z_i || !d) return CG_ERR_NULL;
+    if (d->B < 1 || d->H < 1 || d->W < 1 || d->Cin < 1 || d->Cout < 1 || d->kh < 1 || d->kw < 1 ||
+        d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0)
+        return CG_ERR_SHAPE;
+    // keep every intermediate far from int64 overflow
+    const int64_t LIM = (int64_t)1 << 40;
+    if (d->B > LIM || d->H > LIM || d->W > LIM || d->Cin > LIM || d->Cout > LIM || d->kh > LIM || d->kw > LIM ||
+        d->stride_h > LIM || d->stride_w > LIM || d->pad_h > LIM || d->pad_w > LIM)
+        return CG_ERR_SHAPE;
+    const int64_t span_h = d->H + 2 * d->pad_h - d->kh, span_w = d->W + 2 * d->pad_w - d->kw;
+    if (span_h < 0 || span_w < 0) return CG_ERR_SHAPE;
+    const int64_t Ho = span_h / d->stride_h + 1, Wo = span_w / d->stride_w + 1;
+    int64_t img, x_el, K, w_el, howo, M, z_el, tmp;
+    if (mul_overflows(d->H, d->W, &tmp) || mul_overflows(tmp, d->Cin, &img) || mul_overflows(img, d->B, &x_el) ||
+        mul_overflows(d->kh, d->kw, &tmp) || mul_overflows(tmp, d->Cin, &K) || mul_overflows(K, d->Cout, &w_el) ||
+        mul_overflows(Ho, Wo, &howo) || mul_overflows(howo, d->B, &M) || mul_overflows(M, d->Cout, &z_el) ||
+        mul_overflows(x_el, 8, &tmp) || mul_overflows(w_el, 8, &tmp) || mul_overflows(z_el, 8, &tmp))
+        return CG_ERR_SHAPE;
+    if (cg_status st = check_product_ptrs(x_i, x_ip1, w_i, w_ip1, z_i, (u64)x_el * 8, (u64)w_el * 8, (u64)z_el * 8))
+        return st;
+    if (M > MAX_DIM || d->Cout > MAX_DIM || K > MAX_ROW_WORDS || img > ((int64_t)1 << 27) ||
+        d->pad_h > 32767 || d->pad_w > 32767 || d->stride_h > 32767 || d->stride_w > 32767)
+        return CG_ERR_UNSUPPORTED;
+
+    cg::GemmParams p = {};
+    p.x_a = x_i; p.x_b = x_ip1; p.w_a = w_i; p.w_b = w_ip1; p.z = z_i;
+    p.M = (int)M; p.N = (int)d->Cout; p.K = (int)K;
+    p.x_elems = (u64)x_el;
+    p.img_elems = (u64)img;
+    p.H = (int)d->H; p.W = (int)d->W; p.Cin = (int)d->Cin; p.Ho = (int)Ho; p.Wo = (int)Wo;
+    p.kh = (int)d->kh; p.kw = (int)d->kw; p.sh = (int)d->stride_h; p.sw = (int)d->stride_w;
+    p.ph = (int)d->pad_h; p.pw = (int)d->pad_w;
+    p.div_cin = cg::make_fast_div((uint32_t)d->Cin);
+    p.div_kw = cg::make_fast_div((uint32_t)d->kw);
+
+    const void* in[4] = {x_i, x_ip1, w_i, w_ip1};
+    const bool a16 = all_aligned16(in, 4);
+    int amode;
+    bool bvec = a16 && (K % 2 == 0);
+    const bool pointwise = d->kh == 1 && d->kw == 1 && d->stride_h == 1 && d->stride_w == 1 &&
+                           d->pad_h == 0 && d->pad_w == 0;
+    if (pointwise) {
+        // a 1x1, stride-1, unpadded convolution IS the matrix product [B*H*W, Cin] x [Cout, Cin]^T
+        p.lda = (int)d->Cin;
+        amode = bvec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR;
+        bvec = amode == cg::A_LINEAR_VEC;
+    } else {
+        // one block's rows touch at most this many consecutive images; their bytes must fit a 2^31 view
+        const int64_t span_imgs = (cg::MAX_TILE_ROWS - 1) / howo + 2;
+        const int64_t view = (span_imgs < d->B ? span_imgs : d->B) * img * 8;
+        if (view > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;
+        amode = (a16 && d->Cin % 32 == 0) ? cg::A_CONV_C32 : cg::A_CONV_GEN;
+    }
+    const hipError_t e = cg::launch_share_gemm(p, amode, bvec, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+cg_status cg_share_add(const uint64_t* xa, const uint64_t* xb, const uint64_t* ya, const uint64_t* yb,
+                       uint64_t* za, uint64_t* zb, size_t n, void* stream) {
+    if (n == 0) return CG_OK;  // nothing to do: pointers are not looked at
+    const void* ptrs[6] = {xa, xb, ya, yb, za, zb};
+    if (cg_status st = check_ptrs(ptrs, 6)) return st;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    for (int o = 4; o < 6; ++o)
+        for (int i = 0; i < 4; ++i)
+            if (bad_overlap(ptrs[o], ptrs[i], bytes)) return CG_ERR_ALIAS;
+    if (n && overlap(za, bytes, zb, bytes)) return CG_ERR_ALIAS;
+    AddOp f = {xa, xb, ya, yb, za, zb};
+    return launch_ew(n, all_aligned16(ptrs, 6), f, stream);
+}
+
+cg_status cg_share_mul_public(const uint64_t* xa, const uint64_t* xb, uint64_t alpha, uint64_t* za,
+                              uint64_t* zb, size_t n, void* stream) {
+    if (n == 0) return CG_OK;  // nothing to do: pointers are not looked at
+    const void* ptrs[4] = {xa, xb, za, zb};
+    if (cg_status st = check_ptrs(ptrs, 4)) return st;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    for (int o = 2; o < 4; ++o)
+        for (int i = 0; i < 2; ++i)
+            if (bad_overlap(ptrs[o], ptrs[i], bytes)) return CG_ERR_ALIAS;
+    if (n && overlap(za, bytes, zb, bytes)) return CG_ERR_ALIAS;
+    MulPublicOp f = {xa, xb, alpha, za, zb};
+    return launch_ew(n, all_aligned16(ptrs, 4), f, stream);
+}
+
+cg_status cg_share_add_public(const uint64_t* xa, const uint64_t* xb, uint64_t gamma, int party,
+                              uint64_t* za, uint64_t* zb, size_t n, void* stream) {
+    if (n == 0) return CG_OK;  // nothing to do: pointers are not looked at
+    const void* ptrs[4] = {xa, xb, za, zb};
+    if (cg_status st = check_ptrs(ptrs, 4)) return st;
+    if (party < 0 || party > 2 || n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    for (int o = 2; o < 4; ++o)
+        for (int i = 0; i < 2; ++i)
+            if (bad_overlap(ptrs[o], ptrs[i], bytes)) return CG_ERR_ALIAS;
+    if (n && overlap(za, bytes, zb, bytes)) return CG_ERR_ALIAS;
+    // share index 0 is the first component of party 0 and the second component of party 2
+    AddPublicOp f = {xa, xb, party == 0 ? gamma : 0, party == 2 ? gamma : 0, za, zb};
+    return launch_ew(n, all_aligned16(ptrs, 4), f, stream);
+}
+
+cg_status cg_reconstruct(const uint64_t* s0, const uint64_t* s1, const uint64_t* s2, uint64_t* out,
+                         size_t n, void* stream) {
+    if (n == 0) return CG_OK;  // nothing to do: pointers are not looked at
+    const void* ptrs[4] = {s0, s1, s2, out};
+    if (cg_status st = check_ptrs(ptrs, 4)) return st;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    for (int i = 0; i < 3; ++i)
+        if (bad_overlap(out, ptrs[i], bytes)) return CG_ERR_ALIAS;
+    ReconstructOp f = {s0, s1, s2, out};
+    return launch_ew(n, all_aligned16(ptrs, 4), f, stream);
+}
+
+}  // extern "C"

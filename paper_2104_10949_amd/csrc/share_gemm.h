@@ -1,0 +1,53 @@
+// Internal interface between the C-ABI entry points and the fused share-product kernel.
+#ifndef CG_SHARE_GEMM_H
+#define CG_SHARE_GEMM_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cg {
+
+// Division of a 32-bit unsigned n < 2^31 by a run-time constant as multiply-high,
+// add, shift (round-up method of Granlund and Montgomery).
+struct FastDiv {
+    uint32_t mul, shift;
+};
+
+inline FastDiv make_fast_div(uint32_t d) {
+    FastDiv f;
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    f.shift = s;
+    f.mul = (uint32_t)((((1ull << s) - d) << 32) / d + 1);
+    return f;
+}
+
+// How the left operand's words are addressed.
+enum AMode {
+    A_LINEAR_VEC = 0,     // row-major [M, lda], 16-byte loads (lda even, 16-byte aligned base)
+    A_LINEAR_SCALAR = 1,  // row-major [M, lda], 8-byte loads
+    A_CONV_C32 = 2,       // NHWC patch gather, Cin % 32 == 0, 16-byte loads
+    A_CONV_GEN = 3        // NHWC patch gather, any Cin, 8-byte loads
+};
+
+struct GemmParams {
+    const uint64_t *x_a, *x_b;  // left operand shares  s_i, s_{i+1}
+    const uint64_t *w_a, *w_b;  // right operand shares s_i, s_{i+1}, [N, K] row-major
+    uint64_t* z;                // [M, N] row-major
+    int M, N, K;                // matrix-product view
+    int lda;                    // leading dimension of the left operand (linear modes)
+    uint64_t x_elems;           // words in one left-operand share tensor
+    uint64_t img_elems;         // H*W*Cin (patch modes)
+    int H, W, Cin, Ho, Wo, kh, kw, sh, sw, ph, pw;
+    FastDiv div_cin, div_kw;
+    int group_m;                // tile-rows per launch-order group (set by the launcher)
+};
+
+// Largest block-tile height any instantiation uses; the host checks 32-bit
+// offset ranges against it.
+static const int MAX_TILE_ROWS = 256;
+
+hipError_t launch_share_gemm(const GemmParams& p, int amode, bool bvec, hipStream_t stream);
+
+}  // namespace cg
+#endif

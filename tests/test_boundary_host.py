@@ -1,0 +1,113 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads,
+exports every symbol the header declares, and rejects bad arguments before any
+HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2104_10949_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2104_10949_amd import build
+        build.build()
+    return binding.lib()
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "cg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_entry_points():
+    syms = header_symbols()
+    for name in ("cg_share_matmul", "cg_share_conv2d", "cg_share_add", "cg_share_mul_public",
+                 "cg_reconstruct", "cg_status_string", "cg_version"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol(L):
+    from paper_2104_10949_amd import binding
+    for name in header_symbols():
+        assert hasattr(L, name), name
+    assert sorted(binding.EXPORTS) == header_symbols()
+    assert binding.version() >= 100
+    assert binding.status_string(0) == "CG_OK"
+    for s in range(1, 7):
+        assert binding.status_string(s).startswith("CG_ERR_")
+
+
+P = 0x10000  # fake, well-aligned, non-null "device" addresses; never dereferenced on the host
+
+
+def test_matmul_validation_happens_before_any_device_work(L):
+    from paper_2104_10949_amd import binding as b
+    f = L.cg_share_matmul
+    ok = [P, 2 * P, 3 * P, 4 * P, 5 * P]
+    assert f(0, *ok[1:], 4, 4, 4, None) == b.CG_ERR_NULL
+    assert f(*ok[:4], 0, 4, 4, 4, None) == b.CG_ERR_NULL
+    assert f(*ok, 0, 4, 4, None) == b.CG_ERR_SHAPE
+    assert f(*ok, 4, -1, 4, None) == b.CG_ERR_SHAPE
+    assert f(*ok, 4, 4, 0, None) == b.CG_ERR_SHAPE
+    assert f(*ok, 1 << 40, 1 << 40, 4, None) == b.CG_ERR_SHAPE          # M*N*8 overflows int64
+    assert f(P + 4, *ok[1:], 4, 4, 4, None) == b.CG_ERR_ALIGN
+    assert f(*ok[:4], P + 8, 4, 4, 4, None) == b.CG_ERR_ALIAS              # z inside x_i
+    assert f(*ok[:4], 4 * P + 64, 4, 4, 4, None) == b.CG_ERR_ALIAS         # z inside y_ip1
+    big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
+    assert f(*big, 4, 4, (1 << 20) + 1, None) == b.CG_ERR_UNSUPPORTED
+    assert f(*big, 1 << 31, 1, 1, None) == b.CG_ERR_UNSUPPORTED
+
+
+def test_conv_validation(L):
+    from paper_2104_10949_amd import binding as b
+    f = L.cg_share_conv2d
+    ok = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
+
+    def desc(**kw):
+        base = dict(B=1, H=8, W=8, Cin=3, Cout=4, kh=3, kw=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1)
+        base.update(kw)
+        return ctypes.byref(b.ConvDesc(**base))
+
+    assert f(*ok, None, None) == b.CG_ERR_NULL
+    assert f(0, *ok[1:], desc(), None) == b.CG_ERR_NULL
+    assert f(*ok, desc(B=0), None) == b.CG_ERR_SHAPE
+    assert f(*ok, desc(stride_h=0), None) == b.CG_ERR_SHAPE
+    assert f(*ok, desc(pad_w=-1), None) == b.CG_ERR_SHAPE
+    assert f(*ok, desc(kh=11, pad_h=1), None) == b.CG_ERR_SHAPE            # empty output
+    assert f(*ok, desc(H=1 << 50), None) == b.CG_ERR_SHAPE
+    assert f(ok[0] + 2, *ok[1:], desc(), None) == b.CG_ERR_ALIGN
+    assert f(*ok[:4], ok[0] + 16, desc(), None) == b.CG_ERR_ALIAS
+    assert f(*ok, desc(H=1 << 14, W=1 << 14), None) == b.CG_ERR_UNSUPPORTED  # one image too large for a view
+
+
+def test_elementwise_validation(L):
+    from paper_2104_10949_amd import binding as b
+    a = [P, 2 * P, 3 * P, 4 * P, 5 * P, 6 * P]
+    assert L.cg_share_add(*a[:5], 0, 16, None) == b.CG_ERR_NULL
+    assert L.cg_share_add(*a[:5], 6 * P + 1, 16, None) == b.CG_ERR_ALIGN
+    assert L.cg_share_add(*a[:4], P + 8, 6 * P, 16, None) == b.CG_ERR_ALIAS     # za partially overlaps xa
+    assert L.cg_share_add(*a[:4], 5 * P, 5 * P + 8, 16, None) == b.CG_ERR_ALIAS  # za overlaps zb
+    assert L.cg_share_add(*a, 0, None) == b.CG_OK                               # n == 0: nothing to do
+    assert L.cg_share_mul_public(P, 2 * P, 3, 0, 4 * P, 8, None) == b.CG_ERR_NULL
+    assert L.cg_share_mul_public(P, 2 * P, 3, P + 16, 4 * P, 8, None) == b.CG_ERR_ALIAS
+    assert L.cg_share_add_public(P, 2 * P, 3, 3, 3 * P, 4 * P, 8, None) == b.CG_ERR_SHAPE
+    assert L.cg_share_add_public(P, 2 * P, 3, -1, 3 * P, 4 * P, 8, None) == b.CG_ERR_SHAPE
+    assert L.cg_reconstruct(P, 2 * P, 0, 4 * P, 8, None) == b.CG_ERR_NULL
+    assert L.cg_reconstruct(P, 2 * P, 3 * P, 3 * P + 8, 8, None) == b.CG_ERR_ALIAS
+    assert L.cg_reconstruct(P, 2 * P, 3 * P, 4 * P, 0, None) == b.CG_OK
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    from paper_2104_10949_amd import binding as b
+    x = torch.zeros((2, 2), dtype=torch.int64)
+    with pytest.raises(ValueError):
+        b._ptr(x)
+    with pytest.raises(TypeError):
+        b._ptr(torch.zeros((2, 2), dtype=torch.float32))

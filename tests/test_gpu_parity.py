@@ -1,0 +1,219 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from tests.gpu_util import first_mismatch, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def cg():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2104_10949_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ro():
+    from oracle import ring_oracle
+    return ring_oracle
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_2104_10949_amd import workloads
+    return workloads
+
+
+def run_matmul(cg, ops):
+    d = [cg.to_device(a) for a in ops]
+    z = cg.cg_share_matmul(*d)
+    torch.cuda.synchronize()
+    return cg.to_host(z)
+
+
+def run_conv(cg, ops, stride, pad):
+    d = [cg.to_device(a) for a in ops]
+    z = cg.cg_share_conv2d(*d, stride=stride, pad=pad)
+    torch.cuda.synchronize()
+    return cg.to_host(z)
+
+
+MATMUL_SHAPES = [
+    (1, 1, 1), (1, 1, 2), (3, 5, 7), (32, 32, 32), (33, 31, 34), (17, 63, 65), (128, 64, 32),
+    (129, 65, 33), (130, 70, 100), (200, 100, 31), (256, 256, 256), (300, 129, 130), (64, 200, 512),
+    (5, 1000, 96), (1000, 3, 40),
+]
+
+
+@pytest.mark.parametrize("M,N,K", MATMUL_SHAPES)
+def test_matmul_random_shares(cg, ro, wl, M, N, K):
+    say(f"cg_share_matmul random M={M} N={N} K={K}")
+    seed = 7000 + M * 31 + N * 17 + K
+    ops = (wl.draw_ring((M, K), seed), wl.draw_ring((M, K), seed + 1),
+           wl.draw_ring((N, K), seed + 2), wl.draw_ring((N, K), seed + 3))
+    got = run_matmul(cg, ops)
+    want = ro.party_matmul(*ops)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+@pytest.mark.parametrize("word", [0x8080808080808080, 0xFFFFFFFFFFFFFFFF, 0x7F7F7F7F7F7F7F7F, 0, 1,
+                                  0x8000000000000000, 0x00000000FFFFFFFF, 0x0100000000000000,
+                                  0x80FF7F0080FF7F00])
+def test_matmul_adversarial_constant_words(cg, ro, word):
+    M, N, K = 70, 40, 300
+    say(f"cg_share_matmul constant word 0x{word:016x} M={M} N={N} K={K}")
+    x = np.full((M, K), word, dtype=np.uint64)
+    y = np.full((N, K), word, dtype=np.uint64)
+    got = run_matmul(cg, (x, x, y, y))
+    want = ro.party_matmul(x, x, y, y)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+    assert int(got[0, 0]) == (3 * K * word * word) % (1 << 64)
+
+
+def test_matmul_mixed_adversarial_words(cg, ro, wl):
+    M, N, K = 96, 80, 257
+    say(f"cg_share_matmul adversarial word mix M={M} N={N} K={K}")
+    words = np.array(wl.ADVERSARIAL_WORDS, dtype=np.uint64)
+    rng = np.random.default_rng(99)
+    ops = tuple(words[rng.integers(0, len(words), size=s)] for s in ((M, K), (M, K), (N, K), (N, K)))
+    got = run_matmul(cg, ops)
+    want = ro.party_matmul(*ops)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+@pytest.mark.parametrize("K", [8192, 16352, 16384, 16400, 40000])
+def test_matmul_long_k_crosses_accumulator_folds(cg, ro, wl, K):
+    """Worst-case digits (every byte 0x80, every digit product +2^14) through one
+    or more folds of the 32-bit partial sums, plus random words."""
+    M, N = 40, 33
+    say(f"cg_share_matmul long K={K} worst-case bytes")
+    x = np.full((M, K), 0x8080808080808080, dtype=np.uint64)
+    y = np.full((N, K), 0x8080808080808080, dtype=np.uint64)
+    got = run_matmul(cg, (x, x, y, y))
+    expect = (3 * K * 0x8080808080808080 * 0x8080808080808080) % (1 << 64)
+    assert np.all(got == np.uint64(expect))
+    say(f"cg_share_matmul long K={K} random")
+    ops = (wl.draw_ring((M, K), K), wl.draw_ring((M, K), K + 1), wl.draw_ring((N, K), K + 2),
+           wl.draw_ring((N, K), K + 3))
+    got = run_matmul(cg, ops)
+    want = ro.party_matmul(*ops)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+def test_matmul_unaligned_views_take_the_8_byte_path(cg, ro, wl):
+    M, N, K = 50, 37, 64
+    say("cg_share_matmul with 8-byte-aligned (not 16) operand pointers")
+    ops = (wl.draw_ring((M, K), 1), wl.draw_ring((M, K), 2), wl.draw_ring((N, K), 3), wl.draw_ring((N, K), 4))
+    dev = []
+    for a in ops:
+        buf = torch.empty(a.size + 1, dtype=torch.int64, device="cuda")
+        view = buf[1:].view(a.shape)
+        view.copy_(torch.from_numpy(a.view(np.int64)))
+        assert view.data_ptr() % 16 == 8
+        dev.append(view)
+    z = cg.cg_share_matmul(*dev)
+    torch.cuda.synchronize()
+    want = ro.party_matmul(*ops)
+    assert not first_mismatch(cg.to_host(z), want)
+
+
+CONV_CASES = [
+    # B, H, W, Cin, Cout, kh, kw, stride, pad
+    (1, 4, 4, 1, 1, 1, 1, (1, 1), (0, 0)),
+    (2, 8, 8, 3, 5, 3, 3, (1, 1), (1, 1)),
+    (2, 9, 7, 3, 64, 5, 5, (1, 1), (2, 2)),
+    (1, 32, 32, 3, 70, 11, 11, (4, 4), (9, 9)),
+    (3, 10, 12, 32, 40, 3, 3, (1, 1), (1, 1)),
+    (2, 12, 12, 64, 130, 3, 3, (2, 2), (1, 1)),
+    (2, 14, 14, 64, 96, 1, 1, (1, 1), (0, 0)),
+    (2, 14, 14, 64, 96, 1, 1, (2, 2), (0, 0)),
+    (1, 30, 30, 3, 64, 7, 7, (2, 2), (3, 3)),
+    (2, 6, 5, 16, 33, 2, 3, (1, 2), (1, 0)),
+    (5, 3, 3, 96, 20, 3, 3, (1, 1), (1, 1)),
+    (2, 7, 7, 6, 10, 1, 1, (1, 1), (0, 0)),
+    (4, 5, 5, 7, 9, 1, 1, (1, 1), (0, 0)),
+    (200, 1, 1, 32, 16, 3, 3, (1, 1), (1, 1)),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_random_shares(cg, ro, wl, case):
+    B, H, W, Cin, Cout, kh, kw, stride, pad = case
+    say(f"cg_share_conv2d random {case}")
+    seed = 9000 + sum(case[:7])
+    xs, ws = (B, H, W, Cin), (Cout, kh, kw, Cin)
+    ops = (wl.draw_ring(xs, seed), wl.draw_ring(xs, seed + 1), wl.draw_ring(ws, seed + 2),
+           wl.draw_ring(ws, seed + 3))
+    got = run_conv(cg, ops, stride, pad)
+    want = ro.party_conv2d(*ops, stride, pad)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+def test_three_parties_reconstruct_to_the_product_config1(cg, ro, wl):
+    """Config 1: 256^3 matmul of fixed-point N(0,1) reals, all three parties on the GPU,
+    outputs opened on the GPU and compared with the plaintext product."""
+    L = wl.config_layers(1)[0]
+    seed = wl.layer_seed(1, 0)
+    say("config 1: three parties, reconstruct, decode")
+    t = wl.FRAC_BITS
+    X, Y = wl.draw_reals(L.x_shape, L.x_dist, seed), wl.draw_reals(L.w_shape, L.w_dist, seed + 1)
+    ex, ey = ro.encode(X, t), ro.encode(Y, t)
+    sx = ro.share(ex, wl.draw_ring(ex.shape, seed + 2), wl.draw_ring(ex.shape, seed + 3))
+    sy = ro.share(ey, wl.draw_ring(ey.shape, seed + 4), wl.draw_ring(ey.shape, seed + 5))
+    dx, dy = [cg.to_device(s) for s in sx], [cg.to_device(s) for s in sy]
+    z = []
+    for i in range(3):
+        zi = cg.cg_share_matmul(dx[i], dx[(i + 1) % 3], dy[i], dy[(i + 1) % 3])
+        torch.cuda.synchronize()
+        want = ro.party_matmul(sx[i], sx[(i + 1) % 3], sy[i], sy[(i + 1) % 3])
+        assert not first_mismatch(cg.to_host(zi), want), f"party {i}"
+        z.append(zi)
+    opened = cg.to_host(cg.cg_reconstruct(*z))
+    torch.cuda.synchronize()
+    assert np.array_equal(opened, ro.matmul(ex, ey))
+    got = ro.decode(opened, 2 * t)
+    assert np.max(np.abs(got - ro.decode(ex, t) @ ro.decode(ey, t).T)) <= 2.0 ** -12
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 3, 255, 256, 257, 1 << 16, (1 << 20) + 3])
+def test_elementwise_ops(cg, ro, wl, n):
+    say(f"element-wise share ops n={n}")
+    a, b, c, d = (wl.draw_ring((n,), 500 + i) for i in range(4))
+    da, db, dc, dd = (cg.to_device(v) for v in (a, b, c, d))
+    alpha, gamma = 0x9E3779B97F4A7C15, 0xFEDCBA9876543210
+    za, zb = cg.cg_share_add(da, db, dc, dd)
+    wa, wb = ro.share_add(a, b, c, d)
+    assert np.array_equal(cg.to_host(za), wa) and np.array_equal(cg.to_host(zb), wb)
+    za, zb = cg.cg_share_mul_public(da, db, alpha)
+    wa, wb = ro.share_mul_public(a, b, alpha)
+    assert np.array_equal(cg.to_host(za), wa) and np.array_equal(cg.to_host(zb), wb)
+    for party in range(3):
+        za, zb = cg.cg_share_add_public(da, db, gamma, party)
+        wa, wb = ro.share_add_public(a, b, gamma, party)
+        assert np.array_equal(cg.to_host(za), wa) and np.array_equal(cg.to_host(zb), wb)
+    out = cg.cg_reconstruct(da, db, dc)
+    assert np.array_equal(cg.to_host(out), ro.reconstruct(a, b, c))
+    # in place
+    ea, eb = da.clone(), db.clone()
+    cg.cg_share_add(ea, eb, dc, dd, za=ea, zb=eb)
+    wa, wb = ro.share_add(a, b, c, d)
+    assert np.array_equal(cg.to_host(ea), wa) and np.array_equal(cg.to_host(eb), wb)
+
+
+def test_elementwise_unaligned(cg, ro, wl):
+    n = 1001
+    say("element-wise ops on 8-byte-aligned views")
+    a, b, c = (wl.draw_ring((n,), 600 + i) for i in range(3))
+    dev = []
+    for v in (a, b, c):
+        buf = torch.empty(n + 1, dtype=torch.int64, device="cuda")
+        buf[1:].copy_(torch.from_numpy(v.view(np.int64)))
+        dev.append(buf[1:])
+    out = cg.cg_reconstruct(*dev)
+    assert np.array_equal(cg.to_host(out), ro.reconstruct(a, b, c))
