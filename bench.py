@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of one party's local linear-layer products on replicated shares over Z_{2^64}.
+
+One "step" is one pass of the hot path over one batch: every layer of the
+VGG16-shaped configuration (batch 32, 64x64x3 input, thirteen 3x3 convolutions
+and three fully connected layers), each computed by one party from its four
+share tensors with cg_share_conv2d / cg_share_matmul.  Inputs are uniform
+64-bit words (the distribution of any two of the three shares), seeded,
+resident in HBM before the timed region.
+
+Prints ONE JSON line: effective 64-bit ring MAC/s (three ring products per
+party and output element, as the protocol states them), the int8-MFMA roofline
+fraction of the share-product kernel measured over the same timed region, and
+the CPU oracle timed on the host cores for the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "Z_2^64 share-GEMM effective 64-bit MAC/s (1 party) + % MFMA peak"
+INT8_PEAK_TOPS = 5000.0  # MI355X dense int8 MFMA, published: 5.0 POP/s (2 ops per MAC)
+DIGIT_MACS_PER_RING_MAC_TRIPLE = 72  # 2 ring products x 36 signed-byte digit pairs per (m, n, k)
+WORKLOAD_CONFIG = 4
+
+
+def parse_args():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=WORKLOAD_CONFIG, choices=[1, 2, 3, 4, 5],
+                    help="benchmark configuration (default: the VGG16-shaped one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-budget-s", type=float, default=30.0,
+                    help="stop adding layers to the CPU-oracle sample after this many seconds")
+    ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
+    return ap.parse_args()
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one party's local product); "
+              f"--gpus {args.gpus} is not supported. Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2104_10949_amd import binding as cg
+    from paper_2104_10949_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback for the product path", file=sys.stderr)
+        return 3
+    cg.lib()  # fails loudly if libcg.so has not been built
+    torch.cuda.set_device(0)
+
+    layers = wl.config_layers(args.config)
+    host_ops, dev_ops, outs = [], [], []
+    for li, L in enumerate(layers):
+        ops = wl.party_operands(L, wl.layer_seed(args.config, li))
+        host_ops.append(ops)
+        dev_ops.append([cg.to_device(a) for a in ops])
+        outs.append(torch.empty(L.z_shape, dtype=torch.int64, device="cuda"))
+    torch.cuda.synchronize()
+
+    def run_layer(li: int) -> None:
+        L = layers[li]
+        for _ in range(L.repeat):
+            if L.kind == "conv":
+                cg.cg_share_conv2d(*dev_ops[li], stride=(L.stride, L.stride), pad=(L.pad, L.pad), z_i=outs[li])
+            else:
+                cg.cg_share_matmul(*dev_ops[li], z_i=outs[li])
+
+    def step() -> None:
+        for li in range(len(layers)):
+            run_layer(li)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    total_mnk = sum(L.mnk * L.repeat for L in layers)
+    launches = sum(L.repeat for L in layers)
+    value = 3.0 * total_mnk / (ms_per_step * 1e-3)
+
+    # Per-layer durations of the share-product kernel, HIP events on the launch stream,
+    # measured right after the timed region on the same buffers.
+    per_layer_ms = []
+    reps = max(3, min(args.steps, 10))
+    for li, L in enumerate(layers):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            run_layer(li)
+        b.record()
+        torch.cuda.synchronize()
+        per_layer_ms.append(a.elapsed_time(b) / (reps * L.repeat))
+    kernel_ms_sum = sum(ms * L.repeat for ms, L in zip(per_layer_ms, layers))
+
+    int8_ops_per_step = 2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * total_mnk
+    achieved_tops = int8_ops_per_step / (kernel_ms_sum * 1e-3) / 1e12
+    big = max(range(len(layers)), key=lambda i: layers[i].mnk)
+    big_tops = 2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * layers[big].mnk / (per_layer_ms[big] * 1e-3) / 1e12
+    roofline = {
+        "bound": "mfma", "kernel": "share_gemm_kernel (int8 MFMA, i32 accumulate)",
+        "achieved": round(achieved_tops, 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+        "frac": round(achieved_tops / INT8_PEAK_TOPS, 4),
+        "launches_per_step": launches,
+        "avg_launch_ms": round(kernel_ms_sum / launches, 5),
+        "ops_per_launch": int8_ops_per_step / launches,
+        "largest_layer": {"name": layers[big].name, "gemm": list(layers[big].gemm),
+                          "ms": round(per_layer_ms[big], 5), "achieved": round(big_tops, 2),
+                          "frac": round(big_tops / INT8_PEAK_TOPS, 4)},
+        "traffic": None,
+    }
+
+    if args.layers:
+        for L, ms in zip(layers, per_layer_ms):
+            m, n, k = L.gemm
+            tops = 2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * L.mnk / (ms * 1e-3) / 1e12
+            print(f"{L.name:28s} M={m:7d} N={n:5d} K={k:5d} x{L.repeat}  {ms * 1e3:9.1f} us  "
+                  f"{3.0 * L.mnk / (ms * 1e-3):.3e} ringMAC/s  {tops:7.1f} TOP/s ({100 * tops / INT8_PEAK_TOPS:4.1f}%)  "
+                  f"{L.algorithmic_bytes / (ms * 1e-3) / 1e9:7.0f} GB/s", file=sys.stderr)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ring_oracle as ro  # the benchmark's cpu_baseline leg only
+        done_mnk, t_cpu, covered = 0, 0.0, []
+        for li, L in enumerate(layers):
+            if t_cpu > args.cpu_budget_s:
+                break
+            t0 = time.perf_counter()
+            if L.kind == "conv":
+                ro.party_conv2d(*host_ops[li], (L.stride, L.stride), (L.pad, L.pad))
+            else:
+                ro.party_matmul(*host_ops[li])
+            t_cpu += time.perf_counter() - t0
+            done_mnk += L.mnk
+            covered.append(L.name)
+        cpu = {"value": 3.0 * done_mnk / t_cpu, "unit": "ring MAC/s", "cores": ro.num_threads(),
+               "kind": "oracle", "seconds": round(t_cpu, 2),
+               "sample": (f"{len(covered)} of {len(layers)} layers of config {args.config} at full size, one party, "
+                          f"one pass each ({covered[0]} .. {covered[-1]}), {3 * done_mnk:.3e} ring MACs")}
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "ring MAC/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "dtype_note": "u64 ring elements as 8 signed-byte digits on int8 MFMA, i32 accumulate, exact",
+        "data": "synthetic",
+        "config": {"workload": {1: "config 1: share matmul 256^3",
+                                2: "config 2: FC stack 784-128-128-10, batch 128",
+                                3: "config 3: small CNN conv layers, batch 128, 32x32x3",
+                                4: "config 4: VGG16-shaped 13 conv + 3 FC on shares, batch 32, 64x64x3",
+                                5: "config 5: ResNet-50-shaped 53 conv + 1 FC on shares, batch 8, 224x224x3"}[args.config],
+                   "layers": launches, "ring_macs_per_step": 3 * total_mnk,
+                   "parties_timed": 1, "fixed_point_bits": wl.FRAC_BITS},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "paper_context": "CryptGPU reports no isolated local-product rate; derived from its Fig. 1 "
+                         "(3 V100, LAN, whole protocol): about 6e9-1.1e10 effective ring MAC/s",
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,70 @@
+"""Full-size GPU parity on the five benchmark configurations: every output element of every
+layer, one party, bit for bit against the CPU oracle, in the launch configuration bench.py times."""
+import numpy as np
+import pytest
+
+from tests.gpu_util import first_mismatch, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def env():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from oracle import ring_oracle as ro
+    from paper_2104_10949_amd import binding as cg
+    from paper_2104_10949_amd import workloads as wl
+    cg.lib()
+    return cg, ro, wl
+
+
+def check_layer(cg, ro, wl, cfg, li, L):
+    say(f"config {cfg} layer {li} {L.name} gemm={L.gemm}")
+    ops = wl.party_operands(L, wl.layer_seed(cfg, li))
+    dev = [cg.to_device(a) for a in ops]
+    if L.kind == "conv":
+        z = cg.cg_share_conv2d(*dev, stride=(L.stride, L.stride), pad=(L.pad, L.pad))
+        want = ro.party_conv2d(*ops, (L.stride, L.stride), (L.pad, L.pad))
+    else:
+        z = cg.cg_share_matmul(*dev)
+        want = ro.party_matmul(*ops)
+    torch.cuda.synchronize()
+    got = cg.to_host(z)
+    assert got.shape == tuple(L.z_shape)
+    msg = first_mismatch(got, want)
+    assert not msg, f"config {cfg} {L.name}: {msg}"
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_config_every_layer_bit_exact(env, cfg):
+    cg, ro, wl = env
+    for li, L in enumerate(wl.config_layers(cfg)):
+        check_layer(cg, ro, wl, cfg, li, L)
+
+
+def test_config3_alternate_reading_conv2_at_16x16(env):
+    cg, ro, wl = env
+    L = wl.config3(alt=True)[1]
+    check_layer(cg, ro, wl, 3, 11, L)
+
+
+def test_config2_all_three_parties_open_to_the_fixed_point_product(env):
+    """FC stack, first layer: the three parties' outputs open to enc(X) enc(W)^T and decode to
+    the real product within 2^-12."""
+    cg, ro, wl = env
+    L = wl.config_layers(2)[0]
+    seed = wl.layer_seed(2, 0)
+    t = wl.FRAC_BITS
+    say("config 2 fc1: three parties, open, decode")
+    X, W = wl.draw_reals(L.x_shape, L.x_dist, seed), wl.draw_reals(L.w_shape, L.w_dist, seed + 1)
+    ex, ew = ro.encode(X, t), ro.encode(W, t)
+    sx = ro.share(ex, wl.draw_ring(ex.shape, seed + 2), wl.draw_ring(ex.shape, seed + 3))
+    sw = ro.share(ew, wl.draw_ring(ew.shape, seed + 4), wl.draw_ring(ew.shape, seed + 5))
+    dx, dw = [cg.to_device(s) for s in sx], [cg.to_device(s) for s in sw]
+    z = [cg.cg_share_matmul(dx[i], dx[(i + 1) % 3], dw[i], dw[(i + 1) % 3]) for i in range(3)]
+    opened = cg.to_host(cg.cg_reconstruct(*z))
+    assert np.array_equal(opened, ro.matmul(ex, ew))
+    assert np.max(np.abs(ro.decode(opened, 2 * t) - ro.decode(ex, t) @ ro.decode(ew, t).T)) <= 2.0 ** -12
