@@ -41,6 +41,7 @@ struct GemmParams {
     int H, W, Cin, Ho, Wo, kh, kw, sh, sw, ph, pw;
     FastDiv div_cin, div_kw;
     int group_m;                // tile-rows per launch-order group (set by the launcher)
+    int ksplit;                 // number of K ranges the grid is replicated over (set by the launcher)
 };
 
 // Largest block-tile height any instantiation uses; the host checks 32-bit

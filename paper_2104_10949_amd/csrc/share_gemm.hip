@@ -42,6 +42,20 @@
 
 #include "share_gemm.h"
 
+// tuning knobs of the hand-placed issue order (see half_step() in the kernel)
+#ifndef CG_PIPE
+#define CG_PIPE 1      // 1: words are split in the half-step that loads them; 2: one half-step later
+#endif
+#ifndef CG_PRE_NUM
+#define CG_PRE_NUM 3   // eighths of a half-step's MFMAs issued before the split work starts
+#endif
+#ifndef CG_TILE
+#define CG_TILE 4, 2, 1, 1
+#endif
+#ifndef CG_MINBLOCKS
+#define CG_MINBLOCKS 1
+#endif
+
 namespace cg {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -131,46 +145,54 @@ __device__ __forceinline__ u4 add64x2(u4 a, u4 b) {
 //     k = 32*ks + 16*jh + 8*jj + 2*q + {0,1}.
 // The same (jh, q, jj) -> LDS byte slot map is used for both operands, which is
 // all the contraction needs: digit bytes meet their partner, in any order.
+// An offset of OOB or more is outside every view, so "OOB + something small"
+// still reads zeros: invalid rows need no per-load select.
 // ---------------------------------------------------------------------------
 
 // Row-major [rows, ld] operand, 16-byte loads (ld even, base 16-byte aligned).
 struct LinearVec {
-    u32 rowoff;  // byte offset of the row inside the block's buffer view, or OOB
-    u32 kq;      // 16*jh + 2*q
-    __device__ __forceinline__ void init(const GemmParams&, int row_local, int rows_left, u32 ld,
+    u32 off0;  // byte offset of word k = 16*jh + 2*q of the row inside the view, or OOB
+    u32 kq;    // 16*jh + 2*q
+    __device__ __forceinline__ void init(const GemmParams&, int, int row_local, int rows_left, u32 ld,
                                          int q, int jh) {
-        rowoff = row_local < rows_left ? (u32)row_local * ld * 8u : OOB;
         kq = 16 * jh + 2 * q;
+        off0 = row_local < rows_left ? (u32)row_local * ld * 8u + kq * 8u : OOB;
     }
-    __device__ __forceinline__ void begin_kstep(const GemmParams&, int) {}
-    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int ks, u32 K, u4 out[2]) const {
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const u32 k = 32u * ks + kq + 8u * jj;
-            const u32 off = (k < K && rowoff != OOB) ? rowoff + k * 8u : OOB;
-            out[jj] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+    __device__ __forceinline__ void load(const GemmParams&, __amdgpu_buffer_rsrc_t r, int ks, u32 K,
+                                         u4 out[2]) const {
+        const u32 off = off0 + 256u * ks;
+#ifdef CG_DBG_NOTAIL
+        if (true) {
+#else
+        if (32u * ks + 32u <= K) {  // uniform: whole slice inside K
+#endif
+            out[0] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+            out[1] = __builtin_amdgcn_raw_buffer_load_b128(r, off + 64u, 0, 0);
+        } else {
+            const u32 k = 32u * ks + kq;
+            out[0] = __builtin_amdgcn_raw_buffer_load_b128(r, k < K ? off : OOB, 0, 0);
+            out[1] = __builtin_amdgcn_raw_buffer_load_b128(r, k + 8u < K ? off + 64u : OOB, 0, 0);
         }
     }
 };
 
 // Row-major operand with 8-byte loads: any ld, any 8-byte-aligned base.
 struct LinearScalar {
-    u32 rowoff;
+    u32 off0;
     u32 kq;
-    __device__ __forceinline__ void init(const GemmParams&, int row_local, int rows_left, u32 ld,
+    __device__ __forceinline__ void init(const GemmParams&, int, int row_local, int rows_left, u32 ld,
                                          int q, int jh) {
-        rowoff = row_local < rows_left ? (u32)row_local * ld * 8u : OOB;
         kq = 16 * jh + 2 * q;
+        off0 = row_local < rows_left ? (u32)row_local * ld * 8u + kq * 8u : OOB;
     }
-    __device__ __forceinline__ void begin_kstep(const GemmParams&, int) {}
-    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int ks, u32 K, u4 out[2]) const {
+    __device__ __forceinline__ void load(const GemmParams&, __amdgpu_buffer_rsrc_t r, int ks, u32 K,
+                                         u4 out[2]) const {
+        const u32 off = off0 + 256u * ks;
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const u32 k = 32u * ks + kq + 8u * jj;
-            const u32 o0 = (k < K && rowoff != OOB) ? rowoff + k * 8u : OOB;
-            const u32 o1 = (k + 1 < K && rowoff != OOB) ? rowoff + k * 8u + 8u : OOB;
-            const u2 e0 = __builtin_amdgcn_raw_buffer_load_b64(r, o0, 0, 0);
-            const u2 e1 = __builtin_amdgcn_raw_buffer_load_b64(r, o1, 0, 0);
+            const u2 e0 = __builtin_amdgcn_raw_buffer_load_b64(r, k < K ? off + 64u * jj : OOB, 0, 0);
+            const u2 e1 = __builtin_amdgcn_raw_buffer_load_b64(r, k + 1 < K ? off + 64u * jj + 8u : OOB, 0, 0);
             out[jj].x = e0.x; out[jj].y = e0.y; out[jj].z = e1.x; out[jj].w = e1.y;
         }
     }
@@ -197,40 +219,50 @@ struct PatchRow {
     }
 };
 
-// Patch gather with Cin % 32 == 0: a 32-word slice of K never straddles a filter
-// tap, so the tap (r, s) and the channel offset are uniform over the block.
+// Filter tap of a 32-word slice when Cin % 32 == 0: the slice never straddles a
+// tap, so (r, s) and the channel offset are uniform over the block and advance
+// by scalar increments as ks grows.
+struct TapCursor {
+    int ks, r, s, c0;
+    __device__ __forceinline__ void reset() { ks = 0; r = 0; s = 0; c0 = 0; }
+    __device__ __forceinline__ void advance_to(const GemmParams& p, int want) {
+        while (ks < want) {  // zero or one step per call in the kernel's load order
+            ++ks;
+            c0 += 32;
+            if (c0 == p.Cin) {
+                c0 = 0;
+                if (++s == p.kw) { s = 0; ++r; }
+            }
+        }
+    }
+    __device__ __forceinline__ u32 offset(const GemmParams& p) const {
+        return (((u32)r * (u32)p.W + (u32)s) * (u32)p.Cin + (u32)c0) * 8u;
+    }
+};
+
+// Patch gather with Cin % 32 == 0, 16-byte loads.
 struct ConvC32 {
     PatchRow pr;
-    u32 kq8;       // (16*jh + 2*q) * 8 bytes
-    u32 tap_off;   // per k-step: ((r*W + s)*Cin + c0) * 8, block-uniform
-    int r, s;
-    __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left,
+    u32 kq8;  // (16*jh + 2*q) * 8 bytes
+    __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, u32,
                                          int q, int jh) {
         pr.init(p, m0, row_local, rows_left);
         kq8 = (16 * jh + 2 * q) * 8;
     }
-    __device__ __forceinline__ void begin_kstep(const GemmParams& p, int ks) {
-        const u32 k0 = 32u * ks;
-        const u32 rs = k0 / (u32)p.Cin;           // uniform: scalar ALU
-        const u32 c0 = k0 - rs * (u32)p.Cin;
-        r = (int)(rs / (u32)p.kw);
-        s = (int)(rs - (u32)r * (u32)p.kw);
-        tap_off = (((u32)r * (u32)p.W + (u32)s) * (u32)p.Cin + c0) * 8u;
-    }
-    __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, u4 out[2]) const {
-        const bool v = pr.ok && (u32)(pr.hi0 + r) < (u32)p.H && (u32)(pr.wi0 + s) < (u32)p.W;
-        const u32 off = pr.base + tap_off + kq8;
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-            out[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_, v ? off + 64u * jj : OOB, 0, 0);
+    __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, const TapCursor& t,
+                                         u4 out[2]) const {
+        const bool v = pr.ok && t.r < p.kh && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
+        const u32 off = v ? pr.base + t.offset(p) + kq8 : OOB;
+        out[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off, 0, 0);
+        out[1] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off + 64u, 0, 0);
     }
 };
 
-// Patch gather, any Cin: every word finds its own tap.
+// Patch gather, any Cin: every word finds its own tap; 8-byte loads.
 struct ConvGen {
     PatchRow pr;
     u32 kq;
-    __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left,
+    __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, u32,
                                          int q, int jh) {
         pr.init(p, m0, row_local, rows_left);
         kq = 16 * jh + 2 * q;
@@ -245,7 +277,7 @@ struct ConvGen {
         const u32 off = pr.base + ((r * (u32)p.W + s) * (u32)p.Cin + c) * 8u;
         return __builtin_amdgcn_raw_buffer_load_b64(rs_, v ? off : OOB, 0, 0);
     }
-    __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int ks,
+    __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int ks, u32,
                                          u4 out[2]) const {
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
@@ -256,10 +288,41 @@ struct ConvGen {
     }
 };
 
+// compile-time loop: f(integral_constant<int, I>) for I in [I0, N)
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// The MFMAs of one half-step in issue order: digit l of the left operand
+// outermost, digit m of the right operand (l + m <= 7) next, then the wave's
+// 32x32 sub-tiles.
+struct Slot {
+    int l, m, sm, sn;
+};
+constexpr Slot decode_slot(int slot, int SM, int SN) {
+    const int per = SM * SN;
+    int pair = slot / per;
+    const int in = slot % per;
+    int l = 0, cnt = 8;
+    while (pair >= cnt) { pair -= cnt; ++l; --cnt; }
+    return Slot{l, pair, in / SN, in % SN};
+}
+
+__device__ __forceinline__ void recode2(u4& v) {
+    u32 a = v.x, b = v.y, c = v.z, d = v.w;
+    recode(a, b);
+    recode(c, d);
+    v.x = a; v.y = b; v.z = c; v.w = d;
+}
+
 // ---------------------------------------------------------------------------
 template <class T, int AMODE, bool BVEC>
-__global__ __launch_bounds__(T::NT) void share_gemm_kernel(const GemmParams p) {
-    constexpr int SM = T::SM, SN = T::SN;
+__global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const GemmParams p) {
+    constexpr int SM = T::SM, SN = T::SN, AU = T::A_UNITS, BU = T::B_UNITS;
     __shared__ __attribute__((aligned(16))) char lds[2 * T::STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -271,9 +334,11 @@ __global__ __launch_bounds__(T::NT) void share_gemm_kernel(const GemmParams p) {
     // tiles that share operand rows then share one L2.
     const int tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
     const int nb = tiles_m * tiles_n;
+    // With split-K the grid holds ksplit copies of the tile grid, slowest index first.
+    const int split = blockIdx.x / nb;
     int logical;
     {
-        const int bid = blockIdx.x, xcd = bid & 7, idx = bid >> 3;
+        const int bid = blockIdx.x - split * nb, xcd = bid & 7, idx = bid >> 3;
         const int per = nb >> 3, rem = nb & 7;
         logical = xcd * per + (xcd < rem ? xcd : rem) + idx;
     }
@@ -292,8 +357,9 @@ __global__ __launch_bounds__(T::NT) void share_gemm_kernel(const GemmParams p) {
     const int rows_m = p.M - m0, rows_n = p.N - n0;
 
     // ---- buffer views, rebased per block so that 32-bit offsets suffice
+    constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
     u64 a_base_elems;
-    if (AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR) a_base_elems = (u64)m0 * (u64)p.lda;
+    if (A_LINEAR) a_base_elems = (u64)m0 * (u64)p.lda;
     else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
     const u64 a_left = ((u64)p.x_elems - a_base_elems) * 8u;
     const u32 a_bytes = a_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)a_left;
@@ -310,56 +376,88 @@ __global__ __launch_bounds__(T::NT) void share_gemm_kernel(const GemmParams p) {
             typename std::conditional<AMODE == A_LINEAR_SCALAR, LinearScalar,
             typename std::conditional<AMODE == A_CONV_C32, ConvC32, ConvGen>::type>::type>::type AGen;
     typedef typename std::conditional<BVEC, LinearVec, LinearScalar>::type BGen;
-    AGen ag[T::A_UNITS];
-    BGen bg[T::B_UNITS];
-    int a_dst[T::A_UNITS], b_dst[T::B_UNITS];  // LDS byte offset of digit 0 inside a stage
+    AGen ag[AU];
+    BGen bg[BU];
+    int a_dst[AU], b_dst[BU];  // LDS byte offset of digit 0 inside a stage
 #pragma unroll
-    for (int i = 0; i < T::A_UNITS; ++i) {
+    for (int i = 0; i < AU; ++i) {
         const int u = tid + i * T::NT, q = u & 3, row = (u >> 2) % T::BM, jh = (u >> 2) / T::BM;
-        if constexpr (AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR) ag[i].init(p, row, rows_m, (u32)p.lda, q, jh);
-        else ag[i].init(p, m0, row, rows_m, q, jh);
+        ag[i].init(p, m0, row, rows_m, (u32)p.lda, q, jh);
         a_dst[i] = jh * T::A_RS + row * 16 + q * 4;
     }
 #pragma unroll
-    for (int i = 0; i < T::B_UNITS; ++i) {
+    for (int i = 0; i < BU; ++i) {
         const int u = tid + i * T::NT, q = u & 3, row = (u >> 2) % T::BN, jh = (u >> 2) / T::BN;
-        bg[i].init(p, row, rows_n, (u32)p.K, q, jh);
+        bg[i].init(p, n0, row, rows_n, (u32)p.K, q, jh);
         b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
     }
+    TapCursor tap;
+    tap.reset();
 
-    u4 ra[T::A_UNITS][2], rwa[T::B_UNITS][2], rwb[T::B_UNITS][2];
+    // Two sets of staging registers.  E feeds an even half-step (x_a against
+    // w_a + w_b), O an odd one (x_b against w_a).
+    u4 eA[AU][2], eB[BU][2], eB2[BU][2], oA[AU][2], oB[BU][2];
 
-    auto load_a = [&](__amdgpu_buffer_rsrc_t rs, int ks) {
+    auto load_a = [&](__amdgpu_buffer_rsrc_t rs, int ks, u4 (*dst)[2]) {
         if constexpr (AMODE == A_CONV_C32) {
-            ag[0].begin_kstep(p, ks);
+            tap.advance_to(p, ks);
 #pragma unroll
-            for (int i = 0; i < T::A_UNITS; ++i) {
-                ag[i].r = ag[0].r; ag[i].s = ag[0].s; ag[i].tap_off = ag[0].tap_off;
-                ag[i].load(p, rs, ra[i]);
-            }
-        } else if constexpr (AMODE == A_CONV_GEN) {
-#pragma unroll
-            for (int i = 0; i < T::A_UNITS; ++i) ag[i].load(p, rs, ks, ra[i]);
+            for (int i = 0; i < AU; ++i) ag[i].load(p, rs, tap, dst[i]);
         } else {
 #pragma unroll
-            for (int i = 0; i < T::A_UNITS; ++i) ag[i].load(rs, ks, (u32)p.K, ra[i]);
+            for (int i = 0; i < AU; ++i) ag[i].load(p, rs, ks, (u32)p.K, dst[i]);
         }
     };
     auto load_b = [&](__amdgpu_buffer_rsrc_t rs, int ks, u4 (*dst)[2]) {
 #pragma unroll
-        for (int i = 0; i < T::B_UNITS; ++i) bg[i].load(rs, ks, (u32)p.K, dst[i]);
+        for (int i = 0; i < BU; ++i) bg[i].load(p, rs, ks, (u32)p.K, dst[i]);
     };
-    auto store_a = [&](char* stage) {
-#pragma unroll
-        for (int i = 0; i < T::A_UNITS; ++i) split_store<T::A_RS>(ra[i][0], ra[i][1], stage + a_dst[i]);
+    auto load_even = [&](int ks) {
+        load_a(rs_xa, ks, eA);
+        load_b(rs_wa, ks, eB);
+        load_b(rs_wb, ks, eB2);
     };
-    auto store_b = [&](char* stage, bool sum) {
+    auto load_odd = [&](int ks) {
+        load_a(rs_xb, ks, oA);
+        load_b(rs_wa, ks, oB);
+    };
+
+    // The split of one unit in four pieces, so that they can be placed between MFMAs:
+    // 0: recode the first two words, 1: the last two, 2: digits 0-3 to LDS, 3: digits 4-7.
+    // `add` (the second share of the right operand) is summed in before recoding.
+    auto unit_op = [&](u4 (&v)[2], const u4 (*add)[2], char* dst, auto rs_c, auto phase_c) {
+        constexpr int RS = decltype(rs_c)::value, phase = decltype(phase_c)::value;
+        if constexpr (phase < 2) {
+            if (add) v[phase] = add64x2(v[phase], (*add)[phase]);
+            recode2(v[phase]);
+        } else {
+            u32 d[4];
+            if constexpr (phase == 2) transpose4(v[0].x, v[0].z, v[1].x, v[1].z, d);
+            else transpose4(v[0].y, v[0].w, v[1].y, v[1].w, d);
+            constexpr int l0 = phase == 2 ? 0 : 4;
 #pragma unroll
-        for (int i = 0; i < T::B_UNITS; ++i) {
-            u4 v0 = rwa[i][0], v1 = rwa[i][1];
-            if (sum) { v0 = add64x2(v0, rwb[i][0]); v1 = add64x2(v1, rwb[i][1]); }
-            split_store<T::B_RS>(v0, v1, stage + b_dst[i]);
+            for (int l = 0; l < 4; ++l) *reinterpret_cast<u32*>(dst + (l0 + l) * 2 * RS) = d[l];
         }
+    };
+    constexpr int NOPS = 4 * (AU + BU);
+    // op index -> (unit, piece); A units first, then B units
+    auto split_op = [&](auto op_c, auto even_c, char* stage) {
+        constexpr int op = decltype(op_c)::value, unit = op / 4;
+        constexpr bool even_set = decltype(even_c)::value;
+        const std::integral_constant<int, op % 4> phase;
+        if constexpr (unit < AU) {
+            const std::integral_constant<int, T::A_RS> rs;
+            if constexpr (even_set) unit_op(eA[unit], nullptr, stage + a_dst[unit], rs, phase);
+            else unit_op(oA[unit], nullptr, stage + a_dst[unit], rs, phase);
+        } else {
+            constexpr int b = unit - AU;
+            const std::integral_constant<int, T::B_RS> rs;
+            if constexpr (even_set) unit_op(eB[b], &eB2[b], stage + b_dst[b], rs, phase);
+            else unit_op(oB[b], nullptr, stage + b_dst[b], rs, phase);
+        }
+    };
+    auto split_all = [&](auto even_c, char* stage) {
+        static_for<0, NOPS>([&](auto op_c) { split_op(op_c, even_c, stage); });
     };
 
     const int a_frag = h * T::A_RS + (wm * SM * 32 + r32) * 16;
@@ -367,36 +465,74 @@ __global__ __launch_bounds__(T::NT) void share_gemm_kernel(const GemmParams p) {
 
     v16i acc[SM][SN][8];
 
-    auto compute = [&](const char* stage) {
+    // One half-step with a hand-placed issue order.  MFMAs go digit l of the left
+    // operand outermost.  Only the fragments of the first MFMA are awaited after
+    // the barrier; every other fragment is fetched a slot or two ahead of its
+    // first use, and the global loads for a later half-step (`issue_loads`) go out
+    // in the shadow of the first MFMA.  From slot PRE on, the NOPS split pieces
+    // are spread evenly over the MFMA slots up to LAST, so the vector ALU works
+    // while the matrix pipe is busy.  A full scheduling fence after every slot
+    // keeps the compiler from regrouping them.  Every index is a compile-time
+    // constant.
+    constexpr int NMFMA = 36 * SM * SN;
+    constexpr int PRE = CG_PIPE == 2 ? 1 : NMFMA * CG_PRE_NUM / 8;
+    constexpr int LAST = NMFMA - 2 * SM * SN;  // the final slots only drain
+    auto half_step = [&](const char* cur, char* nxt, auto even_c, auto&& issue_loads) {
         v4i bf[SN][8];
+        v4i af[2][SM];
+        auto read_b = [&](int m) {
 #pragma unroll
-        for (int sn = 0; sn < SN; ++sn)
-#pragma unroll
-            for (int m = 0; m < 8; ++m)
-                bf[sn][m] = *reinterpret_cast<const v4i*>(stage + b_frag + m * 2 * T::B_RS + sn * 512);
-#pragma unroll
-        for (int l = 0; l < 8; ++l) {
-            v4i af[SM];
+            for (int sn = 0; sn < SN; ++sn)
+                bf[sn][m] = *reinterpret_cast<const v4i*>(cur + b_frag + m * 2 * T::B_RS + sn * 512);
+        };
+        auto read_a = [&](int l) {
 #pragma unroll
             for (int sm = 0; sm < SM; ++sm)
-                af[sm] = *reinterpret_cast<const v4i*>(stage + a_frag + l * 2 * T::A_RS + sm * 512);
-#pragma unroll
-            for (int m = 0; m + l < 8; ++m)
-#pragma unroll
-                for (int sm = 0; sm < SM; ++sm)
-#pragma unroll
-                    for (int sn = 0; sn < SN; ++sn)
-                        acc[sm][sn][l + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                            af[sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
-        }
+                af[l & 1][sm] = *reinterpret_cast<const v4i*>(cur + a_frag + l * 2 * T::A_RS + sm * 512);
+        };
+#ifdef CG_DBG_SLEEP
+        __builtin_amdgcn_s_sleep(CG_DBG_SLEEP);
+#endif
+        read_a(0);
+        read_b(0);
+        read_b(1);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, NMFMA>([&](auto slot_c) {
+            constexpr int slot = decltype(slot_c)::value;
+            constexpr Slot sl = decode_slot(slot, SM, SN);
+            constexpr int l = sl.l, m = sl.m, sm = sl.sm, sn = sl.sn;
+            if constexpr (sm == 0 && sn == 0) {
+                if constexpr (l == 0 && m + 2 < 8) read_b(m + 2);
+                if constexpr (m == (l < 7 ? 1 : 0) && l < 7) read_a(l + 1);
+            }
+#ifndef CG_DBG_NOMFMA
+            acc[sm][sn][l + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                af[l & 1][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
+#else
+            acc[sm][sn][l + m][0] ^= af[l & 1][sm][0] + bf[sn][m][1];
+#endif
+            if constexpr (slot == 0) issue_loads();
+#ifndef CG_DBG_NOSPLIT
+            if constexpr (slot >= PRE && slot < LAST) {
+                constexpr int lo = (slot - PRE) * NOPS / (LAST - PRE);
+                constexpr int hi = (slot - PRE + 1) * NOPS / (LAST - PRE);
+                static_for<lo, hi>([&](auto op_c) { split_op(op_c, even_c, nxt); });
+            }
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
 
     char* const st0 = lds;
     char* const st1 = lds + T::STAGE;
-    const int nk = (int)((p.K + 31) / 32);
+    // this block's slices of K: [k_begin, k_end)
+    const int nk_all = (int)((p.K + 31) / 32);
+    const int per_split = (nk_all + p.ksplit - 1) / p.ksplit;
+    const int k_begin = split * per_split;
+    const int nk = k_begin + per_split < nk_all ? k_begin + per_split : nk_all;
+    if (k_begin >= nk) return;  // uniform over the block; only possible when ksplit does not divide evenly
 
-    for (int kb = 0, seg = 0; kb < nk; kb += SEG_KSTEPS, ++seg) {
-        const int ke = kb + SEG_KSTEPS < nk ? kb + SEG_KSTEPS : nk;
+    auto clear_acc = [&]() {
 #pragma unroll
         for (int sm = 0; sm < SM; ++sm)
 #pragma unroll
@@ -405,47 +541,27 @@ __global__ __launch_bounds__(T::NT) void share_gemm_kernel(const GemmParams p) {
                 for (int s = 0; s < 8; ++s)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[sm][sn][s][i] = 0;
+    };
 
-        // even half-step of the first slice
-        load_a(rs_xa, kb);
-        load_b(rs_wa, kb, rwa);
-        load_b(rs_wb, kb, rwb);
-        store_a(st0);
-        store_b(st0, true);
-        __syncthreads();
-
-        for (int ks = kb; ks < ke; ++ks) {
-            // even: x_a against w_a + w_b, while the odd half-step's words arrive
-            load_a(rs_xb, ks);
-            load_b(rs_wa, ks, rwa);
-            compute(st0);
-            store_a(st1);
-            store_b(st1, false);
-            __syncthreads();
-            // odd: x_b against w_a, while the next slice's words arrive
-            const bool more = ks + 1 < ke;
-            if (more) {
-                load_a(rs_xa, ks + 1);
-                load_b(rs_wa, ks + 1, rwa);
-                load_b(rs_wb, ks + 1, rwb);
-            }
-            compute(st1);
-            if (more) {
-                store_a(st0);
-                store_b(st0, true);
-            }
-            __syncthreads();
-        }
-
-        // fold: z (+)= sum_s sext(P_s) << 8s.  P_4..P_7 only reach bits 32..63.
+    // fold: z (+)= sum_s sext(P_s) << 8s.  P_4..P_7 only reach bits 32..63.
+    // The lane index passes through an empty asm so that none of the output
+    // addresses or bounds tests can be computed ahead of the K loop, where they
+    // would sit in registers the loop needs.
+    // Modes: plain store (one fold, one split), read-add-write by the owning lane
+    // (later folds of a single split), atomic add into a zero-filled z (split-K:
+    // integer sums mod 2^64 are exact in any order).
+    auto fold = [&](bool accumulate) {
+        int lane_f = lane;
+        asm volatile("" : "+v"(lane_f));
+        const int r32f = lane_f & 31, hf = lane_f >> 5;
 #pragma unroll
         for (int sm = 0; sm < SM; ++sm)
 #pragma unroll
             for (int sn = 0; sn < SN; ++sn) {
-                const int col = n0 + (wn * SN + sn) * 32 + r32;
+                const int col = n0 + (wn * SN + sn) * 32 + r32f;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int row = m0 + (wm * SM + sm) * 32 + 8 * (i / 4) + 4 * h + (i % 4);
+                    const int row = m0 + (wm * SM + sm) * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
                     u64 v = (u64)(int64_t)acc[sm][sn][0][i];
                     v += (u64)(int64_t)acc[sm][sn][1][i] << 8;
                     v += (u64)(int64_t)acc[sm][sn][2][i] << 16;
@@ -455,27 +571,95 @@ __global__ __launch_bounds__(T::NT) void share_gemm_kernel(const GemmParams p) {
                     v += (u64)hi << 32;
                     if (row < p.M && col < p.N) {
                         u64* dst = p.z + (u64)row * (u64)p.N + (u64)col;
-                        if (seg > 0) v += *dst;
-                        *dst = v;
+                        if (p.ksplit > 1) {
+                            atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
+                        } else {
+                            if (accumulate) v += *dst;
+                            *dst = v;
+                        }
                     }
                 }
             }
+    };
+
+#ifdef CG_DBG_CLOCK
+    const long long dbg_c0 = __builtin_readcyclecounter();
+    const long long dbg_t0 = wall_clock64();
+#endif
+    // Prologue: the even half-step of the first slice goes to LDS.  Loads past the end of
+    // K are out of range and return zeros that are never used, so the loop body
+    // needs no "is there a next slice" branch.
+    load_even(k_begin);
+    split_all(std::true_type{}, st0);
+    if (CG_PIPE == 2) load_odd(k_begin);
+    __syncthreads();
+
+    // Outer loop: one pass per segment of at most SEG_KSTEPS slices (a single pass
+    // unless K > 32*SEG_KSTEPS); the LDS pipeline runs straight through.
+    for (int ks0 = k_begin; ks0 < nk; ks0 += SEG_KSTEPS) {
+        const int ke = ks0 + SEG_KSTEPS < nk ? ks0 + SEG_KSTEPS : nk;
+        clear_acc();
+        for (int ks = ks0; ks < ke; ++ks) {
+            // even half-step: x_a against w_a + w_b from st0; odd words are split into st1
+            half_step(st0, st1, std::false_type{}, [&]() {
+                if (CG_PIPE == 2) load_even(ks + 1); else load_odd(ks);
+            });
+            __syncthreads();
+            // odd half-step: x_b against w_a from st1; the next slice's even words go to st0
+            half_step(st1, st0, std::true_type{}, [&]() {
+                if (CG_PIPE == 2) load_odd(ks + 1); else load_even(ks + 1);
+            });
+            __syncthreads();
+        }
+        fold(ks0 > k_begin);
     }
+#ifdef CG_DBG_CLOCK
+    if (blockIdx.x == 0 && tid == 0) {
+        p.z[0] = (u64)(__builtin_readcyclecounter() - dbg_c0);
+        p.z[1] = (u64)(wall_clock64() - dbg_t0);
+    }
+#endif
 }
 
 // ---------------------------------------------------------------------------
+// z = 0 ahead of a split-K launch (a kernel, not a memset, so that callers may
+// capture the stream into a graph)
+__global__ __launch_bounds__(256) void zero_fill_kernel(u64* z, size_t n) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) z[i] = 0;
+}
+
 template <class T, int AMODE, bool BVEC>
 static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
+    const int64_t tiles = tiles_m * tiles_n;
+    const int nk = (p.K + 31) / 32;
     GemmParams q = p;
     q.group_m = tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);
-    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BVEC>), dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), 0,
+    // Split K when the tile grid alone cannot fill the 256 compute units: aim at
+    // two blocks per unit, keep at least 4 slices of K per block.
+    int ksplit = 1;
+    if (tiles < 256) {
+        ksplit = (int)((512 + tiles - 1) / tiles);
+        if (ksplit > nk / 4) ksplit = nk / 4;
+        if (ksplit < 1) ksplit = 1;
+        const int per = (nk + ksplit - 1) / ksplit;
+        ksplit = (nk + per - 1) / per;  // no empty splits
+    }
+    q.ksplit = ksplit;
+    if (ksplit > 1) {
+        const size_t n = (size_t)p.M * (size_t)p.N;
+        size_t blocks = (n + 255) / 256;
+        if (blocks > 2048) blocks = 2048;
+        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, q.z, n);
+    }
+    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BVEC>), dim3((unsigned)(tiles * ksplit)), dim3(T::NT), 0,
                        stream, q);
     return hipGetLastError();
 }
 
 hipError_t launch_share_gemm(const GemmParams& p, int amode, bool bvec, hipStream_t stream) {
-    typedef Tile<4, 2, 1, 1> T;  // 8 waves, 128 x 64 block tile, 32 x 32 per wave
+    typedef Tile<CG_TILE> T;  // waves along M, waves along N, 32x32 sub-tiles per wave along M, along N
     switch (amode) {
         case A_LINEAR_VEC:    return launch<T, A_LINEAR_VEC, true>(p, stream);
         case A_LINEAR_SCALAR: return launch<T, A_LINEAR_SCALAR, false>(p, stream);
