@@ -29,6 +29,11 @@ METRIC = "Z_2^64 share-GEMM effective 64-bit MAC/s (1 party) + % MFMA peak"
 INT8_PEAK_TOPS = 5000.0  # MI355X dense int8 MFMA, published: 5.0 POP/s (2 ops per MAC)
 DIGIT_MACS_PER_RING_MAC_TRIPLE = 72  # 2 ring products x 36 signed-byte digit pairs per (m, n, k)
 WORKLOAD_CONFIG = 4
+# HBM bytes per share_gemm_kernel launch on the config-4 step, from the two rocprofv3 --pmc runs summarised in
+# profiles/share_gemm_config4_hbm_traffic.txt (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000 by the 1 GiB copy calibration).
+PROFILED_TRAFFIC_CONFIG4 = {"read_bytes_per_launch": 172.7e6, "write_bytes_per_launch": 30.9e6,
+                            "algorithmic_bytes_per_launch": 61.0e6,
+                            "source": "profiles/share_gemm_config4_hbm_traffic.txt"}
 
 
 def parse_args():
@@ -39,9 +44,16 @@ def parse_args():
     ap.add_argument("--config", type=int, default=WORKLOAD_CONFIG, choices=[1, 2, 3, 4, 5],
                     help="benchmark configuration (default: the VGG16-shaped one)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-min-s", type=float, default=10.0,
+                    help="repeat whole passes of the CPU oracle until this many seconds are collected")
     ap.add_argument("--cpu-budget-s", type=float, default=30.0,
                     help="stop adding layers to the CPU-oracle sample after this many seconds")
     ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the register-only MFMA issue-rate measurement")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="after the timed region, run one plain device copy of this many MiB (a kernel of "
+                         "known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -112,6 +124,45 @@ def main() -> int:
         per_layer_ms.append(a.elapsed_time(b) / (reps * L.repeat))
     kernel_ms_sum = sum(ms * L.repeat for ms, L in zip(per_layer_ms, layers))
 
+    def mfma_ceiling(random_bytes: bool) -> float:
+        """int8 TOP/s of a register-only MFMA loop on all compute units (2 waves per SIMD)."""
+        import ctypes
+        import numpy as np
+        from paper_2104_10949_amd import build as hip_build
+        probe = ctypes.CDLL(hip_build.PROBE_LIB)
+        probe.cg_probe_mfma_rate.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 3 + [ctypes.c_void_p]
+        probe.cg_probe_mfma_rate.restype = ctypes.c_int
+        if random_bytes:
+            ops = cg.to_device(wl.draw_ring((8192,), 12345))
+        else:
+            ops = cg.to_device(np.full((8192,), 0x0101010101010101, dtype=np.uint64))
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        sink = torch.empty(n_cu * 512, dtype=torch.int32, device="cuda")
+        iters, stream = 20000, torch.cuda.current_stream().cuda_stream
+
+        def launch():
+            rc = probe.cg_probe_mfma_rate(ops.data_ptr(), sink.data_ptr(), n_cu, 2, iters, stream)
+            if rc != 0:
+                raise RuntimeError(f"cg_probe_mfma_rate returned {rc}")
+        launch()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        launch()
+        b.record()
+        torch.cuda.synchronize()
+        macs = n_cu * 8 * iters * 8 * 32768.0
+        return 2.0 * macs / (a.elapsed_time(b) * 1e-3) / 1e12
+
+    if args.calib_copy_mib > 0:
+        n = args.calib_copy_mib * (1 << 20) // 8
+        src = torch.arange(n, dtype=torch.int64, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)  # reads n*8 bytes, writes n*8 bytes
+        torch.cuda.synchronize()
+
     int8_ops_per_step = 2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * total_mnk
     achieved_tops = int8_ops_per_step / (kernel_ms_sum * 1e-3) / 1e12
     big = max(range(len(layers)), key=lambda i: layers[i].mnk)
@@ -126,8 +177,15 @@ def main() -> int:
         "largest_layer": {"name": layers[big].name, "gemm": list(layers[big].gemm),
                           "ms": round(per_layer_ms[big], 5), "achieved": round(big_tops, 2),
                           "frac": round(big_tops / INT8_PEAK_TOPS, 4)},
-        "traffic": None,
+        "traffic": PROFILED_TRAFFIC_CONFIG4 if args.config == WORKLOAD_CONFIG else None,
     }
+    if not args.no_mfma_probe:
+        # register-only MFMA loop on the same box: what the matrix cores sustain at the power limit
+        peak_const, peak_random = mfma_ceiling(False), mfma_ceiling(True)
+        roofline["measured_mfma_loop"] = {
+            "constant_operands": round(peak_const, 1), "random_operands": round(peak_random, 1), "unit": "TOP/s",
+            "frac_of_random_operand_loop": round(achieved_tops / peak_random, 4),
+            "largest_layer_frac_of_random_operand_loop": round(big_tops / peak_random, 4)}
 
     if args.layers:
         for L, ms in zip(layers, per_layer_ms):
@@ -140,22 +198,27 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import ring_oracle as ro  # the benchmark's cpu_baseline leg only
-        done_mnk, t_cpu, covered = 0, 0.0, []
-        for li, L in enumerate(layers):
-            if t_cpu > args.cpu_budget_s:
-                break
-            t0 = time.perf_counter()
-            if L.kind == "conv":
-                ro.party_conv2d(*host_ops[li], (L.stride, L.stride), (L.pad, L.pad))
-            else:
-                ro.party_matmul(*host_ops[li])
-            t_cpu += time.perf_counter() - t0
-            done_mnk += L.mnk
-            covered.append(L.name)
+        done_mnk, t_cpu, covered, passes = 0, 0.0, [], 0
+        # whole passes over the workload until about 10 s of CPU work are collected (one pass at least,
+        # cut short at the budget)
+        while t_cpu < args.cpu_min_s and t_cpu <= args.cpu_budget_s:
+            for li, L in enumerate(layers):
+                if t_cpu > args.cpu_budget_s:
+                    break
+                t0 = time.perf_counter()
+                if L.kind == "conv":
+                    ro.party_conv2d(*host_ops[li], (L.stride, L.stride), (L.pad, L.pad))
+                else:
+                    ro.party_matmul(*host_ops[li])
+                t_cpu += time.perf_counter() - t0
+                done_mnk += L.mnk
+                if passes == 0:
+                    covered.append(L.name)
+            passes += 1
         cpu = {"value": 3.0 * done_mnk / t_cpu, "unit": "ring MAC/s", "cores": ro.num_threads(),
                "kind": "oracle", "seconds": round(t_cpu, 2),
-               "sample": (f"{len(covered)} of {len(layers)} layers of config {args.config} at full size, one party, "
-                          f"one pass each ({covered[0]} .. {covered[-1]}), {3 * done_mnk:.3e} ring MACs")}
+               "sample": (f"{passes} pass(es) over {len(covered)} of {len(layers)} layers of config {args.config} at "
+                          f"full size, one party ({covered[0]} .. {covered[-1]}), {3 * done_mnk:.3e} ring MACs")}
 
     out = {
         "metric": METRIC, "value": value, "unit": "ring MAC/s", "n_gpus": 1,

@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcg.so")
+PROBE_LIB = os.path.join(HERE, "libcg_probe.so")  # MFMA issue-rate microbenchmark for bench.py, not part of libcg
 SOURCES = ["cg_api.hip", "share_gemm.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -26,6 +27,10 @@ def build(verbose: bool = False) -> str:
         subprocess.run(cmd, check=True)
         objs.append(obj)
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    cmd = ["hipcc", *FLAGS, "-shared", "-o", PROBE_LIB, os.path.join(CSRC, "mfma_probe.hip")]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

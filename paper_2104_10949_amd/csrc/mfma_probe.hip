@@ -1,0 +1,63 @@
+// Register-only int8 MFMA issue loop: the matrix-core rate this chip sustains for
+// given operand bytes, with no memory traffic in the loop.  Used by bench.py to
+// report the share-product kernel against a MEASURED ceiling next to the
+// published one: operand bit patterns change the power drawn and with it the
+// clock, and secret shares are uniformly random bytes.  Not part of libcg.so.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Eight rotating accumulators, as in the share-product kernel; operands are read
+// once from `src` (16 bytes per lane and operand) before the loop.
+template <int NT>
+__global__ __launch_bounds__(NT) void mfma_rate_kernel(const v4i* __restrict__ src, int* __restrict__ sink,
+                                                       int iters) {
+    const int t = threadIdx.x;
+    v4i a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = src[(t * 8 + i) & 4095];
+        b[i] = src[(t * 8 + 4 + i) & 4095];
+    }
+    v16i c[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[s][i] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+            c[s] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[s & 3], b[(s >> 1) & 3], c[s], 0, 0, 0);
+    }
+    int acc = 0;
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc += c[s][i];
+    sink[(size_t)blockIdx.x * NT + t] = acc;
+}
+
+extern "C" {
+
+// Launch the loop on `blocks` blocks of 4*waves_per_simd waves.
+//   operands : device, 64 KiB of operand bytes (4096 x 16 B)
+//   sink     : device, blocks * 256 * waves_per_simd ints, receives a checksum
+// Each wave issues 8*iters MFMAs of 32*32*32 MACs.  Returns 0 on success, 1 on bad
+// arguments, 2 if the launch failed.  The caller times the stream.
+__attribute__((visibility("default")))
+int cg_probe_mfma_rate(const void* operands, void* sink, int blocks, int waves_per_simd, int iters,
+                       void* stream) {
+    if (!operands || !sink || blocks < 1 || iters < 1 || (waves_per_simd != 1 && waves_per_simd != 2)) return 1;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (waves_per_simd == 1)
+        hipLaunchKernelGGL(mfma_rate_kernel<256>, dim3(blocks), dim3(256), 0, s,
+                           static_cast<const v4i*>(operands), static_cast<int*>(sink), iters);
+    else
+        hipLaunchKernelGGL(mfma_rate_kernel<512>, dim3(blocks), dim3(512), 0, s,
+                           static_cast<const v4i*>(operands), static_cast<int*>(sink), iters);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+}  // extern "C"
