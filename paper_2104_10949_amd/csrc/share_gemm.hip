@@ -417,17 +417,17 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         load_b(rs_wa, ks, eB);
         load_b(rs_wb, ks, eB2);
     };
-    auto load_odd = [&](int ks) {
-        load_a(rs_xb, ks, oA);
-        load_b(rs_wa, ks, oB);
-    };
+    // w_a of a slice is fetched once, with the even set; the odd set's copy is
+    // taken from there before the even set is summed and recoded.
+    auto load_odd = [&](int ks) { load_a(rs_xb, ks, oA); };
 
     // The split of one unit in four pieces, so that they can be placed between MFMAs:
     // 0: recode the first two words, 1: the last two, 2: digits 0-3 to LDS, 3: digits 4-7.
     // `add` (the second share of the right operand) is summed in before recoding.
-    auto unit_op = [&](u4 (&v)[2], const u4 (*add)[2], char* dst, auto rs_c, auto phase_c) {
+    auto unit_op = [&](u4 (&v)[2], const u4 (*add)[2], u4 (*keep)[2], char* dst, auto rs_c, auto phase_c) {
         constexpr int RS = decltype(rs_c)::value, phase = decltype(phase_c)::value;
         if constexpr (phase < 2) {
+            if (keep) (*keep)[phase] = v[phase];
             if (add) v[phase] = add64x2(v[phase], (*add)[phase]);
             recode2(v[phase]);
         } else {
@@ -447,13 +447,13 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         const std::integral_constant<int, op % 4> phase;
         if constexpr (unit < AU) {
             const std::integral_constant<int, T::A_RS> rs;
-            if constexpr (even_set) unit_op(eA[unit], nullptr, stage + a_dst[unit], rs, phase);
-            else unit_op(oA[unit], nullptr, stage + a_dst[unit], rs, phase);
+            if constexpr (even_set) unit_op(eA[unit], nullptr, nullptr, stage + a_dst[unit], rs, phase);
+            else unit_op(oA[unit], nullptr, nullptr, stage + a_dst[unit], rs, phase);
         } else {
             constexpr int b = unit - AU;
             const std::integral_constant<int, T::B_RS> rs;
-            if constexpr (even_set) unit_op(eB[b], &eB2[b], stage + b_dst[b], rs, phase);
-            else unit_op(oB[b], nullptr, stage + b_dst[b], rs, phase);
+            if constexpr (even_set) unit_op(eB[b], &eB2[b], &oB[b], stage + b_dst[b], rs, phase);
+            else unit_op(oB[b], nullptr, nullptr, stage + b_dst[b], rs, phase);
         }
     };
     auto split_all = [&](auto even_c, char* stage) {
