@@ -42,7 +42,8 @@ typedef enum {
     CG_ERR_ALIAS = 4,       /* an output overlaps an input where that is not allowed */
     CG_ERR_UNSUPPORTED = 5, /* valid mathematics, but outside what the kernels address
                                (see each call) */
-    CG_ERR_DEVICE = 6       /* the HIP runtime reported an error at launch */
+    CG_ERR_DEVICE = 6,      /* the HIP runtime reported an error at launch */
+    CG_ERR_WORKSPACE = 7    /* the scratch memory passed to a *_ws call is too small */
 } cg_status;
 
 /* Human-readable name of a status; static storage, never freed. */
@@ -77,6 +78,28 @@ CG_API cg_status cg_share_matmul(const uint64_t *x_i, const uint64_t *x_ip1,
                           uint64_t *z_i, int64_t M, int64_t N, int64_t K, void *stream);
 
 /*
+ * The same product with caller-supplied scratch memory (device memory, 16-byte
+ * aligned, at least cg_share_matmul_workspace_bytes(M, N, K) bytes, not
+ * overlapping any operand).  With scratch memory each share tensor is split
+ * into its eight signed-byte digits ONCE, by a streaming pass that writes the
+ * digits there, instead of once per output tile that needs it inside the product
+ * kernel; the product kernel then only moves bytes.  Result and argument rules
+ * are those of cg_share_matmul, bit for bit.  The scratch contents are
+ * undefined afterwards and carry no state between calls.  When the digit route
+ * does not apply (odd K, or a pointer that is only 8-byte aligned) the call
+ * computes exactly as cg_share_matmul and does not touch the scratch memory;
+ * cg_share_matmul_workspace_bytes then returns 0 (as it does for invalid sizes).
+ * CG_ERR_WORKSPACE if workspace_bytes is too small, CG_ERR_NULL / CG_ERR_ALIGN /
+ * CG_ERR_ALIAS for a missing, misaligned or overlapping workspace.
+ */
+CG_API size_t cg_share_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+CG_API cg_status cg_share_matmul_ws(const uint64_t *x_i, const uint64_t *x_ip1,
+                             const uint64_t *y_i, const uint64_t *y_ip1,
+                             uint64_t *z_i, int64_t M, int64_t N, int64_t K,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Same local step for a 2-D convolution (Sec. III-B, "Convolutions and matrix
  * multiplication"), evaluated as an implicit matrix product: no patch matrix
  * is ever written to memory.  Convolution means cross-correlation with zero
@@ -105,6 +128,18 @@ typedef struct {
 CG_API cg_status cg_share_conv2d(const uint64_t *x_i, const uint64_t *x_ip1,
                           const uint64_t *w_i, const uint64_t *w_ip1,
                           uint64_t *z_i, const cg_conv2d_desc *desc, void *stream);
+
+/*
+ * cg_share_conv2d with caller-supplied scratch memory; see cg_share_matmul_ws.
+ * The digit route applies when Cin is a multiple of 32 (or the convolution is
+ * 1x1, stride 1, unpadded with even Cin) and all pointers are 16-byte aligned.
+ */
+CG_API size_t cg_share_conv2d_workspace_bytes(const cg_conv2d_desc *desc);
+
+CG_API cg_status cg_share_conv2d_ws(const uint64_t *x_i, const uint64_t *x_ip1,
+                             const uint64_t *w_i, const uint64_t *w_ip1,
+                             uint64_t *z_i, const cg_conv2d_desc *desc,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Local linear operations on a replicated pair (a = s_i, b = s_{i+1}), over n

@@ -17,10 +17,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # CG_LIBRARY may name another build of the same library (tuning experiments)
 LIB_PATH = os.environ.get("CG_LIBRARY") or os.path.join(_HERE, "libcg.so")
 
-CG_OK, CG_ERR_NULL, CG_ERR_SHAPE, CG_ERR_ALIGN, CG_ERR_ALIAS, CG_ERR_UNSUPPORTED, CG_ERR_DEVICE = range(7)
+(CG_OK, CG_ERR_NULL, CG_ERR_SHAPE, CG_ERR_ALIGN, CG_ERR_ALIAS, CG_ERR_UNSUPPORTED, CG_ERR_DEVICE,
+ CG_ERR_WORKSPACE) = range(8)
 
 EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d", "cg_share_add",
-           "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct")
+           "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct",
+           "cg_share_matmul_ws", "cg_share_conv2d_ws",
+           "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
 class ConvDesc(ctypes.Structure):
@@ -58,8 +61,14 @@ def lib() -> ctypes.CDLL:
         L.cg_share_mul_public.argtypes = [vp, vp, u64, vp, vp, sz, vp]
         L.cg_share_add_public.argtypes = [vp, vp, u64, ctypes.c_int, vp, vp, sz, vp]
         L.cg_reconstruct.argtypes = [vp] * 4 + [sz, vp]
-        for name in EXPORTS[2:]:
+        L.cg_share_matmul_ws.argtypes = [vp] * 5 + [i64] * 3 + [vp, sz, vp]
+        L.cg_share_conv2d_ws.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp, sz, vp]
+        L.cg_share_matmul_workspace_bytes.argtypes = [i64] * 3
+        L.cg_share_conv2d_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+        for name in EXPORTS[2:10]:
             getattr(L, name).restype = ctypes.c_int
+        for name in EXPORTS[10:]:
+            getattr(L, name).restype = sz
         _lib = L
     return _lib
 
@@ -108,6 +117,34 @@ def cg_share_matmul(x_i, x_ip1, y_i, y_ip1, z_i=None, stream=None) -> torch.Tens
     return z_i
 
 
+def cg_share_matmul_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().cg_share_matmul_workspace_bytes(M, N, K))
+
+
+def _ws(workspace) -> Tuple[int, int]:
+    if workspace is None:
+        return 0, 0
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def cg_share_matmul_ws(x_i, x_ip1, y_i, y_ip1, workspace, z_i=None, stream=None) -> torch.Tensor:
+    """cg_share_matmul with caller-supplied scratch memory (any contiguous GPU tensor)."""
+    M, K = x_i.shape
+    N = y_i.shape[0]
+    if x_ip1.shape != x_i.shape or y_ip1.shape != y_i.shape or y_i.shape[1] != K:
+        raise ValueError("operand shapes do not match")
+    if z_i is None:
+        z_i = torch.empty((M, N), dtype=torch.int64, device=x_i.device)
+    elif tuple(z_i.shape) != (M, N):
+        raise ValueError("output shape does not match")
+    wp, wb = _ws(workspace)
+    _check(lib().cg_share_matmul_ws(_ptr(x_i), _ptr(x_ip1), _ptr(y_i), _ptr(y_ip1), _ptr(z_i),
+                                    M, N, K, wp, wb, _stream(stream)), "cg_share_matmul_ws")
+    return z_i
+
+
 def conv_out_shape(x_shape: Sequence[int], w_shape: Sequence[int], stride: Tuple[int, int],
                    pad: Tuple[int, int]) -> Tuple[int, int, int, int]:
     B, H, W, _ = x_shape
@@ -131,6 +168,34 @@ def cg_share_conv2d(x_i, x_ip1, w_i, w_ip1, stride=(1, 1), pad=(0, 0), z_i=None,
         raise ValueError("output shape does not match")
     _check(lib().cg_share_conv2d(_ptr(x_i), _ptr(x_ip1), _ptr(w_i), _ptr(w_ip1), _ptr(z_i),
                                  ctypes.byref(d), _stream(stream)), "cg_share_conv2d")
+    return z_i
+
+
+def cg_share_conv2d_workspace_bytes(x_shape, w_shape, stride=(1, 1), pad=(0, 0)) -> int:
+    B, H, W, Cin = x_shape
+    Cout, kh, kw, _ = w_shape
+    d = ConvDesc(B, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    return int(lib().cg_share_conv2d_workspace_bytes(ctypes.byref(d)))
+
+
+def cg_share_conv2d_ws(x_i, x_ip1, w_i, w_ip1, workspace, stride=(1, 1), pad=(0, 0), z_i=None,
+                       stream=None) -> torch.Tensor:
+    """cg_share_conv2d with caller-supplied scratch memory (any contiguous GPU tensor)."""
+    B, H, W, Cin = x_i.shape
+    Cout, kh, kw, Cin2 = w_i.shape
+    if x_ip1.shape != x_i.shape or w_ip1.shape != w_i.shape or Cin2 != Cin:
+        raise ValueError("operand shapes do not match")
+    d = ConvDesc(B, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    zs = conv_out_shape(x_i.shape, w_i.shape, stride, pad)
+    if z_i is None:
+        if zs[1] < 1 or zs[2] < 1:
+            _check(CG_ERR_SHAPE, "cg_share_conv2d_ws")
+        z_i = torch.empty(zs, dtype=torch.int64, device=x_i.device)
+    elif tuple(z_i.shape) != zs:
+        raise ValueError("output shape does not match")
+    wp, wb = _ws(workspace)
+    _check(lib().cg_share_conv2d_ws(_ptr(x_i), _ptr(x_ip1), _ptr(w_i), _ptr(w_ip1), _ptr(z_i),
+                                    ctypes.byref(d), wp, wb, _stream(stream)), "cg_share_conv2d_ws")
     return z_i
 
 

@@ -155,40 +155,72 @@ const char* cg_status_string(cg_status s) {
         case CG_ERR_ALIAS: return "CG_ERR_ALIAS: output overlaps an input";
         case CG_ERR_UNSUPPORTED: return "CG_ERR_UNSUPPORTED: shape outside the kernels' addressing range";
         case CG_ERR_DEVICE: return "CG_ERR_DEVICE: HIP launch error";
+        case CG_ERR_WORKSPACE: return "CG_ERR_WORKSPACE: scratch memory smaller than cg_*_workspace_bytes()";
     }
     return "unknown cg_status";
 }
 
 int cg_version(void) { return 100; }
 
-cg_status cg_share_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
-                          const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
-                          void* stream) {
-    if (!x_i || !x_ip1 || !y_i || !y_ip1 || !z_i) return CG_ERR_NULL;
+}  // extern "C"
+
+namespace {
+
+// What a validated call resolves to.
+struct Plan {
+    cg::GemmParams p;
+    int amode;        // address generator of the direct route
+    bool bvec;
+    bool planes_ok;   // the digit-plane route applies
+    bool planes_conv; // ... with the patch gather
+    int64_t x_rows, x_k;  // left operand seen as [x_rows, x_k] words for the plane conversion
+    u64 xp_bytes, wp_bytes;  // bytes of one left / right plane tensor
+    u64 x_bytes, w_bytes, z_bytes;
+};
+
+u64 round_up(u64 v, u64 a) { return (v + a - 1) / a * a; }
+
+u64 plan_workspace_bytes(const Plan& pl) {
+    return pl.planes_ok ? 2 * round_up(pl.xp_bytes, 256) + 2 * round_up(pl.wp_bytes, 256) : 0;
+}
+
+cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i, const uint64_t* y_ip1,
+                      uint64_t* z_i, int64_t M, int64_t N, int64_t K, bool check_ptrs_too, Plan* out) {
+    if (check_ptrs_too && (!x_i || !x_ip1 || !y_i || !y_ip1 || !z_i)) return CG_ERR_NULL;
     if (M < 1 || N < 1 || K < 1) return CG_ERR_SHAPE;
     int64_t mk, nk, mn, tmp;
     if (mul_overflows(M, K, &mk) || mul_overflows(N, K, &nk) || mul_overflows(M, N, &mn) ||
         mul_overflows(mk, 8, &tmp) || mul_overflows(nk, 8, &tmp) || mul_overflows(mn, 8, &tmp))
         return CG_ERR_SHAPE;
-    if (cg_status st = check_product_ptrs(x_i, x_ip1, y_i, y_ip1, z_i, (u64)mk * 8, (u64)nk * 8, (u64)mn * 8))
-        return st;
+    if (check_ptrs_too)
+        if (cg_status st = check_product_ptrs(x_i, x_ip1, y_i, y_ip1, z_i, (u64)mk * 8, (u64)nk * 8, (u64)mn * 8))
+            return st;
     if (M > MAX_DIM || N > MAX_DIM || K > MAX_ROW_WORDS) return CG_ERR_UNSUPPORTED;
 
-    cg::GemmParams p = {};
+    Plan pl = {};
+    cg::GemmParams& p = pl.p;
     p.x_a = x_i; p.x_b = x_ip1; p.w_a = y_i; p.w_b = y_ip1; p.z = z_i;
     p.M = (int)M; p.N = (int)N; p.K = (int)K; p.lda = (int)K;
     p.x_elems = (u64)mk;
     p.Ho = p.Wo = 1;
     const void* in[4] = {x_i, x_ip1, y_i, y_ip1};
-    const bool vec = (K % 2 == 0) && all_aligned16(in, 4);
-    const hipError_t e = cg::launch_share_gemm(p, vec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR, vec,
-                                               static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+    const bool vec = (K % 2 == 0) && (!check_ptrs_too || all_aligned16(in, 4));
+    pl.amode = vec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR;
+    pl.bvec = vec;
+    const int64_t KS = (K + 31) / 32;
+    pl.planes_ok = vec;
+    pl.planes_conv = false;
+    pl.x_rows = M; pl.x_k = K;
+    pl.xp_bytes = (u64)M * (u64)KS * 256; pl.wp_bytes = (u64)N * (u64)KS * 256;
+    pl.x_bytes = (u64)mk * 8; pl.w_bytes = (u64)nk * 8; pl.z_bytes = (u64)mn * 8;
+    *out = pl;
+    return CG_OK;
 }
 
-cg_status cg_share_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i,
-                          const uint64_t* w_ip1, uint64_t* z_i, const cg_conv2d_desc* d, void* stream) {
-    if (!x_i || !x_ip1 || !w_i || !w_ip1 || !z_i || !d) return CG_ERR_NULL;
+cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i, const uint64_t* w_ip1,
+                      uint64_t* z_i, const cg_conv2d_desc* d, bool check_ptrs_too, Plan* out) {
+    if (!d) return CG_ERR_NULL;
+    if (check_ptrs_too && (!x_i || !x_ip1 || !w_i || !w_ip1 || !z_i)) return CG_ERR_NULL;
     if (d->B < 1 || d->H < 1 || d->W < 1 || d->Cin < 1 || d->Cout < 1 || d->kh < 1 || d->kw < 1 ||
         d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0)
         return CG_ERR_SHAPE;
@@ -206,13 +238,15 @@ cg_status cg_share_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint
         mul_overflows(Ho, Wo, &howo) || mul_overflows(howo, d->B, &M) || mul_overflows(M, d->Cout, &z_el) ||
         mul_overflows(x_el, 8, &tmp) || mul_overflows(w_el, 8, &tmp) || mul_overflows(z_el, 8, &tmp))
         return CG_ERR_SHAPE;
-    if (cg_status st = check_product_ptrs(x_i, x_ip1, w_i, w_ip1, z_i, (u64)x_el * 8, (u64)w_el * 8, (u64)z_el * 8))
-        return st;
+    if (check_ptrs_too)
+        if (cg_status st = check_product_ptrs(x_i, x_ip1, w_i, w_ip1, z_i, (u64)x_el * 8, (u64)w_el * 8, (u64)z_el * 8))
+            return st;
     if (M > MAX_DIM || d->Cout > MAX_DIM || K > MAX_ROW_WORDS || img > ((int64_t)1 << 27) ||
         d->pad_h > 32767 || d->pad_w > 32767 || d->stride_h > 32767 || d->stride_w > 32767)
         return CG_ERR_UNSUPPORTED;
 
-    cg::GemmParams p = {};
+    Plan pl = {};
+    cg::GemmParams& p = pl.p;
     p.x_a = x_i; p.x_b = x_ip1; p.w_a = w_i; p.w_b = w_ip1; p.z = z_i;
     p.M = (int)M; p.N = (int)d->Cout; p.K = (int)K;
     p.x_elems = (u64)x_el;
@@ -224,7 +258,7 @@ cg_status cg_share_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint
     p.div_kw = cg::make_fast_div((uint32_t)d->kw);
 
     const void* in[4] = {x_i, x_ip1, w_i, w_ip1};
-    const bool a16 = all_aligned16(in, 4);
+    const bool a16 = !check_ptrs_too || all_aligned16(in, 4);
     int amode;
     bool bvec = a16 && (K % 2 == 0);
     const bool pointwise = d->kh == 1 && d->kw == 1 && d->stride_h == 1 && d->stride_w == 1 &&
@@ -241,8 +275,106 @@ cg_status cg_share_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint
         if (view > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;
         amode = (a16 && d->Cin % 32 == 0) ? cg::A_CONV_C32 : cg::A_CONV_GEN;
     }
-    const hipError_t e = cg::launch_share_gemm(p, amode, bvec, static_cast<hipStream_t>(stream));
+    pl.amode = amode;
+    pl.bvec = bvec;
+    const int64_t KS = (K + 31) / 32;
+    if (pointwise) {
+        pl.planes_ok = bvec;
+        pl.planes_conv = false;
+        pl.x_rows = M; pl.x_k = d->Cin;
+        pl.xp_bytes = (u64)M * (u64)KS * 256;
+    } else {
+        pl.planes_ok = amode == cg::A_CONV_C32;
+        pl.planes_conv = true;
+        pl.x_rows = d->B * d->H * d->W; pl.x_k = d->Cin;
+        pl.xp_bytes = (u64)x_el * 8;
+    }
+    pl.wp_bytes = (u64)d->Cout * (u64)KS * 256;
+    pl.x_bytes = (u64)x_el * 8; pl.w_bytes = (u64)w_el * 8; pl.z_bytes = (u64)z_el * 8;
+    *out = pl;
+    return CG_OK;
+}
+
+cg_status run_direct(const Plan& pl, void* stream) {
+    const hipError_t e = cg::launch_share_gemm(pl.p, pl.amode, pl.bvec, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+// Digit-plane route: four conversions into the caller's scratch memory, then the contraction.
+cg_status run_planes(Plan& pl, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!workspace) return CG_ERR_NULL;
+    if (!aligned(workspace, 16)) return CG_ERR_ALIGN;
+    const u64 need = plan_workspace_bytes(pl);
+    if (workspace_bytes < need) return CG_ERR_WORKSPACE;
+    const cg::GemmParams& q = pl.p;
+    if (overlap(workspace, need, q.x_a, pl.x_bytes) || overlap(workspace, need, q.x_b, pl.x_bytes) ||
+        overlap(workspace, need, q.w_a, pl.w_bytes) || overlap(workspace, need, q.w_b, pl.w_bytes) ||
+        overlap(workspace, need, q.z, pl.z_bytes))
+        return CG_ERR_ALIAS;
+    char* ws = static_cast<char*>(workspace);
+    char* xp_a = ws;
+    char* xp_b = xp_a + round_up(pl.xp_bytes, 256);
+    char* wp_sum = xp_b + round_up(pl.xp_bytes, 256);
+    char* wp_a = wp_sum + round_up(pl.wp_bytes, 256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = cg::launch_to_planes(q.x_a, nullptr, xp_a, pl.x_rows, pl.x_k, s);
+    if (e == hipSuccess) e = cg::launch_to_planes(q.x_b, nullptr, xp_b, pl.x_rows, pl.x_k, s);
+    if (e == hipSuccess) e = cg::launch_to_planes(q.w_a, q.w_b, wp_sum, q.N, q.K, s);
+    if (e == hipSuccess) e = cg::launch_to_planes(q.w_a, nullptr, wp_a, q.N, q.K, s);
+    if (e != hipSuccess) return CG_ERR_DEVICE;
+    pl.p.xp_a = xp_a; pl.p.xp_b = xp_b; pl.p.wp_sum = wp_sum; pl.p.wp_a = wp_a;
+    pl.p.xp_bytes = pl.xp_bytes;
+    e = cg::launch_share_gemm_planes(pl.p, pl.planes_conv, s);
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+cg_status cg_share_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
+                          const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
+                          void* stream) {
+    Plan pl;
+    if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl)) return st;
+    return run_direct(pl, stream);
+}
+
+size_t cg_share_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    Plan pl;
+    if (plan_matmul(nullptr, nullptr, nullptr, nullptr, nullptr, M, N, K, false, &pl) != CG_OK) return 0;
+    return (size_t)plan_workspace_bytes(pl);
+}
+
+cg_status cg_share_matmul_ws(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
+                             const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    Plan pl;
+    if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl)) return st;
+    if (!pl.planes_ok) return run_direct(pl, stream);
+    return run_planes(pl, workspace, workspace_bytes, stream);
+}
+
+cg_status cg_share_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i,
+                          const uint64_t* w_ip1, uint64_t* z_i, const cg_conv2d_desc* d, void* stream) {
+    Plan pl;
+    if (cg_status st = plan_conv2d(x_i, x_ip1, w_i, w_ip1, z_i, d, true, &pl)) return st;
+    return run_direct(pl, stream);
+}
+
+size_t cg_share_conv2d_workspace_bytes(const cg_conv2d_desc* d) {
+    Plan pl;
+    if (plan_conv2d(nullptr, nullptr, nullptr, nullptr, nullptr, d, false, &pl) != CG_OK) return 0;
+    return (size_t)plan_workspace_bytes(pl);
+}
+
+cg_status cg_share_conv2d_ws(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i,
+                             const uint64_t* w_ip1, uint64_t* z_i, const cg_conv2d_desc* d,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    Plan pl;
+    if (cg_status st = plan_conv2d(x_i, x_ip1, w_i, w_ip1, z_i, d, true, &pl)) return st;
+    if (!pl.planes_ok) return run_direct(pl, stream);
+    return run_planes(pl, workspace, workspace_bytes, stream);
 }
 
 cg_status cg_share_add(const uint64_t* xa, const uint64_t* xb, const uint64_t* ya, const uint64_t* yb,

@@ -40,6 +40,9 @@ struct GemmParams {
     uint64_t img_elems;         // H*W*Cin (patch modes)
     int H, W, Cin, Ho, Wo, kh, kw, sh, sw, ph, pw;
     FastDiv div_cin, div_kw;
+    // digit-plane route: planes of x_i, x_{i+1}, y_i + y_{i+1}, y_i (see to_planes_kernel)
+    const char *xp_a, *xp_b, *wp_sum, *wp_a;
+    uint64_t xp_bytes;          // bytes of one left-operand plane tensor
     int group_m;                // tile-rows per launch-order group (set by the launcher)
     int ksplit;                 // number of K ranges the grid is replicated over (set by the launcher)
 };
@@ -49,6 +52,13 @@ struct GemmParams {
 static const int MAX_TILE_ROWS = 256;
 
 hipError_t launch_share_gemm(const GemmParams& p, int amode, bool bvec, hipStream_t stream);
+
+// Digit-plane route.  launch_to_planes converts a row-major [R, K] operand (K even,
+// 16-byte aligned), optionally summed with `add` first, into planes of
+// R * ceil(K/32) * 256 bytes; launch_share_gemm_planes contracts four plane tensors.
+hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,
+                            hipStream_t stream);
+hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t stream);
 
 }  // namespace cg
 #endif

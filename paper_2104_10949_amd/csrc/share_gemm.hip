@@ -43,9 +43,6 @@
 #include "share_gemm.h"
 
 // tuning knobs of the hand-placed issue order (see half_step() in the kernel)
-#ifndef CG_PIPE
-#define CG_PIPE 1      // 1: words are split in the half-step that loads them; 2: one half-step later
-#endif
 #ifndef CG_PRE_NUM
 #define CG_PRE_NUM 3   // eighths of a half-step's MFMAs issued before the split work starts
 #endif
@@ -161,11 +158,7 @@ struct LinearVec {
     __device__ __forceinline__ void load(const GemmParams&, __amdgpu_buffer_rsrc_t r, int ks, u32 K,
                                          u4 out[2]) const {
         const u32 off = off0 + 256u * ks;
-#ifdef CG_DBG_NOTAIL
-        if (true) {
-#else
         if (32u * ks + 32u <= K) {  // uniform: whole slice inside K
-#endif
             out[0] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
             out[1] = __builtin_amdgcn_raw_buffer_load_b128(r, off + 64u, 0, 0);
         } else {
@@ -319,6 +312,67 @@ __device__ __forceinline__ void recode2(u4& v) {
     v.x = a; v.y = b; v.z = c; v.w = d;
 }
 
+// block -> (K split, output tile).  Consecutive block ids go to different XCDs
+// (round robin over 8), so each XCD gets a contiguous run of logical tiles and
+// tiles that share operand rows share one L2.  Inside a run, tiles are taken in
+// groups of group_m tile-rows, tile-row fastest.  With split-K the grid holds
+// ksplit copies of the tile grid, slowest index first.
+__device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int BN, int& split, int& tm, int& tn) {
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    const int nb = tiles_m * tiles_n;
+    split = blockIdx.x / nb;
+    const int bid = blockIdx.x - split * nb, xcd = bid & 7, idx = bid >> 3;
+    const int per = nb >> 3, rem = nb & 7;
+    const int logical = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    const int GM = p.group_m;
+    const int per_group = GM * tiles_n;
+    const int g = logical / per_group, in_g = logical - g * per_group;
+    const int first = g * GM;
+    const int gsz = tiles_m - first < GM ? tiles_m - first : GM;
+    tm = first + in_g % gsz;
+    tn = in_g / gsz;
+}
+
+// fold: z (+)= sum_s sext(P_s) << 8s for the wave's sub-tiles.  P_4..P_7 only
+// reach bits 32..63.  Modes: plain store (one fold, one split), read-add-write by
+// the owning lane (later folds of a single split), atomic add into a zero-filled z
+// (split-K: integer sums mod 2^64 are exact in any order).  The lane index passes
+// through an empty asm so that none of the output addresses or bounds tests can be
+// computed ahead of the K loop, where they would sit in registers the loop needs.
+template <int SM, int SN>
+__device__ __forceinline__ void fold_tile(const GemmParams& p, v16i (&acc)[SM][SN][8], int row0, int col0,
+                                          int lane, bool accumulate) {
+    int lane_f = lane;
+    asm volatile("" : "+v"(lane_f));
+    const int r32f = lane_f & 31, hf = lane_f >> 5;
+#pragma unroll
+    for (int sm = 0; sm < SM; ++sm)
+#pragma unroll
+        for (int sn = 0; sn < SN; ++sn) {
+            const int col = col0 + sn * 32 + r32f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = row0 + sm * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
+                u64 v = (u64)(int64_t)acc[sm][sn][0][i];
+                v += (u64)(int64_t)acc[sm][sn][1][i] << 8;
+                v += (u64)(int64_t)acc[sm][sn][2][i] << 16;
+                v += (u64)(int64_t)acc[sm][sn][3][i] << 24;
+                const u32 hi = (u32)acc[sm][sn][4][i] + ((u32)acc[sm][sn][5][i] << 8) +
+                               ((u32)acc[sm][sn][6][i] << 16) + ((u32)acc[sm][sn][7][i] << 24);
+                v += (u64)hi << 32;
+                if (row < p.M && col < p.N) {
+                    u64* dst = p.z + (u64)row * (u64)p.N + (u64)col;
+                    if (p.ksplit > 1) {
+                        atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
+                    } else {
+                        if (accumulate) v += *dst;
+                        *dst = v;
+                    }
+                }
+            }
+        }
+}
+
 // ---------------------------------------------------------------------------
 template <class T, int AMODE, bool BVEC>
 __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const GemmParams p) {
@@ -329,30 +383,8 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     const int wm = wave % T::WM, wn = wave / T::WM;
     const int r32 = lane & 31, h = lane >> 5;
 
-    // ---- block -> output tile.  Consecutive block ids go to different XCDs
-    // (round robin over 8), so give each XCD a contiguous run of logical tiles:
-    // tiles that share operand rows then share one L2.
-    const int tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
-    const int nb = tiles_m * tiles_n;
-    // With split-K the grid holds ksplit copies of the tile grid, slowest index first.
-    const int split = blockIdx.x / nb;
-    int logical;
-    {
-        const int bid = blockIdx.x - split * nb, xcd = bid & 7, idx = bid >> 3;
-        const int per = nb >> 3, rem = nb & 7;
-        logical = xcd * per + (xcd < rem ? xcd : rem) + idx;
-    }
-    // inside the run: groups of GM tile-rows, tile-row fastest inside a group
-    int tm, tn;
-    {
-        const int GM = p.group_m;
-        const int per_group = GM * tiles_n;
-        const int g = logical / per_group, in_g = logical - g * per_group;
-        const int first = g * GM;
-        const int gsz = tiles_m - first < GM ? tiles_m - first : GM;
-        tm = first + in_g % gsz;
-        tn = in_g / gsz;
-    }
+    int split, tm, tn;
+    block_to_tile(p, T::BM, T::BN, split, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int rows_m = p.M - m0, rows_n = p.N - n0;
 
@@ -475,7 +507,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     // keeps the compiler from regrouping them.  Every index is a compile-time
     // constant.
     constexpr int NMFMA = 36 * SM * SN;
-    constexpr int PRE = CG_PIPE == 2 ? 1 : NMFMA * CG_PRE_NUM / 8;
+    constexpr int PRE = NMFMA * CG_PRE_NUM / 8;
     constexpr int LAST = NMFMA - 2 * SM * SN;  // the final slots only drain
     auto half_step = [&](const char* cur, char* nxt, auto even_c, auto&& issue_loads) {
         v4i bf[SN][8];
@@ -490,9 +522,6 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             for (int sm = 0; sm < SM; ++sm)
                 af[l & 1][sm] = *reinterpret_cast<const v4i*>(cur + a_frag + l * 2 * T::A_RS + sm * 512);
         };
-#ifdef CG_DBG_SLEEP
-        __builtin_amdgcn_s_sleep(CG_DBG_SLEEP);
-#endif
         read_a(0);
         read_b(0);
         read_b(1);
@@ -505,20 +534,14 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
                 if constexpr (l == 0 && m + 2 < 8) read_b(m + 2);
                 if constexpr (m == (l < 7 ? 1 : 0) && l < 7) read_a(l + 1);
             }
-#ifndef CG_DBG_NOMFMA
             acc[sm][sn][l + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
                 af[l & 1][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
-#else
-            acc[sm][sn][l + m][0] ^= af[l & 1][sm][0] + bf[sn][m][1];
-#endif
             if constexpr (slot == 0) issue_loads();
-#ifndef CG_DBG_NOSPLIT
             if constexpr (slot >= PRE && slot < LAST) {
                 constexpr int lo = (slot - PRE) * NOPS / (LAST - PRE);
                 constexpr int hi = (slot - PRE + 1) * NOPS / (LAST - PRE);
                 static_for<lo, hi>([&](auto op_c) { split_op(op_c, even_c, nxt); });
             }
-#endif
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -543,55 +566,15 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
                     for (int i = 0; i < 16; ++i) acc[sm][sn][s][i] = 0;
     };
 
-    // fold: z (+)= sum_s sext(P_s) << 8s.  P_4..P_7 only reach bits 32..63.
-    // The lane index passes through an empty asm so that none of the output
-    // addresses or bounds tests can be computed ahead of the K loop, where they
-    // would sit in registers the loop needs.
-    // Modes: plain store (one fold, one split), read-add-write by the owning lane
-    // (later folds of a single split), atomic add into a zero-filled z (split-K:
-    // integer sums mod 2^64 are exact in any order).
     auto fold = [&](bool accumulate) {
-        int lane_f = lane;
-        asm volatile("" : "+v"(lane_f));
-        const int r32f = lane_f & 31, hf = lane_f >> 5;
-#pragma unroll
-        for (int sm = 0; sm < SM; ++sm)
-#pragma unroll
-            for (int sn = 0; sn < SN; ++sn) {
-                const int col = n0 + (wn * SN + sn) * 32 + r32f;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = m0 + (wm * SM + sm) * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
-                    u64 v = (u64)(int64_t)acc[sm][sn][0][i];
-                    v += (u64)(int64_t)acc[sm][sn][1][i] << 8;
-                    v += (u64)(int64_t)acc[sm][sn][2][i] << 16;
-                    v += (u64)(int64_t)acc[sm][sn][3][i] << 24;
-                    const u32 hi = (u32)acc[sm][sn][4][i] + ((u32)acc[sm][sn][5][i] << 8) +
-                                   ((u32)acc[sm][sn][6][i] << 16) + ((u32)acc[sm][sn][7][i] << 24);
-                    v += (u64)hi << 32;
-                    if (row < p.M && col < p.N) {
-                        u64* dst = p.z + (u64)row * (u64)p.N + (u64)col;
-                        if (p.ksplit > 1) {
-                            atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
-                        } else {
-                            if (accumulate) v += *dst;
-                            *dst = v;
-                        }
-                    }
-                }
-            }
+        fold_tile<SM, SN>(p, acc, m0 + wm * SM * 32, n0 + wn * SN * 32, lane, accumulate);
     };
 
-#ifdef CG_DBG_CLOCK
-    const long long dbg_c0 = __builtin_readcyclecounter();
-    const long long dbg_t0 = wall_clock64();
-#endif
     // Prologue: the even half-step of the first slice goes to LDS.  Loads past the end of
     // K are out of range and return zeros that are never used, so the loop body
     // needs no "is there a next slice" branch.
     load_even(k_begin);
     split_all(std::true_type{}, st0);
-    if (CG_PIPE == 2) load_odd(k_begin);
     __syncthreads();
 
     // Outer loop: one pass per segment of at most SEG_KSTEPS slices (a single pass
@@ -602,26 +585,250 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         for (int ks = ks0; ks < ke; ++ks) {
             // even half-step: x_a against w_a + w_b from st0; odd words are split into st1
             half_step(st0, st1, std::false_type{}, [&]() {
-                if (CG_PIPE == 2) load_even(ks + 1); else load_odd(ks);
+                load_odd(ks);
             });
             __syncthreads();
             // odd half-step: x_b against w_a from st1; the next slice's even words go to st0
             half_step(st1, st0, std::true_type{}, [&]() {
-                if (CG_PIPE == 2) load_odd(ks + 1); else load_even(ks + 1);
+                load_even(ks + 1);
             });
             __syncthreads();
         }
         fold(ks0 > k_begin);
     }
-#ifdef CG_DBG_CLOCK
-    if (blockIdx.x == 0 && tid == 0) {
-        p.z[0] = (u64)(__builtin_readcyclecounter() - dbg_c0);
-        p.z[1] = (u64)(wall_clock64() - dbg_t0);
-    }
-#endif
 }
 
 // ---------------------------------------------------------------------------
+// ===========================================================================
+// Digit-plane route.  The split of a word into digits is the same whoever uses
+// the word, yet a tile of the left operand is needed by every block column and,
+// in a convolution, by every filter tap.  With caller-supplied scratch memory
+// the split is therefore done ONCE per operand by to_planes_kernel, which writes
+// the digits as int8 "planes", and the contraction kernel below only moves
+// 16-byte pieces from HBM to LDS: no vector-ALU work per MFMA.
+//
+// Plane format of a row-major [R, K] operand, KS = ceil(K/32) slices per row:
+//     byte (row, ks, c, j) at ((row*KS + ks)*16 + c)*16 + j,  c = 8*g + l,
+// holds digit l of word k = 32*ks + 16*g + j (zero beyond K): per row and slice
+// 256 bytes = 16 pieces of 16 bytes, a piece being one MFMA operand register set
+// for one k-half g.  The format has the size of the raw operand (rows padded to
+// whole slices).
+// ===========================================================================
+
+// One thread converts four consecutive words of a row: the four lanes of a quad
+// read 128 contiguous bytes and write, digit by digit, 16 contiguous bytes.
+__global__ __launch_bounds__(256) void to_planes_kernel(const u64* __restrict__ src, const u64* __restrict__ add,
+                                                        char* __restrict__ dst, u32 R, u32 K, u32 KS) {
+    const u64 units = (u64)R * KS * 8;  // 8 four-word units per 32-word slice
+    for (u64 ui = (u64)blockIdx.x * 256 + threadIdx.x; ui < units; ui += (u64)gridDim.x * 256) {
+        const u32 row = (u32)(ui / (8 * KS)), in_row = (u32)(ui - (u64)row * 8 * KS);
+        const u32 k0 = 4 * in_row;  // first word of the unit
+        const u64* s = src + (u64)row * K + k0;
+        const u64* a = add ? add + (u64)row * K + k0 : nullptr;
+        u4 v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
+        if (k0 < K) {  // K is even: words come in valid pairs
+            v0 = *reinterpret_cast<const u4*>(s);
+            if (a) v0 = add64x2(v0, *reinterpret_cast<const u4*>(a));
+        }
+        if (k0 + 2 < K) {
+            v1 = *reinterpret_cast<const u4*>(s + 2);
+            if (a) v1 = add64x2(v1, *reinterpret_cast<const u4*>(a + 2));
+        }
+        recode2(v0);
+        recode2(v1);
+        u32 d[8];
+        transpose4(v0.x, v0.z, v1.x, v1.z, d);
+        transpose4(v0.y, v0.w, v1.y, v1.w, d + 4);
+        // slice ks = in_row / 8, k-half g = (in_row / 4) & 1, dword q = in_row & 3 of each piece
+        char* o = dst + ((u64)row * KS + in_row / 8) * 256 + ((in_row >> 2) & 1) * 128 + (in_row & 3) * 4;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) *reinterpret_cast<u32*>(o + l * 16) = d[l];
+    }
+}
+
+// Piece addressing of the contraction kernel: piece (row, c) of slice ks.
+struct PlanesLinear {
+    u32 off0;  // byte offset of piece c of slice 0 of the row inside the view, or OOB
+    __device__ __forceinline__ void init(const GemmParams&, int, int row_local, int rows_left, u32 row_bytes,
+                                         int c) {
+        off0 = row_local < rows_left ? (u32)row_local * row_bytes + (u32)c * 16u : OOB;
+    }
+    __device__ __forceinline__ u4 load(const GemmParams&, __amdgpu_buffer_rsrc_t r, int ks, const TapCursor&) const {
+        return __builtin_amdgcn_raw_buffer_load_b128(r, off0 + 256u * ks, 0, 0);
+    }
+};
+
+// Patch gather from activation planes [pixel][Cin/32][256 bytes], Cin % 32 == 0.
+struct PlanesConv {
+    PatchRow pr;  // pr.base in units of pixels*Cin*8 bytes, as for raw words: planes have the same pitch
+    u32 c16;
+    __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, u32, int c) {
+        pr.init(p, m0, row_local, rows_left);
+        c16 = (u32)c * 16u;
+    }
+    __device__ __forceinline__ u4 load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int, const TapCursor& t) const {
+        const bool v = pr.ok && t.r < p.kh && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
+        // a pixel's Cin words occupy Cin*8 bytes of planes; slice c0/32 starts at c0*8 bytes
+        return __builtin_amdgcn_raw_buffer_load_b128(rs_, v ? pr.base + t.offset(p) + c16 : OOB, 0, 0);
+    }
+};
+
+template <class T, bool CONV>
+__global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_planes_kernel(const GemmParams p) {
+    constexpr int SM = T::SM, SN = T::SN;
+    constexpr int AP = T::BM * 16 / T::NT, BP = T::BN * 16 / T::NT;  // 16-byte pieces per thread and half-step
+    static_assert(T::BM * 16 % T::NT == 0 && T::BN * 16 % T::NT == 0, "tile does not divide over the threads");
+    constexpr int A_BYTES = T::BM * 256, STAGE = (T::BM + T::BN) * 256;
+    __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % T::WM, wn = wave / T::WM;
+    const int r32 = lane & 31, h = lane >> 5;
+
+    int split, tm, tn;
+    block_to_tile(p, T::BM, T::BN, split, tm, tn);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const int rows_m = p.M - m0, rows_n = p.N - n0;
+
+    // ---- buffer views on the four plane tensors, rebased per block
+    const int KS = (p.K + 31) / 32;
+    const u32 b_row_bytes = (u32)KS * 256u;
+    const u32 a_row_bytes = CONV ? 0u : b_row_bytes;
+    u64 a_base;
+    if (CONV) a_base = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems * 8u;
+    else a_base = (u64)m0 * a_row_bytes;
+    const u64 a_left = p.xp_bytes - a_base;
+    const u32 a_bytes = a_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)a_left;
+    const __amdgpu_buffer_rsrc_t rs_a0 = make_rsrc(p.xp_a + a_base, a_bytes);
+    const __amdgpu_buffer_rsrc_t rs_a1 = make_rsrc(p.xp_b + a_base, a_bytes);
+    const u64 b_base = (u64)n0 * b_row_bytes;
+    const u64 b_left = (u64)p.N * b_row_bytes - b_base;
+    const u32 b_bytes = b_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)b_left;
+    const __amdgpu_buffer_rsrc_t rs_b0 = make_rsrc(p.wp_sum + b_base, b_bytes);
+    const __amdgpu_buffer_rsrc_t rs_b1 = make_rsrc(p.wp_a + b_base, b_bytes);
+
+    // ---- per-thread pieces.  LDS keeps a tile row-major, 256 bytes per row, with
+    // the piece index XOR-ed by the row's low four bits: 16 consecutive lanes then
+    // hit 16 different piece slots both when a row is written (16 pieces of one row)
+    // and when fragments are read (one piece of 16 rows).
+    typedef typename std::conditional<CONV, PlanesConv, PlanesLinear>::type AGen;
+    AGen ag[AP];
+    PlanesLinear bg[BP];
+    int a_dst[AP], b_dst[BP];
+#pragma unroll
+    for (int i = 0; i < AP; ++i) {
+        const int u = tid + i * T::NT, c = u & 15, row = u >> 4;
+        ag[i].init(p, m0, row, rows_m, a_row_bytes, c);
+        a_dst[i] = row * 256 + ((c ^ (row & 15)) << 4);
+    }
+#pragma unroll
+    for (int i = 0; i < BP; ++i) {
+        const int u = tid + i * T::NT, c = u & 15, row = u >> 4;
+        bg[i].init(p, n0, row, rows_n, b_row_bytes, c);
+        b_dst[i] = A_BYTES + row * 256 + ((c ^ (row & 15)) << 4);
+    }
+    TapCursor tap;
+    tap.reset();
+
+    u4 eA[AP], eB[BP], oA[AP], oB[BP];
+    auto load_set = [&](__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, int ks, u4* da, u4* db) {
+        if (CONV) tap.advance_to(p, ks);
+#pragma unroll
+        for (int i = 0; i < AP; ++i) da[i] = ag[i].load(p, ra, ks, tap);
+#pragma unroll
+        for (int i = 0; i < BP; ++i) db[i] = bg[i].load(p, rb, ks, tap);
+    };
+    auto load_even = [&](int ks) { load_set(rs_a0, rs_b0, ks, eA, eB); };
+    auto load_odd = [&](int ks) { load_set(rs_a1, rs_b1, ks, oA, oB); };
+    constexpr int NOPS = AP + BP;
+    auto store_op = [&](auto op_c, auto even_c, char* stage) {
+        constexpr int op = decltype(op_c)::value;
+        constexpr bool even_set = decltype(even_c)::value;
+        if constexpr (op < AP) *reinterpret_cast<u4*>(stage + a_dst[op]) = even_set ? eA[op] : oA[op];
+        else *reinterpret_cast<u4*>(stage + b_dst[op - AP]) = even_set ? eB[op - AP] : oB[op - AP];
+    };
+
+    // fragment addresses: row part and, per digit, the swizzled piece slot
+    const int x16 = r32 & 15;
+    int a_frag[8], b_frag[8];
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+        const int slot = ((h * 8 + l) ^ x16) << 4;
+        a_frag[l] = (wm * SM * 32 + r32) * 256 + slot;
+        b_frag[l] = A_BYTES + (wn * SN * 32 + r32) * 256 + slot;
+    }
+
+    v16i acc[SM][SN][8];
+    constexpr int NMFMA = 36 * SM * SN;
+    constexpr int PRE = NMFMA * CG_PRE_NUM / 8;
+    constexpr int LAST = NMFMA - 2 * SM * SN;
+    auto half_step = [&](const char* cur, char* nxt, auto even_c, auto&& issue_loads) {
+        v4i bf[SN][8];
+        v4i af[2][SM];
+        auto read_b = [&](int m) {
+#pragma unroll
+            for (int sn = 0; sn < SN; ++sn)
+                bf[sn][m] = *reinterpret_cast<const v4i*>(cur + b_frag[m] + sn * 8192);
+        };
+        auto read_a = [&](int l) {
+#pragma unroll
+            for (int sm = 0; sm < SM; ++sm)
+                af[l & 1][sm] = *reinterpret_cast<const v4i*>(cur + a_frag[l] + sm * 8192);
+        };
+        read_a(0);
+        read_b(0);
+        read_b(1);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, NMFMA>([&](auto slot_c) {
+            constexpr int slot = decltype(slot_c)::value;
+            constexpr Slot sl = decode_slot(slot, SM, SN);
+            constexpr int l = sl.l, m = sl.m, sm = sl.sm, sn = sl.sn;
+            if constexpr (sm == 0 && sn == 0) {
+                if constexpr (l == 0 && m + 2 < 8) read_b(m + 2);
+                if constexpr (m == 1 && l < 7) read_a(l + 1);
+            }
+            acc[sm][sn][l + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                af[l & 1][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
+            if constexpr (slot == 0) issue_loads();
+            if constexpr (slot >= PRE && slot < LAST) {
+                constexpr int lo = (slot - PRE) * NOPS / (LAST - PRE);
+                constexpr int hi = (slot - PRE + 1) * NOPS / (LAST - PRE);
+                static_for<lo, hi>([&](auto op_c) { store_op(op_c, even_c, nxt); });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
+    char* const st0 = lds;
+    char* const st1 = lds + STAGE;
+    const int per_split = (KS + p.ksplit - 1) / p.ksplit;
+    const int k_begin = split * per_split;
+    const int nk = k_begin + per_split < KS ? k_begin + per_split : KS;
+    if (k_begin >= nk) return;
+
+    load_even(k_begin);
+    static_for<0, NOPS>([&](auto op_c) { store_op(op_c, std::true_type{}, st0); });
+    __syncthreads();
+    for (int ks0 = k_begin; ks0 < nk; ks0 += SEG_KSTEPS) {
+        const int ke = ks0 + SEG_KSTEPS < nk ? ks0 + SEG_KSTEPS : nk;
+#pragma unroll
+        for (int sm = 0; sm < SM; ++sm)
+#pragma unroll
+            for (int sn = 0; sn < SN; ++sn)
+#pragma unroll
+                for (int s_ = 0; s_ < 8; ++s_)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[sm][sn][s_][i] = 0;
+        for (int ks = ks0; ks < ke; ++ks) {
+            half_step(st0, st1, std::false_type{}, [&]() { load_odd(ks); });
+            __syncthreads();
+            half_step(st1, st0, std::true_type{}, [&]() { load_even(ks + 1); });
+            __syncthreads();
+        }
+        fold_tile<SM, SN>(p, acc, m0 + wm * SM * 32, n0 + wn * SN * 32, lane, ks0 > k_begin);
+    }
+}
+
 // z = 0 ahead of a split-K launch (a kernel, not a memset, so that callers may
 // capture the stream into a graph)
 __global__ __launch_bounds__(256) void zero_fill_kernel(u64* z, size_t n) {
@@ -630,12 +837,9 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(u64* z, size_t n) {
 }
 
 template <class T, int AMODE, bool BVEC>
-static hipError_t launch(const GemmParams& p, hipStream_t stream) {
-    const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
-    const int64_t tiles = tiles_m * tiles_n;
-    const int nk = (p.K + 31) / 32;
-    GemmParams q = p;
-    q.group_m = tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);
+static hipError_t launch(const GemmParams& p, hipStream_t stream);
+
+static int choose_ksplit(int64_t tiles, int nk) {
     // Split K when the tile grid alone cannot fill the 256 compute units: aim at
     // two blocks per unit, keep at least 4 slices of K per block.
     int ksplit = 1;
@@ -646,15 +850,49 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
         const int per = (nk + ksplit - 1) / ksplit;
         ksplit = (nk + per - 1) / per;  // no empty splits
     }
-    q.ksplit = ksplit;
-    if (ksplit > 1) {
-        const size_t n = (size_t)p.M * (size_t)p.N;
-        size_t blocks = (n + 255) / 256;
-        if (blocks > 2048) blocks = 2048;
-        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, q.z, n);
-    }
-    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BVEC>), dim3((unsigned)(tiles * ksplit)), dim3(T::NT), 0,
-                       stream, q);
+    return ksplit;
+}
+
+static void launch_zero_fill(const GemmParams& p, hipStream_t stream) {
+    const size_t n = (size_t)p.M * (size_t)p.N;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p.z, n);
+}
+
+hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,
+                            hipStream_t stream) {
+    const int64_t KS = (K + 31) / 32;
+    const int64_t units = R * KS * 8;
+    int64_t blocks = (units + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(to_planes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, add,
+                       static_cast<char*>(dst), (u32)R, (u32)K, (u32)KS);
+    return hipGetLastError();
+}
+
+hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t stream) {
+    typedef Tile<CG_TILE> T;
+    const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
+    GemmParams q = p;
+    q.group_m = tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);
+    q.ksplit = choose_ksplit(tiles_m * tiles_n, (p.K + 31) / 32);
+    if (q.ksplit > 1) launch_zero_fill(q, stream);
+    const dim3 grid((unsigned)(tiles_m * tiles_n * q.ksplit));
+    if (conv) hipLaunchKernelGGL((share_gemm_planes_kernel<T, true>), grid, dim3(T::NT), 0, stream, q);
+    else hipLaunchKernelGGL((share_gemm_planes_kernel<T, false>), grid, dim3(T::NT), 0, stream, q);
+    return hipGetLastError();
+}
+
+template <class T, int AMODE, bool BVEC>
+static hipError_t launch(const GemmParams& p, hipStream_t stream) {
+    const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
+    GemmParams q = p;
+    q.group_m = tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);
+    q.ksplit = choose_ksplit(tiles_m * tiles_n, (p.K + 31) / 32);
+    if (q.ksplit > 1) launch_zero_fill(q, stream);
+    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BVEC>), dim3((unsigned)(tiles_m * tiles_n * q.ksplit)),
+                       dim3(T::NT), 0, stream, q);
     return hipGetLastError();
 }
 

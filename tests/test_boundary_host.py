@@ -39,7 +39,7 @@ def test_library_exports_every_declared_symbol(L):
     assert sorted(binding.EXPORTS) == header_symbols()
     assert binding.version() >= 100
     assert binding.status_string(0) == "CG_OK"
-    for s in range(1, 7):
+    for s in range(1, 8):
         assert binding.status_string(s).startswith("CG_ERR_")
 
 
@@ -62,6 +62,30 @@ def test_matmul_validation_happens_before_any_device_work(L):
     big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
     assert f(*big, 4, 4, (1 << 20) + 1, None) == b.CG_ERR_UNSUPPORTED
     assert f(*big, 1 << 31, 1, 1, None) == b.CG_ERR_UNSUPPORTED
+
+
+def test_workspace_entry_points_validate_like_the_plain_ones(L):
+    from paper_2104_10949_amd import binding as b
+    big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
+    ws = 6 << 40
+    f = L.cg_share_matmul_ws
+    assert f(0, *big[1:], 4, 4, 4, ws, 1 << 20, None) == b.CG_ERR_NULL
+    assert f(*big, 4, 0, 4, ws, 1 << 20, None) == b.CG_ERR_SHAPE
+    assert f(*big, 64, 64, 64, 0, 1 << 20, None) == b.CG_ERR_NULL            # digit route needs scratch memory
+    assert f(*big, 64, 64, 64, ws + 8, 1 << 20, None) == b.CG_ERR_ALIGN
+    need = L.cg_share_matmul_workspace_bytes(64, 64, 64)
+    assert need == 4 * 64 * 2 * 256
+    assert f(*big, 64, 64, 64, ws, need - 1, None) == b.CG_ERR_WORKSPACE
+    assert f(*big, 64, 64, 64, big[0] + 256, need, None) == b.CG_ERR_ALIAS   # scratch inside x_i
+    assert L.cg_share_matmul_workspace_bytes(64, 64, 65) == 0                # odd K: no digit route
+    assert L.cg_share_matmul_workspace_bytes(-1, 64, 64) == 0
+    d = b.ConvDesc(2, 8, 8, 32, 16, 3, 3, 1, 1, 1, 1)
+    need = L.cg_share_conv2d_workspace_bytes(ctypes.byref(d))
+    assert need == 2 * (2 * 8 * 8 * 32 * 8) + 2 * (16 * 9 * 256)
+    assert L.cg_share_conv2d_ws(*big, ctypes.byref(d), ws, need - 1, None) == b.CG_ERR_WORKSPACE
+    d3 = b.ConvDesc(2, 8, 8, 3, 16, 3, 3, 1, 1, 1, 1)
+    assert L.cg_share_conv2d_workspace_bytes(ctypes.byref(d3)) == 0          # Cin = 3: direct route only
+    assert L.cg_share_conv2d_workspace_bytes(None) == 0
 
 
 def test_conv_validation(L):

@@ -22,20 +22,28 @@ def env():
 
 
 def check_layer(cg, ro, wl, cfg, li, L):
+    """Both routes (allocation-free entry point, and the *_ws entry point bench.py times) against the oracle."""
     say(f"config {cfg} layer {li} {L.name} gemm={L.gemm}")
     ops = wl.party_operands(L, wl.layer_seed(cfg, li))
     dev = [cg.to_device(a) for a in ops]
+    sp = ((L.stride, L.stride), (L.pad, L.pad))
     if L.kind == "conv":
-        z = cg.cg_share_conv2d(*dev, stride=(L.stride, L.stride), pad=(L.pad, L.pad))
-        want = ro.party_conv2d(*ops, (L.stride, L.stride), (L.pad, L.pad))
+        z = cg.cg_share_conv2d(*dev, stride=sp[0], pad=sp[1])
+        ws = torch.empty(cg.cg_share_conv2d_workspace_bytes(L.x_shape, L.w_shape, *sp) // 8 + 2,
+                         dtype=torch.int64, device="cuda")
+        z2 = cg.cg_share_conv2d_ws(*dev, ws, stride=sp[0], pad=sp[1])
+        want = ro.party_conv2d(*ops, *sp)
     else:
         z = cg.cg_share_matmul(*dev)
+        ws = torch.empty(cg.cg_share_matmul_workspace_bytes(*L.gemm) // 8 + 2, dtype=torch.int64, device="cuda")
+        z2 = cg.cg_share_matmul_ws(*dev, ws)
         want = ro.party_matmul(*ops)
     torch.cuda.synchronize()
-    got = cg.to_host(z)
-    assert got.shape == tuple(L.z_shape)
-    msg = first_mismatch(got, want)
-    assert not msg, f"config {cfg} {L.name}: {msg}"
+    for route, out in (("direct", z), ("workspace", z2)):
+        got = cg.to_host(out)
+        assert got.shape == tuple(L.z_shape)
+        msg = first_mismatch(got, want)
+        assert not msg, f"config {cfg} {L.name} route {route}: {msg}"
 
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])

@@ -30,16 +30,33 @@ def wl():
     return workloads
 
 
-def run_matmul(cg, ops):
+ROUTES = ["direct", "workspace"]
+
+
+def make_workspace(nbytes):
+    # poisoned scratch memory: nothing may depend on its previous contents
+    return torch.full((max(nbytes, 16) // 8 + 2,), 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")
+
+
+def run_matmul(cg, ops, route="direct"):
     d = [cg.to_device(a) for a in ops]
-    z = cg.cg_share_matmul(*d)
+    if route == "direct":
+        z = cg.cg_share_matmul(*d)
+    else:
+        M, K = ops[0].shape
+        ws = make_workspace(cg.cg_share_matmul_workspace_bytes(M, ops[2].shape[0], K))
+        z = cg.cg_share_matmul_ws(*d, ws)
     torch.cuda.synchronize()
     return cg.to_host(z)
 
 
-def run_conv(cg, ops, stride, pad):
+def run_conv(cg, ops, stride, pad, route="direct"):
     d = [cg.to_device(a) for a in ops]
-    z = cg.cg_share_conv2d(*d, stride=stride, pad=pad)
+    if route == "direct":
+        z = cg.cg_share_conv2d(*d, stride=stride, pad=pad)
+    else:
+        ws = make_workspace(cg.cg_share_conv2d_workspace_bytes(ops[0].shape, ops[2].shape, stride, pad))
+        z = cg.cg_share_conv2d_ws(*d, ws, stride=stride, pad=pad)
     torch.cuda.synchronize()
     return cg.to_host(z)
 
@@ -51,57 +68,61 @@ MATMUL_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("route", ROUTES)
 @pytest.mark.parametrize("M,N,K", MATMUL_SHAPES)
-def test_matmul_random_shares(cg, ro, wl, M, N, K):
-    say(f"cg_share_matmul random M={M} N={N} K={K}")
+def test_matmul_random_shares(cg, ro, wl, M, N, K, route):
+    say(f"cg_share_matmul random M={M} N={N} K={K} route={route}")
     seed = 7000 + M * 31 + N * 17 + K
     ops = (wl.draw_ring((M, K), seed), wl.draw_ring((M, K), seed + 1),
            wl.draw_ring((N, K), seed + 2), wl.draw_ring((N, K), seed + 3))
-    got = run_matmul(cg, ops)
+    got = run_matmul(cg, ops, route)
     want = ro.party_matmul(*ops)
     assert not first_mismatch(got, want), first_mismatch(got, want)
 
 
+@pytest.mark.parametrize("route", ROUTES)
 @pytest.mark.parametrize("word", [0x8080808080808080, 0xFFFFFFFFFFFFFFFF, 0x7F7F7F7F7F7F7F7F, 0, 1,
                                   0x8000000000000000, 0x00000000FFFFFFFF, 0x0100000000000000,
                                   0x80FF7F0080FF7F00])
-def test_matmul_adversarial_constant_words(cg, ro, word):
+def test_matmul_adversarial_constant_words(cg, ro, word, route):
     M, N, K = 70, 40, 300
-    say(f"cg_share_matmul constant word 0x{word:016x} M={M} N={N} K={K}")
+    say(f"cg_share_matmul constant word 0x{word:016x} M={M} N={N} K={K} route={route}")
     x = np.full((M, K), word, dtype=np.uint64)
     y = np.full((N, K), word, dtype=np.uint64)
-    got = run_matmul(cg, (x, x, y, y))
+    got = run_matmul(cg, (x, x, y, y), route)
     want = ro.party_matmul(x, x, y, y)
     assert not first_mismatch(got, want), first_mismatch(got, want)
     assert int(got[0, 0]) == (3 * K * word * word) % (1 << 64)
 
 
-def test_matmul_mixed_adversarial_words(cg, ro, wl):
-    M, N, K = 96, 80, 257
-    say(f"cg_share_matmul adversarial word mix M={M} N={N} K={K}")
+@pytest.mark.parametrize("route,K", [("direct", 257), ("direct", 258), ("workspace", 258)])
+def test_matmul_mixed_adversarial_words(cg, ro, wl, route, K):
+    M, N = 96, 80
+    say(f"cg_share_matmul adversarial word mix M={M} N={N} K={K} route={route}")
     words = np.array(wl.ADVERSARIAL_WORDS, dtype=np.uint64)
     rng = np.random.default_rng(99)
     ops = tuple(words[rng.integers(0, len(words), size=s)] for s in ((M, K), (M, K), (N, K), (N, K)))
-    got = run_matmul(cg, ops)
+    got = run_matmul(cg, ops, route)
     want = ro.party_matmul(*ops)
     assert not first_mismatch(got, want), first_mismatch(got, want)
 
 
+@pytest.mark.parametrize("route", ROUTES)
 @pytest.mark.parametrize("K", [8192, 16352, 16384, 16400, 40000])
-def test_matmul_long_k_crosses_accumulator_folds(cg, ro, wl, K):
+def test_matmul_long_k_crosses_accumulator_folds(cg, ro, wl, K, route):
     """Worst-case digits (every byte 0x80, every digit product +2^14) through one
     or more folds of the 32-bit partial sums, plus random words."""
     M, N = 40, 33
-    say(f"cg_share_matmul long K={K} worst-case bytes")
+    say(f"cg_share_matmul long K={K} worst-case bytes route={route}")
     x = np.full((M, K), 0x8080808080808080, dtype=np.uint64)
     y = np.full((N, K), 0x8080808080808080, dtype=np.uint64)
-    got = run_matmul(cg, (x, x, y, y))
+    got = run_matmul(cg, (x, x, y, y), route)
     expect = (3 * K * 0x8080808080808080 * 0x8080808080808080) % (1 << 64)
     assert np.all(got == np.uint64(expect))
     say(f"cg_share_matmul long K={K} random")
     ops = (wl.draw_ring((M, K), K), wl.draw_ring((M, K), K + 1), wl.draw_ring((N, K), K + 2),
            wl.draw_ring((N, K), K + 3))
-    got = run_matmul(cg, ops)
+    got = run_matmul(cg, ops, route)
     want = ro.party_matmul(*ops)
     assert not first_mismatch(got, want), first_mismatch(got, want)
 
@@ -142,17 +163,42 @@ CONV_CASES = [
 ]
 
 
+@pytest.mark.parametrize("route", ROUTES)
 @pytest.mark.parametrize("case", CONV_CASES)
-def test_conv_random_shares(cg, ro, wl, case):
+def test_conv_random_shares(cg, ro, wl, case, route):
     B, H, W, Cin, Cout, kh, kw, stride, pad = case
-    say(f"cg_share_conv2d random {case}")
+    say(f"cg_share_conv2d random {case} route={route}")
     seed = 9000 + sum(case[:7])
     xs, ws = (B, H, W, Cin), (Cout, kh, kw, Cin)
     ops = (wl.draw_ring(xs, seed), wl.draw_ring(xs, seed + 1), wl.draw_ring(ws, seed + 2),
            wl.draw_ring(ws, seed + 3))
-    got = run_conv(cg, ops, stride, pad)
+    got = run_conv(cg, ops, stride, pad, route)
     want = ro.party_conv2d(*ops, stride, pad)
     assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+def test_workspace_errors(cg):
+    say("workspace argument errors")
+    x = torch.zeros((64, 64), dtype=torch.int64, device="cuda")
+    y = torch.zeros((64, 64), dtype=torch.int64, device="cuda")
+    need = cg.cg_share_matmul_workspace_bytes(64, 64, 64)
+    assert need == 4 * 64 * 2 * 256
+    assert cg.cg_share_matmul_workspace_bytes(64, 64, 63) == 0      # odd K: direct route only
+    assert cg.cg_share_matmul_workspace_bytes(0, 64, 64) == 0
+    small = torch.zeros(need // 8 - 1, dtype=torch.int64, device="cuda")
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_share_matmul_ws(x, x, y, y, small)
+    assert e.value.status == cg.CG_ERR_WORKSPACE
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_share_matmul_ws(x, x, y, y, None)
+    assert e.value.status == cg.CG_ERR_NULL
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_share_matmul_ws(x, x, y, y, x.view(-1))               # workspace overlaps an operand
+    assert e.value.status in (cg.CG_ERR_ALIAS, cg.CG_ERR_WORKSPACE)
+    # odd K never touches the workspace
+    xo = torch.zeros((8, 7), dtype=torch.int64, device="cuda")
+    cg.cg_share_matmul_ws(xo, xo, xo, xo, None)
+    torch.cuda.synchronize()
 
 
 def test_three_parties_reconstruct_to_the_product_config1(cg, ro, wl):
