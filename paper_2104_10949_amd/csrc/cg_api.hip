@@ -34,11 +34,25 @@ typedef unsigned long long ull2 __attribute__((ext_vector_type(2)));
 
 const int EW_THREADS = 256;
 
+// Each thread handles EW_UNROLL 16-byte pairs per trip, one block-width apart, so
+// that several independent loads per stream are in flight before the first add.
+const int EW_UNROLL = 4;
+
 template <class F>
 __global__ __launch_bounds__(EW_THREADS) void ew_kernel(size_t n, F f) {
     const size_t n2 = n >> 1;
-    const size_t stride = (size_t)gridDim.x * EW_THREADS;
-    for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n2; i += stride) f.pair(i);
+    const size_t chunk = (size_t)EW_THREADS * EW_UNROLL;
+    const size_t stride = (size_t)gridDim.x * chunk;
+    for (size_t base = (size_t)blockIdx.x * chunk; base < n2; base += stride) {
+        const size_t i0 = base + threadIdx.x;
+        if (base + chunk <= n2) {
+            f.template pairs<EW_UNROLL>(i0, EW_THREADS);
+        } else {
+#pragma unroll
+            for (int u = 0; u < EW_UNROLL; ++u)
+                if (i0 + (size_t)u * EW_THREADS < n2) f.template pairs<1>(i0 + (size_t)u * EW_THREADS, EW_THREADS);
+        }
+    }
     if (blockIdx.x == 0 && threadIdx.x == 0 && (n & 1)) f.one(n - 1);
 }
 
@@ -48,16 +62,30 @@ __global__ __launch_bounds__(EW_THREADS) void ew_kernel_scalar(size_t n, F f) {
     for (size_t i = (size_t)blockIdx.x * EW_THREADS + threadIdx.x; i < n; i += stride) f.one(i);
 }
 
-#define LD2(p, i) (reinterpret_cast<const ull2*>(p)[i])
-#define ST2(p, i) (reinterpret_cast<ull2*>(p)[i])
+// streaming (non-temporal) 16-byte accesses: every element is touched once
+__device__ __forceinline__ ull2 ld2(const u64* p, size_t i) {
+    return __builtin_nontemporal_load(reinterpret_cast<const ull2*>(p) + i);
+}
+__device__ __forceinline__ void st2(u64* p, size_t i, ull2 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<ull2*>(p) + i);
+}
 
 struct AddOp {  // (za, zb) = (xa + ya, xb + yb)
     const u64 *xa, *xb, *ya, *yb;
     u64 *za, *zb;
-    __device__ void pair(size_t i) const {
-        const ull2 a = LD2(xa, i) + LD2(ya, i), b = LD2(xb, i) + LD2(yb, i);
-        ST2(za, i) = a;
-        ST2(zb, i) = b;
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 a[U], b[U], c[U], d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = ld2(xa, i + u * step); c[u] = ld2(ya, i + u * step);
+            b[u] = ld2(xb, i + u * step); d[u] = ld2(yb, i + u * step);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            st2(za, i + u * step, a[u] + c[u]);
+            st2(zb, i + u * step, b[u] + d[u]);
+        }
     }
     __device__ void one(size_t i) const {
         const u64 a = xa[i] + ya[i], b = xb[i] + yb[i];
@@ -70,10 +98,16 @@ struct MulPublicOp {  // (za, zb) = (alpha xa, alpha xb)
     const u64 *xa, *xb;
     u64 alpha;
     u64 *za, *zb;
-    __device__ void pair(size_t i) const {
-        const ull2 a = LD2(xa, i) * alpha, b = LD2(xb, i) * alpha;
-        ST2(za, i) = a;
-        ST2(zb, i) = b;
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { a[u] = ld2(xa, i + u * step); b[u] = ld2(xb, i + u * step); }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            st2(za, i + u * step, a[u] * alpha);
+            st2(zb, i + u * step, b[u] * alpha);
+        }
     }
     __device__ void one(size_t i) const {
         const u64 a = xa[i] * alpha, b = xb[i] * alpha;
@@ -86,10 +120,16 @@ struct AddPublicOp {  // (za, zb) = (xa + ga, xb + gb)
     const u64 *xa, *xb;
     u64 ga, gb;
     u64 *za, *zb;
-    __device__ void pair(size_t i) const {
-        const ull2 a = LD2(xa, i) + ga, b = LD2(xb, i) + gb;
-        ST2(za, i) = a;
-        ST2(zb, i) = b;
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { a[u] = ld2(xa, i + u * step); b[u] = ld2(xb, i + u * step); }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            st2(za, i + u * step, a[u] + ga);
+            st2(zb, i + u * step, b[u] + gb);
+        }
     }
     __device__ void one(size_t i) const {
         const u64 a = xa[i] + ga, b = xb[i] + gb;
@@ -101,14 +141,23 @@ struct AddPublicOp {  // (za, zb) = (xa + ga, xb + gb)
 struct ReconstructOp {  // out = s0 + s1 + s2
     const u64 *s0, *s1, *s2;
     u64* out;
-    __device__ void pair(size_t i) const { ST2(out, i) = LD2(s0, i) + LD2(s1, i) + LD2(s2, i); }
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 a[U], b[U], c[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = ld2(s0, i + u * step); b[u] = ld2(s1, i + u * step); c[u] = ld2(s2, i + u * step);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) st2(out, i + u * step, a[u] + b[u] + c[u]);
+    }
     __device__ void one(size_t i) const { out[i] = s0[i] + s1[i] + s2[i]; }
 };
 
 template <class F>
 cg_status launch_ew(size_t n, bool vec, const F& f, void* stream) {
     if (n == 0) return CG_OK;
-    const size_t work = vec ? (n + 1) / 2 : n;
+    const size_t work = vec ? ((n + 1) / 2 + EW_UNROLL - 1) / EW_UNROLL : n;
     size_t blocks = (work + EW_THREADS - 1) / EW_THREADS;
     const size_t cap = 256 * 16;  // 16 resident blocks per compute unit, grid-stride beyond that
     if (blocks > cap) blocks = cap;
