@@ -177,6 +177,49 @@ def test_conv_random_shares(cg, ro, wl, case, route):
     assert not first_mismatch(got, want), first_mismatch(got, want)
 
 
+@pytest.mark.parametrize("route", ROUTES)
+def test_matmul_operand_larger_than_2_gib(cg, ro, wl, route):
+    """Left operand shares of 2.3 GB each: block views are rebased, offsets stay 32-bit.
+    Sampled outputs and the last (ragged) tile rows against the oracle."""
+    M, N, K = 70001, 96, 4096
+    say(f"cg_share_matmul M={M} N={N} K={K} (x shares > 2 GiB) route={route}")
+    rng = np.random.default_rng(4242)
+    xa = rng.integers(0, 1 << 64, size=(M, K), dtype=np.uint64, endpoint=False)
+    xb = rng.integers(0, 1 << 64, size=(M, K), dtype=np.uint64, endpoint=False)
+    ya, yb = wl.draw_ring((N, K), 4243), wl.draw_ring((N, K), 4244)
+    assert xa.nbytes > (1 << 31)
+    got = run_matmul(cg, (xa, xb, ya, yb), route)
+    rows = sorted(set([0, 1, 127, 128, 65535, 65536, 65537, 69999, 70000] +
+                      [int(v) for v in rng.integers(0, M, size=40)]))
+    for m in rows:
+        want = ro.party_matmul(xa[m:m + 1], xb[m:m + 1], ya, yb)
+        assert np.array_equal(got[m:m + 1], want), f"row {m}"
+    for m, n in zip(rng.integers(0, M, size=200), rng.integers(0, N, size=200)):
+        assert int(got[m, n]) == ro.party_matmul_at(xa, xb, ya, yb, int(m), int(n))
+
+
+def test_conv_input_larger_than_2_gib(cg, ro, wl):
+    """Convolution whose input shares exceed 2 GiB (per-block view rebasing on image boundaries)."""
+    B, H, W, Cin, Cout = 460, 96, 96, 64, 64
+    say(f"cg_share_conv2d B={B} {H}x{W}x{Cin} -> {Cout}, 3x3 pad 1 (x shares > 2 GiB)")
+    rng = np.random.default_rng(777)
+    xs, ws = (B, H, W, Cin), (Cout, 3, 3, Cin)
+    xa = rng.integers(0, 1 << 64, size=xs, dtype=np.uint64, endpoint=False)
+    xb = rng.integers(0, 1 << 64, size=xs, dtype=np.uint64, endpoint=False)
+    wa, wb = wl.draw_ring(ws, 778), wl.draw_ring(ws, 779)
+    assert xa.nbytes > (1 << 31)
+    for route in ROUTES:
+        got = run_conv(cg, (xa, xb, wa, wb), (1, 1), (1, 1), route)
+        assert got.shape == (B, H, W, Cout)
+        for b in (0, 1, 230, 458, 459):   # whole images, first, middle and last
+            want = ro.party_conv2d(xa[b:b + 1], xb[b:b + 1], wa, wb, (1, 1), (1, 1))
+            assert np.array_equal(got[b:b + 1], want), f"image {b} route {route}"
+        for b, ho, wo, co in zip(rng.integers(0, B, 100), rng.integers(0, H, 100), rng.integers(0, W, 100),
+                                 rng.integers(0, Cout, 100)):
+            want = ro.party_conv2d_at(xa, xb, wa, wb, int(b), int(ho), int(wo), int(co), (1, 1), (1, 1))
+            assert int(got[b, ho, wo, co]) == want
+
+
 def test_workspace_errors(cg):
     say("workspace argument errors")
     x = torch.zeros((64, 64), dtype=torch.int64, device="cuda")
