@@ -165,6 +165,32 @@ CG_API cg_status cg_share_add_public(const uint64_t *xa, const uint64_t *xb, uin
                               uint64_t *za, uint64_t *zb, size_t n, void *stream);
 
 /*
+ * Zero shares and the reshare step (Sec. III-B "Protocol initialization" and
+ * "Multiplication"; Sec. IV "Pseudorandom generators on the GPU").
+ *
+ * Party P_i holds its own PRF key k_i (key_self) and its predecessor's k_{i-1}
+ * (key_prev); both are 16-byte AES-128 keys in HOST memory, read during the call.
+ *
+ *   cg_zero_share : alpha[j] = F(k_i, first + j) - F(k_{i-1}, first + j)   (mod 2^64), j < n
+ *   cg_reshare    : out[j]   = z_i[j] + alpha[j]: the blinded additive share that
+ *                   P_i sends to P_{i+1} after a share product; out may equal z_i.
+ *
+ * Over the three parties (keys k_0, k_1, k_2, predecessors taken cyclically) the
+ * alpha_i sum to zero for every index, so the blinded shares still open to the
+ * product.  The paper fixes AES as the PRF and nothing else; here F(k, j) is
+ * AES-128 in counter mode: the input block is (j >> 1) as a 64-bit little-endian
+ * integer followed by `nonce` as a 64-bit little-endian integer, and F(k, j) is
+ * ciphertext bytes 0..7 (even j) or 8..15 (odd j) read as a little-endian integer.
+ * `first` lets a caller continue a stream: never reuse (nonce, index) pairs under
+ * the same keys.  n == 0 returns CG_OK.  alpha / z_i / out are device pointers.
+ */
+CG_API cg_status cg_zero_share(const uint8_t *key_self, const uint8_t *key_prev, uint64_t nonce,
+                        uint64_t first, uint64_t *alpha, size_t n, void *stream);
+
+CG_API cg_status cg_reshare(const uint64_t *z_i, const uint8_t *key_self, const uint8_t *key_prev,
+                     uint64_t nonce, uint64_t first, uint64_t *out, size_t n, void *stream);
+
+/*
  * out = s0 + s1 + s2 (mod 2^64), element-wise over n (Sec. III-B, "Secret
  * sharing").  Opens a replicated sharing (pass its three distinct shares) and
  * equally the three parties' additive outputs z_0, z_1, z_2 of

@@ -252,3 +252,154 @@ u64 oracle_party_conv2d_at(const u64 *x_i, const u64 *x_ip1, const u64 *w_i, con
          + conv_at(x_ip1, w_i,   b, ho, wo, co, H, Wd, Cin, kh, kw, sh, sw, ph, pw)
          + conv_at(x_i,   w_ip1, b, ho, wo, co, H, Wd, Cin, kh, kw, sh, sw, ph, pw);
 }
+
+/* =========================================================================
+ * Zero shares from a PRF, and the reshare step (Sec. III-B "Protocol
+ * initialization" and "Multiplication"; Sec. IV "Pseudorandom generators on
+ * the GPU": AES is the PRF).
+ *
+ * Party P_i holds its own key k_i and its predecessor's key k_{i-1}.  The j-th
+ * zero share is alpha_i[j] = F(k_i, j) - F(k_{i-1}, j) (mod 2^64); over the
+ * three parties the terms telescope to 0.  After the local product, P_i
+ * re-randomises its additive share as z_i + alpha_i before sending it on.
+ *
+ * Reading adopted where the paper is silent (it only says "AES as the PRF"):
+ * F(k, j) is AES-128 in counter mode.  The 16-byte input block holds the block
+ * index b = j >> 1 as a little-endian 64-bit integer in bytes 0..7 and a
+ * caller-chosen 64-bit nonce (little-endian) in bytes 8..15; F(k, j) is the
+ * little-endian 64-bit integer formed by bytes 0..7 of the ciphertext for even
+ * j and bytes 8..15 for odd j.
+ *
+ * AES itself is FIPS-197 written out byte by byte: S-box from the field inverse
+ * in GF(2^8) mod x^8+x^4+x^3+x+1 followed by the affine map, KeyExpansion,
+ * SubBytes / ShiftRows / MixColumns / AddRoundKey.  Pinned by the FIPS-197
+ * Appendix C.1 vector in the tests.
+ * ========================================================================= */
+static uint8_t gf_mul(uint8_t a, uint8_t b)
+{
+    uint8_t p = 0;
+    for (int i = 0; i < 8; ++i) {
+        if (b & 1) p ^= a;
+        const uint8_t carry = a & 0x80;
+        a = (uint8_t)(a << 1);
+        if (carry) a ^= 0x1B;
+        b >>= 1;
+    }
+    return p;
+}
+
+static uint8_t aes_sbox_entry(uint8_t x)
+{
+    uint8_t inv = 0;
+    if (x)
+        for (int c = 1; c < 256; ++c)
+            if (gf_mul(x, (uint8_t)c) == 1) { inv = (uint8_t)c; break; }
+    uint8_t r = 0x63, b = inv;
+    for (int i = 0; i < 5; ++i) {   /* b ^ rotl(b,1) ^ rotl(b,2) ^ rotl(b,3) ^ rotl(b,4) ^ 0x63 */
+        r ^= b;
+        b = (uint8_t)((b << 1) | (b >> 7));
+    }
+    return r;
+}
+
+static void aes_sbox_table(uint8_t sbox[256])
+{
+    for (int i = 0; i < 256; ++i) sbox[i] = aes_sbox_entry((uint8_t)i);
+}
+
+/* 11 round keys of 16 bytes, byte order as in the key (w[i] occupies bytes 4i..4i+3). */
+static void aes128_expand(const uint8_t key[16], const uint8_t sbox[256], uint8_t rk[176])
+{
+    memcpy(rk, key, 16);
+    uint8_t rcon = 1;
+    for (int i = 4; i < 44; ++i) {
+        uint8_t t[4];
+        memcpy(t, rk + 4 * (i - 1), 4);
+        if (i % 4 == 0) {
+            const uint8_t t0 = t[0];
+            t[0] = sbox[t[1]] ^ rcon; t[1] = sbox[t[2]]; t[2] = sbox[t[3]]; t[3] = sbox[t0];
+            rcon = gf_mul(rcon, 2);
+        }
+        for (int b = 0; b < 4; ++b) rk[4 * i + b] = rk[4 * (i - 4) + b] ^ t[b];
+    }
+}
+
+static void aes128_encrypt(const uint8_t rk[176], const uint8_t sbox[256], const uint8_t in[16], uint8_t out[16])
+{
+    uint8_t s[16];   /* state byte (row r, column c) at s[r + 4c], the order of the input bytes */
+    for (int i = 0; i < 16; ++i) s[i] = in[i] ^ rk[i];
+    for (int round = 1; round <= 10; ++round) {
+        uint8_t t[16];
+        for (int c = 0; c < 4; ++c)             /* SubBytes + ShiftRows: row r moves left by r */
+            for (int r = 0; r < 4; ++r)
+                t[r + 4 * c] = sbox[s[r + 4 * ((c + r) % 4)]];
+        if (round < 10) {
+            for (int c = 0; c < 4; ++c) {       /* MixColumns */
+                const uint8_t a0 = t[4 * c], a1 = t[4 * c + 1], a2 = t[4 * c + 2], a3 = t[4 * c + 3];
+                s[4 * c]     = gf_mul(a0, 2) ^ gf_mul(a1, 3) ^ a2 ^ a3;
+                s[4 * c + 1] = a0 ^ gf_mul(a1, 2) ^ gf_mul(a2, 3) ^ a3;
+                s[4 * c + 2] = a0 ^ a1 ^ gf_mul(a2, 2) ^ gf_mul(a3, 3);
+                s[4 * c + 3] = gf_mul(a0, 3) ^ a1 ^ a2 ^ gf_mul(a3, 2);
+            }
+        } else {
+            memcpy(s, t, 16);
+        }
+        for (int i = 0; i < 16; ++i) s[i] ^= rk[16 * round + i];
+    }
+    memcpy(out, s, 16);
+}
+
+/* One AES-128 block, for the published test vectors. */
+void oracle_aes128_encrypt_block(const uint8_t key[16], const uint8_t in[16], uint8_t out[16])
+{
+    uint8_t sbox[256], rk[176];
+    aes_sbox_table(sbox);
+    aes128_expand(key, sbox, rk);
+    aes128_encrypt(rk, sbox, in, out);
+}
+
+/* out[j] = F(key, first + j) for j < n. */
+void oracle_prf_words(const uint8_t key[16], u64 nonce, u64 first, u64 *out, size_t n)
+{
+    uint8_t sbox[256], rk[176];
+    aes_sbox_table(sbox);
+    aes128_expand(key, sbox, rk);
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < (int64_t)n; ++j) {
+        const u64 idx = first + (u64)j, block = idx >> 1;
+        uint8_t in[16], ct[16];
+        for (int b = 0; b < 8; ++b) {
+            in[b] = (uint8_t)(block >> (8 * b));
+            in[8 + b] = (uint8_t)(nonce >> (8 * b));
+        }
+        aes128_encrypt(rk, sbox, in, ct);
+        u64 w = 0;
+        for (int b = 0; b < 8; ++b) w |= (u64)ct[8 * (idx & 1) + b] << (8 * b);
+        out[j] = w;
+    }
+}
+
+/* alpha[j] = F(key_self, first + j) - F(key_prev, first + j). */
+int oracle_zero_share(const uint8_t key_self[16], const uint8_t key_prev[16], u64 nonce, u64 first,
+                      u64 *alpha, size_t n)
+{
+    u64 *t = (u64 *)malloc((n ? n : 1) * sizeof(u64));
+    if (!t) return -1;
+    oracle_prf_words(key_self, nonce, first, alpha, n);
+    oracle_prf_words(key_prev, nonce, first, t, n);
+    for (size_t j = 0; j < n; ++j) alpha[j] -= t[j];
+    free(t);
+    return 0;
+}
+
+/* out[j] = z[j] + alpha[j]: the blinded additive share P_i sends to P_{i+1}. */
+int oracle_reshare(const u64 *z, const uint8_t key_self[16], const uint8_t key_prev[16], u64 nonce, u64 first,
+                   u64 *out, size_t n)
+{
+    u64 *a = (u64 *)malloc((n ? n : 1) * sizeof(u64));
+    if (!a) return -1;
+    if (oracle_zero_share(key_self, key_prev, nonce, first, a, n)) { free(a); return -1; }
+    for (size_t j = 0; j < n; ++j) out[j] = z[j] + a[j];
+    free(a);
+    return 0;
+}

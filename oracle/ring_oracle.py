@@ -63,6 +63,13 @@ def lib() -> ctypes.CDLL:
         L.oracle_party_matmul_at.restype = ctypes.c_uint64
         L.oracle_party_conv2d_at.argtypes = [_u64p] * 4 + [_i64] * 13
         L.oracle_party_conv2d_at.restype = ctypes.c_uint64
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        L.oracle_aes128_encrypt_block.argtypes = [u8p, u8p, u8p]
+        L.oracle_prf_words.argtypes = [u8p, ctypes.c_uint64, ctypes.c_uint64, _u64p, _sz]
+        L.oracle_zero_share.argtypes = [u8p, u8p, ctypes.c_uint64, ctypes.c_uint64, _u64p, _sz]
+        L.oracle_zero_share.restype = ctypes.c_int
+        L.oracle_reshare.argtypes = [_u64p, u8p, u8p, ctypes.c_uint64, ctypes.c_uint64, _u64p, _sz]
+        L.oracle_reshare.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -209,3 +216,37 @@ def party_conv2d_at(x_i, x_ip1, w_i, w_ip1, b, ho, wo, co, stride=(1, 1), pad=(0
     _, kh, kw, _ = w_i.shape
     return int(lib().oracle_party_conv2d_at(_p(x_i), _p(x_ip1), _p(w_i), _p(w_ip1), b, ho, wo, co,
                                             H, Wd, Cin, kh, kw, stride[0], stride[1], pad[0], pad[1]))
+
+
+def _key(key: bytes):
+    if len(key) != 16:
+        raise ValueError("AES-128 keys are 16 bytes")
+    return (ctypes.c_uint8 * 16).from_buffer_copy(bytes(key))
+
+
+def aes128_encrypt_block(key: bytes, block: bytes) -> bytes:
+    out = (ctypes.c_uint8 * 16)()
+    lib().oracle_aes128_encrypt_block(_key(key), _key(block), out)
+    return bytes(out)
+
+
+def prf_words(key: bytes, nonce: int, first: int, n: int) -> np.ndarray:
+    """F(key, first + j) for j < n (AES-128 counter mode, see ring_oracle.c)."""
+    out = np.empty(n, dtype=np.uint64)
+    lib().oracle_prf_words(_key(key), nonce, first, _p(out), n)
+    return out
+
+
+def zero_share(key_self: bytes, key_prev: bytes, nonce: int, first: int, n: int) -> np.ndarray:
+    out = np.empty(n, dtype=np.uint64)
+    if lib().oracle_zero_share(_key(key_self), _key(key_prev), nonce, first, _p(out), n):
+        raise MemoryError("oracle_zero_share")
+    return out
+
+
+def reshare(z, key_self: bytes, key_prev: bytes, nonce: int, first: int) -> np.ndarray:
+    z = _u(z)
+    out = np.empty(z.shape, dtype=np.uint64)
+    if lib().oracle_reshare(_p(z), _key(key_self), _key(key_prev), nonce, first, _p(out), z.size):
+        raise MemoryError("oracle_reshare")
+    return out

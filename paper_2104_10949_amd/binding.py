@@ -22,7 +22,7 @@ LIB_PATH = os.environ.get("CG_LIBRARY") or os.path.join(_HERE, "libcg.so")
 
 EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d", "cg_share_add",
            "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct",
-           "cg_share_matmul_ws", "cg_share_conv2d_ws",
+           "cg_share_matmul_ws", "cg_share_conv2d_ws", "cg_zero_share", "cg_reshare",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -65,9 +65,12 @@ def lib() -> ctypes.CDLL:
         L.cg_share_conv2d_ws.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp, sz, vp]
         L.cg_share_matmul_workspace_bytes.argtypes = [i64] * 3
         L.cg_share_conv2d_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
-        for name in EXPORTS[2:10]:
+        key = ctypes.c_char_p
+        L.cg_zero_share.argtypes = [key, key, u64, u64, vp, sz, vp]
+        L.cg_reshare.argtypes = [vp, key, key, u64, u64, vp, sz, vp]
+        for name in EXPORTS[2:12]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[10:]:
+        for name in EXPORTS[12:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -227,6 +230,37 @@ def cg_share_add_public(xa, xb, gamma: int, party: int, za=None, zb=None, stream
     _check(lib().cg_share_add_public(_ptr(xa), _ptr(xb), int(gamma) % (1 << 64), int(party), _ptr(za), _ptr(zb),
                                      xa.numel(), _stream(stream)), "cg_share_add_public")
     return za, zb
+
+
+def _key16(key: bytes) -> bytes:
+    key = bytes(key)
+    if len(key) != 16:
+        raise ValueError("PRF keys are 16 bytes (AES-128)")
+    return key
+
+
+def cg_zero_share(key_self: bytes, key_prev: bytes, nonce: int, first: int, n: int, out=None,
+                  stream=None) -> torch.Tensor:
+    """alpha[j] = F(key_self, first + j) - F(key_prev, first + j) for j < n."""
+    if out is None:
+        out = torch.empty((n,), dtype=torch.int64, device="cuda")
+    elif out.numel() != n:
+        raise ValueError("output size does not match")
+    _check(lib().cg_zero_share(_key16(key_self), _key16(key_prev), nonce % (1 << 64), first % (1 << 64),
+                               _ptr(out) if n else 0, n, _stream(stream)), "cg_zero_share")
+    return out
+
+
+def cg_reshare(z_i, key_self: bytes, key_prev: bytes, nonce: int, first: int = 0, out=None,
+               stream=None) -> torch.Tensor:
+    """out = z_i + alpha_i, the blinded additive share sent to the next party."""
+    out = torch.empty_like(z_i) if out is None else out
+    if out.shape != z_i.shape:
+        raise ValueError("output shape does not match")
+    n = z_i.numel()
+    _check(lib().cg_reshare(_ptr(z_i) if n else 0, _key16(key_self), _key16(key_prev), nonce % (1 << 64),
+                            first % (1 << 64), _ptr(out) if n else 0, n, _stream(stream)), "cg_reshare")
+    return out
 
 
 def cg_reconstruct(s0, s1, s2, out=None, stream=None) -> torch.Tensor:

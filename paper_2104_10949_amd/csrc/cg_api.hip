@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "cg.h"
+#include "prf.h"
 #include "share_gemm.h"
 
 namespace {
@@ -470,6 +471,31 @@ cg_status cg_share_add_public(const uint64_t* xa, const uint64_t* xb, uint64_t g
     // share index 0 is the first component of party 0 and the second component of party 2
     AddPublicOp f = {xa, xb, party == 0 ? gamma : 0, party == 2 ? gamma : 0, za, zb};
     return launch_ew(n, all_aligned16(ptrs, 4), f, stream);
+}
+
+cg_status cg_zero_share(const uint8_t* key_self, const uint8_t* key_prev, uint64_t nonce, uint64_t first,
+                        uint64_t* alpha, size_t n, void* stream) {
+    if (!key_self || !key_prev) return CG_ERR_NULL;
+    if (n == 0) return CG_OK;
+    if (!alpha) return CG_ERR_NULL;
+    if (!aligned(alpha, 8)) return CG_ERR_ALIGN;
+    if (n > (SIZE_MAX >> 4) || first + n < first) return CG_ERR_SHAPE;
+    const hipError_t e = cg::launch_zero_share(nullptr, alpha, n, key_self, key_prev, nonce, first,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+cg_status cg_reshare(const uint64_t* z_i, const uint8_t* key_self, const uint8_t* key_prev, uint64_t nonce,
+                     uint64_t first, uint64_t* out, size_t n, void* stream) {
+    if (!key_self || !key_prev) return CG_ERR_NULL;
+    if (n == 0) return CG_OK;
+    if (!z_i || !out) return CG_ERR_NULL;
+    if (!aligned(z_i, 8) || !aligned(out, 8)) return CG_ERR_ALIGN;
+    if (n > (SIZE_MAX >> 4) || first + n < first) return CG_ERR_SHAPE;
+    if (bad_overlap(out, z_i, (u64)n * 8)) return CG_ERR_ALIAS;
+    const hipError_t e = cg::launch_zero_share(z_i, out, n, key_self, key_prev, nonce, first,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
 
 cg_status cg_reconstruct(const uint64_t* s0, const uint64_t* s1, const uint64_t* s2, uint64_t* out,

@@ -1,0 +1,168 @@
+// Zero shares from an AES-128 PRF and the reshare step z_i + alpha_i
+// (CryptGPU Sec. III-B "Protocol initialization", "Multiplication"; Sec. IV
+// "Pseudorandom generators on the GPU": AES is the PRF).
+//
+// alpha_i[j] = F(k_i, j) - F(k_{i-1}, j) mod 2^64.  F(k, j) is AES-128 in counter
+// mode: input block = (block index j >> 1 as 64-bit little-endian, nonce as 64-bit
+// little-endian), output word = ciphertext bytes 0..7 (j even) or 8..15 (j odd) as
+// a little-endian integer.  One thread encrypts one block under both keys and
+// produces two consecutive words of alpha.
+//
+// AES rounds use the classic 32-bit table formulation of FIPS-197: one table
+// T0[x] = (2 S[x], S[x], S[x], 3 S[x]), the other three columns of the MixColumns
+// matrix being byte rotations of it; the last round uses the S-box byte of the same
+// table.  The table sits in LDS once per bank (64 copies, 64 KiB): lane i reads
+// entry x at dword 64*x + i, i.e. always from bank i, so the data-dependent
+// lookups of a wave never collide.  Round keys are expanded on the host and passed
+// by value.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "prf.h"
+
+namespace cg {
+
+namespace {
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+
+// ---- host: tables and key schedule ------------------------------------------
+// S-box via discrete logarithms to the generator 3 of GF(2^8)*, then the affine map.
+struct AesTables {
+    uint8_t sbox[256];
+    u32 t0[256];
+    AesTables() {
+        uint8_t exp3[256], log3[256];
+        uint8_t x = 1;
+        for (int i = 0; i < 255; ++i) {
+            exp3[i] = x;
+            log3[x] = (uint8_t)i;
+            const uint8_t x2 = (uint8_t)((x << 1) ^ ((x & 0x80) ? 0x1B : 0));  // x * 2
+            x = (uint8_t)(x2 ^ x);                                             // x * 3
+        }
+        for (int v = 0; v < 256; ++v) {
+            const uint8_t inv = v ? exp3[(255 - log3[v]) % 255] : 0;
+            uint8_t s = inv;
+            s ^= (uint8_t)((inv << 1) | (inv >> 7));
+            s ^= (uint8_t)((inv << 2) | (inv >> 6));
+            s ^= (uint8_t)((inv << 3) | (inv >> 5));
+            s ^= (uint8_t)((inv << 4) | (inv >> 4));
+            s ^= 0x63;
+            sbox[v] = s;
+            const uint8_t s2 = (uint8_t)((s << 1) ^ ((s & 0x80) ? 0x1B : 0));
+            const uint8_t s3 = (uint8_t)(s2 ^ s);
+            t0[v] = (u32)s2 | ((u32)s << 8) | ((u32)s << 16) | ((u32)s3 << 24);
+        }
+    }
+};
+
+const AesTables& tables() {
+    static const AesTables t;
+    return t;
+}
+
+// Round keys as 44 little-endian column words.
+void expand_key(const uint8_t key[16], u32 rk[44]) {
+    const uint8_t* sb = tables().sbox;
+    for (int i = 0; i < 4; ++i)
+        rk[i] = (u32)key[4 * i] | ((u32)key[4 * i + 1] << 8) | ((u32)key[4 * i + 2] << 16) | ((u32)key[4 * i + 3] << 24);
+    u32 rcon = 1;
+    for (int i = 4; i < 44; ++i) {
+        u32 t = rk[i - 1];
+        if ((i & 3) == 0) {
+            t = (t >> 8) | (t << 24);  // RotWord on little-endian bytes
+            t = (u32)sb[t & 0xFF] | ((u32)sb[(t >> 8) & 0xFF] << 8) | ((u32)sb[(t >> 16) & 0xFF] << 16) |
+                ((u32)sb[t >> 24] << 24);
+            t ^= rcon;
+            rcon = (rcon << 1) ^ ((rcon & 0x80) ? 0x11B : 0);
+        }
+        rk[i] = rk[i - 4] ^ t;
+    }
+}
+
+struct PrfKeys {
+    u32 self[44], prev[44];
+};
+
+// ---- device ------------------------------------------------------------------
+__device__ __forceinline__ u32 rotl(u32 v, int s) { return (v << s) | (v >> (32 - s)); }
+
+// t0 points at this lane's column of the replicated table: entry x at t0[64 * x]
+__device__ __forceinline__ void aes_block(const u32* __restrict__ t0, const u32 (&rk)[44], u32 c0, u32 c1, u32 c2,
+                                          u32 c3, u32 out[4]) {
+#define T(x) (t0[(x) << 6])
+    u32 s0 = c0 ^ rk[0], s1 = c1 ^ rk[1], s2 = c2 ^ rk[2], s3 = c3 ^ rk[3];
+#pragma unroll
+    for (int r = 1; r < 10; ++r) {
+        const u32 n0 = T(s0 & 0xFF) ^ rotl(T((s1 >> 8) & 0xFF), 8) ^ rotl(T((s2 >> 16) & 0xFF), 16) ^
+                       rotl(T(s3 >> 24), 24) ^ rk[4 * r];
+        const u32 n1 = T(s1 & 0xFF) ^ rotl(T((s2 >> 8) & 0xFF), 8) ^ rotl(T((s3 >> 16) & 0xFF), 16) ^
+                       rotl(T(s0 >> 24), 24) ^ rk[4 * r + 1];
+        const u32 n2 = T(s2 & 0xFF) ^ rotl(T((s3 >> 8) & 0xFF), 8) ^ rotl(T((s0 >> 16) & 0xFF), 16) ^
+                       rotl(T(s1 >> 24), 24) ^ rk[4 * r + 2];
+        const u32 n3 = T(s3 & 0xFF) ^ rotl(T((s0 >> 8) & 0xFF), 8) ^ rotl(T((s1 >> 16) & 0xFF), 16) ^
+                       rotl(T(s2 >> 24), 24) ^ rk[4 * r + 3];
+        s0 = n0; s1 = n1; s2 = n2; s3 = n3;
+    }
+    // last round: SubBytes + ShiftRows + AddRoundKey; S[x] is byte 1 of T0[x]
+#define SB(v) ((T((v)&0xFF) >> 8) & 0xFF)
+    out[0] = (SB(s0) | (SB(s1 >> 8) << 8) | (SB(s2 >> 16) << 16) | (SB(s3 >> 24) << 24)) ^ rk[40];
+    out[1] = (SB(s1) | (SB(s2 >> 8) << 8) | (SB(s3 >> 16) << 16) | (SB(s0 >> 24) << 24)) ^ rk[41];
+    out[2] = (SB(s2) | (SB(s3 >> 8) << 8) | (SB(s0 >> 16) << 16) | (SB(s1 >> 24) << 24)) ^ rk[42];
+    out[3] = (SB(s3) | (SB(s0 >> 8) << 8) | (SB(s1 >> 16) << 16) | (SB(s2 >> 24) << 24)) ^ rk[43];
+#undef SB
+#undef T
+}
+
+struct T0Table {
+    u32 v[256];
+};
+
+// words [first, first + n) of alpha, optionally added to z (z == nullptr: alpha alone)
+__global__ __launch_bounds__(256) void zero_share_kernel(const u64* __restrict__ z, u64* __restrict__ out, size_t n,
+                                                         u64 first, u64 nonce, const PrfKeys keys,
+                                                         const T0Table table) {
+    __shared__ u32 t0_all[256 * 64];
+    {
+        const u32 mine = table.v[threadIdx.x];
+#pragma unroll 8
+        for (int c = 0; c < 64; ++c) t0_all[threadIdx.x * 64 + ((c + threadIdx.x) & 63)] = mine;
+    }
+    __syncthreads();
+    const u32* t0 = t0_all + (threadIdx.x & 63);
+    const u64 b_first = first >> 1, b_last = (first + n - 1) >> 1;  // n >= 1
+    const u64 nblocks = b_last - b_first + 1;
+    for (u64 bi = (u64)blockIdx.x * 256 + threadIdx.x; bi < nblocks; bi += (u64)gridDim.x * 256) {
+        const u64 block = b_first + bi;
+        u32 a[4], b[4];
+        aes_block(t0, keys.self, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), a);
+        aes_block(t0, keys.prev, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), b);
+        const u64 w0 = (((u64)a[1] << 32) | a[0]) - (((u64)b[1] << 32) | b[0]);
+        const u64 w1 = (((u64)a[3] << 32) | a[2]) - (((u64)b[3] << 32) | b[2]);
+        const u64 j0 = 2 * block, j1 = j0 + 1;  // word indices
+        if (j0 >= first && j0 - first < n) out[j0 - first] = (z ? z[j0 - first] : 0) + w0;
+        if (j1 >= first && j1 - first < n) out[j1 - first] = (z ? z[j1 - first] : 0) + w1;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_zero_share(const uint64_t* z, uint64_t* out, size_t n, const uint8_t key_self[16],
+                             const uint8_t key_prev[16], uint64_t nonce, uint64_t first, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    PrfKeys keys;
+    expand_key(key_self, keys.self);
+    expand_key(key_prev, keys.prev);
+    T0Table table;
+    memcpy(table.v, tables().t0, sizeof(table.v));
+    const size_t nblocks = (n + 1) / 2 + 1;
+    size_t grid = (nblocks + 255) / 256;
+    if (grid > 256 * 8) grid = 256 * 8;
+    hipLaunchKernelGGL(zero_share_kernel, dim3((unsigned)grid), dim3(256), 0, stream, z, out, n, (u64)first,
+                       (u64)nonce, keys, table);
+    return hipGetLastError();
+}
+
+}  // namespace cg

@@ -127,6 +127,20 @@ def test_elementwise_validation(L):
     assert L.cg_reconstruct(P, 2 * P, 3 * P, 4 * P, 0, None) == b.CG_OK
 
 
+def test_prf_entry_points_validation(L):
+    from paper_2104_10949_amd import binding as b
+    k = bytes(16)
+    assert L.cg_zero_share(None, k, 0, 0, P, 8, None) == b.CG_ERR_NULL
+    assert L.cg_zero_share(k, k, 0, 0, 0, 8, None) == b.CG_ERR_NULL
+    assert L.cg_zero_share(k, k, 0, 0, P + 4, 8, None) == b.CG_ERR_ALIGN
+    assert L.cg_zero_share(k, k, 0, (1 << 64) - 4, P, 8, None) == b.CG_ERR_SHAPE   # index range wraps
+    assert L.cg_zero_share(k, k, 0, 0, 0, 0, None) == b.CG_OK
+    assert L.cg_reshare(0, k, k, 0, 0, P, 8, None) == b.CG_ERR_NULL
+    assert L.cg_reshare(P, k, None, 0, 0, P, 8, None) == b.CG_ERR_NULL
+    assert L.cg_reshare(P, k, k, 0, 0, P + 8, 8, None) == b.CG_ERR_ALIAS           # partial overlap
+    assert L.cg_reshare(0, k, k, 0, 0, 0, 0, None) == b.CG_OK
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     from paper_2104_10949_amd import binding as b

@@ -306,3 +306,40 @@ def test_elementwise_unaligned(cg, ro, wl):
         dev.append(buf[1:])
     out = cg.cg_reconstruct(*dev)
     assert np.array_equal(cg.to_host(out), ro.reconstruct(a, b, c))
+
+
+PRF_KEYS = [bytes(range(16)), bytes(range(16, 32)), bytes([7 * i % 251 for i in range(16)])]
+
+
+@pytest.mark.parametrize("n,first", [(1, 0), (1, 1), (2, 0), (2, 1), (3, 5), (255, 2), (256, 3), (1000, 0),
+                                     (65537, 11), ((1 << 20) + 1, (1 << 40) + 7)])
+def test_zero_share_matches_the_oracle(cg, ro, n, first):
+    say(f"cg_zero_share n={n} first={first}")
+    nonce = 0xA5A5000011112222
+    for i in range(3):
+        got = cg.to_host(cg.cg_zero_share(PRF_KEYS[i], PRF_KEYS[(i - 1) % 3], nonce, first, n))
+        want = ro.zero_share(PRF_KEYS[i], PRF_KEYS[(i - 1) % 3], nonce, first, n)
+        assert not first_mismatch(got, want), first_mismatch(got, want)
+    assert cg.cg_zero_share(PRF_KEYS[0], PRF_KEYS[2], nonce, first, 0).numel() == 0
+
+
+def test_reshare_after_matmul_opens_to_the_product(cg, ro, wl):
+    M, N, K = 130, 70, 96
+    say(f"three parties: cg_share_matmul + cg_reshare + cg_reconstruct, M={M} N={N} K={K}")
+    x, y = wl.draw_ring((M, K), 31), wl.draw_ring((N, K), 32)
+    sx = ro.share(x, wl.draw_ring((M, K), 33), wl.draw_ring((M, K), 34))
+    sy = ro.share(y, wl.draw_ring((N, K), 35), wl.draw_ring((N, K), 36))
+    dx, dy = [cg.to_device(s) for s in sx], [cg.to_device(s) for s in sy]
+    blinded = []
+    for i in range(3):
+        z = cg.cg_share_matmul(dx[i], dx[(i + 1) % 3], dy[i], dy[(i + 1) % 3])
+        zh = cg.to_host(z)
+        b = cg.cg_reshare(z, PRF_KEYS[i], PRF_KEYS[(i - 1) % 3], nonce=5, first=3)
+        want = ro.reshare(zh, PRF_KEYS[i], PRF_KEYS[(i - 1) % 3], 5, 3)
+        assert not first_mismatch(cg.to_host(b), want), f"party {i}"
+        # in place
+        cg.cg_reshare(z, PRF_KEYS[i], PRF_KEYS[(i - 1) % 3], nonce=5, first=3, out=z)
+        assert np.array_equal(cg.to_host(z), want)
+        blinded.append(b)
+    # party i's new replicated pair is (blinded_i, blinded_{i+1}); opening gives x y^T
+    assert np.array_equal(cg.to_host(cg.cg_reconstruct(*blinded)), ro.matmul(x, y))
