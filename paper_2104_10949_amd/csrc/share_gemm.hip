@@ -839,13 +839,21 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(u64* z, size_t n) {
 template <class T, int AMODE, bool BVEC>
 static hipError_t launch(const GemmParams& p, hipStream_t stream);
 
+#ifndef CG_SPLIT_TARGET
+#define CG_SPLIT_TARGET 256
+#endif
+#ifndef CG_SPLIT_MIN_SLICES
+#define CG_SPLIT_MIN_SLICES 2
+#endif
+
 static int choose_ksplit(int64_t tiles, int nk) {
-    // Split K when the tile grid alone cannot fill the 256 compute units: aim at
-    // two blocks per unit, keep at least 4 slices of K per block.
+    // Split K when the tile grid alone cannot fill the 256 compute units.  A block's
+    // 96 KB of LDS leaves room for one block per unit, so aim at one round of 256
+    // blocks and keep at least two slices of K per block.
     int ksplit = 1;
-    if (tiles < 256) {
-        ksplit = (int)((512 + tiles - 1) / tiles);
-        if (ksplit > nk / 4) ksplit = nk / 4;
+    if (tiles < CG_SPLIT_TARGET) {
+        ksplit = (int)(CG_SPLIT_TARGET / tiles);
+        if (ksplit > nk / CG_SPLIT_MIN_SLICES) ksplit = nk / CG_SPLIT_MIN_SLICES;
         if (ksplit < 1) ksplit = 1;
         const int per = (nk + ksplit - 1) / ksplit;
         ksplit = (nk + per - 1) / per;  // no empty splits
