@@ -216,36 +216,53 @@ struct PatchRow {
 // tap, so (r, s) and the channel offset are uniform over the block and advance
 // by scalar increments as ks grows.
 struct TapCursor {
-    int ks, r, s, c0;
-    __device__ __forceinline__ void reset() { ks = 0; r = 0; s = 0; c0 = 0; }
+    int ks, r, s, c0, tap;
+    u32 off;  // ((r*W + s)*Cin + c0) * 8: byte offset of the slice relative to the row's pixel (hi0, wi0)
+    __device__ __forceinline__ void reset() { ks = 0; r = 0; s = 0; c0 = 0; tap = 0; off = 0; }
     __device__ __forceinline__ void advance_to(const GemmParams& p, int want) {
         while (ks < want) {  // zero or one step per call in the kernel's load order
             ++ks;
             c0 += 32;
+            off += 256u;
             if (c0 == p.Cin) {
                 c0 = 0;
+                ++tap;
                 if (++s == p.kw) { s = 0; ++r; }
+                off = ((u32)r * (u32)p.W + (u32)s) * (u32)p.Cin * 8u;
             }
         }
     }
-    __device__ __forceinline__ u32 offset(const GemmParams& p) const {
-        return (((u32)r * (u32)p.W + (u32)s) * (u32)p.Cin + (u32)c0) * 8u;
-    }
 };
 
-// Patch gather with Cin % 32 == 0, 16-byte loads.
+// Patch gather with Cin % 32 == 0, 16-byte loads.  Which filter taps fall inside
+// the image for this unit's output pixel is decided once, as a bit mask over the
+// (up to 64) taps; windows with more taps test the bounds per load.
 struct ConvC32 {
     PatchRow pr;
-    u32 kq8;  // (16*jh + 2*q) * 8 bytes
+    u32 base_kq;  // pr.base + (16*jh + 2*q) * 8 bytes
+    u64 inside;   // bit t: tap t = r*kw + s reads a pixel inside the image
     __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, u32,
                                          int q, int jh) {
         pr.init(p, m0, row_local, rows_left);
-        kq8 = (16 * jh + 2 * q) * 8;
+        base_kq = pr.base + (u32)(16 * jh + 2 * q) * 8u;
+        inside = 0;
+        const int taps = p.kh * p.kw;
+        if (pr.ok && taps <= 64) {
+            int t = 0;
+            for (int r = 0; r < p.kh; ++r)
+                for (int s_ = 0; s_ < p.kw; ++s_, ++t)
+                    if ((u32)(pr.hi0 + r) < (u32)p.H && (u32)(pr.wi0 + s_) < (u32)p.W) inside |= 1ull << t;
+        }
     }
     __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, const TapCursor& t,
                                          u4 out[2]) const {
-        const bool v = pr.ok && t.r < p.kh && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
-        const u32 off = v ? pr.base + t.offset(p) + kq8 : OOB;
+        bool v;
+        if (p.kh * p.kw <= 64) {  // uniform
+            v = t.tap < 64 && ((inside >> t.tap) & 1);
+        } else {
+            v = pr.ok && t.r < p.kh && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
+        }
+        const u32 off = v ? base_kq + t.off : OOB;
         out[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off, 0, 0);
         out[1] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off + 64u, 0, 0);
     }
@@ -669,7 +686,7 @@ struct PlanesConv {
     __device__ __forceinline__ u4 load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int, const TapCursor& t) const {
         const bool v = pr.ok && t.r < p.kh && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
         // a pixel's Cin words occupy Cin*8 bytes of planes; slice c0/32 starts at c0*8 bytes
-        return __builtin_amdgcn_raw_buffer_load_b128(rs_, v ? pr.base + t.offset(p) + c16 : OOB, 0, 0);
+        return __builtin_amdgcn_raw_buffer_load_b128(rs_, v ? pr.base + t.off + c16 : OOB, 0, 0);
     }
 };
 
