@@ -78,6 +78,27 @@ CG_API cg_status cg_share_matmul(const uint64_t *x_i, const uint64_t *x_ip1,
                           uint64_t *z_i, int64_t M, int64_t N, int64_t K, void *stream);
 
 /*
+ * The same product with either operand stored transposed: the share products of
+ * the backward pass of a fully connected layer are matrix products of the same
+ * kind on gradients (Sec. III-C: linear-layer gradients are computed with the
+ * same protocols).  With Z = X W^T the forward product (X [M,K], W [N,K]):
+ *
+ *   dX = dZ W    : cg_share_matmul_t(dZ.., W.., dX, M, K, N, 0, 1)   (W  is [N,K] = stored [K', N'])
+ *   dW = dZ^T X  : cg_share_matmul_t(dZ.., X.., dW, N, K, M, 1, 1)   (dZ is [M,N] = stored [K', M'])
+ *
+ * In general z_i [M,N] is the three-term product of the left operand L [M,K] and
+ * the right operand R [N,K] (contracted over K, as in cg_share_matmul), where
+ *   trans_x = 0: x_i, x_ip1 hold L row-major [M,K];  trans_x = 1: they hold L^T, row-major [K,M];
+ *   trans_y = 0: y_i, y_ip1 hold R row-major [N,K];  trans_y = 1: they hold R^T, row-major [K,N].
+ * trans_x = trans_y = 0 is cg_share_matmul.  CG_ERR_SHAPE if a flag is not 0 or 1;
+ * CG_ERR_UNSUPPORTED additionally if a transposed operand has more than 2^22 columns.
+ */
+CG_API cg_status cg_share_matmul_t(const uint64_t *x_i, const uint64_t *x_ip1,
+                            const uint64_t *y_i, const uint64_t *y_ip1,
+                            uint64_t *z_i, int64_t M, int64_t N, int64_t K,
+                            int trans_x, int trans_y, void *stream);
+
+/*
  * The same product with caller-supplied scratch memory (device memory, 16-byte
  * aligned, at least cg_share_matmul_workspace_bytes(M, N, K) bytes, not
  * overlapping any operand).  With scratch memory each share tensor is split

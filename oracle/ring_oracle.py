@@ -188,6 +188,13 @@ def party_matmul(x_i, x_ip1, y_i, y_ip1) -> np.ndarray:
     return z
 
 
+def party_matmul_t(x_i, x_ip1, y_i, y_ip1, trans_x: bool, trans_y: bool) -> np.ndarray:
+    """party_matmul on operands that are stored transposed: the stored arrays are transposed back
+    (a copy, no arithmetic) and handed to the same C routine."""
+    t = lambda a, flag: np.ascontiguousarray(_u(a).T) if flag else _u(a)
+    return party_matmul(t(x_i, trans_x), t(x_ip1, trans_x), t(y_i, trans_y), t(y_ip1, trans_y))
+
+
 def party_conv2d(x_i, x_ip1, w_i, w_ip1, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
     x_i, x_ip1, w_i, w_ip1 = _u(x_i), _u(x_ip1), _u(w_i), _u(w_ip1)
     B, H, Wd, Cin = x_i.shape

@@ -22,7 +22,7 @@ LIB_PATH = os.environ.get("CG_LIBRARY") or os.path.join(_HERE, "libcg.so")
 
 EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d", "cg_share_add",
            "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct",
-           "cg_share_matmul_ws", "cg_share_conv2d_ws", "cg_zero_share", "cg_reshare",
+           "cg_share_matmul_ws", "cg_share_conv2d_ws", "cg_zero_share", "cg_reshare", "cg_share_matmul_t",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -68,9 +68,10 @@ def lib() -> ctypes.CDLL:
         key = ctypes.c_char_p
         L.cg_zero_share.argtypes = [key, key, u64, u64, vp, sz, vp]
         L.cg_reshare.argtypes = [vp, key, key, u64, u64, vp, sz, vp]
-        for name in EXPORTS[2:12]:
+        L.cg_share_matmul_t.argtypes = [vp] * 5 + [i64] * 3 + [ctypes.c_int] * 2 + [vp]
+        for name in EXPORTS[2:13]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[12:]:
+        for name in EXPORTS[13:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -117,6 +118,29 @@ def cg_share_matmul(x_i, x_ip1, y_i, y_ip1, z_i=None, stream=None) -> torch.Tens
         raise ValueError("output shape does not match")
     _check(lib().cg_share_matmul(_ptr(x_i), _ptr(x_ip1), _ptr(y_i), _ptr(y_ip1), _ptr(z_i),
                                  M, N, K, _stream(stream)), "cg_share_matmul")
+    return z_i
+
+
+def cg_share_matmul_t(x_i, x_ip1, y_i, y_ip1, trans_x: bool, trans_y: bool, z_i=None, stream=None) -> torch.Tensor:
+    """Three-term product of L [M,K] and R [N,K] where x holds L ([M,K]) or L^T ([K,M], trans_x) and
+    y holds R ([N,K]) or R^T ([K,N], trans_y)."""
+    if trans_x:
+        K, M = x_i.shape
+    else:
+        M, K = x_i.shape
+    if trans_y:
+        K2, N = y_i.shape
+    else:
+        N, K2 = y_i.shape
+    if x_ip1.shape != x_i.shape or y_ip1.shape != y_i.shape or K2 != K:
+        raise ValueError("operand shapes do not match")
+    if z_i is None:
+        z_i = torch.empty((M, N), dtype=torch.int64, device=x_i.device)
+    elif tuple(z_i.shape) != (M, N):
+        raise ValueError("output shape does not match")
+    _check(lib().cg_share_matmul_t(_ptr(x_i), _ptr(x_ip1), _ptr(y_i), _ptr(y_ip1), _ptr(z_i),
+                                   M, N, K, int(bool(trans_x)), int(bool(trans_y)), _stream(stream)),
+           "cg_share_matmul_t")
     return z_i
 
 

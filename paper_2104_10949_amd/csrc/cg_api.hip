@@ -220,7 +220,7 @@ namespace {
 struct Plan {
     cg::GemmParams p;
     int amode;        // address generator of the direct route
-    bool bvec;
+    int bmode;
     bool planes_ok;   // the digit-plane route applies
     bool planes_conv; // ... with the patch gather
     int64_t x_rows, x_k;  // left operand seen as [x_rows, x_k] words for the plane conversion
@@ -235,7 +235,8 @@ u64 plan_workspace_bytes(const Plan& pl) {
 }
 
 cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i, const uint64_t* y_ip1,
-                      uint64_t* z_i, int64_t M, int64_t N, int64_t K, bool check_ptrs_too, Plan* out) {
+                      uint64_t* z_i, int64_t M, int64_t N, int64_t K, bool check_ptrs_too, Plan* out,
+                      bool trans_x = false, bool trans_y = false) {
     if (check_ptrs_too && (!x_i || !x_ip1 || !y_i || !y_ip1 || !z_i)) return CG_ERR_NULL;
     if (M < 1 || N < 1 || K < 1) return CG_ERR_SHAPE;
     int64_t mk, nk, mn, tmp;
@@ -255,10 +256,14 @@ cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     p.Ho = p.Wo = 1;
     const void* in[4] = {x_i, x_ip1, y_i, y_ip1};
     const bool vec = (K % 2 == 0) && (!check_ptrs_too || all_aligned16(in, 4));
-    pl.amode = vec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR;
-    pl.bvec = vec;
+    pl.amode = trans_x ? cg::A_TRANS : (vec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR);
+    pl.bmode = trans_y ? cg::B_TRANS : (vec ? cg::B_VEC : cg::B_SCALAR);
+    if (trans_x && !trans_y && !vec) pl.bmode = cg::B_SCALAR;
+    if (!trans_x && trans_y) pl.amode = vec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR;
+    // a transposed operand is addressed slice by slice: 32 rows of its pitch must fit a 2^31-byte view
+    if ((trans_x && M > (1 << 22)) || (trans_y && N > (1 << 22))) return CG_ERR_UNSUPPORTED;
     const int64_t KS = (K + 31) / 32;
-    pl.planes_ok = vec;
+    pl.planes_ok = vec && !trans_x && !trans_y;
     pl.planes_conv = false;
     pl.x_rows = M; pl.x_k = K;
     pl.xp_bytes = (u64)M * (u64)KS * 256; pl.wp_bytes = (u64)N * (u64)KS * 256;
@@ -326,7 +331,7 @@ cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
         amode = (a16 && d->Cin % 32 == 0) ? cg::A_CONV_C32 : cg::A_CONV_GEN;
     }
     pl.amode = amode;
-    pl.bvec = bvec;
+    pl.bmode = bvec ? cg::B_VEC : cg::B_SCALAR;
     const int64_t KS = (K + 31) / 32;
     if (pointwise) {
         pl.planes_ok = bvec;
@@ -346,7 +351,7 @@ cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
 }
 
 cg_status run_direct(const Plan& pl, void* stream) {
-    const hipError_t e = cg::launch_share_gemm(pl.p, pl.amode, pl.bvec, static_cast<hipStream_t>(stream));
+    const hipError_t e = cg::launch_share_gemm(pl.p, pl.amode, pl.bmode, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
 
@@ -387,6 +392,15 @@ cg_status cg_share_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint
                           void* stream) {
     Plan pl;
     if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl)) return st;
+    return run_direct(pl, stream);
+}
+
+cg_status cg_share_matmul_t(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
+                            const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
+                            int trans_x, int trans_y, void* stream) {
+    if ((trans_x != 0 && trans_x != 1) || (trans_y != 0 && trans_y != 1)) return CG_ERR_SHAPE;
+    Plan pl;
+    if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl, trans_x, trans_y)) return st;
     return run_direct(pl, stream);
 }
 

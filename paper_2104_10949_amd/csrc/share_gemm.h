@@ -27,7 +27,15 @@ enum AMode {
     A_LINEAR_VEC = 0,     // row-major [M, lda], 16-byte loads (lda even, 16-byte aligned base)
     A_LINEAR_SCALAR = 1,  // row-major [M, lda], 8-byte loads
     A_CONV_C32 = 2,       // NHWC patch gather, Cin % 32 == 0, 16-byte loads
-    A_CONV_GEN = 3        // NHWC patch gather, any Cin, 8-byte loads
+    A_CONV_GEN = 3,       // NHWC patch gather, any Cin, 8-byte loads
+    A_TRANS = 4           // stored transposed, [K, M] with M contiguous, 8-byte loads
+};
+
+// How the right operand's words are addressed.
+enum BMode {
+    B_VEC = 0,     // row-major [N, K], 16-byte loads
+    B_SCALAR = 1,  // row-major [N, K], 8-byte loads
+    B_TRANS = 2    // stored transposed, [K, N] with N contiguous, 8-byte loads
 };
 
 struct GemmParams {
@@ -51,7 +59,7 @@ struct GemmParams {
 // offset ranges against it.
 static const int MAX_TILE_ROWS = 256;
 
-hipError_t launch_share_gemm(const GemmParams& p, int amode, bool bvec, hipStream_t stream);
+hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream);
 
 // Digit-plane route.  launch_to_planes converts a row-major [R, K] operand (K even,
 // 16-byte aligned), optionally summed with `add` first, into planes of

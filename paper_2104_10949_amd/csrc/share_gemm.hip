@@ -191,6 +191,32 @@ struct LinearScalar {
     }
 };
 
+// Transposed operand: memory holds [K, rows] with the rows contiguous (the operand of
+// a backward-pass product).  Consecutive lanes take consecutive rows, so each of the
+// unit's four 8-byte loads is one contiguous run per wave.  The view is rebased at
+// every K slice (offsets inside a slice stay below 32 * pitch * 8 bytes).
+struct TransScalar {
+    u32 off0;  // (row + (16*jh + 2*q) * pitch) * 8, or OOB
+    u32 kq, pitch8;
+    __device__ __forceinline__ void init(const GemmParams&, int, int row_local, int rows_left, u32 pitch,
+                                         int q, int jh) {
+        kq = 16 * jh + 2 * q;
+        pitch8 = pitch * 8u;
+        off0 = row_local < rows_left ? ((u32)row_local + kq * pitch) * 8u : OOB;
+    }
+    __device__ __forceinline__ void load(const GemmParams&, __amdgpu_buffer_rsrc_t r, int ks, u32 K,
+                                         u4 out[2]) const {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const u32 k = 32u * ks + kq + 8u * jj;
+            const u32 o = off0 + 8u * jj * pitch8;
+            const u2 e0 = __builtin_amdgcn_raw_buffer_load_b64(r, k < K ? o : OOB, 0, 0);
+            const u2 e1 = __builtin_amdgcn_raw_buffer_load_b64(r, k + 1 < K ? o + pitch8 : OOB, 0, 0);
+            out[jj].x = e0.x; out[jj].y = e0.y; out[jj].z = e1.x; out[jj].w = e1.y;
+        }
+    }
+};
+
 // Decomposition of an output-pixel row index shared by both patch gatherers.
 // Offsets are 32-bit unsigned and may wrap for taps that fall outside the image;
 // those are never used (the load is redirected to OOB).
@@ -391,7 +417,7 @@ __device__ __forceinline__ void fold_tile(const GemmParams& p, v16i (&acc)[SM][S
 }
 
 // ---------------------------------------------------------------------------
-template <class T, int AMODE, bool BVEC>
+template <class T, int AMODE, int BMODE>
 __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const GemmParams p) {
     constexpr int SM = T::SM, SN = T::SN, AU = T::A_UNITS, BU = T::B_UNITS;
     __shared__ __attribute__((aligned(16))) char lds[2 * T::STAGE];
@@ -407,37 +433,67 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
 
     // ---- buffer views, rebased per block so that 32-bit offsets suffice
     constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
+    constexpr bool A_TR = AMODE == A_TRANS, B_TR = BMODE == B_TRANS;
     u64 a_base_elems;
     if (A_LINEAR) a_base_elems = (u64)m0 * (u64)p.lda;
+    else if (A_TR) a_base_elems = (u64)m0;
     else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
-    const u64 a_left = ((u64)p.x_elems - a_base_elems) * 8u;
-    const u32 a_bytes = a_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)a_left;
-    const __amdgpu_buffer_rsrc_t rs_xa = make_rsrc(p.x_a + a_base_elems, a_bytes);
-    const __amdgpu_buffer_rsrc_t rs_xb = make_rsrc(p.x_b + a_base_elems, a_bytes);
-    const u64 b_base_elems = (u64)n0 * (u64)p.K;
-    const u64 b_left = ((u64)p.N * (u64)p.K - b_base_elems) * 8u;
-    const u32 b_bytes = b_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)b_left;
-    const __amdgpu_buffer_rsrc_t rs_wa = make_rsrc(p.w_a + b_base_elems, b_bytes);
-    const __amdgpu_buffer_rsrc_t rs_wb = make_rsrc(p.w_b + b_base_elems, b_bytes);
+    const u64 b_base_elems = B_TR ? (u64)n0 : (u64)n0 * (u64)p.K;
+    const u64 w_elems = (u64)p.N * (u64)p.K;
+    // view on `elems_total` words starting `base` words in, advanced by `adv` words
+    auto view = [&](const u64* ptr, u64 elems_total, u64 base) {
+        const u64 left = (elems_total - base) * 8u;
+        return make_rsrc(ptr + base, left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left);
+    };
+    const __amdgpu_buffer_rsrc_t rs_xa = view(p.x_a, p.x_elems, a_base_elems);
+    const __amdgpu_buffer_rsrc_t rs_xb = view(p.x_b, p.x_elems, a_base_elems);
+    const __amdgpu_buffer_rsrc_t rs_wa = view(p.w_a, w_elems, b_base_elems);
+    const __amdgpu_buffer_rsrc_t rs_wb = view(p.w_b, w_elems, b_base_elems);
+    // transposed operands: one view per K slice
+    auto a_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
+        if constexpr (A_TR) {
+            const u64 base = a_base_elems + (u64)ks * 32u * (u64)p.M;
+            return base < p.x_elems ? view(ptr, p.x_elems, base) : make_rsrc(ptr, 0);
+        } else {
+            return fixed;
+        }
+    };
+    auto b_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
+        if constexpr (B_TR) {
+            const u64 base = b_base_elems + (u64)ks * 32u * (u64)p.N;
+            return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
+        } else {
+            return fixed;
+        }
+    };
 
-    // ---- per-thread units
+    // ---- per-thread units.  Row-major operands put the four 16-byte quarters of a
+    // 64-byte run on consecutive lanes; transposed operands put consecutive rows there.
     typedef typename std::conditional<AMODE == A_LINEAR_VEC, LinearVec,
             typename std::conditional<AMODE == A_LINEAR_SCALAR, LinearScalar,
-            typename std::conditional<AMODE == A_CONV_C32, ConvC32, ConvGen>::type>::type>::type AGen;
-    typedef typename std::conditional<BVEC, LinearVec, LinearScalar>::type BGen;
+            typename std::conditional<AMODE == A_CONV_C32, ConvC32,
+            typename std::conditional<AMODE == A_TRANS, TransScalar, ConvGen>::type>::type>::type>::type AGen;
+    typedef typename std::conditional<BMODE == B_VEC, LinearVec,
+            typename std::conditional<BMODE == B_SCALAR, LinearScalar, TransScalar>::type>::type BGen;
     AGen ag[AU];
     BGen bg[BU];
     int a_dst[AU], b_dst[BU];  // LDS byte offset of digit 0 inside a stage
 #pragma unroll
     for (int i = 0; i < AU; ++i) {
-        const int u = tid + i * T::NT, q = u & 3, row = (u >> 2) % T::BM, jh = (u >> 2) / T::BM;
-        ag[i].init(p, m0, row, rows_m, (u32)p.lda, q, jh);
+        const int u = tid + i * T::NT;
+        const int q = A_TR ? (u / T::BM) & 3 : u & 3;
+        const int row = A_TR ? u % T::BM : (u >> 2) % T::BM;
+        const int jh = (u >> 2) / T::BM;
+        ag[i].init(p, m0, row, rows_m, A_TR ? (u32)p.M : (u32)p.lda, q, jh);
         a_dst[i] = jh * T::A_RS + row * 16 + q * 4;
     }
 #pragma unroll
     for (int i = 0; i < BU; ++i) {
-        const int u = tid + i * T::NT, q = u & 3, row = (u >> 2) % T::BN, jh = (u >> 2) / T::BN;
-        bg[i].init(p, n0, row, rows_n, (u32)p.K, q, jh);
+        const int u = tid + i * T::NT;
+        const int q = B_TR ? (u / T::BN) & 3 : u & 3;
+        const int row = B_TR ? u % T::BN : (u >> 2) % T::BN;
+        const int jh = (u >> 2) / T::BN;
+        bg[i].init(p, n0, row, rows_n, B_TR ? (u32)p.N : (u32)p.K, q, jh);
         b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
     }
     TapCursor tap;
@@ -462,13 +518,13 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         for (int i = 0; i < BU; ++i) bg[i].load(p, rs, ks, (u32)p.K, dst[i]);
     };
     auto load_even = [&](int ks) {
-        load_a(rs_xa, ks, eA);
-        load_b(rs_wa, ks, eB);
-        load_b(rs_wb, ks, eB2);
+        load_a(a_view(p.x_a, rs_xa, ks), ks, eA);
+        load_b(b_view(p.w_a, rs_wa, ks), ks, eB);
+        load_b(b_view(p.w_b, rs_wb, ks), ks, eB2);
     };
     // w_a of a slice is fetched once, with the even set; the odd set's copy is
     // taken from there before the even set is summed and recoded.
-    auto load_odd = [&](int ks) { load_a(rs_xb, ks, oA); };
+    auto load_odd = [&](int ks) { load_a(a_view(p.x_b, rs_xb, ks), ks, oA); };
 
     // The split of one unit in four pieces, so that they can be placed between MFMAs:
     // 0: recode the first two words, 1: the last two, 2: digits 0-3 to LDS, 3: digits 4-7.
@@ -853,7 +909,7 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(u64* z, size_t n) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) z[i] = 0;
 }
 
-template <class T, int AMODE, bool BVEC>
+template <class T, int AMODE, int BMODE>
 static hipError_t launch(const GemmParams& p, hipStream_t stream);
 
 #ifndef CG_SPLIT_TARGET
@@ -909,27 +965,32 @@ hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t 
     return hipGetLastError();
 }
 
-template <class T, int AMODE, bool BVEC>
+template <class T, int AMODE, int BMODE>
 static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
     GemmParams q = p;
     q.group_m = tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);
     q.ksplit = choose_ksplit(tiles_m * tiles_n, (p.K + 31) / 32);
     if (q.ksplit > 1) launch_zero_fill(q, stream);
-    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BVEC>), dim3((unsigned)(tiles_m * tiles_n * q.ksplit)),
+    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BMODE>), dim3((unsigned)(tiles_m * tiles_n * q.ksplit)),
                        dim3(T::NT), 0, stream, q);
     return hipGetLastError();
 }
 
-hipError_t launch_share_gemm(const GemmParams& p, int amode, bool bvec, hipStream_t stream) {
+hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream) {
     typedef Tile<CG_TILE> T;  // waves along M, waves along N, 32x32 sub-tiles per wave along M, along N
-    switch (amode) {
-        case A_LINEAR_VEC:    return launch<T, A_LINEAR_VEC, true>(p, stream);
-        case A_LINEAR_SCALAR: return launch<T, A_LINEAR_SCALAR, false>(p, stream);
-        case A_CONV_C32:      return launch<T, A_CONV_C32, true>(p, stream);
-        case A_CONV_GEN:
-            return bvec ? launch<T, A_CONV_GEN, true>(p, stream) : launch<T, A_CONV_GEN, false>(p, stream);
-    }
+#define CG_CASE(A, B) if (amode == A && bmode == B) return launch<T, A, B>(p, stream)
+    CG_CASE(A_LINEAR_VEC, B_VEC);
+    CG_CASE(A_LINEAR_SCALAR, B_SCALAR);
+    CG_CASE(A_CONV_C32, B_VEC);
+    CG_CASE(A_CONV_GEN, B_VEC);
+    CG_CASE(A_CONV_GEN, B_SCALAR);
+    CG_CASE(A_LINEAR_VEC, B_TRANS);
+    CG_CASE(A_LINEAR_SCALAR, B_TRANS);
+    CG_CASE(A_TRANS, B_VEC);
+    CG_CASE(A_TRANS, B_SCALAR);
+    CG_CASE(A_TRANS, B_TRANS);
+#undef CG_CASE
     return hipErrorInvalidValue;
 }
 

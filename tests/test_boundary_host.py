@@ -127,6 +127,18 @@ def test_elementwise_validation(L):
     assert L.cg_reconstruct(P, 2 * P, 3 * P, 4 * P, 0, None) == b.CG_OK
 
 
+def test_transposed_matmul_validation(L):
+    from paper_2104_10949_amd import binding as b
+    big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
+    f = L.cg_share_matmul_t
+    assert f(*big, 4, 4, 4, 2, 0, None) == b.CG_ERR_SHAPE
+    assert f(*big, 4, 4, 4, 0, -1, None) == b.CG_ERR_SHAPE
+    assert f(0, *big[1:], 4, 4, 4, 1, 1, None) == b.CG_ERR_NULL
+    assert f(*big, 4, 0, 4, 1, 1, None) == b.CG_ERR_SHAPE
+    assert f(*big, (1 << 22) + 1, 4, 4, 1, 0, None) == b.CG_ERR_UNSUPPORTED
+    assert f(*big, 4, (1 << 22) + 1, 4, 0, 1, None) == b.CG_ERR_UNSUPPORTED
+
+
 def test_prf_entry_points_validation(L):
     from paper_2104_10949_amd import binding as b
     k = bytes(16)

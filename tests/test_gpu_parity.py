@@ -343,3 +343,38 @@ def test_reshare_after_matmul_opens_to_the_product(cg, ro, wl):
         blinded.append(b)
     # party i's new replicated pair is (blinded_i, blinded_{i+1}); opening gives x y^T
     assert np.array_equal(cg.to_host(cg.cg_reconstruct(*blinded)), ro.matmul(x, y))
+
+
+@pytest.mark.parametrize("trans_x,trans_y", [(False, True), (True, True), (True, False), (False, False)])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (3, 5, 7), (128, 64, 32), (129, 65, 33), (130, 70, 100),
+                                   (300, 129, 130), (64, 200, 513), (1000, 3, 40), (5, 1000, 96), (40, 33, 16400)])
+def test_matmul_transposed_operands(cg, ro, wl, M, N, K, trans_x, trans_y):
+    say(f"cg_share_matmul_t M={M} N={N} K={K} trans_x={trans_x} trans_y={trans_y}")
+    seed = 12000 + M * 31 + N * 17 + K
+    xs = (K, M) if trans_x else (M, K)
+    ys = (K, N) if trans_y else (N, K)
+    ops = (wl.draw_ring(xs, seed), wl.draw_ring(xs, seed + 1), wl.draw_ring(ys, seed + 2), wl.draw_ring(ys, seed + 3))
+    d = [cg.to_device(a) for a in ops]
+    z = cg.cg_share_matmul_t(*d, trans_x, trans_y)
+    torch.cuda.synchronize()
+    want = ro.party_matmul_t(*ops, trans_x, trans_y)
+    got = cg.to_host(z)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+def test_fc_backward_products_open_to_the_gradients(cg, ro, wl):
+    """Forward Z = X W^T; backward dX = dZ W and dW = dZ^T X as share products on the
+    stored tensors, all three parties, opened and compared with the ring products."""
+    Mb, Nout, Kin = 96, 40, 136
+    say(f"FC backward on shares: batch {Mb}, {Kin} -> {Nout}")
+    X, W, dZ = wl.draw_ring((Mb, Kin), 1), wl.draw_ring((Nout, Kin), 2), wl.draw_ring((Mb, Nout), 3)
+    sh = lambda a, s: ro.share(a, wl.draw_ring(a.shape, s), wl.draw_ring(a.shape, s + 1))
+    sX, sW, sdZ = sh(X, 10), sh(W, 20), sh(dZ, 30)
+    dX_, dW_, ddZ = ([cg.to_device(v) for v in s] for s in (sX, sW, sdZ))
+    p = lambda t, i: (t[i], t[(i + 1) % 3])
+    dX = [cg.cg_share_matmul_t(*p(ddZ, i), *p(dW_, i), False, True) for i in range(3)]
+    dW = [cg.cg_share_matmul_t(*p(ddZ, i), *p(dX_, i), True, True) for i in range(3)]
+    torch.cuda.synchronize()
+    assert np.array_equal(cg.to_host(cg.cg_reconstruct(*dX)), ro.matmul(dZ, np.ascontiguousarray(W.T)))
+    assert np.array_equal(cg.to_host(cg.cg_reconstruct(*dW)),
+                          ro.matmul(np.ascontiguousarray(dZ.T), np.ascontiguousarray(X.T)))
