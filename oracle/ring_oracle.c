@@ -20,7 +20,11 @@
  * 1x1 convolution == matmul, delta-kernel shift, output sizes printed in the
  * paper's AlexNet/VGG tables, share/reconstruct identity, sum of the three
  * parties' local products == product of the plaintext encodings, and the
- * decoded fixed-point product against an fp64 product.
+ * decoded fixed-point product against an fp64 product; for the PRF part at
+ * the end of this file (tests/test_oracle_prf.py): the FIPS-197 known-answer
+ * vectors, the counter-mode word layout rebuilt block by block, stream
+ * continuation, zero shares summing to zero, reshare keeping the opened value.
+ * Every function here is covered by at least one of these pins.
  */
 #include <stdint.h>
 #include <stdlib.h>
