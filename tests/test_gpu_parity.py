@@ -127,6 +127,34 @@ def test_matmul_long_k_crosses_accumulator_folds(cg, ro, wl, K, route):
     assert not first_mismatch(got, want), first_mismatch(got, want)
 
 
+@pytest.mark.parametrize("route", ROUTES)
+def test_matmul_long_k_without_split_k_folds_in_place(cg, ro, wl, route):
+    """256 output tiles (no split-K) and K = 16400 = 513 slices: the 32-bit partial sums are folded
+    into z twice, the second time by read-add-write.  Worst-case digits over the whole output, then
+    random words on sampled rows."""
+    M, N, K = 2048, 1024, 16400
+    say(f"cg_share_matmul M={M} N={N} K={K}: two folds per block, no split-K, route={route}")
+    x = np.full((M, K), 0x8080808080808080, dtype=np.uint64)
+    y = np.full((N, K), 0x8080808080808080, dtype=np.uint64)
+    got = run_matmul(cg, (x, x, y, y), route)
+    expect = (3 * K * 0x8080808080808080 * 0x8080808080808080) % (1 << 64)
+    assert np.all(got == np.uint64(expect))
+    ops = (wl.draw_ring((M, K), 51), wl.draw_ring((M, K), 52), wl.draw_ring((N, K), 53), wl.draw_ring((N, K), 54))
+    got = run_matmul(cg, ops, route)
+    for r0 in (0, 1000, 2040):
+        want = ro.party_matmul(ops[0][r0:r0 + 8], ops[1][r0:r0 + 8], ops[2], ops[3])
+        assert not first_mismatch(got[r0:r0 + 8], want), f"rows {r0}.."
+
+
+def test_matmul_largest_supported_k(cg, ro, wl):
+    M, N, K = 3, 2, 1 << 20
+    say(f"cg_share_matmul M={M} N={N} K=2^20 (the documented limit)")
+    ops = (wl.draw_ring((M, K), 61), wl.draw_ring((M, K), 62), wl.draw_ring((N, K), 63), wl.draw_ring((N, K), 64))
+    got = run_matmul(cg, ops)
+    want = ro.party_matmul(*ops)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
 def test_matmul_unaligned_views_take_the_8_byte_path(cg, ro, wl):
     M, N, K = 50, 37, 64
     say("cg_share_matmul with 8-byte-aligned (not 16) operand pointers")
