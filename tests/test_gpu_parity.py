@@ -406,3 +406,52 @@ def test_fc_backward_products_open_to_the_gradients(cg, ro, wl):
     assert np.array_equal(cg.to_host(cg.cg_reconstruct(*dX)), ro.matmul(dZ, np.ascontiguousarray(W.T)))
     assert np.array_equal(cg.to_host(cg.cg_reconstruct(*dW)),
                           ro.matmul(np.ascontiguousarray(dZ.T), np.ascontiguousarray(X.T)))
+
+
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed(cg, ro, wl):
+    """Every entry point only enqueues kernels on the caller's stream (split-K clears its output with
+    a fill kernel, not a memset), so a sequence of calls can be captured once and replayed.  Each replay,
+    with fresh inputs copied in between, must equal the eager result."""
+    M, N, K = 192, 130, 512          # 2 x 3 tiles -> split-K with the zero-fill kernel
+    say(f"HIP graph capture/replay of cg_share_matmul + cg_reshare + cg_share_add, M={M} N={N} K={K}")
+    key_a, key_b = bytes(range(16)), bytes(range(32, 48))
+    x = [torch.empty((M, K), dtype=torch.int64, device="cuda") for _ in range(2)]
+    y = [torch.empty((N, K), dtype=torch.int64, device="cuda") for _ in range(2)]
+    z = torch.empty((M, N), dtype=torch.int64, device="cuda")
+    zb = torch.empty_like(z)
+    sa, sb = torch.empty_like(z), torch.empty_like(z)
+
+    def run():
+        cg.cg_share_matmul(x[0], x[1], y[0], y[1], z_i=z)
+        cg.cg_reshare(z, key_a, key_b, nonce=9, first=0, out=zb)
+        cg.cg_share_add(z, zb, zb, z, za=sa, zb=sb)
+
+    def fill(seed):
+        host = [wl.draw_ring((M, K), seed), wl.draw_ring((M, K), seed + 1),
+                wl.draw_ring((N, K), seed + 2), wl.draw_ring((N, K), seed + 3)]
+        for dst, h in zip(x + y, host):
+            dst.copy_(torch.from_numpy(h.view(np.int64)))
+        torch.cuda.synchronize()
+        return host
+
+    fill(100)
+    run()                      # warm-up outside capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        host = fill(200 + 10 * rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        want_z = ro.party_matmul(*host)
+        want_zb = ro.reshare(want_z, key_a, key_b, 9, 0)
+        with np.errstate(over="ignore"):
+            want_s = want_z + want_zb
+        assert np.array_equal(cg.to_host(z), want_z), f"replay {rep}: product"
+        assert np.array_equal(cg.to_host(zb), want_zb), f"replay {rep}: reshare"
+        assert np.array_equal(cg.to_host(sa), want_s) and np.array_equal(cg.to_host(sb), want_s), f"replay {rep}"
+        # eager work between replays
+        run()
+        torch.cuda.synchronize()
+        assert np.array_equal(cg.to_host(z), want_z)
