@@ -186,6 +186,41 @@ CG_API cg_status cg_share_add_public(const uint64_t *xa, const uint64_t *xb, uin
                               uint64_t *za, uint64_t *zb, size_t n, void *stream);
 
 /*
+ * Element-wise local step of the share multiplication (Sec. III-B "Multiplication"):
+ *
+ *     z_i[j] = x_i[j]*y_i[j'] + x_{i+1}[j]*y_i[j'] + x_i[j]*y_{i+1}[j'],   j' = j mod period
+ *
+ * over n elements; like cg_share_matmul the result is one component of a
+ * 3-out-of-3 additive sharing of the element-wise product, not re-shared, not
+ * truncated.  period == n is the plain element-wise product; a smaller period
+ * (a divisor of n) broadcasts y, e.g. one secret scale per channel of an NHWC
+ * tensor with period = C, which is how a batch normalisation with secret-shared
+ * parameters is applied at inference (an affine map; add the shift with
+ * cg_share_add).  y_i, y_ip1 have `period` elements.  z_i may equal x_i or x_ip1
+ * (and y_i or y_ip1 when period == n).  CG_ERR_SHAPE if period is 0 or does not
+ * divide n.  n == 0 returns CG_OK.
+ */
+CG_API cg_status cg_share_mul(const uint64_t *x_i, const uint64_t *x_ip1,
+                       const uint64_t *y_i, const uint64_t *y_ip1,
+                       uint64_t *z_i, size_t n, size_t period, void *stream);
+
+/*
+ * Window sums of both components of a replicated pair, NHWC, zero padded: the
+ * linear, hence local, part of average pooling (Sec. V "Average pooling").
+ *   z[b][ho][wo][c] = sum over the kh x kw window at (ho*stride_h - pad_h, wo*stride_w - pad_w) of x[b][.][.][c]
+ * Output [B,Ho,Wo,C] with Ho = floor((H + 2*pad_h - kh)/stride_h) + 1, same for Wo.
+ * The average is this sum times the public fixed-point constant 1/(kh*kw)
+ * (cg_share_mul_public) followed by the protocol's truncation.  Outputs must not
+ * overlap inputs or each other.
+ */
+typedef struct {
+    int64_t B, H, W, C, kh, kw, stride_h, stride_w, pad_h, pad_w;
+} cg_pool2d_desc;
+
+CG_API cg_status cg_share_sum_pool2d(const uint64_t *xa, const uint64_t *xb, uint64_t *za, uint64_t *zb,
+                              const cg_pool2d_desc *desc, void *stream);
+
+/*
  * Zero shares and the reshare step (Sec. III-B "Protocol initialization" and
  * "Multiplication"; Sec. IV "Pseudorandom generators on the GPU").
  *

@@ -407,3 +407,49 @@ int oracle_reshare(const u64 *z, const uint8_t key_self[16], const uint8_t key_p
     free(a);
     return 0;
 }
+
+/* =========================================================================
+ * Other local linear-layer pieces on replicated shares.
+ * ========================================================================= */
+
+/* Element-wise local step of the multiplication protocol (Sec. III-B
+ * "Multiplication"): z_i[j] = x_i[j] y_i[j'] + x_{i+1}[j] y_i[j'] + x_i[j] y_{i+1}[j'],
+ * with j' = j mod period.  period == n is the plain element-wise product;
+ * a smaller period broadcasts y along the leading dimensions, e.g. one secret
+ * scale per channel of an NHWC tensor (batch normalisation at inference is such
+ * an affine map with secret-shared parameters, Sec. V footnote on batch norm). */
+void oracle_party_mul(const u64 *x_i, const u64 *x_ip1, const u64 *y_i, const u64 *y_ip1,
+                      u64 *z_i, size_t n, size_t period)
+{
+    for (size_t j = 0; j < n; ++j) {
+        const size_t jp = j % period;
+        const u64 t0 = x_i[j] * y_i[jp];
+        const u64 t1 = x_ip1[j] * y_i[jp];
+        const u64 t2 = x_i[j] * y_ip1[jp];
+        z_i[j] = t0 + t1 + t2;
+    }
+}
+
+/* Window sums of an NHWC tensor, zero padded: the linear part of average
+ * pooling (Sec. V "Average pooling": pooling by averaging is linear, hence local
+ * on shares).  Applied to each component of a replicated pair separately.  The
+ * average is this sum times the public constant 1/(kh*kw) in fixed point. */
+void oracle_sum_pool2d(const u64 *X, u64 *Z, int64_t B, int64_t H, int64_t Wd, int64_t C,
+                       int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    const int64_t Ho = oracle_conv_out_dim(H, kh, sh, ph);
+    const int64_t Wo = oracle_conv_out_dim(Wd, kw, sw, pw);
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo)
+                for (int64_t c = 0; c < C; ++c) {
+                    u64 acc = 0;
+                    for (int64_t r = 0; r < kh; ++r)
+                        for (int64_t s = 0; s < kw; ++s) {
+                            const int64_t hi = ho * sh - ph + r, wi = wo * sw - pw + s;
+                            if (hi >= 0 && hi < H && wi >= 0 && wi < Wd)
+                                acc += X[((b * H + hi) * Wd + wi) * C + c];
+                        }
+                    Z[((b * Ho + ho) * Wo + wo) * C + c] = acc;
+                }
+}

@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_party_matmul_at.restype = ctypes.c_uint64
         L.oracle_party_conv2d_at.argtypes = [_u64p] * 4 + [_i64] * 13
         L.oracle_party_conv2d_at.restype = ctypes.c_uint64
+        L.oracle_party_mul.argtypes = [_u64p] * 5 + [_sz, _sz]
+        L.oracle_sum_pool2d.argtypes = [_u64p, _u64p] + [_i64] * 10
         u8p = ctypes.POINTER(ctypes.c_uint8)
         L.oracle_aes128_encrypt_block.argtypes = [u8p, u8p, u8p]
         L.oracle_prf_words.argtypes = [u8p, ctypes.c_uint64, ctypes.c_uint64, _u64p, _sz]
@@ -257,3 +259,24 @@ def reshare(z, key_self: bytes, key_prev: bytes, nonce: int, first: int) -> np.n
     if lib().oracle_reshare(_p(z), _key(key_self), _key(key_prev), nonce, first, _p(out), z.size):
         raise MemoryError("oracle_reshare")
     return out
+
+
+def party_mul(x_i, x_ip1, y_i, y_ip1) -> np.ndarray:
+    """Element-wise local multiplication step; y is broadcast along the leading dimensions of x
+    (y.size must divide x.size and match x's trailing elements)."""
+    x_i, x_ip1, y_i, y_ip1 = _u(x_i), _u(x_ip1), _u(y_i), _u(y_ip1)
+    assert x_i.shape == x_ip1.shape and y_i.shape == y_ip1.shape and x_i.size % max(y_i.size, 1) == 0
+    z = np.empty(x_i.shape, dtype=np.uint64)
+    if x_i.size:
+        lib().oracle_party_mul(_p(x_i), _p(x_ip1), _p(y_i), _p(y_ip1), _p(z), x_i.size, y_i.size)
+    return z
+
+
+def sum_pool2d(X, window, stride, pad=(0, 0)) -> np.ndarray:
+    X = _u(X)
+    B, H, Wd, C = X.shape
+    kh, kw = window
+    Ho, Wo = conv_out_dim(H, kh, stride[0], pad[0]), conv_out_dim(Wd, kw, stride[1], pad[1])
+    Z = np.empty((B, Ho, Wo, C), dtype=np.uint64)
+    lib().oracle_sum_pool2d(_p(X), _p(Z), B, H, Wd, C, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    return Z

@@ -23,6 +23,7 @@ LIB_PATH = os.environ.get("CG_LIBRARY") or os.path.join(_HERE, "libcg.so")
 EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d", "cg_share_add",
            "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct",
            "cg_share_matmul_ws", "cg_share_conv2d_ws", "cg_zero_share", "cg_reshare", "cg_share_matmul_t",
+           "cg_share_mul", "cg_share_sum_pool2d",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -30,6 +31,12 @@ class ConvDesc(ctypes.Structure):
     """Mirror of cg_conv2d_desc."""
     _fields_ = [(n, ctypes.c_int64) for n in
                 ("B", "H", "W", "Cin", "Cout", "kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w")]
+
+
+class PoolDesc(ctypes.Structure):
+    """Mirror of cg_pool2d_desc."""
+    _fields_ = [(n, ctypes.c_int64) for n in
+                ("B", "H", "W", "C", "kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w")]
 
 
 class CgError(RuntimeError):
@@ -69,9 +76,11 @@ def lib() -> ctypes.CDLL:
         L.cg_zero_share.argtypes = [key, key, u64, u64, vp, sz, vp]
         L.cg_reshare.argtypes = [vp, key, key, u64, u64, vp, sz, vp]
         L.cg_share_matmul_t.argtypes = [vp] * 5 + [i64] * 3 + [ctypes.c_int] * 2 + [vp]
-        for name in EXPORTS[2:13]:
+        L.cg_share_mul.argtypes = [vp] * 5 + [sz, sz, vp]
+        L.cg_share_sum_pool2d.argtypes = [vp] * 4 + [ctypes.POINTER(PoolDesc), vp]
+        for name in EXPORTS[2:15]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[13:]:
+        for name in EXPORTS[15:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -253,6 +262,37 @@ def cg_share_add_public(xa, xb, gamma: int, party: int, za=None, zb=None, stream
         raise ValueError("operand shapes do not match")
     _check(lib().cg_share_add_public(_ptr(xa), _ptr(xb), int(gamma) % (1 << 64), int(party), _ptr(za), _ptr(zb),
                                      xa.numel(), _stream(stream)), "cg_share_add_public")
+    return za, zb
+
+
+def cg_share_mul(x_i, x_ip1, y_i, y_ip1, z_i=None, stream=None) -> torch.Tensor:
+    """Element-wise three-term product; y (y.numel() divides x.numel()) is broadcast along x's leading dims."""
+    if x_ip1.shape != x_i.shape or y_ip1.shape != y_i.shape:
+        raise ValueError("operand shapes do not match")
+    z_i = torch.empty_like(x_i) if z_i is None else z_i
+    if z_i.shape != x_i.shape:
+        raise ValueError("output shape does not match")
+    n = x_i.numel()
+    _check(lib().cg_share_mul(_ptr(x_i) if n else 0, _ptr(x_ip1) if n else 0, _ptr(y_i) if n else 0,
+                              _ptr(y_ip1) if n else 0, _ptr(z_i) if n else 0, n, y_i.numel(), _stream(stream)),
+           "cg_share_mul")
+    return z_i
+
+
+def cg_share_sum_pool2d(xa, xb, window, stride, pad=(0, 0), za=None, zb=None, stream=None):
+    """Window sums (zero padded) of both components of a replicated pair, NHWC."""
+    B, H, W, C = xa.shape
+    if xb.shape != xa.shape:
+        raise ValueError("operand shapes do not match")
+    d = PoolDesc(B, H, W, C, window[0], window[1], stride[0], stride[1], pad[0], pad[1])
+    Ho = (H + 2 * pad[0] - window[0]) // stride[0] + 1
+    Wo = (W + 2 * pad[1] - window[1]) // stride[1] + 1
+    if Ho < 1 or Wo < 1:
+        _check(CG_ERR_SHAPE, "cg_share_sum_pool2d")
+    za = torch.empty((B, Ho, Wo, C), dtype=torch.int64, device=xa.device) if za is None else za
+    zb = torch.empty((B, Ho, Wo, C), dtype=torch.int64, device=xa.device) if zb is None else zb
+    _check(lib().cg_share_sum_pool2d(_ptr(xa), _ptr(xb), _ptr(za), _ptr(zb), ctypes.byref(d), _stream(stream)),
+           "cg_share_sum_pool2d")
     return za, zb
 
 

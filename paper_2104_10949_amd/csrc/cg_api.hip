@@ -155,6 +155,73 @@ struct ReconstructOp {  // out = s0 + s1 + s2
     __device__ void one(size_t i) const { out[i] = s0[i] + s1[i] + s2[i]; }
 };
 
+// z[j] = x_a[j] y_a[j'] + x_b[j] y_a[j'] + x_a[j] y_b[j'],  j' = j mod period
+// (two ring products per element by distributivity: x_a (y_a + y_b) + x_b y_a)
+struct PartyMulOp {
+    const u64 *xa, *xb, *ya, *yb;
+    u64* z;
+    size_t period;   // in elements; the pair path requires it to be even (or equal to n)
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        const size_t hp = period >> 1;
+        ull2 a[U], b[U], c[U], d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t k = i + u * step, kp = k % hp;
+            a[u] = ld2(xa, k); b[u] = ld2(xb, k);
+            c[u] = reinterpret_cast<const ull2*>(ya)[kp];
+            d[u] = reinterpret_cast<const ull2*>(yb)[kp];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) st2(z, i + u * step, a[u] * (c[u] + d[u]) + b[u] * c[u]);
+    }
+    __device__ void one(size_t i) const {
+        const size_t ip = i % period;
+        z[i] = xa[i] * (ya[ip] + yb[ip]) + xb[i] * ya[ip];
+    }
+};
+
+// One thread per output pixel and channel pair: sums the window of both components.
+__global__ __launch_bounds__(256) void sum_pool_kernel(const u64* __restrict__ xa, const u64* __restrict__ xb,
+                                                       u64* __restrict__ za, u64* __restrict__ zb,
+                                                       int B, int H, int W, int C, int Ho, int Wo, int kh, int kw,
+                                                       int sh, int sw, int ph, int pw, int vec) {
+    const int cw = vec ? C / 2 : C;   // channel groups per pixel
+    const size_t total = (size_t)B * Ho * Wo * cw;
+    for (size_t t = (size_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (size_t)gridDim.x * 256) {
+        const int cg_ = (int)(t % cw);
+        size_t pix = t / cw;
+        const int wo = (int)(pix % Wo);
+        pix /= Wo;
+        const int ho = (int)(pix % Ho), b = (int)(pix / Ho);
+        ull2 sa = {0, 0}, sb = {0, 0};
+        for (int r = 0; r < kh; ++r) {
+            const int hi = ho * sh - ph + r;
+            if (hi < 0 || hi >= H) continue;
+            for (int s = 0; s < kw; ++s) {
+                const int wi = wo * sw - pw + s;
+                if (wi < 0 || wi >= W) continue;
+                const size_t off = (((size_t)b * H + hi) * W + wi) * C;
+                if (vec) {
+                    sa += reinterpret_cast<const ull2*>(xa + off)[cg_];
+                    sb += reinterpret_cast<const ull2*>(xb + off)[cg_];
+                } else {
+                    sa.x += xa[off + cg_];
+                    sb.x += xb[off + cg_];
+                }
+            }
+        }
+        const size_t o = (((size_t)b * Ho + ho) * Wo + wo) * C;
+        if (vec) {
+            reinterpret_cast<ull2*>(za + o)[cg_] = sa;
+            reinterpret_cast<ull2*>(zb + o)[cg_] = sb;
+        } else {
+            za[o + cg_] = sa.x;
+            zb[o + cg_] = sb.x;
+        }
+    }
+}
+
 template <class F>
 cg_status launch_ew(size_t n, bool vec, const F& f, void* stream) {
     if (n == 0) return CG_OK;
@@ -485,6 +552,59 @@ cg_status cg_share_add_public(const uint64_t* xa, const uint64_t* xb, uint64_t g
     // share index 0 is the first component of party 0 and the second component of party 2
     AddPublicOp f = {xa, xb, party == 0 ? gamma : 0, party == 2 ? gamma : 0, za, zb};
     return launch_ew(n, all_aligned16(ptrs, 4), f, stream);
+}
+
+cg_status cg_share_mul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i, const uint64_t* y_ip1,
+                       uint64_t* z_i, size_t n, size_t period, void* stream) {
+    if (n == 0) return CG_OK;
+    const void* ptrs[5] = {x_i, x_ip1, y_i, y_ip1, z_i};
+    if (cg_status st = check_ptrs(ptrs, 5)) return st;
+    if (period == 0 || period > n || n % period != 0 || n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8, ybytes = (u64)period * 8;
+    if (bad_overlap(z_i, x_i, bytes) || bad_overlap(z_i, x_ip1, bytes)) return CG_ERR_ALIAS;
+    if (overlap(z_i, bytes, y_i, ybytes) || overlap(z_i, bytes, y_ip1, ybytes)) {
+        // in place over y is only sound when y is not broadcast and the pointers coincide
+        if (!(period == n && (z_i == y_i || z_i == y_ip1) && !bad_overlap(z_i, y_i, bytes) &&
+              !bad_overlap(z_i, y_ip1, bytes)))
+            return CG_ERR_ALIAS;
+    }
+    PartyMulOp f = {x_i, x_ip1, y_i, y_ip1, z_i, period};
+    const bool vec = all_aligned16(ptrs, 5) && period % 2 == 0;
+    return launch_ew(n, vec, f, stream);
+}
+
+cg_status cg_share_sum_pool2d(const uint64_t* xa, const uint64_t* xb, uint64_t* za, uint64_t* zb,
+                              const cg_pool2d_desc* d, void* stream) {
+    if (!xa || !xb || !za || !zb || !d) return CG_ERR_NULL;
+    if (d->B < 1 || d->H < 1 || d->W < 1 || d->C < 1 || d->kh < 1 || d->kw < 1 || d->stride_h < 1 ||
+        d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0)
+        return CG_ERR_SHAPE;
+    const int64_t LIM = 0x7FFFFFFF;
+    if (d->B > LIM || d->H > LIM || d->W > LIM || d->C > LIM || d->kh > LIM || d->kw > LIM ||
+        d->stride_h > LIM || d->stride_w > LIM || d->pad_h > LIM || d->pad_w > LIM)
+        return CG_ERR_UNSUPPORTED;
+    const int64_t span_h = d->H + 2 * d->pad_h - d->kh, span_w = d->W + 2 * d->pad_w - d->kw;
+    if (span_h < 0 || span_w < 0) return CG_ERR_SHAPE;
+    const int64_t Ho = span_h / d->stride_h + 1, Wo = span_w / d->stride_w + 1;
+    int64_t x_el, z_el, tmp;
+    if (mul_overflows(d->B, d->H, &tmp) || mul_overflows(tmp, d->W, &tmp) || mul_overflows(tmp, d->C, &x_el) ||
+        mul_overflows(d->B, Ho, &tmp) || mul_overflows(tmp, Wo, &tmp) || mul_overflows(tmp, d->C, &z_el) ||
+        mul_overflows(x_el, 8, &tmp) || mul_overflows(z_el, 8, &tmp))
+        return CG_ERR_SHAPE;
+    const void* ptrs[4] = {xa, xb, za, zb};
+    if (cg_status st = check_ptrs(ptrs, 4)) return st;
+    const u64 xb_ = (u64)x_el * 8, zb_ = (u64)z_el * 8;
+    if (overlap(za, zb_, xa, xb_) || overlap(za, zb_, xb, xb_) || overlap(zb, zb_, xa, xb_) ||
+        overlap(zb, zb_, xb, xb_) || overlap(za, zb_, zb, zb_))
+        return CG_ERR_ALIAS;
+    const int vec = (d->C % 2 == 0) && all_aligned16(ptrs, 4);
+    const size_t total = (size_t)z_el / (vec ? 2 : 1);
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(sum_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), xa, xb,
+                       za, zb, (int)d->B, (int)d->H, (int)d->W, (int)d->C, (int)Ho, (int)Wo, (int)d->kh, (int)d->kw,
+                       (int)d->stride_h, (int)d->stride_w, (int)d->pad_h, (int)d->pad_w, vec);
+    return hipGetLastError() == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
 
 cg_status cg_zero_share(const uint8_t* key_self, const uint8_t* key_prev, uint64_t nonce, uint64_t first,

@@ -139,6 +139,26 @@ def test_transposed_matmul_validation(L):
     assert f(*big, 4, (1 << 22) + 1, 4, 0, 1, None) == b.CG_ERR_UNSUPPORTED
 
 
+def test_mul_and_pool_validation(L):
+    from paper_2104_10949_amd import binding as b
+    q = [P, 2 * P, 3 * P, 4 * P, 5 * P]
+    assert L.cg_share_mul(*q, 0, 0, None) == b.CG_OK
+    assert L.cg_share_mul(0, *q[1:], 8, 8, None) == b.CG_ERR_NULL
+    assert L.cg_share_mul(*q, 8, 0, None) == b.CG_ERR_SHAPE
+    assert L.cg_share_mul(*q, 8, 3, None) == b.CG_ERR_SHAPE          # period must divide n
+    assert L.cg_share_mul(*q, 8, 16, None) == b.CG_ERR_SHAPE
+    assert L.cg_share_mul(*q[:4], P + 8, 8, 8, None) == b.CG_ERR_ALIAS
+    assert L.cg_share_mul(*q[:4], 3 * P, 8, 4, None) == b.CG_ERR_ALIAS  # in place over a broadcast y
+    d = b.PoolDesc(1, 8, 8, 4, 2, 2, 2, 2, 0, 0)
+    assert L.cg_share_sum_pool2d(P, 2 * P, 3 * P, 4 * P, None, None) == b.CG_ERR_NULL
+    assert L.cg_share_sum_pool2d(0, 2 * P, 3 * P, 4 * P, ctypes.byref(d), None) == b.CG_ERR_NULL
+    assert L.cg_share_sum_pool2d(P, 2 * P, P + 64, 4 * P, ctypes.byref(d), None) == b.CG_ERR_ALIAS
+    bad = b.PoolDesc(1, 2, 2, 4, 3, 3, 1, 1, 0, 0)
+    assert L.cg_share_sum_pool2d(P, 2 * P, 3 * P, 4 * P, ctypes.byref(bad), None) == b.CG_ERR_SHAPE
+    bad = b.PoolDesc(1, 8, 8, 4, 2, 2, 0, 2, 0, 0)
+    assert L.cg_share_sum_pool2d(P, 2 * P, 3 * P, 4 * P, ctypes.byref(bad), None) == b.CG_ERR_SHAPE
+
+
 def test_prf_entry_points_validation(L):
     from paper_2104_10949_amd import binding as b
     k = bytes(16)

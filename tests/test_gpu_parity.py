@@ -455,3 +455,45 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(cg, ro, wl):
         run()
         torch.cuda.synchronize()
         assert np.array_equal(cg.to_host(z), want_z)
+
+
+@pytest.mark.parametrize("shape,period", [((1,), 1), ((7,), 7), ((1000,), 1000), ((1001,), 1001), ((4, 5, 6, 8), 8),
+                                          ((2, 9, 9, 3), 3), ((3, 64, 64, 64), 64), ((1 << 20,), 1 << 20),
+                                          ((33, 1 << 10), 1 << 10)])
+def test_share_mul_elementwise_and_broadcast(cg, ro, wl, shape, period):
+    say(f"cg_share_mul shape={shape} period={period}")
+    x = [wl.draw_ring(shape, 700 + i) for i in range(2)]
+    y = [wl.draw_ring((period,), 710 + i) for i in range(2)]
+    got = cg.to_host(cg.cg_share_mul(*[cg.to_device(v) for v in x + y]))
+    want = ro.party_mul(*x, *y)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+    # in place over x_i
+    dx = [cg.to_device(v) for v in x]
+    cg.cg_share_mul(dx[0], dx[1], cg.to_device(y[0]), cg.to_device(y[1]), z_i=dx[0])
+    assert np.array_equal(cg.to_host(dx[0]), want)
+
+
+def test_share_mul_three_parties_open_to_the_product(cg, ro, wl):
+    shape, C = (4, 7, 7, 32), 32
+    say("cg_share_mul: per-channel secret scale, three parties, opened")
+    x, a = wl.draw_ring(shape, 720), wl.draw_ring((C,), 721)
+    sx = ro.share(x, wl.draw_ring(shape, 722), wl.draw_ring(shape, 723))
+    sa = ro.share(a, wl.draw_ring((C,), 724), wl.draw_ring((C,), 725))
+    dx, da = [cg.to_device(v) for v in sx], [cg.to_device(v) for v in sa]
+    z = [cg.cg_share_mul(dx[i], dx[(i + 1) % 3], da[i], da[(i + 1) % 3]) for i in range(3)]
+    with np.errstate(over="ignore"):
+        assert np.array_equal(cg.to_host(cg.cg_reconstruct(*z)), x * a)
+
+
+@pytest.mark.parametrize("shape,window,stride,pad", [
+    ((1, 4, 4, 1), (2, 2), (2, 2), (0, 0)), ((2, 10, 10, 96), (3, 3), (2, 2), (0, 0)),
+    ((3, 32, 32, 64), (2, 2), (2, 2), (0, 0)), ((2, 7, 6, 3), (3, 3), (2, 2), (1, 1)),
+    ((2, 9, 8, 5), (2, 3), (1, 2), (0, 1)), ((8, 56, 56, 64), (3, 3), (2, 2), (1, 1)),
+    ((2, 7, 7, 2048), (7, 7), (7, 7), (0, 0)),
+])
+def test_sum_pool_matches_the_oracle(cg, ro, wl, shape, window, stride, pad):
+    say(f"cg_share_sum_pool2d shape={shape} window={window} stride={stride} pad={pad}")
+    xa, xb = wl.draw_ring(shape, 730), wl.draw_ring(shape, 731)
+    za, zb = cg.cg_share_sum_pool2d(cg.to_device(xa), cg.to_device(xb), window, stride, pad)
+    assert not first_mismatch(cg.to_host(za), ro.sum_pool2d(xa, window, stride, pad))
+    assert not first_mismatch(cg.to_host(zb), ro.sum_pool2d(xb, window, stride, pad))

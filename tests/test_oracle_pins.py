@@ -309,3 +309,79 @@ def test_fixed_point_product_decodes_to_the_real_product(cfg, layer_idx):
     # against the un-rounded reals the error is bounded by the encoding error
     kmax = L.K * (np.max(np.abs(X)) + np.max(np.abs(Y))) * 2.0 ** -(t + 1) + L.K * 2.0 ** -(2 * t + 2)
     assert np.max(np.abs(got - X @ Y.T)) <= kmax
+
+
+# ---------------------------------------------------------------- element-wise product, pooling
+def test_party_mul_is_the_three_term_scalar_protocol():
+    n = 23
+    xi, xi1, yi, yi1 = ring((n,), 201), ring((n,), 202), ring((n,), 203), ring((n,), 204)
+    z = ro.party_mul(xi, xi1, yi, yi1)
+    for j in range(n):
+        a, a1, b, b1 = int(xi[j]), int(xi1[j]), int(yi[j]), int(yi1[j])
+        assert int(z[j]) == (a * b + a1 * b + a * b1) % MOD
+    # the diagonal of the outer-product matmul with K = 1 is the element-wise product
+    full = ro.party_matmul(xi.reshape(n, 1), xi1.reshape(n, 1), yi.reshape(n, 1), yi1.reshape(n, 1))
+    assert np.array_equal(np.diagonal(full), z)
+
+
+def test_party_mul_broadcast_and_three_party_sum():
+    shape, C = (2, 3, 4, 6), 6
+    x, a = ring(shape, 211), ring((C,), 212)
+    sx = ro.share(x, ring(shape, 213), ring(shape, 214))
+    sa = ro.share(a, ring((C,), 215), ring((C,), 216))
+    z = [ro.party_mul(*ro.party_pair(sx, i), *ro.party_pair(sa, i)) for i in range(3)]
+    opened = ro.reconstruct(*z)
+    xs, as_ = x.tolist(), a.tolist()
+    for idx in np.ndindex(*shape):
+        assert int(opened[idx]) == (int(x[idx]) * as_[idx[-1]]) % MOD
+
+
+def bf_sum_pool(X, window, stride, pad):
+    B, H, Wd, C = X.shape
+    kh, kw = window
+    Ho = (H + 2 * pad[0] - kh) // stride[0] + 1
+    Wo = (Wd + 2 * pad[1] - kw) // stride[1] + 1
+    x = X.tolist()
+    Z = np.zeros((B, Ho, Wo, C), dtype=np.uint64)
+    for b in range(B):
+        for ho in range(Ho):
+            for wo in range(Wo):
+                for c in range(C):
+                    acc = 0
+                    for r in range(kh):
+                        for s in range(kw):
+                            hi, wi = ho * stride[0] - pad[0] + r, wo * stride[1] - pad[1] + s
+                            if 0 <= hi < H and 0 <= wi < Wd:
+                                acc += x[b][hi][wi][c]
+                    Z[b, ho, wo, c] = acc % MOD
+    return Z
+
+
+@pytest.mark.parametrize("shape,window,stride,pad", [
+    ((1, 4, 4, 1), (2, 2), (2, 2), (0, 0)), ((2, 7, 6, 3), (3, 3), (2, 2), (1, 1)),
+    ((1, 10, 10, 2), (3, 3), (2, 2), (0, 0)), ((2, 5, 4, 5), (2, 3), (1, 2), (0, 1)),
+])
+def test_sum_pool_bruteforce(shape, window, stride, pad):
+    X = ring(shape, 221 + sum(shape))
+    assert np.array_equal(ro.sum_pool2d(X, window, stride, pad), bf_sum_pool(X, window, stride, pad))
+
+
+def test_sum_pool_closed_forms_and_paper_sizes():
+    X = ring((2, 6, 6, 3), 231)
+    assert np.array_equal(ro.sum_pool2d(X, (1, 1), (1, 1)), X)                  # 1x1 window: identity
+    whole = ro.sum_pool2d(X, (6, 6), (6, 6))
+    for b in range(2):
+        for c in range(3):
+            assert int(whole[b, 0, 0, c]) == sum(int(v) for v in X[b, :, :, c].reshape(-1)) % MOD
+    # pooling is the convolution with a per-channel all-ones kernel
+    W = np.zeros((3, 2, 2, 3), dtype=np.uint64)
+    for c in range(3):
+        W[c, :, :, c] = 1
+    assert np.array_equal(ro.sum_pool2d(X, (2, 2), (2, 2)), ro.conv2d(X, W, (2, 2), (0, 0)))
+    # sizes printed in the paper's AlexNet / VGG tables: 10x10 with 3x3/2 -> 4x4; 32x32 with 2x2/2 -> 16x16
+    assert ro.sum_pool2d(ring((1, 10, 10, 1), 232), (3, 3), (2, 2)).shape == (1, 4, 4, 1)
+    assert ro.sum_pool2d(ring((1, 32, 32, 1), 233), (2, 2), (2, 2)).shape == (1, 16, 16, 1)
+    # linear, hence local on shares: pooling the shares and opening = pooling the secret
+    s = ro.share(X, ring(X.shape, 234), ring(X.shape, 235))
+    pooled = [ro.sum_pool2d(v, (3, 3), (2, 2), (1, 1)) for v in s]
+    assert np.array_equal(ro.reconstruct(*pooled), ro.sum_pool2d(X, (3, 3), (2, 2), (1, 1)))
