@@ -46,6 +46,9 @@
 #ifndef CG_PRE_NUM
 #define CG_PRE_NUM 3   // eighths of a half-step's MFMAs issued before the split work starts
 #endif
+#ifndef CG_PIPE
+#define CG_PIPE 1      // 1: words are split in the half-step that loads them; 2: one half-step later
+#endif
 #ifndef CG_TILE
 #define CG_TILE 4, 2, 1, 1
 #endif
@@ -648,6 +651,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     // needs no "is there a next slice" branch.
     load_even(k_begin);
     split_all(std::true_type{}, st0);
+    if (CG_PIPE == 2) load_odd(k_begin);
     __syncthreads();
 
     // Outer loop: one pass per segment of at most SEG_KSTEPS slices (a single pass
@@ -658,12 +662,12 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         for (int ks = ks0; ks < ke; ++ks) {
             // even half-step: x_a against w_a + w_b from st0; odd words are split into st1
             half_step(st0, st1, std::false_type{}, [&]() {
-                load_odd(ks);
+                if (CG_PIPE == 2) load_even(ks + 1); else load_odd(ks);
             });
             __syncthreads();
             // odd half-step: x_b against w_a from st1; the next slice's even words go to st0
             half_step(st1, st0, std::true_type{}, [&]() {
-                load_even(ks + 1);
+                if (CG_PIPE == 2) load_odd(ks + 1); else load_even(ks + 1);
             });
             __syncthreads();
         }
