@@ -154,6 +154,34 @@ def main() -> int:
         macs = n_cu * 8 * iters * 8 * 32768.0
         return 2.0 * macs / (a.elapsed_time(b) * 1e-3) / 1e12
 
+    def mfma_f64_ceiling() -> float:
+        """float64 MAC/s of a register-only v_mfma_f64_16x16x4_f64 loop on all compute units, with
+        random 16-bit integer operands (the paper's limb width)."""
+        import ctypes
+        import numpy as np
+        from paper_2104_10949_amd import build as hip_build
+        probe = ctypes.CDLL(hip_build.PROBE_LIB)
+        probe.cg_probe_mfma_f64_rate.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 3 + [ctypes.c_void_p]
+        probe.cg_probe_mfma_f64_rate.restype = ctypes.c_int
+        limbs = (wl.draw_ring((8192,), 54321) & np.uint64(0xFFFF)).astype(np.float64)
+        ops = torch.from_numpy(limbs).cuda()
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        sink = torch.empty(n_cu * 512, dtype=torch.float64, device="cuda")
+        iters, stream = 4000, torch.cuda.current_stream().cuda_stream
+
+        def launch():
+            rc = probe.cg_probe_mfma_f64_rate(ops.data_ptr(), sink.data_ptr(), n_cu, 2, iters, stream)
+            if rc != 0:
+                raise RuntimeError(f"cg_probe_mfma_f64_rate returned {rc}")
+        launch()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        launch()
+        b.record()
+        torch.cuda.synchronize()
+        return n_cu * 8 * iters * 8 * 1024.0 / (a.elapsed_time(b) * 1e-3)
+
     if args.calib_copy_mib > 0:
         n = args.calib_copy_mib * (1 << 20) // 8
         src = torch.arange(n, dtype=torch.int64, device="cuda")
@@ -186,6 +214,14 @@ def main() -> int:
             "constant_operands": round(peak_const, 1), "random_operands": round(peak_random, 1), "unit": "TOP/s",
             "frac_of_random_operand_loop": round(achieved_tops / peak_random, 4),
             "largest_layer_frac_of_random_operand_loop": round(big_tops / peak_random, 4)}
+        # Limb-choice check: the paper's embedding (four 16-bit limbs in float64, 10 limb products per ring
+        # product) would need 20 float64 MACs per (m,n,k) for the fused two-product form; even at the measured
+        # float64 MFMA issue rate that caps the effective ring MAC/s below what the int8 kernel delivers.
+        f64_macs = mfma_f64_ceiling()
+        roofline["fp64_limb_route_upper_bound"] = {
+            "measured_f64_mfma_macs_per_s": f64_macs, "f64_macs_per_mnk": 20,
+            "effective_ring_macs_per_s_at_100pct": 3.0 * f64_macs / 20.0,
+            "int8_kernel_vs_bound": round(value / (3.0 * f64_macs / 20.0), 2)}
 
     if args.layers:
         for L, ms in zip(layers, per_layer_ms):

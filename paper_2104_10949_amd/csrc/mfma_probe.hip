@@ -39,6 +39,34 @@ __global__ __launch_bounds__(NT) void mfma_rate_kernel(const v4i* __restrict__ s
     sink[(size_t)blockIdx.x * NT + t] = acc;
 }
 
+// The same loop for the float64 matrix instruction the paper's 16-bit-limb embedding
+// would run on (v_mfma_f64_16x16x4_f64: 16*16*4 MACs per instruction and wave).
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+template <int NT>
+__global__ __launch_bounds__(NT) void mfma_f64_rate_kernel(const double* __restrict__ src, double* __restrict__ sink,
+                                                           int iters) {
+    const int t = threadIdx.x;
+    double a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = src[(t * 8 + i) & 8191];
+        b[i] = src[(t * 8 + 4 + i) & 8191];
+    }
+    v4d c[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) c[s] = v4d{0.0, 0.0, 0.0, 0.0};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+            c[s] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s & 3], b[(s >> 1) & 3], c[s], 0, 0, 0);
+    }
+    double acc = 0.0;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) acc += c[s][0] + c[s][1] + c[s][2] + c[s][3];
+    sink[(size_t)blockIdx.x * NT + t] = acc;
+}
+
 extern "C" {
 
 // Launch the loop on `blocks` blocks of 4*waves_per_simd waves.
@@ -57,6 +85,23 @@ int cg_probe_mfma_rate(const void* operands, void* sink, int blocks, int waves_p
     else
         hipLaunchKernelGGL(mfma_rate_kernel<512>, dim3(blocks), dim3(512), 0, s,
                            static_cast<const v4i*>(operands), static_cast<int*>(sink), iters);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+// float64 variant: `operands` holds 8192 doubles (16-bit integers as doubles keep the
+// sums exact, as in the paper's embedding), `sink` blocks * 256 * waves_per_simd doubles.
+// Each wave issues 8*iters MFMAs of 16*16*4 MACs.
+__attribute__((visibility("default")))
+int cg_probe_mfma_f64_rate(const void* operands, void* sink, int blocks, int waves_per_simd, int iters,
+                           void* stream) {
+    if (!operands || !sink || blocks < 1 || iters < 1 || (waves_per_simd != 1 && waves_per_simd != 2)) return 1;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (waves_per_simd == 1)
+        hipLaunchKernelGGL(mfma_f64_rate_kernel<256>, dim3(blocks), dim3(256), 0, s,
+                           static_cast<const double*>(operands), static_cast<double*>(sink), iters);
+    else
+        hipLaunchKernelGGL(mfma_f64_rate_kernel<512>, dim3(blocks), dim3(512), 0, s,
+                           static_cast<const double*>(operands), static_cast<double*>(sink), iters);
     return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
