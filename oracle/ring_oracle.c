@@ -217,6 +217,106 @@ int oracle_party_conv2d(const u64 *x_i, const u64 *x_ip1, const u64 *w_i, const 
     return 0;
 }
 
+/* ---- backward products of a convolution layer (Sec. III-C: the gradients of a
+ * linear / convolution layer are linear functions of the incoming gradient and are
+ * evaluated with the same share protocols) --------------------------------------
+ * For Z = conv(X, W) the two gradients are the adjoints of the map in each argument,
+ * written here as the forward loop nest with the roles of "read" and "accumulate"
+ * exchanged: every forward term X[b,hi,wi,c] * W[co,r,s,c] -> Z[b,ho,wo,co] becomes
+ *   input gradient : G[b,ho,wo,co] * W[co,r,s,c] -> DX[b,hi,wi,c]
+ *   weight gradient: G[b,ho,wo,co] * X[b,hi,wi,c] -> DW[co,r,s,c]
+ * over Z_{2^64}.  G has the shape of Z; DX the shape of X; DW the shape of W. */
+void oracle_conv2d_dgrad_u64(const u64 *G, const u64 *W, u64 *DX,
+                             int64_t B, int64_t H, int64_t Wd, int64_t Cin, int64_t Cout,
+                             int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    const int64_t Ho = oracle_conv_out_dim(H, kh, sh, ph);
+    const int64_t Wo = oracle_conv_out_dim(Wd, kw, sw, pw);
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < B; ++b) {            /* images do not share entries of DX */
+        for (int64_t j = 0; j < H * Wd * Cin; ++j) DX[b * H * Wd * Cin + j] = 0;
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    const u64 g = G[((b * Ho + ho) * Wo + wo) * Cout + co];
+                    for (int64_t r = 0; r < kh; ++r) {
+                        const int64_t hi = ho * sh - ph + r;
+                        if (hi < 0 || hi >= H) continue;
+                        for (int64_t s = 0; s < kw; ++s) {
+                            const int64_t wi = wo * sw - pw + s;
+                            if (wi < 0 || wi >= Wd) continue;
+                            for (int64_t c = 0; c < Cin; ++c)
+                                DX[((b * H + hi) * Wd + wi) * Cin + c] +=
+                                    g * W[((co * kh + r) * kw + s) * Cin + c];
+                        }
+                    }
+                }
+    }
+}
+
+void oracle_conv2d_wgrad_u64(const u64 *G, const u64 *X, u64 *DW,
+                             int64_t B, int64_t H, int64_t Wd, int64_t Cin, int64_t Cout,
+                             int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    const int64_t Ho = oracle_conv_out_dim(H, kh, sh, ph);
+    const int64_t Wo = oracle_conv_out_dim(Wd, kw, sw, pw);
+#pragma omp parallel for schedule(static)
+    for (int64_t co = 0; co < Cout; ++co) {      /* output channels do not share entries of DW */
+        for (int64_t j = 0; j < kh * kw * Cin; ++j) DW[co * kh * kw * Cin + j] = 0;
+        for (int64_t b = 0; b < B; ++b)
+            for (int64_t ho = 0; ho < Ho; ++ho)
+                for (int64_t wo = 0; wo < Wo; ++wo) {
+                    const u64 g = G[((b * Ho + ho) * Wo + wo) * Cout + co];
+                    for (int64_t r = 0; r < kh; ++r) {
+                        const int64_t hi = ho * sh - ph + r;
+                        if (hi < 0 || hi >= H) continue;
+                        for (int64_t s = 0; s < kw; ++s) {
+                            const int64_t wi = wo * sw - pw + s;
+                            if (wi < 0 || wi >= Wd) continue;
+                            for (int64_t c = 0; c < Cin; ++c)
+                                DW[((co * kh + r) * kw + s) * Cin + c] +=
+                                    g * X[((b * H + hi) * Wd + wi) * Cin + c];
+                        }
+                    }
+                }
+    }
+}
+
+/* One party's share of the two gradients: the three-term product with the incoming
+ * gradient as the first factor, d_i = g_i*y_i + g_{i+1}*y_i + g_i*y_{i+1}, y the
+ * filter (input gradient) or the layer input (weight gradient). */
+int oracle_party_conv2d_dgrad(const u64 *g_i, const u64 *g_ip1, const u64 *w_i, const u64 *w_ip1,
+                              u64 *dx_i,
+                              int64_t B, int64_t H, int64_t Wd, int64_t Cin, int64_t Cout,
+                              int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    const size_t n = (size_t)B * (size_t)H * (size_t)Wd * (size_t)Cin;
+    u64 *t1 = (u64 *)malloc(n * sizeof(u64)), *t2 = (u64 *)malloc(n * sizeof(u64));
+    if (!t1 || !t2) { free(t1); free(t2); return -1; }
+    oracle_conv2d_dgrad_u64(g_i,   w_i,   dx_i, B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    oracle_conv2d_dgrad_u64(g_ip1, w_i,   t1,   B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    oracle_conv2d_dgrad_u64(g_i,   w_ip1, t2,   B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    for (size_t j = 0; j < n; ++j) dx_i[j] = dx_i[j] + t1[j] + t2[j];
+    free(t1); free(t2);
+    return 0;
+}
+
+int oracle_party_conv2d_wgrad(const u64 *g_i, const u64 *g_ip1, const u64 *x_i, const u64 *x_ip1,
+                              u64 *dw_i,
+                              int64_t B, int64_t H, int64_t Wd, int64_t Cin, int64_t Cout,
+                              int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw)
+{
+    const size_t n = (size_t)Cout * (size_t)kh * (size_t)kw * (size_t)Cin;
+    u64 *t1 = (u64 *)malloc(n * sizeof(u64)), *t2 = (u64 *)malloc(n * sizeof(u64));
+    if (!t1 || !t2) { free(t1); free(t2); return -1; }
+    oracle_conv2d_wgrad_u64(g_i,   x_i,   dw_i, B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    oracle_conv2d_wgrad_u64(g_ip1, x_i,   t1,   B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    oracle_conv2d_wgrad_u64(g_i,   x_ip1, t2,   B, H, Wd, Cin, Cout, kh, kw, sh, sw, ph, pw);
+    for (size_t j = 0; j < n; ++j) dw_i[j] = dw_i[j] + t1[j] + t2[j];
+    free(t1); free(t2);
+    return 0;
+}
+
 /* Single output element of one party's local matmul / conv, for spot checks on
  * shapes too large to compute in full.  Same three literal products. */
 u64 oracle_party_matmul_at(const u64 *x_i, const u64 *x_ip1, const u64 *y_i, const u64 *y_ip1,

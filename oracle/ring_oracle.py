@@ -59,6 +59,12 @@ def lib() -> ctypes.CDLL:
         L.oracle_party_matmul.restype = ctypes.c_int
         L.oracle_party_conv2d.argtypes = [_u64p] * 5 + [_i64] * 11
         L.oracle_party_conv2d.restype = ctypes.c_int
+        L.oracle_conv2d_dgrad_u64.argtypes = [_u64p, _u64p, _u64p] + [_i64] * 11
+        L.oracle_conv2d_wgrad_u64.argtypes = [_u64p, _u64p, _u64p] + [_i64] * 11
+        L.oracle_party_conv2d_dgrad.argtypes = [_u64p] * 5 + [_i64] * 11
+        L.oracle_party_conv2d_dgrad.restype = ctypes.c_int
+        L.oracle_party_conv2d_wgrad.argtypes = [_u64p] * 5 + [_i64] * 11
+        L.oracle_party_conv2d_wgrad.restype = ctypes.c_int
         L.oracle_party_matmul_at.argtypes = [_u64p] * 4 + [_i64] * 3
         L.oracle_party_matmul_at.restype = ctypes.c_uint64
         L.oracle_party_conv2d_at.argtypes = [_u64p] * 4 + [_i64] * 13
@@ -211,6 +217,53 @@ def party_conv2d(x_i, x_ip1, w_i, w_ip1, stride=(1, 1), pad=(0, 0)) -> np.ndarra
     if rc != 0:
         raise MemoryError("oracle_party_conv2d")
     return z
+
+
+def _conv_dims(x_shape, w_shape, g_shape, stride, pad):
+    B, H, Wd, Cin = x_shape
+    Cout, kh, kw, Cin2 = w_shape
+    assert Cin == Cin2
+    Ho, Wo = conv_out_dim(H, kh, stride[0], pad[0]), conv_out_dim(Wd, kw, stride[1], pad[1])
+    assert tuple(g_shape) == (B, Ho, Wo, Cout), (g_shape, (B, Ho, Wo, Cout))
+    return B, H, Wd, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1]
+
+
+def conv2d_dgrad(G, W, x_shape, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    """Gradient of conv2d(X, W) with respect to X: G [B,Ho,Wo,Cout], W [Cout,kh,kw,Cin] -> [B,H,W,Cin]."""
+    G, W = _u(G), _u(W)
+    dims = _conv_dims(x_shape, W.shape, G.shape, stride, pad)
+    DX = np.empty(tuple(x_shape), dtype=np.uint64)
+    lib().oracle_conv2d_dgrad_u64(_p(G), _p(W), _p(DX), *dims)
+    return DX
+
+
+def conv2d_wgrad(G, X, w_shape, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    """Gradient of conv2d(X, W) with respect to W: G [B,Ho,Wo,Cout], X [B,H,W,Cin] -> [Cout,kh,kw,Cin]."""
+    G, X = _u(G), _u(X)
+    dims = _conv_dims(X.shape, w_shape, G.shape, stride, pad)
+    DW = np.empty(tuple(w_shape), dtype=np.uint64)
+    lib().oracle_conv2d_wgrad_u64(_p(G), _p(X), _p(DW), *dims)
+    return DW
+
+
+def party_conv2d_dgrad(g_i, g_ip1, w_i, w_ip1, x_shape, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    g_i, g_ip1, w_i, w_ip1 = _u(g_i), _u(g_ip1), _u(w_i), _u(w_ip1)
+    assert g_ip1.shape == g_i.shape and w_ip1.shape == w_i.shape
+    dims = _conv_dims(x_shape, w_i.shape, g_i.shape, stride, pad)
+    dx = np.empty(tuple(x_shape), dtype=np.uint64)
+    if lib().oracle_party_conv2d_dgrad(_p(g_i), _p(g_ip1), _p(w_i), _p(w_ip1), _p(dx), *dims) != 0:
+        raise MemoryError("oracle_party_conv2d_dgrad")
+    return dx
+
+
+def party_conv2d_wgrad(g_i, g_ip1, x_i, x_ip1, w_shape, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    g_i, g_ip1, x_i, x_ip1 = _u(g_i), _u(g_ip1), _u(x_i), _u(x_ip1)
+    assert g_ip1.shape == g_i.shape and x_ip1.shape == x_i.shape
+    dims = _conv_dims(x_i.shape, w_shape, g_i.shape, stride, pad)
+    dw = np.empty(tuple(w_shape), dtype=np.uint64)
+    if lib().oracle_party_conv2d_wgrad(_p(g_i), _p(g_ip1), _p(x_i), _p(x_ip1), _p(dw), *dims) != 0:
+        raise MemoryError("oracle_party_conv2d_wgrad")
+    return dw
 
 
 def party_matmul_at(x_i, x_ip1, y_i, y_ip1, m: int, n: int) -> int:
