@@ -163,6 +163,47 @@ CG_API cg_status cg_share_conv2d_ws(const uint64_t *x_i, const uint64_t *x_ip1,
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Backward products of a convolution layer on shares (Sec. III-C: the gradients of
+ * a linear / convolution layer are linear functions of the incoming gradient and
+ * are evaluated with the protocols of Sec. III-B, i.e. with the same three-term
+ * local product).  `desc` is the descriptor of the FORWARD layer; G denotes the
+ * gradient with respect to the layer output, NHWC [B,Ho,Wo,Cout].  Both gradients
+ * are the adjoints of the forward map: every forward term
+ * X[b][hi][wi][c] * W[co][r][s][c] -> Z[b][ho][wo][co] contributes
+ *
+ *   cg_share_conv2d_dgrad : G[b][ho][wo][co] * W[co][r][s][c] -> DX[b][hi][wi][c]
+ *   cg_share_conv2d_wgrad : G[b][ho][wo][co] * X[b][hi][wi][c] -> DW[co][r][s][c]
+ *
+ * and the party's output is g_i*y_i + g_{i+1}*y_i + g_i*y_{i+1} with y the filter
+ * (dgrad) or the layer input (wgrad): one additive share of the gradient, not
+ * re-shared, not truncated.
+ *
+ *   g_i, g_ip1 : NHWC [B,Ho,Wo,Cout]
+ *   w_i, w_ip1 : [Cout,kh,kw,Cin]        x_i, x_ip1 : NHWC [B,H,W,Cin]
+ *   dx_i       : NHWC [B,H,W,Cin]        dw_i       : [Cout,kh,kw,Cin]
+ *
+ * All device pointers, 8-byte aligned, the output fully overwritten and disjoint
+ * from the inputs (CG_ERR_ALIAS).  Nothing is written to memory besides the output:
+ * the filter is read in place with its taps reversed, the gradient of a strided
+ * layer is read as if zeros stood between its pixels, and the patch entries of the
+ * weight gradient are gathered from the input.  Shape errors as cg_share_conv2d.
+ * CG_ERR_UNSUPPORTED: dgrad if kh*kw*Cout exceeds 2^20, B*H*W exceeds 2^31-1, the
+ * gradient images one 256-row block can touch exceed 2^31-1 bytes, or (strided
+ * layers, Cout not a multiple of 32, or 16-byte-unaligned pointers) the filter
+ * exceeds 2^31-1 bytes; wgrad if B*Ho*Wo exceeds 2^30, Cout exceeds 2^22,
+ * kh*kw*Cin exceeds 2^31-1 or the (31/(Ho*Wo) + 2) input images a run of 32
+ * output pixels can touch exceed 2^31-1 bytes; either if a stride, padding or
+ * window side exceeds 32767.
+ */
+CG_API cg_status cg_share_conv2d_dgrad(const uint64_t *g_i, const uint64_t *g_ip1,
+                                const uint64_t *w_i, const uint64_t *w_ip1,
+                                uint64_t *dx_i, const cg_conv2d_desc *desc, void *stream);
+
+CG_API cg_status cg_share_conv2d_wgrad(const uint64_t *g_i, const uint64_t *g_ip1,
+                                const uint64_t *x_i, const uint64_t *x_ip1,
+                                uint64_t *dw_i, const cg_conv2d_desc *desc, void *stream);
+
+/*
  * Local linear operations on a replicated pair (a = s_i, b = s_{i+1}), over n
  * elements (Sec. III-B, "Linear operations": shares of alpha*x + beta*y are
  * the same combination of the shares, component by component).

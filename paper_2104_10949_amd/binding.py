@@ -23,7 +23,7 @@ LIB_PATH = os.environ.get("CG_LIBRARY") or os.path.join(_HERE, "libcg.so")
 EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d", "cg_share_add",
            "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct",
            "cg_share_matmul_ws", "cg_share_conv2d_ws", "cg_zero_share", "cg_reshare", "cg_share_matmul_t",
-           "cg_share_mul", "cg_share_sum_pool2d",
+           "cg_share_mul", "cg_share_sum_pool2d", "cg_share_conv2d_dgrad", "cg_share_conv2d_wgrad",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -78,9 +78,11 @@ def lib() -> ctypes.CDLL:
         L.cg_share_matmul_t.argtypes = [vp] * 5 + [i64] * 3 + [ctypes.c_int] * 2 + [vp]
         L.cg_share_mul.argtypes = [vp] * 5 + [sz, sz, vp]
         L.cg_share_sum_pool2d.argtypes = [vp] * 4 + [ctypes.POINTER(PoolDesc), vp]
-        for name in EXPORTS[2:15]:
+        L.cg_share_conv2d_dgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
+        L.cg_share_conv2d_wgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
+        for name in EXPORTS[2:17]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[15:]:
+        for name in EXPORTS[17:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -233,6 +235,46 @@ def cg_share_conv2d_ws(x_i, x_ip1, w_i, w_ip1, workspace, stride=(1, 1), pad=(0,
     _check(lib().cg_share_conv2d_ws(_ptr(x_i), _ptr(x_ip1), _ptr(w_i), _ptr(w_ip1), _ptr(z_i),
                                     ctypes.byref(d), wp, wb, _stream(stream)), "cg_share_conv2d_ws")
     return z_i
+
+
+def cg_share_conv2d_dgrad(g_i, g_ip1, w_i, w_ip1, x_shape, stride=(1, 1), pad=(0, 0), dx_i=None,
+                          stream=None) -> torch.Tensor:
+    """Party-local input gradient of a convolution layer; g NHWC [B,Ho,Wo,Cout], w [Cout,kh,kw,Cin],
+    x_shape = (B,H,W,Cin) of the layer input, result NHWC of that shape."""
+    B, H, W, Cin = (int(v) for v in x_shape)
+    Cout, kh, kw, Cin2 = w_i.shape
+    if g_ip1.shape != g_i.shape or w_ip1.shape != w_i.shape or Cin2 != Cin:
+        raise ValueError("operand shapes do not match")
+    if tuple(g_i.shape) != conv_out_shape((B, H, W, Cin), w_i.shape, stride, pad):
+        raise ValueError("gradient shape does not match the layer")
+    d = ConvDesc(B, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    if dx_i is None:
+        dx_i = torch.empty((B, H, W, Cin), dtype=torch.int64, device=g_i.device)
+    elif tuple(dx_i.shape) != (B, H, W, Cin):
+        raise ValueError("output shape does not match")
+    _check(lib().cg_share_conv2d_dgrad(_ptr(g_i), _ptr(g_ip1), _ptr(w_i), _ptr(w_ip1), _ptr(dx_i),
+                                       ctypes.byref(d), _stream(stream)), "cg_share_conv2d_dgrad")
+    return dx_i
+
+
+def cg_share_conv2d_wgrad(g_i, g_ip1, x_i, x_ip1, w_shape, stride=(1, 1), pad=(0, 0), dw_i=None,
+                          stream=None) -> torch.Tensor:
+    """Party-local weight gradient of a convolution layer; g NHWC [B,Ho,Wo,Cout], x NHWC [B,H,W,Cin],
+    w_shape = (Cout,kh,kw,Cin), result of that shape."""
+    B, H, W, Cin = x_i.shape
+    Cout, kh, kw, Cin2 = (int(v) for v in w_shape)
+    if g_ip1.shape != g_i.shape or x_ip1.shape != x_i.shape or Cin2 != Cin:
+        raise ValueError("operand shapes do not match")
+    if tuple(g_i.shape) != conv_out_shape(x_i.shape, (Cout, kh, kw, Cin), stride, pad):
+        raise ValueError("gradient shape does not match the layer")
+    d = ConvDesc(B, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    if dw_i is None:
+        dw_i = torch.empty((Cout, kh, kw, Cin), dtype=torch.int64, device=g_i.device)
+    elif tuple(dw_i.shape) != (Cout, kh, kw, Cin):
+        raise ValueError("output shape does not match")
+    _check(lib().cg_share_conv2d_wgrad(_ptr(g_i), _ptr(g_ip1), _ptr(x_i), _ptr(x_ip1), _ptr(dw_i),
+                                       ctypes.byref(d), _stream(stream)), "cg_share_conv2d_wgrad")
+    return dw_i
 
 
 def cg_share_add(xa, xb, ya, yb, za=None, zb=None, stream=None):

@@ -320,6 +320,7 @@ cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     p.x_a = x_i; p.x_b = x_ip1; p.w_a = y_i; p.w_b = y_ip1; p.z = z_i;
     p.M = (int)M; p.N = (int)N; p.K = (int)K; p.lda = (int)K;
     p.x_elems = (u64)mk;
+    p.w_elems = (u64)nk;
     p.Ho = p.Wo = 1;
     const void* in[4] = {x_i, x_ip1, y_i, y_ip1};
     const bool vec = (K % 2 == 0) && (!check_ptrs_too || all_aligned16(in, 4));
@@ -339,10 +340,12 @@ cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     return CG_OK;
 }
 
-cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i, const uint64_t* w_ip1,
-                      uint64_t* z_i, const cg_conv2d_desc* d, bool check_ptrs_too, Plan* out) {
-    if (!d) return CG_ERR_NULL;
-    if (check_ptrs_too && (!x_i || !x_ip1 || !w_i || !w_ip1 || !z_i)) return CG_ERR_NULL;
+// Sizes of a convolution layer, with every product checked against int64 overflow.
+struct ConvDims {
+    int64_t Ho, Wo, img, x_el, K, w_el, howo, M, z_el;
+};
+
+cg_status conv_dims(const cg_conv2d_desc* d, ConvDims* o) {
     if (d->B < 1 || d->H < 1 || d->W < 1 || d->Cin < 1 || d->Cout < 1 || d->kh < 1 || d->kw < 1 ||
         d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0)
         return CG_ERR_SHAPE;
@@ -353,13 +356,27 @@ cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
         return CG_ERR_SHAPE;
     const int64_t span_h = d->H + 2 * d->pad_h - d->kh, span_w = d->W + 2 * d->pad_w - d->kw;
     if (span_h < 0 || span_w < 0) return CG_ERR_SHAPE;
-    const int64_t Ho = span_h / d->stride_h + 1, Wo = span_w / d->stride_w + 1;
-    int64_t img, x_el, K, w_el, howo, M, z_el, tmp;
-    if (mul_overflows(d->H, d->W, &tmp) || mul_overflows(tmp, d->Cin, &img) || mul_overflows(img, d->B, &x_el) ||
-        mul_overflows(d->kh, d->kw, &tmp) || mul_overflows(tmp, d->Cin, &K) || mul_overflows(K, d->Cout, &w_el) ||
-        mul_overflows(Ho, Wo, &howo) || mul_overflows(howo, d->B, &M) || mul_overflows(M, d->Cout, &z_el) ||
-        mul_overflows(x_el, 8, &tmp) || mul_overflows(w_el, 8, &tmp) || mul_overflows(z_el, 8, &tmp))
+    o->Ho = span_h / d->stride_h + 1;
+    o->Wo = span_w / d->stride_w + 1;
+    int64_t tmp;
+    if (mul_overflows(d->H, d->W, &tmp) || mul_overflows(tmp, d->Cin, &o->img) ||
+        mul_overflows(o->img, d->B, &o->x_el) || mul_overflows(d->kh, d->kw, &tmp) ||
+        mul_overflows(tmp, d->Cin, &o->K) || mul_overflows(o->K, d->Cout, &o->w_el) ||
+        mul_overflows(o->Ho, o->Wo, &o->howo) || mul_overflows(o->howo, d->B, &o->M) ||
+        mul_overflows(o->M, d->Cout, &o->z_el) || mul_overflows(o->x_el, 8, &tmp) ||
+        mul_overflows(o->w_el, 8, &tmp) || mul_overflows(o->z_el, 8, &tmp))
         return CG_ERR_SHAPE;
+    return CG_OK;
+}
+
+cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i, const uint64_t* w_ip1,
+                      uint64_t* z_i, const cg_conv2d_desc* d, bool check_ptrs_too, Plan* out) {
+    if (!d) return CG_ERR_NULL;
+    if (check_ptrs_too && (!x_i || !x_ip1 || !w_i || !w_ip1 || !z_i)) return CG_ERR_NULL;
+    ConvDims cd;
+    if (cg_status st = conv_dims(d, &cd)) return st;
+    const int64_t Ho = cd.Ho, Wo = cd.Wo, img = cd.img, x_el = cd.x_el, K = cd.K, w_el = cd.w_el, howo = cd.howo,
+                  M = cd.M, z_el = cd.z_el;
     if (check_ptrs_too)
         if (cg_status st = check_product_ptrs(x_i, x_ip1, w_i, w_ip1, z_i, (u64)x_el * 8, (u64)w_el * 8, (u64)z_el * 8))
             return st;
@@ -372,6 +389,7 @@ cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     p.x_a = x_i; p.x_b = x_ip1; p.w_a = w_i; p.w_b = w_ip1; p.z = z_i;
     p.M = (int)M; p.N = (int)d->Cout; p.K = (int)K;
     p.x_elems = (u64)x_el;
+    p.w_elems = (u64)w_el;
     p.img_elems = (u64)img;
     p.H = (int)d->H; p.W = (int)d->W; p.Cin = (int)d->Cin; p.Ho = (int)Ho; p.Wo = (int)Wo;
     p.kh = (int)d->kh; p.kw = (int)d->kw; p.sh = (int)d->stride_h; p.sw = (int)d->stride_w;
@@ -413,6 +431,117 @@ cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     }
     pl.wp_bytes = (u64)d->Cout * (u64)KS * 256;
     pl.x_bytes = (u64)x_el * 8; pl.w_bytes = (u64)w_el * 8; pl.z_bytes = (u64)z_el * 8;
+    *out = pl;
+    return CG_OK;
+}
+
+// Input gradient of a convolution layer as a product of the kernel's form: rows are the
+// pixels of the layer INPUT, the contraction runs over (tap, output channel), the left
+// operand gathers patches of the incoming gradient (zero-interleaved when the layer is
+// strided) with padding k - 1 - pad, and the right operand is the filter with its taps
+// reversed and its channel roles exchanged, addressed in place.
+cg_status plan_conv2d_dgrad(const uint64_t* g_i, const uint64_t* g_ip1, const uint64_t* w_i, const uint64_t* w_ip1,
+                            uint64_t* dx_i, const cg_conv2d_desc* d, Plan* out) {
+    if (!d || !g_i || !g_ip1 || !w_i || !w_ip1 || !dx_i) return CG_ERR_NULL;
+    ConvDims cd;
+    if (cg_status st = conv_dims(d, &cd)) return st;
+    if (cg_status st = check_product_ptrs(g_i, g_ip1, w_i, w_ip1, dx_i, (u64)cd.z_el * 8, (u64)cd.w_el * 8,
+                                          (u64)cd.x_el * 8))
+        return st;
+    const int64_t taps = d->kh * d->kw;
+    const int64_t Kg = taps * d->Cout;                 // contraction length
+    const int64_t Mg = d->B * d->H * d->W;             // one row per input pixel
+    const int64_t g_img = cd.howo * d->Cout;           // words of one image of the gradient
+    if (Mg > MAX_DIM || d->Cin > MAX_DIM || Kg > MAX_ROW_WORDS || g_img > ((int64_t)1 << 27) ||
+        d->pad_h > 32767 || d->pad_w > 32767 || d->stride_h > 32767 || d->stride_w > 32767 ||
+        d->kh > 32767 || d->kw > 32767)
+        return CG_ERR_UNSUPPORTED;
+
+    const bool pointwise = taps == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 && d->pad_w == 0;
+    if (pointwise)  // dX [B*H*W, Cin] = G [B*H*W, Cout] x W, the filter [Cout, Cin] being the right operand stored transposed
+        return plan_matmul(g_i, g_ip1, w_i, w_ip1, dx_i, Mg, d->Cin, d->Cout, true, out, false, true);
+
+    Plan pl = {};
+    cg::GemmParams& p = pl.p;
+    p.x_a = g_i; p.x_b = g_ip1; p.w_a = w_i; p.w_b = w_ip1; p.z = dx_i;
+    p.M = (int)Mg; p.N = (int)d->Cin; p.K = (int)Kg;
+    p.x_elems = (u64)cd.z_el;
+    p.w_elems = (u64)cd.w_el;
+    p.img_elems = (u64)g_img;
+    // the gathered tensor is the gradient [B, Ho, Wo, Cout]; the "output" grid is the layer input's
+    p.H = (int)cd.Ho; p.W = (int)cd.Wo; p.Cin = (int)d->Cout; p.Ho = (int)d->H; p.Wo = (int)d->W;
+    p.kh = (int)d->kh; p.kw = (int)d->kw; p.sh = 1; p.sw = 1;
+    p.ph = (int)(d->kh - 1 - d->pad_h); p.pw = (int)(d->kw - 1 - d->pad_w);
+    p.div_cin = cg::make_fast_div((uint32_t)d->Cout);
+    p.div_kw = cg::make_fast_div((uint32_t)d->kw);
+    p.dil_h = (int)d->stride_h; p.dil_w = (int)d->stride_w;
+    p.div_dil_h = cg::make_fast_div((uint32_t)d->stride_h);
+    p.div_dil_w = cg::make_fast_div((uint32_t)d->stride_w);
+
+    // one block's rows touch at most this many consecutive images of the gradient
+    const int64_t hw = d->H * d->W;
+    const int64_t span_imgs = (cg::MAX_TILE_ROWS - 1) / hw + 2;
+    if ((span_imgs < d->B ? span_imgs : d->B) * g_img * 8 > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;
+
+    const void* in[4] = {g_i, g_ip1, w_i, w_ip1};
+    const bool strided = d->stride_h != 1 || d->stride_w != 1;
+    const bool c32 = !strided && all_aligned16(in, 4) && d->Cout % 32 == 0 && taps * d->Cin <= ((int64_t)1 << 22);
+    if (c32) {
+        pl.amode = cg::A_CONV_C32; pl.bmode = cg::B_FLIP_C32;
+    } else {
+        // every word of the filter is addressed from one view
+        if (cd.w_el * 8 > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;
+        pl.amode = strided ? cg::A_CONV_DIL : cg::A_CONV_GEN;
+        pl.bmode = cg::B_FLIP_GEN;
+    }
+    pl.x_bytes = (u64)cd.z_el * 8; pl.w_bytes = (u64)cd.w_el * 8; pl.z_bytes = (u64)cd.x_el * 8;
+    *out = pl;
+    return CG_OK;
+}
+
+// Weight gradient: DW [Cout, kh*kw*Cin] = G^T [Cout, pixels] x patches [pixels, kh*kw*Cin].  The
+// gradient [pixels, Cout] is the left operand stored transposed; the right operand gathers the
+// patch entries from the layer input, one K slice (32 output pixels) at a time.
+cg_status plan_conv2d_wgrad(const uint64_t* g_i, const uint64_t* g_ip1, const uint64_t* x_i, const uint64_t* x_ip1,
+                            uint64_t* dw_i, const cg_conv2d_desc* d, Plan* out) {
+    if (!d || !g_i || !g_ip1 || !x_i || !x_ip1 || !dw_i) return CG_ERR_NULL;
+    ConvDims cd;
+    if (cg_status st = conv_dims(d, &cd)) return st;
+    if (cg_status st = check_product_ptrs(g_i, g_ip1, x_i, x_ip1, dw_i, (u64)cd.z_el * 8, (u64)cd.x_el * 8,
+                                          (u64)cd.w_el * 8))
+        return st;
+    // pixels are the contraction index here; slices are rebased one by one, so K may be long
+    if (cd.M > ((int64_t)1 << 30) || cd.K > MAX_DIM || d->Cout > ((int64_t)1 << 22) || cd.img > ((int64_t)1 << 27) ||
+        d->pad_h > 32767 || d->pad_w > 32767 || d->stride_h > 32767 || d->stride_w > 32767 ||
+        d->kh > 32767 || d->kw > 32767)
+        return CG_ERR_UNSUPPORTED;
+
+    const bool pointwise = d->kh == 1 && d->kw == 1 && d->stride_h == 1 && d->stride_w == 1 &&
+                           d->pad_h == 0 && d->pad_w == 0;
+    if (pointwise && cd.M <= MAX_ROW_WORDS && d->Cin <= ((int64_t)1 << 22))
+        // DW [Cout, Cin] = G^T x X with both operands stored [pixels, .]
+        return plan_matmul(g_i, g_ip1, x_i, x_ip1, dw_i, d->Cout, d->Cin, cd.M, true, out, true, true);
+
+    // a slice of 32 pixels touches at most this many consecutive images of the input
+    const int64_t span_imgs = 31 / cd.howo + 2;
+    if ((span_imgs < d->B ? span_imgs : d->B) * cd.img * 8 > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;
+
+    Plan pl = {};
+    cg::GemmParams& p = pl.p;
+    p.x_a = g_i; p.x_b = g_ip1; p.w_a = x_i; p.w_b = x_ip1; p.z = dw_i;
+    p.M = (int)d->Cout; p.N = (int)cd.K; p.K = (int)cd.M;
+    p.x_elems = (u64)cd.z_el;
+    p.w_elems = (u64)cd.x_el;
+    p.img_elems = (u64)cd.img;
+    p.H = (int)d->H; p.W = (int)d->W; p.Cin = (int)d->Cin; p.Ho = (int)cd.Ho; p.Wo = (int)cd.Wo;
+    p.kh = (int)d->kh; p.kw = (int)d->kw; p.sh = (int)d->stride_h; p.sw = (int)d->stride_w;
+    p.ph = (int)d->pad_h; p.pw = (int)d->pad_w;
+    p.div_cin = cg::make_fast_div((uint32_t)d->Cin);
+    p.div_kw = cg::make_fast_div((uint32_t)d->kw);
+    p.div_howo = cg::make_fast_div((uint32_t)cd.howo);
+    p.div_wo = cg::make_fast_div((uint32_t)cd.Wo);
+    pl.amode = cg::A_TRANS; pl.bmode = cg::B_PATCH_T;
+    pl.x_bytes = (u64)cd.z_el * 8; pl.w_bytes = (u64)cd.x_el * 8; pl.z_bytes = (u64)cd.w_el * 8;
     *out = pl;
     return CG_OK;
 }
@@ -506,6 +635,20 @@ cg_status cg_share_conv2d_ws(const uint64_t* x_i, const uint64_t* x_ip1, const u
     if (cg_status st = plan_conv2d(x_i, x_ip1, w_i, w_ip1, z_i, d, true, &pl)) return st;
     if (!pl.planes_ok) return run_direct(pl, stream);
     return run_planes(pl, workspace, workspace_bytes, stream);
+}
+
+cg_status cg_share_conv2d_dgrad(const uint64_t* g_i, const uint64_t* g_ip1, const uint64_t* w_i,
+                                const uint64_t* w_ip1, uint64_t* dx_i, const cg_conv2d_desc* d, void* stream) {
+    Plan pl;
+    if (cg_status st = plan_conv2d_dgrad(g_i, g_ip1, w_i, w_ip1, dx_i, d, &pl)) return st;
+    return run_direct(pl, stream);
+}
+
+cg_status cg_share_conv2d_wgrad(const uint64_t* g_i, const uint64_t* g_ip1, const uint64_t* x_i,
+                                const uint64_t* x_ip1, uint64_t* dw_i, const cg_conv2d_desc* d, void* stream) {
+    Plan pl;
+    if (cg_status st = plan_conv2d_wgrad(g_i, g_ip1, x_i, x_ip1, dw_i, d, &pl)) return st;
+    return run_direct(pl, stream);
 }
 
 cg_status cg_share_add(const uint64_t* xa, const uint64_t* xb, const uint64_t* ya, const uint64_t* yb,

@@ -28,14 +28,22 @@ enum AMode {
     A_LINEAR_SCALAR = 1,  // row-major [M, lda], 8-byte loads
     A_CONV_C32 = 2,       // NHWC patch gather, Cin % 32 == 0, 16-byte loads
     A_CONV_GEN = 3,       // NHWC patch gather, any Cin, 8-byte loads
-    A_TRANS = 4           // stored transposed, [K, M] with M contiguous, 8-byte loads
+    A_TRANS = 4,          // stored transposed, [K, M] with M contiguous, 8-byte loads
+    A_CONV_DIL = 5        // NHWC patch gather from an image whose pixels sit dil_h, dil_w apart
+                          // with zeros between them (input gradient of a strided convolution)
 };
 
 // How the right operand's words are addressed.
 enum BMode {
     B_VEC = 0,     // row-major [N, K], 16-byte loads
     B_SCALAR = 1,  // row-major [N, K], 8-byte loads
-    B_TRANS = 2    // stored transposed, [K, N] with N contiguous, 8-byte loads
+    B_TRANS = 2,   // stored transposed, [K, N] with N contiguous, 8-byte loads
+    // Input gradient of a convolution: the right operand is the filter [Cout, kh, kw, N] read as
+    // B[n, (r', s', co)] = W[co, kh-1-r', kw-1-s', n].
+    B_FLIP_C32 = 3,  // ... Cout % 32 == 0: a slice of K has one tap, rebased per slice
+    B_FLIP_GEN = 4,  // ... any Cout: every word finds its own tap
+    // Weight gradient: the right operand is the layer input, B[(r, s, c), pixel] = patch entry
+    B_PATCH_T = 5
 };
 
 struct GemmParams {
@@ -45,9 +53,13 @@ struct GemmParams {
     int M, N, K;                // matrix-product view
     int lda;                    // leading dimension of the left operand (linear modes)
     uint64_t x_elems;           // words in one left-operand share tensor
+    uint64_t w_elems;           // words in one right-operand share tensor
     uint64_t img_elems;         // H*W*Cin (patch modes)
     int H, W, Cin, Ho, Wo, kh, kw, sh, sw, ph, pw;
     FastDiv div_cin, div_kw;
+    int dil_h, dil_w;           // A_CONV_DIL: spacing of the stored pixels inside the gathered image
+    FastDiv div_dil_h, div_dil_w;
+    FastDiv div_howo, div_wo;   // B_PATCH_T: decomposition of a pixel index into (b, ho, wo)
     // digit-plane route: planes of x_i, x_{i+1}, y_i + y_{i+1}, y_i (see to_planes_kernel)
     const char *xp_a, *xp_b, *wp_sum, *wp_a;
     uint64_t xp_bytes;          // bytes of one left-operand plane tensor

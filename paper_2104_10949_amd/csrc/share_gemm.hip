@@ -327,6 +327,123 @@ struct ConvGen {
     }
 };
 
+// Patch gather from a zero-interleaved image (any channel count, 8-byte loads).  The
+// gathered image is the stored [H, W, Cin] tensor with dil_h - 1 rows and dil_w - 1
+// columns of zeros between neighbouring pixels: position (hd, wd) holds stored pixel
+// (hd / dil_h, wd / dil_w) when both divisions are exact and is zero otherwise.  This is
+// what the input gradient of a strided convolution correlates the filter with.
+struct ConvDil {
+    u32 img_off;  // byte offset of this row's image relative to the view
+    int hi0, wi0;
+    bool ok;
+    u32 kq;
+    __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, u32,
+                                         int q, int jh) {
+        ok = row_local < rows_left;
+        const u32 m = (u32)(m0 + (ok ? row_local : 0));
+        const u32 HoWo = (u32)(p.Ho * p.Wo);
+        const u32 b = m / HoWo, b0 = (u32)m0 / HoWo;
+        const u32 rem = m - b * HoWo;
+        const u32 ho = rem / (u32)p.Wo, wo = rem - ho * (u32)p.Wo;
+        hi0 = (int)ho * p.sh - p.ph;
+        wi0 = (int)wo * p.sw - p.pw;
+        img_off = (b - b0) * (u32)p.H * (u32)p.W * (u32)p.Cin * 8u;
+        kq = 16 * jh + 2 * q;
+    }
+    __device__ __forceinline__ u2 one(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, u32 k) const {
+        const u32 rs = fast_div(k, p.div_cin);
+        const u32 c = k - rs * (u32)p.Cin;
+        const u32 r = fast_div(rs, p.div_kw);
+        const u32 s = rs - r * (u32)p.kw;
+        const int hd = hi0 + (int)r, wd = wi0 + (int)s;
+        // negative positions wrap to huge unsigned values and fail the range test below
+        const u32 hq = fast_div((u32)hd & 0x7FFFFFFFu, p.div_dil_h), wq = fast_div((u32)wd & 0x7FFFFFFFu, p.div_dil_w);
+        const bool v = ok && k < (u32)p.K && hd >= 0 && wd >= 0 && hq < (u32)p.H && wq < (u32)p.W &&
+                       hq * (u32)p.dil_h == (u32)hd && wq * (u32)p.dil_w == (u32)wd;
+        const u32 off = img_off + ((hq * (u32)p.W + wq) * (u32)p.Cin + c) * 8u;
+        return __builtin_amdgcn_raw_buffer_load_b64(rs_, v ? off : OOB, 0, 0);
+    }
+    __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int ks, u32,
+                                         u4 out[2]) const {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const u32 k = 32u * ks + kq + 8u * jj;
+            const u2 e0 = one(p, rs_, k), e1 = one(p, rs_, k + 1);
+            out[jj].x = e0.x; out[jj].y = e0.y; out[jj].z = e1.x; out[jj].w = e1.y;
+        }
+    }
+};
+
+// Right operand of the input gradient, any Cout: word (n, k) with k = (r', s', co) is
+// W[co, kh-1-r', kw-1-s', n] of the filter [Cout, kh, kw, N].  The view starts at column
+// n0 of the filter and covers the rest of it (the host keeps a filter below 2^31 bytes).
+struct FlipGen {
+    u32 row8, kq;
+    bool ok;
+    __device__ __forceinline__ void init(const GemmParams&, int, int row_local, int rows_left, u32,
+                                         int q, int jh) {
+        kq = 16 * jh + 2 * q;
+        ok = row_local < rows_left;
+        row8 = (u32)row_local * 8u;
+    }
+    __device__ __forceinline__ u2 one(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, u32 k) const {
+        const u32 taps = (u32)(p.kh * p.kw);
+        const u32 tap = fast_div(k, p.div_cin);       // p.Cin is the gathered channel count = Cout
+        const u32 co = k - tap * (u32)p.Cin;
+        const bool v = ok && k < (u32)p.K;
+        const u32 off = (co * taps + (taps - 1u - tap)) * (u32)p.N * 8u + row8;
+        return __builtin_amdgcn_raw_buffer_load_b64(rs_, v ? off : OOB, 0, 0);
+    }
+    __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int ks, u32,
+                                         u4 out[2]) const {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const u32 k = 32u * ks + kq + 8u * jj;
+            const u2 e0 = one(p, rs_, k), e1 = one(p, rs_, k + 1);
+            out[jj].x = e0.x; out[jj].y = e0.y; out[jj].z = e1.x; out[jj].w = e1.y;
+        }
+    }
+};
+
+// Right operand of the weight gradient: row n = (r, s, c) of the filter layout, column
+// k = output pixel (b, ho, wo); the word is X[b, ho*sh - ph + r, wo*sw - pw + s, c] or zero
+// outside the image.  Consecutive lanes take consecutive n, i.e. consecutive channels of
+// one pixel.  The view is rebased at every K slice to the image of the slice's first pixel.
+struct PatchTrans {
+    int r, s;
+    u32 c8, kq;
+    bool ok;
+    __device__ __forceinline__ void init(const GemmParams& p, int n0, int row_local, int rows_left, u32,
+                                         int q, int jh) {
+        kq = 16 * jh + 2 * q;
+        ok = row_local < rows_left;
+        const u32 n = (u32)(n0 + (ok ? row_local : 0));
+        const u32 tap = fast_div(n, p.div_cin);
+        c8 = (n - tap * (u32)p.Cin) * 8u;
+        r = (int)fast_div(tap, p.div_kw);
+        s = (int)tap - r * p.kw;
+    }
+    __device__ __forceinline__ u2 one(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, u32 k, u32 b0) const {
+        const u32 b = fast_div(k, p.div_howo);
+        const u32 rem = k - b * (u32)(p.Ho * p.Wo);
+        const u32 ho = fast_div(rem, p.div_wo), wo = rem - ho * (u32)p.Wo;
+        const int hi = (int)ho * p.sh - p.ph + r, wi = (int)wo * p.sw - p.pw + s;
+        const bool v = ok && k < (u32)p.K && (u32)hi < (u32)p.H && (u32)wi < (u32)p.W;
+        const u32 off = ((((b - b0) * (u32)p.H + (u32)hi) * (u32)p.W + (u32)wi) * (u32)p.Cin) * 8u + c8;
+        return __builtin_amdgcn_raw_buffer_load_b64(rs_, v ? off : OOB, 0, 0);
+    }
+    __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int ks, u32,
+                                         u4 out[2]) const {
+        const u32 b0 = fast_div(32u * (u32)ks, p.div_howo);  // the image the slice's view starts at
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const u32 k = 32u * ks + kq + 8u * jj;
+            const u2 e0 = one(p, rs_, k, b0), e1 = one(p, rs_, k + 1, b0);
+            out[jj].x = e0.x; out[jj].y = e0.y; out[jj].z = e1.x; out[jj].w = e1.y;
+        }
+    }
+};
+
 // compile-time loop: f(integral_constant<int, I>) for I in [I0, N)
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -436,13 +553,17 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
 
     // ---- buffer views, rebased per block so that 32-bit offsets suffice
     constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
-    constexpr bool A_TR = AMODE == A_TRANS, B_TR = BMODE == B_TRANS;
+    constexpr bool A_TR = AMODE == A_TRANS;
+    // right-operand modes whose memory is contiguous along n: consecutive lanes take consecutive rows
+    constexpr bool B_TR = BMODE == B_TRANS || BMODE == B_FLIP_C32 || BMODE == B_FLIP_GEN || BMODE == B_PATCH_T;
     u64 a_base_elems;
     if (A_LINEAR) a_base_elems = (u64)m0 * (u64)p.lda;
     else if (A_TR) a_base_elems = (u64)m0;
     else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
-    const u64 b_base_elems = B_TR ? (u64)n0 : (u64)n0 * (u64)p.K;
-    const u64 w_elems = (u64)p.N * (u64)p.K;
+    const u64 b_base_elems = BMODE == B_PATCH_T ? 0 : (B_TR ? (u64)n0 : (u64)n0 * (u64)p.K);
+    const u64 w_elems = p.w_elems;
+    TapCursor tap;
+    tap.reset();
     // view on `elems_total` words starting `base` words in, advanced by `adv` words
     auto view = [&](const u64* ptr, u64 elems_total, u64 base) {
         const u64 left = (elems_total - base) * 8u;
@@ -461,9 +582,18 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             return fixed;
         }
     };
+    // (B_FLIP_C32 reads the tap cursor, which load_a has moved to slice ks before this is called)
     auto b_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
-        if constexpr (B_TR) {
+        if constexpr (BMODE == B_TRANS) {
             const u64 base = b_base_elems + (u64)ks * 32u * (u64)p.N;
+            return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
+        } else if constexpr (BMODE == B_FLIP_C32) {
+            const int taps = p.kh * p.kw;
+            if (tap.tap >= taps) return make_rsrc(ptr, 0);  // past the end of K
+            const u64 base = b_base_elems + ((u64)tap.c0 * (u64)taps + (u64)(taps - 1 - tap.tap)) * (u64)p.N;
+            return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
+        } else if constexpr (BMODE == B_PATCH_T) {
+            const u64 base = (u64)fast_div(32u * (u32)ks, p.div_howo) * p.img_elems;
             return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
         } else {
             return fixed;
@@ -475,9 +605,12 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     typedef typename std::conditional<AMODE == A_LINEAR_VEC, LinearVec,
             typename std::conditional<AMODE == A_LINEAR_SCALAR, LinearScalar,
             typename std::conditional<AMODE == A_CONV_C32, ConvC32,
-            typename std::conditional<AMODE == A_TRANS, TransScalar, ConvGen>::type>::type>::type>::type AGen;
+            typename std::conditional<AMODE == A_TRANS, TransScalar,
+            typename std::conditional<AMODE == A_CONV_DIL, ConvDil, ConvGen>::type>::type>::type>::type>::type AGen;
     typedef typename std::conditional<BMODE == B_VEC, LinearVec,
-            typename std::conditional<BMODE == B_SCALAR, LinearScalar, TransScalar>::type>::type BGen;
+            typename std::conditional<BMODE == B_SCALAR, LinearScalar,
+            typename std::conditional<BMODE == B_FLIP_GEN, FlipGen,
+            typename std::conditional<BMODE == B_PATCH_T, PatchTrans, TransScalar>::type>::type>::type>::type BGen;
     AGen ag[AU];
     BGen bg[BU];
     int a_dst[AU], b_dst[BU];  // LDS byte offset of digit 0 inside a stage
@@ -496,11 +629,12 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         const int q = B_TR ? (u / T::BN) & 3 : u & 3;
         const int row = B_TR ? u % T::BN : (u >> 2) % T::BN;
         const int jh = (u >> 2) / T::BN;
-        bg[i].init(p, n0, row, rows_n, B_TR ? (u32)p.N : (u32)p.K, q, jh);
+        // pitch between consecutive k of one row: N for a transposed matrix, one output
+        // channel of the filter (kh*kw*N words) for the flipped filter
+        const u32 pitch = BMODE == B_FLIP_C32 ? (u32)(p.kh * p.kw) * (u32)p.N : (B_TR ? (u32)p.N : (u32)p.K);
+        bg[i].init(p, n0, row, rows_n, pitch, q, jh);
         b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
     }
-    TapCursor tap;
-    tap.reset();
 
     // Two sets of staging registers.  E feeds an even half-step (x_a against
     // w_a + w_b), O an odd one (x_b against w_a).
@@ -994,6 +1128,10 @@ hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStrea
     CG_CASE(A_TRANS, B_VEC);
     CG_CASE(A_TRANS, B_SCALAR);
     CG_CASE(A_TRANS, B_TRANS);
+    CG_CASE(A_CONV_C32, B_FLIP_C32);
+    CG_CASE(A_CONV_GEN, B_FLIP_GEN);
+    CG_CASE(A_CONV_DIL, B_FLIP_GEN);
+    CG_CASE(A_TRANS, B_PATCH_T);
 #undef CG_CASE
     return hipErrorInvalidValue;
 }

@@ -1,0 +1,192 @@
+"""GPU parity of the convolution backward products (input and weight gradient on shares),
+called through the C-ABI, against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from tests.gpu_util import first_mismatch, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def cg():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2104_10949_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ro():
+    from oracle import ring_oracle
+    return ring_oracle
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_2104_10949_amd import workloads
+    return workloads
+
+
+CASES = [
+    # B, H, W, Cin, Cout, kh, kw, stride, pad
+    (1, 4, 4, 1, 1, 1, 1, (1, 1), (0, 0)),
+    (2, 8, 8, 3, 5, 3, 3, (1, 1), (1, 1)),
+    (2, 9, 7, 3, 64, 5, 5, (1, 1), (2, 2)),            # Cout % 32 == 0: one tap per K slice
+    (3, 10, 12, 32, 64, 3, 3, (1, 1), (1, 1)),
+    (2, 12, 12, 64, 128, 3, 3, (1, 1), (1, 1)),
+    (2, 13, 11, 40, 96, 3, 3, (1, 1), (0, 0)),         # no padding: full correlation pads by k-1
+    (1, 9, 9, 70, 32, 3, 3, (1, 1), (2, 2)),           # padding beyond k-1-p >= 0: negative gather padding
+    (3, 10, 12, 32, 40, 3, 3, (1, 1), (1, 1)),         # Cout % 32 != 0: per-word taps
+    (1, 32, 32, 3, 70, 11, 11, (4, 4), (9, 9)),        # strided: zero-interleaved gradient
+    (2, 12, 12, 64, 130, 3, 3, (2, 2), (1, 1)),
+    (2, 12, 12, 64, 128, 3, 3, (2, 2), (1, 1)),
+    (2, 11, 13, 16, 32, 3, 3, (2, 2), (1, 1)),         # stride leaves a remainder row and column
+    (2, 14, 14, 64, 96, 1, 1, (1, 1), (0, 0)),         # pointwise: plain products on transposed operands
+    (2, 14, 14, 64, 96, 1, 1, (2, 2), (0, 0)),
+    (1, 30, 30, 3, 64, 7, 7, (2, 2), (3, 3)),
+    (2, 6, 5, 16, 33, 2, 3, (1, 2), (1, 0)),
+    (5, 3, 3, 96, 20, 3, 3, (1, 1), (1, 1)),
+    (4, 5, 5, 7, 9, 1, 1, (1, 1), (0, 0)),
+    (200, 1, 1, 32, 16, 3, 3, (1, 1), (1, 1)),         # many images per K slice and per row block
+    (40, 2, 2, 8, 24, 2, 2, (1, 1), (1, 1)),
+    (2, 20, 20, 200, 64, 3, 3, (1, 1), (1, 1)),        # ragged tails in every dimension
+]
+
+
+def shapes(case):
+    B, H, W, Cin, Cout, kh, kw, stride, pad = case
+    Ho = (H + 2 * pad[0] - kh) // stride[0] + 1
+    Wo = (W + 2 * pad[1] - kw) // stride[1] + 1
+    return (B, H, W, Cin), (Cout, kh, kw, Cin), (B, Ho, Wo, Cout)
+
+
+def run_dgrad(cg, g_a, g_b, w_a, w_b, xs, stride, pad):
+    d = [cg.to_device(a) for a in (g_a, g_b, w_a, w_b)]
+    out = torch.full(xs, 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")  # must be fully overwritten
+    cg.cg_share_conv2d_dgrad(*d, xs, stride=stride, pad=pad, dx_i=out)
+    torch.cuda.synchronize()
+    return cg.to_host(out)
+
+
+def run_wgrad(cg, g_a, g_b, x_a, x_b, ws, stride, pad):
+    d = [cg.to_device(a) for a in (g_a, g_b, x_a, x_b)]
+    out = torch.full(ws, 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")
+    cg.cg_share_conv2d_wgrad(*d, ws, stride=stride, pad=pad, dw_i=out)
+    torch.cuda.synchronize()
+    return cg.to_host(out)
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_dgrad_random_shares(cg, ro, wl, case):
+    say(f"cg_share_conv2d_dgrad random {case}")
+    xs, ws, gs = shapes(case)
+    stride, pad = case[7], case[8]
+    seed = 31000 + sum(case[:7])
+    ops = (wl.draw_ring(gs, seed), wl.draw_ring(gs, seed + 1), wl.draw_ring(ws, seed + 2),
+           wl.draw_ring(ws, seed + 3))
+    got = run_dgrad(cg, *ops, xs, stride, pad)
+    want = ro.party_conv2d_dgrad(*ops, xs, stride, pad)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_wgrad_random_shares(cg, ro, wl, case):
+    say(f"cg_share_conv2d_wgrad random {case}")
+    xs, ws, gs = shapes(case)
+    stride, pad = case[7], case[8]
+    seed = 32000 + sum(case[:7])
+    ops = (wl.draw_ring(gs, seed), wl.draw_ring(gs, seed + 1), wl.draw_ring(xs, seed + 2),
+           wl.draw_ring(xs, seed + 3))
+    got = run_wgrad(cg, *ops, ws, stride, pad)
+    want = ro.party_conv2d_wgrad(*ops, ws, stride, pad)
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+@pytest.mark.parametrize("word", [0x8080808080808080, 0xFFFFFFFFFFFFFFFF, 0x7F7F7F7F7F7F7F7F, 0x0000000080000000])
+def test_backward_adversarial_constant_words(cg, ro, word):
+    case = (2, 10, 9, 32, 64, 3, 3, (1, 1), (1, 1))
+    say(f"conv backward constant word 0x{word:016x}")
+    xs, ws, gs = shapes(case)
+    full = lambda s: np.full(s, word, dtype=np.uint64)
+    got = run_dgrad(cg, full(gs), full(gs), full(ws), full(ws), xs, (1, 1), (1, 1))
+    assert not first_mismatch(got, ro.party_conv2d_dgrad(full(gs), full(gs), full(ws), full(ws), xs, (1, 1), (1, 1)))
+    got = run_wgrad(cg, full(gs), full(gs), full(xs), full(xs), ws, (1, 1), (1, 1))
+    assert not first_mismatch(got, ro.party_conv2d_wgrad(full(gs), full(gs), full(xs), full(xs), ws, (1, 1), (1, 1)))
+
+
+@pytest.mark.parametrize("case", [(2, 10, 10, 32, 64, 3, 3, (1, 1), (1, 1)), (2, 11, 9, 6, 10, 3, 3, (2, 2), (1, 1))])
+def test_three_parties_open_to_the_plaintext_gradients(cg, ro, wl, case):
+    say(f"conv backward, three parties {case}")
+    xs, ws, gs = shapes(case)
+    stride, pad = case[7], case[8]
+    x, w, g = wl.draw_ring(xs, 401), wl.draw_ring(ws, 402), wl.draw_ring(gs, 403)
+    sx = ro.share(x, wl.draw_ring(xs, 404), wl.draw_ring(xs, 405))
+    sw = ro.share(w, wl.draw_ring(ws, 406), wl.draw_ring(ws, 407))
+    sg = ro.share(g, wl.draw_ring(gs, 408), wl.draw_ring(gs, 409))
+    dx = [run_dgrad(cg, *ro.party_pair(sg, i), *ro.party_pair(sw, i), xs, stride, pad) for i in range(3)]
+    dw = [run_wgrad(cg, *ro.party_pair(sg, i), *ro.party_pair(sx, i), ws, stride, pad) for i in range(3)]
+    opened = cg.to_host(cg.cg_reconstruct(*[cg.to_device(a) for a in dx]))
+    assert not first_mismatch(opened, ro.conv2d_dgrad(g, w, xs, stride, pad))
+    opened = cg.to_host(cg.cg_reconstruct(*[cg.to_device(a) for a in dw]))
+    assert not first_mismatch(opened, ro.conv2d_wgrad(g, x, ws, stride, pad))
+
+
+def test_wgrad_many_pixels_folds_in_place_without_split_k(cg, ro, wl):
+    # 17*32*32 = 17408 output pixels > 511*32: the accumulators are folded twice; 4 x 72 tiles, so K is not split
+    case = (17, 32, 32, 512, 512, 3, 3, (1, 1), (1, 1))
+    say(f"cg_share_conv2d_wgrad long contraction {case}")
+    xs, ws, gs = shapes(case)
+    ops = (wl.draw_ring(gs, 501), wl.draw_ring(gs, 502), wl.draw_ring(xs, 503), wl.draw_ring(xs, 504))
+    got = run_wgrad(cg, *ops, ws, (1, 1), (1, 1))
+    want = ro.party_conv2d_wgrad(*ops, ws, (1, 1), (1, 1))
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+def test_wgrad_contraction_longer_than_a_plain_product_allows(cg, ro, wl):
+    # 2^20 + 2^17 output pixels: beyond the K limit of the row-major products, split over many blocks
+    case = (18, 256, 256, 2, 4, 3, 3, (1, 1), (1, 1))
+    say(f"cg_share_conv2d_wgrad very long contraction {case}")
+    xs, ws, gs = shapes(case)
+    ops = (wl.draw_ring(gs, 511), wl.draw_ring(gs, 512), wl.draw_ring(xs, 513), wl.draw_ring(xs, 514))
+    got = run_wgrad(cg, *ops, ws, (1, 1), (1, 1))
+    want = ro.party_conv2d_wgrad(*ops, ws, (1, 1), (1, 1))
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
+def test_backward_of_every_layer_of_the_vgg_shaped_config(cg, ro, wl):
+    for idx, layer in enumerate(wl.config_layers(4)):
+        if layer.kind != "conv":
+            continue
+        xs, ws = (layer.B, layer.H, layer.W, layer.Cin), (layer.Cout, layer.kh, layer.kw, layer.Cin)
+        stride, pad = (layer.stride, layer.stride), (layer.pad, layer.pad)
+        gs = (layer.B, (layer.H + 2 * layer.pad - layer.kh) // layer.stride + 1,
+              (layer.W + 2 * layer.pad - layer.kw) // layer.stride + 1, layer.Cout)
+        say(f"config 4 backward {layer.name} x={xs} w={ws}")
+        seed = wl.layer_seed(4, idx) + 500000
+        g_a, g_b = wl.draw_ring(gs, seed), wl.draw_ring(gs, seed + 1)
+        x_a, x_b = wl.draw_ring(xs, seed + 2), wl.draw_ring(xs, seed + 3)
+        w_a, w_b = wl.draw_ring(ws, seed + 4), wl.draw_ring(ws, seed + 5)
+        got = run_dgrad(cg, g_a, g_b, w_a, w_b, xs, stride, pad)
+        assert not first_mismatch(got, ro.party_conv2d_dgrad(g_a, g_b, w_a, w_b, xs, stride, pad)), layer.name
+        got = run_wgrad(cg, g_a, g_b, x_a, x_b, ws, stride, pad)
+        assert not first_mismatch(got, ro.party_conv2d_wgrad(g_a, g_b, x_a, x_b, ws, stride, pad)), layer.name
+
+
+def test_backward_argument_errors(cg):
+    xs, ws, gs = (2, 8, 8, 4), (6, 3, 3, 4), (2, 8, 8, 6)
+    z = lambda s: torch.zeros(s, dtype=torch.int64, device="cuda")
+    g, w, x = z(gs), z(ws), z(xs)
+    with pytest.raises(ValueError):
+        cg.cg_share_conv2d_dgrad(g, g, w, w, xs, stride=(1, 1), pad=(0, 0))     # gradient shape of another layer
+    inside_g = g.view(-1)[: x.numel()].view(xs)      # an output that overlaps the gradient
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_share_conv2d_dgrad(g, g, w, w, xs, stride=(1, 1), pad=(1, 1), dx_i=inside_g)
+    assert e.value.status == cg.CG_ERR_ALIAS
+    inside_x = x.view(-1)[: w.numel()].view(ws)      # an output that overlaps the layer input
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_share_conv2d_wgrad(g, g, x, x, ws, stride=(1, 1), pad=(1, 1), dw_i=inside_x)
+    assert e.value.status == cg.CG_ERR_ALIAS
