@@ -1057,19 +1057,38 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream);
 #define CG_SPLIT_MIN_SLICES 2
 #endif
 
+// Cost of the fixed part of a block (prologue, fold of the accumulators into z), in
+// units of one K slice of the main loop, with a plain store and with atomic adds.
+#ifndef CG_SPLIT_COST_PLAIN
+#define CG_SPLIT_COST_PLAIN 1.0
+#endif
+#ifndef CG_SPLIT_COST_ATOMIC
+#define CG_SPLIT_COST_ATOMIC 2.0
+#endif
+
 static int choose_ksplit(int64_t tiles, int nk) {
-    // Split K when the tile grid alone cannot fill the 256 compute units.  A block's
-    // 96 KB of LDS leaves room for one block per unit, so aim at one round of 256
-    // blocks and keep at least two slices of K per block.
-    int ksplit = 1;
-    if (tiles < CG_SPLIT_TARGET) {
-        ksplit = (int)(CG_SPLIT_TARGET / tiles);
-        if (ksplit > nk / CG_SPLIT_MIN_SLICES) ksplit = nk / CG_SPLIT_MIN_SLICES;
-        if (ksplit < 1) ksplit = 1;
-        const int per = (nk + ksplit - 1) / ksplit;
-        ksplit = (nk + per - 1) / per;  // no empty splits
+    // A block's 96 KB of LDS leaves room for one block per compute unit, so a grid runs
+    // in rounds of 256 blocks and the last round costs as much as a full one.  Splitting
+    // K makes the blocks shorter, which fills the chip when the tiles alone cannot and
+    // shrinks the idle part of the last round otherwise.  The split count with the least
+    // modelled time wins: rounds * (slices per block + fixed cost per block).
+    const int units = CG_SPLIT_TARGET;
+    int64_t max_split = 8 * units / tiles;  // at most eight rounds' worth of blocks
+    if (max_split > nk / CG_SPLIT_MIN_SLICES) max_split = nk / CG_SPLIT_MIN_SLICES;
+    int best = 1;
+    double best_cost = 0;
+    for (int64_t ks = 1; ks <= (max_split < 1 ? 1 : max_split); ++ks) {
+        const int64_t per = (nk + ks - 1) / ks;
+        const int64_t eff = (nk + per - 1) / per;  // no empty splits
+        if (eff != ks) continue;
+        const int64_t rounds = (tiles * eff + units - 1) / units;
+        const double cost = (double)rounds * ((double)per + (eff > 1 ? CG_SPLIT_COST_ATOMIC : CG_SPLIT_COST_PLAIN));
+        if (ks == 1 || cost < best_cost * 0.97) {  // a split must pay for itself by a margin
+            best = (int)eff;
+            best_cost = cost;
+        }
     }
-    return ksplit;
+    return best;
 }
 
 static void launch_zero_fill(const GemmParams& p, hipStream_t stream) {
@@ -1117,6 +1136,10 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
 
 hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream) {
     typedef Tile<CG_TILE> T;  // waves along M, waves along N, 32x32 sub-tiles per wave along M, along N
+    // Weight gradients have M = Cout: when the last 128-row tile would be at most half
+    // full, a 64 x 128 block tile wastes fewer MFMAs.
+    if (amode == A_TRANS && bmode == B_PATCH_T && T::BM == 128 && (p.M - 1) % 128 < 64 && p.M <= 448 && p.N > 64)
+        return launch<Tile<2, 4, 1, 1>, A_TRANS, B_PATCH_T>(p, stream);
 #define CG_CASE(A, B) if (amode == A && bmode == B) return launch<T, A, B>(p, stream)
     CG_CASE(A_LINEAR_VEC, B_VEC);
     CG_CASE(A_LINEAR_SCALAR, B_SCALAR);
