@@ -241,24 +241,28 @@ struct PatchRow {
     }
 };
 
-// Filter tap of a 32-word slice when Cin % 32 == 0: the slice never straddles a
-// tap, so (r, s) and the channel offset are uniform over the block and advance
-// by scalar increments as ks grows.
+// Order of the contraction when Cin % 32 == 0.  A 32-word slice never straddles a
+// filter tap, and the order of the slices is free as long as both operands follow it,
+// so the slices are taken channel block by channel block, all taps of one block of 32
+// channels before the next block.  The taps of one channel block read overlapping
+// pixels, so a tile's working set between two uses of the same input word is one
+// 32-channel block of its input rows instead of the whole rows: it stays in the L2
+// cache of the tile's XCD, and every input word is fetched from memory about once
+// instead of once per tap.  Slice ks of the loop is slice `pks` of the filter's own
+// (tap, channel) order.  (r, s), c0 are uniform over the block and advance by scalar
+// increments.
 struct TapCursor {
-    int ks, r, s, c0, tap;
+    int ks, r, s, c0, tap, pks;
     u32 off;  // ((r*W + s)*Cin + c0) * 8: byte offset of the slice relative to the row's pixel (hi0, wi0)
-    __device__ __forceinline__ void reset() { ks = 0; r = 0; s = 0; c0 = 0; tap = 0; off = 0; }
+    __device__ __forceinline__ void reset() { ks = 0; r = 0; s = 0; c0 = 0; tap = 0; pks = 0; off = 0; }
     __device__ __forceinline__ void advance_to(const GemmParams& p, int want) {
         while (ks < want) {  // zero or one step per call in the kernel's load order
             ++ks;
-            c0 += 32;
-            off += 256u;
-            if (c0 == p.Cin) {
-                c0 = 0;
-                ++tap;
-                if (++s == p.kw) { s = 0; ++r; }
-                off = ((u32)r * (u32)p.W + (u32)s) * (u32)p.Cin * 8u;
-            }
+            ++tap;
+            if (++s == p.kw) { s = 0; ++r; }
+            if (r == p.kh) { r = 0; tap = 0; c0 += 32; }  // past the end of K: c0 == Cin
+            off = (((u32)r * (u32)p.W + (u32)s) * (u32)p.Cin + (u32)c0) * 8u;
+            pks = (tap * p.Cin + c0) >> 5;
         }
     }
 };
@@ -287,9 +291,9 @@ struct ConvC32 {
                                          u4 out[2]) const {
         bool v;
         if (p.kh * p.kw <= 64) {  // uniform
-            v = t.tap < 64 && ((inside >> t.tap) & 1);
+            v = t.c0 < p.Cin && ((inside >> t.tap) & 1);
         } else {
-            v = pr.ok && t.r < p.kh && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
+            v = pr.ok && t.c0 < p.Cin && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
         }
         const u32 off = v ? base_kq + t.off : OOB;
         out[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off, 0, 0);
@@ -475,18 +479,22 @@ __device__ __forceinline__ void recode2(u4& v) {
     v.x = a; v.y = b; v.z = c; v.w = d;
 }
 
-// block -> (K split, output tile).  Consecutive block ids go to different XCDs
-// (round robin over 8), so each XCD gets a contiguous run of logical tiles and
-// tiles that share operand rows share one L2.  Inside a run, tiles are taken in
-// groups of group_m tile-rows, tile-row fastest.  With split-K the grid holds
-// ksplit copies of the tile grid, slowest index first.
+// block -> (K split, output tile).  The hardware deals consecutive block ids to the 8
+// XCDs in turn, and each XCD has an L2 cache of its own, so block ids are mapped such
+// that every XCD works through one contiguous run of the launch order
+// (split, group of group_m tile-rows, tile column, tile-row inside the group), split
+// slowest.  With 8 or more splits an XCD therefore sees only its own ranges of K and
+// reads its share of both operands once; with fewer, its run is a box of tile-rows
+// times tile columns whose shape the host picks through group_m.
 __device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int BN, int& split, int& tm, int& tn) {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const int nb = tiles_m * tiles_n;
-    split = blockIdx.x / nb;
-    const int bid = blockIdx.x - split * nb, xcd = bid & 7, idx = bid >> 3;
-    const int per = nb >> 3, rem = nb & 7;
-    const int logical = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    const int total = nb * p.ksplit;
+    const int bid = blockIdx.x, xcd = bid & 7, idx = bid >> 3;
+    const int per = total >> 3, rem = total & 7;
+    const int run = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    split = run / nb;
+    const int logical = run - split * nb;
     const int GM = p.group_m;
     const int per_group = GM * tiles_n;
     const int g = logical / per_group, in_g = logical - g * per_group;
@@ -589,7 +597,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
         } else if constexpr (BMODE == B_FLIP_C32) {
             const int taps = p.kh * p.kw;
-            if (tap.tap >= taps) return make_rsrc(ptr, 0);  // past the end of K
+            if (tap.c0 >= p.Cin) return make_rsrc(ptr, 0);  // past the end of K
             const u64 base = b_base_elems + ((u64)tap.c0 * (u64)taps + (u64)(taps - 1 - tap.tap)) * (u64)p.N;
             return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
         } else if constexpr (BMODE == B_PATCH_T) {
@@ -656,8 +664,10 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     };
     auto load_even = [&](int ks) {
         load_a(a_view(p.x_a, rs_xa, ks), ks, eA);
-        load_b(b_view(p.w_a, rs_wa, ks), ks, eB);
-        load_b(b_view(p.w_b, rs_wb, ks), ks, eB2);
+        // the right operand follows the left operand's slice order (see TapCursor)
+        const int kb = AMODE == A_CONV_C32 ? tap.pks : ks;
+        load_b(b_view(p.w_a, rs_wa, ks), kb, eB);
+        load_b(b_view(p.w_b, rs_wb, ks), kb, eB2);
     };
     // w_a of a slice is fetched once, with the even set; the odd set's copy is
     // taken from there before the even set is summed and recoded.
@@ -878,7 +888,7 @@ struct PlanesConv {
         c16 = (u32)c * 16u;
     }
     __device__ __forceinline__ u4 load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int, const TapCursor& t) const {
-        const bool v = pr.ok && t.r < p.kh && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
+        const bool v = pr.ok && t.c0 < p.Cin && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
         // a pixel's Cin words occupy Cin*8 bytes of planes; slice c0/32 starts at c0*8 bytes
         return __builtin_amdgcn_raw_buffer_load_b128(rs_, v ? pr.base + t.off + c16 : OOB, 0, 0);
     }
@@ -944,10 +954,11 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_planes_kernel(
     u4 eA[AP], eB[BP], oA[AP], oB[BP];
     auto load_set = [&](__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, int ks, u4* da, u4* db) {
         if (CONV) tap.advance_to(p, ks);
+        const int kb = CONV ? tap.pks : ks;  // the right operand follows the left operand's slice order
 #pragma unroll
         for (int i = 0; i < AP; ++i) da[i] = ag[i].load(p, ra, ks, tap);
 #pragma unroll
-        for (int i = 0; i < BP; ++i) db[i] = bg[i].load(p, rb, ks, tap);
+        for (int i = 0; i < BP; ++i) db[i] = bg[i].load(p, rb, kb, tap);
     };
     auto load_even = [&](int ks) { load_set(rs_a0, rs_b0, ks, eA, eB); };
     auto load_odd = [&](int ks) { load_set(rs_a1, rs_b1, ks, oA, oB); };
@@ -1091,6 +1102,38 @@ static int choose_ksplit(int64_t tiles, int nk) {
     return best;
 }
 
+// Tile-rows per launch-order group.  An XCD's run of `run` consecutive tiles covers
+// rows x cols tiles and fetches that many tile-rows of the left operand's tensor and
+// tile-columns of the right operand's (of the split's K range); the group height that
+// minimises the bytes wins (ties go to the smaller group, which keeps the tiles that
+// run at the same time closer together).  For a convolution the left tensor is the
+// image, not the (kh*kw times larger) patch matrix: the taps of a tile hit in L2.
+static int choose_group_m(const GemmParams& p, int64_t tiles_m, int64_t tiles_n, int ksplit) {
+    const double a_row = (double)p.x_elems / (double)tiles_m, b_col = (double)p.w_elems / (double)tiles_n;
+    const int64_t nb = tiles_m * tiles_n;
+    int64_t run = nb * ksplit / 8;
+    if (run < 1) run = 1;
+    if (run >= nb) return tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);  // whole splits per XCD: shape is irrelevant
+    int best = 1;
+    double best_cost = -1;
+    for (int64_t g = 1; g <= tiles_m; g *= 2) {
+        int64_t rows, cols;
+        if (run <= g * tiles_n) {
+            rows = run < g ? run : g;
+            cols = (run + g - 1) / g;
+        } else {
+            rows = g * ((run + g * tiles_n - 1) / (g * tiles_n));
+            cols = tiles_n;
+        }
+        const double cost = (double)rows * a_row + (double)cols * b_col;
+        if (best_cost < 0 || cost < best_cost) {
+            best = (int)g;
+            best_cost = cost;
+        }
+    }
+    return best;
+}
+
 static void launch_zero_fill(const GemmParams& p, hipStream_t stream) {
     const size_t n = (size_t)p.M * (size_t)p.N;
     size_t blocks = (n + 255) / 256;
@@ -1113,8 +1156,8 @@ hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t 
     typedef Tile<CG_TILE> T;
     const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
     GemmParams q = p;
-    q.group_m = tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);
     q.ksplit = choose_ksplit(tiles_m * tiles_n, (p.K + 31) / 32);
+    q.group_m = choose_group_m(p, tiles_m, tiles_n, q.ksplit);
     if (q.ksplit > 1) launch_zero_fill(q, stream);
     const dim3 grid((unsigned)(tiles_m * tiles_n * q.ksplit));
     if (conv) hipLaunchKernelGGL((share_gemm_planes_kernel<T, true>), grid, dim3(T::NT), 0, stream, q);
@@ -1126,8 +1169,8 @@ template <class T, int AMODE, int BMODE>
 static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
     GemmParams q = p;
-    q.group_m = tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);
     q.ksplit = choose_ksplit(tiles_m * tiles_n, (p.K + 31) / 32);
+    q.group_m = choose_group_m(p, tiles_m, tiles_n, q.ksplit);
     if (q.ksplit > 1) launch_zero_fill(q, stream);
     hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BMODE>), dim3((unsigned)(tiles_m * tiles_n * q.ksplit)),
                        dim3(T::NT), 0, stream, q);
