@@ -508,6 +508,50 @@ int oracle_reshare(const u64 *z, const uint8_t key_self[16], const uint8_t key_p
     return 0;
 }
 
+/* ---- rescaling after a product (Sec. III-B "Multiplication": the two-round share
+ * truncation cited from ABY3, which the paper names but does not list) -------------
+ * Reading adopted here.  The parties hold the blinded additive shares
+ * z'_i = z_i + alpha_i of the product.  P_2 sends z'_2 to P_1 (round 1), so that
+ * (z'_0, z'_1 + z'_2) is a two-party additive sharing of z held by P_0 and P_1.  Each
+ * of the two divides its summand by 2^d as a SIGNED integer, rounding down (an
+ * arithmetic shift), which changes the shared value by at most one unit in the last
+ * place unless the two summands wrap, an event of probability about |z| / 2^63.  P_1
+ * and P_2 share the key k_1 and draw r_j = F(k_1, j) from it.  The new shares are
+ *   s_0 = (z'_0) >> d,   s_1 = ((z'_1 + z'_2) >> d) - r,   s_2 = r,
+ * and P_1 sends s_1 to P_0, P_0 sends s_0 to P_2 (round 2), which restores the
+ * replicated form (s_i, s_{i+1}).
+ *
+ * One routine covers every party's local step:
+ *   out[j] = asr64(z[j] + alpha[j] + (msg ? msg[j] : 0), d) - (key_mask ? F(key_mask, first + j) : 0)
+ * with alpha[j] = F(key_self, first + j) - F(key_prev, first + j) under `nonce` and the
+ * mask stream under `mask_nonce`.  d in [0, 63]. */
+static u64 asr64(u64 v, int d)
+{
+    /* floor(v / 2^d) for v read as a two's-complement integer, without relying on the
+     * implementation-defined right shift of negative values */
+    if (d == 0) return v;
+    const u64 shifted = v >> d;
+    const u64 sign_fill = (v >> 63) ? (~(u64)0) << (64 - d) : 0;
+    return shifted | sign_fill;
+}
+
+int oracle_trunc1_local(const u64 *z, const u64 *msg, const uint8_t key_self[16], const uint8_t key_prev[16],
+                        u64 nonce, u64 first, int d, const uint8_t *key_mask, u64 mask_nonce,
+                        u64 *out, size_t n)
+{
+    if (d < 0 || d > 63) return -2;
+    u64 *a = (u64 *)malloc((n ? n : 1) * sizeof(u64)), *r = (u64 *)malloc((n ? n : 1) * sizeof(u64));
+    if (!a || !r) { free(a); free(r); return -1; }
+    if (oracle_zero_share(key_self, key_prev, nonce, first, a, n)) { free(a); free(r); return -1; }
+    if (key_mask) oracle_prf_words(key_mask, mask_nonce, first, r, n);
+    for (size_t j = 0; j < n; ++j) {
+        const u64 sum = z[j] + a[j] + (msg ? msg[j] : 0);
+        out[j] = asr64(sum, d) - (key_mask ? r[j] : 0);
+    }
+    free(a); free(r);
+    return 0;
+}
+
 /* =========================================================================
  * Other local linear-layer pieces on replicated shares.
  * ========================================================================= */

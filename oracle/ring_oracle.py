@@ -78,6 +78,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_zero_share.restype = ctypes.c_int
         L.oracle_reshare.argtypes = [_u64p, u8p, u8p, ctypes.c_uint64, ctypes.c_uint64, _u64p, _sz]
         L.oracle_reshare.restype = ctypes.c_int
+        L.oracle_trunc1_local.argtypes = [_u64p, _u64p, u8p, u8p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int,
+                                          u8p, ctypes.c_uint64, _u64p, _sz]
+        L.oracle_trunc1_local.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -312,6 +315,34 @@ def reshare(z, key_self: bytes, key_prev: bytes, nonce: int, first: int) -> np.n
     if lib().oracle_reshare(_p(z), _key(key_self), _key(key_prev), nonce, first, _p(out), z.size):
         raise MemoryError("oracle_reshare")
     return out
+
+
+def trunc1_local(z, msg, key_self: bytes, key_prev: bytes, nonce: int, first: int, d: int,
+                 key_mask=None, mask_nonce: int = 0) -> np.ndarray:
+    """One party's local step of the share truncation: asr(z + alpha + msg, d) - F(key_mask, .)."""
+    z = _u(z)
+    m = None if msg is None else _u(msg)
+    out = np.empty(z.shape, dtype=np.uint64)
+    rc = lib().oracle_trunc1_local(_p(z), None if m is None else _p(m), _key(key_self), _key(key_prev), nonce, first,
+                                   d, None if key_mask is None else _key(key_mask), mask_nonce, _p(out), z.size)
+    if rc != 0:
+        raise MemoryError("oracle_trunc1_local") if rc == -1 else ValueError("shift outside [0, 63]")
+    return out
+
+
+def trunc1_protocol(z, keys, nonce: int, first: int, d: int, mask_nonce: int):
+    """All three parties' steps of the two-round share truncation on the additive product shares
+    z = (z_0, z_1, z_2); keys = (k_0, k_1, k_2), P_i holding k_i and k_{i-1}.  Messages are plain
+    assignments here.  Returns the new shares (s_0, s_1, s_2); P_i ends up with (s_i, s_{i+1})."""
+    k0, k1, k2 = keys
+    # round 1: P_2 blinds its share and sends it to P_1
+    msg = reshare(z[2], k2, k1, nonce, first)
+    # local steps
+    s0 = trunc1_local(z[0], None, k0, k2, nonce, first, d)                       # P_0
+    s1 = trunc1_local(z[1], msg, k1, k0, nonce, first, d, k1, mask_nonce)        # P_1 (mask key shared with P_2)
+    s2 = prf_words(k1, mask_nonce, first, _u(z[2]).size).reshape(_u(z[2]).shape)  # P_2 and P_1: the mask itself
+    # round 2: P_1 -> P_0: s1, P_0 -> P_2: s0 (no arithmetic)
+    return s0, s1, s2
 
 
 def party_mul(x_i, x_ip1, y_i, y_ip1) -> np.ndarray:
