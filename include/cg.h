@@ -288,6 +288,45 @@ CG_API cg_status cg_reshare(const uint64_t *z_i, const uint8_t *key_self, const 
                      uint64_t nonce, uint64_t first, uint64_t *out, size_t n, void *stream);
 
 /*
+ * Rescaling after a product (Sec. III-B "Multiplication": after a product of
+ * fixed-point encodings the parties divide by the scaling factor with the two-round
+ * share truncation of ABY3, which the paper names without listing its steps).  The
+ * reading implemented here, for parties P_0, P_1, P_2 holding the additive product
+ * shares z_0, z_1, z_2 and PRF keys as above (P_i: k_i and k_{i-1}):
+ *
+ *   round 1   P_2 sends m = z_2 + alpha_2 to P_1                     (cg_reshare)
+ *   local     P_0: s_0 = asr(z_0 + alpha_0, d)
+ *             P_1: s_1 = asr(z_1 + alpha_1 + m, d) - F(k_1, first + j)   (mask stream)
+ *             P_1, P_2: s_2 = F(k_1, first + j)                      (cg_prf_words)
+ *   round 2   P_1 sends s_1 to P_0, P_0 sends s_0 to P_2
+ *
+ * where asr is the signed (two's-complement, rounding down) shift of the 64-bit
+ * word.  P_i ends with (s_i, s_{i+1}).  The opened result differs from
+ * floor(z / 2^d) by at most one unit in the last place unless the two summands
+ * z_0 + alpha_0 and z_1 + alpha_1 + m wrap as signed integers, which happens with
+ * probability about |z| / 2^63 per element.
+ *
+ *   cg_trunc1_local : out[j] = asr(z_i[j] + alpha[j] + (msg ? msg[j] : 0), d)
+ *                              - (key_mask ? F(key_mask, first + j) : 0),   j < n
+ *       alpha as in cg_zero_share under `nonce`; the mask stream uses the same
+ *       indices under `mask_nonce`, which must differ from `nonce` when key_mask is
+ *       one of the two alpha keys.  msg and key_mask may be NULL.  d in [0, 63]
+ *       (CG_ERR_SHAPE otherwise).  out may equal z_i or msg; partial overlap is
+ *       CG_ERR_ALIAS.
+ *   cg_prf_words    : out[j] = F(key, first + j), j < n: the raw PRF stream.
+ *
+ * Keys are 16-byte AES-128 keys in HOST memory; z_i, msg, out are device pointers,
+ * 8-byte aligned.  n == 0 returns CG_OK.
+ */
+CG_API cg_status cg_trunc1_local(const uint64_t *z_i, const uint64_t *msg,
+                          const uint8_t *key_self, const uint8_t *key_prev, uint64_t nonce,
+                          uint64_t first, int d, const uint8_t *key_mask, uint64_t mask_nonce,
+                          uint64_t *out, size_t n, void *stream);
+
+CG_API cg_status cg_prf_words(const uint8_t *key, uint64_t nonce, uint64_t first,
+                       uint64_t *out, size_t n, void *stream);
+
+/*
  * out = s0 + s1 + s2 (mod 2^64), element-wise over n (Sec. III-B, "Secret
  * sharing").  Opens a replicated sharing (pass its three distinct shares) and
  * equally the three parties' additive outputs z_0, z_1, z_2 of

@@ -24,6 +24,7 @@ EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d
            "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct",
            "cg_share_matmul_ws", "cg_share_conv2d_ws", "cg_zero_share", "cg_reshare", "cg_share_matmul_t",
            "cg_share_mul", "cg_share_sum_pool2d", "cg_share_conv2d_dgrad", "cg_share_conv2d_wgrad",
+           "cg_trunc1_local", "cg_prf_words",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -78,11 +79,13 @@ def lib() -> ctypes.CDLL:
         L.cg_share_matmul_t.argtypes = [vp] * 5 + [i64] * 3 + [ctypes.c_int] * 2 + [vp]
         L.cg_share_mul.argtypes = [vp] * 5 + [sz, sz, vp]
         L.cg_share_sum_pool2d.argtypes = [vp] * 4 + [ctypes.POINTER(PoolDesc), vp]
+        L.cg_trunc1_local.argtypes = [vp, vp, key, key, u64, u64, ctypes.c_int, key, u64, vp, sz, vp]
+        L.cg_prf_words.argtypes = [key, u64, u64, vp, sz, vp]
         L.cg_share_conv2d_dgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
         L.cg_share_conv2d_wgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
-        for name in EXPORTS[2:17]:
+        for name in EXPORTS[2:19]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[17:]:
+        for name in EXPORTS[19:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -366,6 +369,29 @@ def cg_reshare(z_i, key_self: bytes, key_prev: bytes, nonce: int, first: int = 0
     n = z_i.numel()
     _check(lib().cg_reshare(_ptr(z_i) if n else 0, _key16(key_self), _key16(key_prev), nonce % (1 << 64),
                             first % (1 << 64), _ptr(out) if n else 0, n, _stream(stream)), "cg_reshare")
+    return out
+
+
+def cg_trunc1_local(z_i, msg, key_self: bytes, key_prev: bytes, nonce: int, first: int, d: int,
+                    key_mask=None, mask_nonce: int = 0, out=None, stream=None) -> torch.Tensor:
+    """One party's local step of the share truncation: asr(z_i + alpha + msg, d) - F(key_mask, .)."""
+    if msg is not None and msg.shape != z_i.shape:
+        raise ValueError("message shape does not match")
+    if out is None:
+        out = torch.empty_like(z_i)
+    _check(lib().cg_trunc1_local(_ptr(z_i), None if msg is None else _ptr(msg), _key16(key_self), _key16(key_prev),
+                                 nonce, first, d, None if key_mask is None else _key16(key_mask), mask_nonce,
+                                 _ptr(out), z_i.numel(), _stream(stream)), "cg_trunc1_local")
+    return out
+
+
+def cg_prf_words(key: bytes, nonce: int, first: int, n: int, out=None, stream=None) -> torch.Tensor:
+    """F(key, first + j) for j < n as a GPU tensor."""
+    if out is None:
+        out = torch.empty((n,), dtype=torch.int64, device="cuda")
+    elif out.numel() != n:
+        raise ValueError("output size does not match")
+    _check(lib().cg_prf_words(_key16(key), nonce, first, _ptr(out) if n else None, n, _stream(stream)), "cg_prf_words")
     return out
 
 

@@ -775,6 +775,33 @@ cg_status cg_reshare(const uint64_t* z_i, const uint8_t* key_self, const uint8_t
     return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
 
+cg_status cg_prf_words(const uint8_t* key, uint64_t nonce, uint64_t first, uint64_t* out, size_t n, void* stream) {
+    if (!key) return CG_ERR_NULL;
+    if (n == 0) return CG_OK;
+    if (!out) return CG_ERR_NULL;
+    if (!aligned(out, 8)) return CG_ERR_ALIGN;
+    if (n > (SIZE_MAX >> 4) || first + n < first) return CG_ERR_SHAPE;
+    const hipError_t e = cg::launch_prf_combine(nullptr, nullptr, out, n, nullptr, nullptr, 0, first, 0, key, nonce,
+                                                true, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+cg_status cg_trunc1_local(const uint64_t* z_i, const uint64_t* msg, const uint8_t* key_self, const uint8_t* key_prev,
+                          uint64_t nonce, uint64_t first, int d, const uint8_t* key_mask, uint64_t mask_nonce,
+                          uint64_t* out, size_t n, void* stream) {
+    if (!key_self || !key_prev) return CG_ERR_NULL;
+    if (d < 0 || d > 63) return CG_ERR_SHAPE;
+    if (n == 0) return CG_OK;
+    if (!z_i || !out) return CG_ERR_NULL;
+    if (!aligned(z_i, 8) || !aligned(out, 8) || (msg && !aligned(msg, 8))) return CG_ERR_ALIGN;
+    if (n > (SIZE_MAX >> 4) || first + n < first) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    if (bad_overlap(out, z_i, bytes) || (msg && bad_overlap(out, msg, bytes))) return CG_ERR_ALIAS;
+    const hipError_t e = cg::launch_prf_combine(z_i, msg, out, n, key_self, key_prev, nonce, first, d, key_mask,
+                                                mask_nonce, false, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
 cg_status cg_reconstruct(const uint64_t* s0, const uint64_t* s1, const uint64_t* s2, uint64_t* out,
                          size_t n, void* stream) {
     if (n == 0) return CG_OK;  // nothing to do: pointers are not looked at

@@ -83,7 +83,7 @@ void expand_key(const uint8_t key[16], u32 rk[44]) {
 }
 
 struct PrfKeys {
-    u32 self[44], prev[44];
+    u32 self[44], prev[44], mask[44];
 };
 
 // ---- device ------------------------------------------------------------------
@@ -120,10 +120,18 @@ struct T0Table {
     u32 v[256];
 };
 
-// words [first, first + n) of alpha, optionally added to z (z == nullptr: alpha alone)
-__global__ __launch_bounds__(256) void zero_share_kernel(const u64* __restrict__ z, u64* __restrict__ out, size_t n,
-                                                         u64 first, u64 nonce, const PrfKeys keys,
-                                                         const T0Table table) {
+// floor(v / 2^d) of v read as a two's-complement integer
+__device__ __forceinline__ u64 asr64(u64 v, int d) { return (u64)((int64_t)v >> d); }
+
+// For the words j = first .. first + n - 1 of the PRF streams:
+//   out = asr64((z ? z : 0) + (msg ? msg : 0) + [ALPHA] (F(self, j) - F(prev, j)), d)  -/+  [MASK] F(mask, j)
+// (alpha under `nonce`, the mask stream under `mask_nonce`; the mask is subtracted unless add_mask).
+// One thread handles one AES block = two consecutive words of each stream.
+template <bool ALPHA, bool MASK>
+__global__ __launch_bounds__(256) void prf_combine_kernel(const u64* __restrict__ z, const u64* __restrict__ msg,
+                                                          u64* __restrict__ out, size_t n, u64 first, u64 nonce,
+                                                          u64 mask_nonce, int d, bool add_mask, const PrfKeys keys,
+                                                          const T0Table table) {
     __shared__ u32 t0_all[256 * 64];
     {
         const u32 mine = table.v[threadIdx.x];
@@ -136,33 +144,68 @@ __global__ __launch_bounds__(256) void zero_share_kernel(const u64* __restrict__
     const u64 nblocks = b_last - b_first + 1;
     for (u64 bi = (u64)blockIdx.x * 256 + threadIdx.x; bi < nblocks; bi += (u64)gridDim.x * 256) {
         const u64 block = b_first + bi;
-        u32 a[4], b[4];
-        aes_block(t0, keys.self, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), a);
-        aes_block(t0, keys.prev, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), b);
-        const u64 w0 = (((u64)a[1] << 32) | a[0]) - (((u64)b[1] << 32) | b[0]);
-        const u64 w1 = (((u64)a[3] << 32) | a[2]) - (((u64)b[3] << 32) | b[2]);
+        u64 w0 = 0, w1 = 0, r0 = 0, r1 = 0;
+        if constexpr (ALPHA) {
+            u32 a[4], b[4];
+            aes_block(t0, keys.self, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), a);
+            aes_block(t0, keys.prev, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), b);
+            w0 = (((u64)a[1] << 32) | a[0]) - (((u64)b[1] << 32) | b[0]);
+            w1 = (((u64)a[3] << 32) | a[2]) - (((u64)b[3] << 32) | b[2]);
+        }
+        if constexpr (MASK) {
+            u32 m[4];
+            aes_block(t0, keys.mask, (u32)block, (u32)(block >> 32), (u32)mask_nonce, (u32)(mask_nonce >> 32), m);
+            r0 = ((u64)m[1] << 32) | m[0];
+            r1 = ((u64)m[3] << 32) | m[2];
+            if (!add_mask) { r0 = 0 - r0; r1 = 0 - r1; }
+        }
         const u64 j0 = 2 * block, j1 = j0 + 1;  // word indices
-        if (j0 >= first && j0 - first < n) out[j0 - first] = (z ? z[j0 - first] : 0) + w0;
-        if (j1 >= first && j1 - first < n) out[j1 - first] = (z ? z[j1 - first] : 0) + w1;
+        if (j0 >= first && j0 - first < n) {
+            const size_t j = j0 - first;
+            out[j] = asr64((z ? z[j] : 0) + (msg ? msg[j] : 0) + w0, d) + r0;
+        }
+        if (j1 >= first && j1 - first < n) {
+            const size_t j = j1 - first;
+            out[j] = asr64((z ? z[j] : 0) + (msg ? msg[j] : 0) + w1, d) + r1;
+        }
     }
 }
 
 }  // namespace
 
-hipError_t launch_zero_share(const uint64_t* z, uint64_t* out, size_t n, const uint8_t key_self[16],
-                             const uint8_t key_prev[16], uint64_t nonce, uint64_t first, hipStream_t stream) {
+hipError_t launch_prf_combine(const uint64_t* z, const uint64_t* msg, uint64_t* out, size_t n,
+                              const uint8_t* key_self, const uint8_t* key_prev, uint64_t nonce, uint64_t first, int d,
+                              const uint8_t* key_mask, uint64_t mask_nonce, bool add_mask, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    PrfKeys keys;
-    expand_key(key_self, keys.self);
-    expand_key(key_prev, keys.prev);
+    const bool alpha = key_self && key_prev, mask = key_mask != nullptr;
+    if (!alpha && !mask) return hipErrorInvalidValue;
+    PrfKeys keys = {};
+    if (alpha) {
+        expand_key(key_self, keys.self);
+        expand_key(key_prev, keys.prev);
+    }
+    if (mask) expand_key(key_mask, keys.mask);
     T0Table table;
     memcpy(table.v, tables().t0, sizeof(table.v));
     const size_t nblocks = (n + 1) / 2 + 1;
     size_t grid = (nblocks + 255) / 256;
     if (grid > 256 * 8) grid = 256 * 8;
-    hipLaunchKernelGGL(zero_share_kernel, dim3((unsigned)grid), dim3(256), 0, stream, z, out, n, (u64)first,
-                       (u64)nonce, keys, table);
+    const dim3 g((unsigned)grid), b(256);
+    if (alpha && mask)
+        hipLaunchKernelGGL((prf_combine_kernel<true, true>), g, b, 0, stream, z, msg, out, n, (u64)first, (u64)nonce,
+                           (u64)mask_nonce, d, add_mask, keys, table);
+    else if (alpha)
+        hipLaunchKernelGGL((prf_combine_kernel<true, false>), g, b, 0, stream, z, msg, out, n, (u64)first, (u64)nonce,
+                           (u64)mask_nonce, d, add_mask, keys, table);
+    else
+        hipLaunchKernelGGL((prf_combine_kernel<false, true>), g, b, 0, stream, z, msg, out, n, (u64)first, (u64)nonce,
+                           (u64)mask_nonce, d, add_mask, keys, table);
     return hipGetLastError();
+}
+
+hipError_t launch_zero_share(const uint64_t* z, uint64_t* out, size_t n, const uint8_t key_self[16],
+                             const uint8_t key_prev[16], uint64_t nonce, uint64_t first, hipStream_t stream) {
+    return launch_prf_combine(z, nullptr, out, n, key_self, key_prev, nonce, first, 0, nullptr, 0, false, stream);
 }
 
 }  // namespace cg

@@ -1,0 +1,112 @@
+"""GPU parity of the share-truncation step (local arithmetic of every party, through the C-ABI)
+against the CPU oracle, bit for bit, and the protocol's error bound on the opened result."""
+import numpy as np
+import pytest
+
+from tests.gpu_util import first_mismatch, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+K0, K1, K2 = bytes(range(16)), bytes(range(16, 32)), bytes(range(32, 48))
+
+
+@pytest.fixture(scope="module")
+def cg():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2104_10949_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ro():
+    from oracle import ring_oracle
+    return ring_oracle
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_2104_10949_amd import workloads
+    return workloads
+
+
+@pytest.mark.parametrize("n,first", [(1, 0), (1, 1), (2, 1), (3, 4), (255, 7), (256, 0), (1001, 3), ((1 << 20) + 5, 2 ** 40 + 1)])
+def test_prf_words_match_the_oracle(cg, ro, n, first):
+    say(f"cg_prf_words n={n} first={first}")
+    got = cg.to_host(cg.cg_prf_words(K1, 77, first, n))
+    assert not first_mismatch(got, ro.prf_words(K1, 77, first, n))
+
+
+@pytest.mark.parametrize("d", [0, 1, 16, 20, 63])
+@pytest.mark.parametrize("n,first", [(1, 0), (2, 1), (257, 5), (100003, 8)])
+def test_local_step_matches_the_oracle(cg, ro, wl, n, first, d):
+    say(f"cg_trunc1_local n={n} first={first} d={d}")
+    z, m = wl.draw_ring((n,), 900 + n), wl.draw_ring((n,), 901 + n)
+    dz, dm = cg.to_device(z), cg.to_device(m)
+    # P_1's step: message and mask
+    got = cg.to_host(cg.cg_trunc1_local(dz, dm, K1, K0, 31, first, d, K1, 32))
+    assert not first_mismatch(got, ro.trunc1_local(z, m, K1, K0, 31, first, d, K1, 32))
+    # P_0's step: neither
+    got = cg.to_host(cg.cg_trunc1_local(dz, None, K0, K2, 31, first, d))
+    assert not first_mismatch(got, ro.trunc1_local(z, None, K0, K2, 31, first, d))
+    # in place over z
+    out = cg.cg_trunc1_local(dz, dm, K1, K0, 31, first, d, K1, 32, out=dz)
+    assert out.data_ptr() == dz.data_ptr()
+    assert not first_mismatch(cg.to_host(dz), ro.trunc1_local(z, m, K1, K0, 31, first, d, K1, 32))
+
+
+def test_local_step_on_edge_words(cg, ro):
+    edge = np.array([0, 1, 0xFFFF, 0x10000, (1 << 63) - 1, 1 << 63, (1 << 63) + 1, (1 << 64) - 1, (1 << 64) - 0x10001,
+                     0x8080808080808080, 0x7F7F7F7F7F7F7F7F], dtype=np.uint64)
+    same = bytes(16)
+    for d in (0, 1, 16, 63):
+        say(f"cg_trunc1_local edge words d={d}")
+        got = cg.to_host(cg.cg_trunc1_local(cg.to_device(edge), None, same, same, 0, 0, d))
+        assert not first_mismatch(got, ro.trunc1_local(edge, None, same, same, 0, 0, d))
+
+
+def test_product_then_truncation_opens_to_the_fixed_point_product(cg, ro, wl):
+    # three parties: local product, blinded message, local truncation steps; opened result vs the real product
+    M, N, K, t = 48, 40, 96, wl.FRAC_BITS
+    say(f"matmul + truncation, three parties, {M}x{N}x{K}")
+    rng = np.random.default_rng(1234)
+    xr, yr = rng.uniform(-1, 1, (M, K)), rng.normal(0, 0.05, (N, K))
+    x, y = ro.encode(xr, t), ro.encode(yr, t)
+    sx = ro.share(x, wl.draw_ring(x.shape, 1), wl.draw_ring(x.shape, 2))
+    sy = ro.share(y, wl.draw_ring(y.shape, 3), wl.draw_ring(y.shape, 4))
+    keys = (K0, K1, K2)
+    z = []
+    for i in range(3):
+        ops = [cg.to_device(a) for a in (*ro.party_pair(sx, i), *ro.party_pair(sy, i))]
+        z.append(cg.cg_share_matmul(*ops))
+    n = M * N
+    msg = cg.cg_reshare(z[2], K2, K1, 5, 0)                                   # round 1: P_2 -> P_1
+    s0 = cg.cg_trunc1_local(z[0], None, K0, K2, 5, 0, t)                      # P_0
+    s1 = cg.cg_trunc1_local(z[1], msg, K1, K0, 5, 0, t, K1, 6)                # P_1
+    s2 = cg.cg_prf_words(K1, 6, 0, n).view(M, N)                              # P_1 and P_2
+    torch.cuda.synchronize()
+    # bit-exact against the oracle's run of the same protocol on the oracle's products
+    zo = [ro.party_matmul(*ro.party_pair(sx, i), *ro.party_pair(sy, i)) for i in range(3)]
+    so = ro.trunc1_protocol(zo, keys, nonce=5, first=0, d=t, mask_nonce=6)
+    for got, want in zip((s0, s1, s2), so):
+        assert not first_mismatch(cg.to_host(got), want)
+    # and the opened value is the product at scale 2^t, at most one unit below the floor
+    opened = cg.to_host(cg.cg_reconstruct(s0, s1, s2)).astype(np.int64)
+    exact = (ro.matmul(x, y).astype(np.int64)) >> t
+    assert set(np.unique(opened - exact).tolist()) <= {-1, 0}
+    real = (np.rint(xr * 2 ** t) / 2 ** t) @ (np.rint(yr * 2 ** t) / 2 ** t).T
+    assert np.max(np.abs(opened / 2 ** t - real)) <= 2.0 ** -t * 2
+
+
+def test_truncation_argument_errors(cg):
+    z = torch.zeros(16, dtype=torch.int64, device="cuda")
+    for d in (-1, 64):
+        with pytest.raises(cg.CgError) as e:
+            cg.cg_trunc1_local(z, None, K0, K2, 0, 0, d)
+        assert e.value.status == cg.CG_ERR_SHAPE
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_trunc1_local(z[:8], None, K0, K2, 0, 0, 16, out=z[4:12])
+    assert e.value.status == cg.CG_ERR_ALIAS
