@@ -51,10 +51,94 @@ def parse_args():
     ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the register-only MFMA issue-rate measurement")
+    ap.add_argument("--extras", action="store_true",
+                    help="after the step, also time the rows outside the five configurations (square share products, "
+                         "the paper's Fig. 1 convolution shapes, backward products, element-wise and PRF kernels) and "
+                         "add them to the JSON line under \"extras\"")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of "
                          "known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
+
+
+def measure_extras(torch, cg, wl, config_layers):
+    """Rows outside the timed step: every figure is the mean of 10 launches after 3 warm-ups, HIP events on the
+    launch stream, uniform random words resident in HBM."""
+    def rnd(shape, seed):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed)
+        return torch.randint(-2 ** 63, 2 ** 63 - 1, tuple(shape), dtype=torch.int64, device="cuda", generator=g)
+
+    def timed(fn, warm=3, iters=10):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters
+
+    def row(name, mnk, ms):
+        tops = 2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * mnk / (ms * 1e-3) / 1e12
+        return {"name": name, "ms": round(ms, 4), "ring_macs_per_s": 3.0 * mnk / (ms * 1e-3),
+                "int8_tops": round(tops, 1), "frac_of_peak": round(tops / INT8_PEAK_TOPS, 4)}
+
+    out = {"square_products": [], "fig1_conv_shapes": [], "backward_config4": [], "streaming": []}
+    for M, N, K in [(1024, 1024, 1024), (4096, 4096, 4096), (8192, 8192, 2048), (8192, 8192, 8192)]:
+        ops = [rnd((M, K), 1), rnd((M, K), 2), rnd((N, K), 3), rnd((N, K), 4)]
+        z = torch.empty((M, N), dtype=torch.int64, device="cuda")
+        out["square_products"].append(row(f"matmul {M}x{N}x{K}", M * N * K, timed(lambda: cg.cg_share_matmul(*ops, z_i=z))))
+        del ops, z
+    # shapes of the paper's Fig. 1 (its times are whole-protocol times on three V100s over a LAN: context only)
+    fig1 = [("11x11 3->64 s4 p2", (1, n, n, 3), (64, 11, 11, 3), 4, 2) for n in (64, 128, 256, 512)]
+    fig1 += [("11x11 3->64 s4 p2 on 32x32x3", (b, 32, 32, 3), (64, 11, 11, 3), 4, 2) for b in (32, 128, 512)]
+    fig1 += [("3x3 512->512 p1", (1, n, n, 512), (512, 3, 3, 512), 1, 1) for n in (8, 16, 32, 64)]
+    for name, xs, ws, st, pd in fig1:
+        ops = [rnd(xs, 1), rnd(xs, 2), rnd(ws, 3), rnd(ws, 4)]
+        zs = cg.conv_out_shape(xs, ws, (st, st), (pd, pd))
+        z = torch.empty(zs, dtype=torch.int64, device="cuda")
+        ms = timed(lambda: cg.cg_share_conv2d(*ops, stride=(st, st), pad=(pd, pd), z_i=z))
+        out["fig1_conv_shapes"].append(row(f"{name}, input {xs[0]}x{xs[1]}x{xs[2]}x{xs[3]}",
+                                           zs[0] * zs[1] * zs[2] * ws[0] * ws[1] * ws[2] * ws[3], ms))
+        del ops, z
+    # forward / input-gradient / weight-gradient products of the configuration's convolution layers
+    tot = {"forward": 0.0, "dgrad": 0.0, "wgrad": 0.0}
+    mnk = 0
+    for L in config_layers:
+        if L.kind != "conv":
+            continue
+        xs, ws, zs = L.x_shape, L.w_shape, L.z_shape
+        g, w, x = [rnd(zs, 1), rnd(zs, 2)], [rnd(ws, 3), rnd(ws, 4)], [rnd(xs, 5), rnd(xs, 6)]
+        dx, dw = torch.empty(xs, dtype=torch.int64, device="cuda"), torch.empty(ws, dtype=torch.int64, device="cuda")
+        z = torch.empty(zs, dtype=torch.int64, device="cuda")
+        st, pd = (L.stride, L.stride), (L.pad, L.pad)
+        tot["forward"] += timed(lambda: cg.cg_share_conv2d(*x, *w, stride=st, pad=pd, z_i=z)) * L.repeat
+        tot["dgrad"] += timed(lambda: cg.cg_share_conv2d_dgrad(*g, *w, xs, stride=st, pad=pd, dx_i=dx)) * L.repeat
+        tot["wgrad"] += timed(lambda: cg.cg_share_conv2d_wgrad(*g, *x, ws, stride=st, pad=pd, dw_i=dw)) * L.repeat
+        mnk += L.mnk * L.repeat
+        del g, w, x, dx, dw, z
+    for k, ms in tot.items():
+        out["backward_config4"].append(row(f"{k}, all convolution layers", mnk, ms))
+    # HBM- and ALU-bound kernels next to the products; n words per stream, beyond the 256 MB last-level cache
+    n = 1 << 26
+    a, b, c, d = (rnd((n,), s) for s in (1, 2, 3, 4))
+    o1, o2 = torch.empty_like(a), torch.empty_like(a)
+    k0, k1 = bytes(range(16)), bytes(range(16, 32))
+    for name, nbytes, fn in [
+        ("cg_share_add", 48, lambda: cg.cg_share_add(a, b, c, d, za=o1, zb=o2)),
+        ("cg_share_mul_public", 32, lambda: cg.cg_share_mul_public(a, b, 12345, za=o1, zb=o2)),
+        ("cg_reconstruct", 32, lambda: cg.cg_reconstruct(a, b, c, out=o1)),
+        ("cg_share_mul", 40, lambda: cg.cg_share_mul(a, b, c, d, z_i=o1)),
+        ("cg_reshare", 16, lambda: cg.cg_reshare(a, k0, k1, 1, 0, out=o1)),
+        ("cg_trunc1_local (message, mask)", 24, lambda: cg.cg_trunc1_local(a, b, k1, k0, 1, 0, 16, k1, 2, out=o1)),
+    ]:
+        ms = timed(fn, warm=2, iters=5)
+        out["streaming"].append({"name": name, "words": n, "ms": round(ms, 4), "words_per_s": n / (ms * 1e-3),
+                                 "GB_per_s": round(nbytes * n / (ms * 1e-3) / 1e9, 1)})
+    return out
 
 
 def main() -> int:
@@ -256,6 +340,8 @@ def main() -> int:
                "sample": (f"{passes} pass(es) over {len(covered)} of {len(layers)} layers of config {args.config} at "
                           f"full size, one party ({covered[0]} .. {covered[-1]}), {3 * done_mnk:.3e} ring MACs")}
 
+    extras = measure_extras(torch, cg, wl, layers) if args.extras else None
+
     out = {
         "metric": METRIC, "value": value, "unit": "ring MAC/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -271,6 +357,7 @@ def main() -> int:
                    "parties_timed": 1, "fixed_point_bits": wl.FRAC_BITS},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "extras": extras,
         "paper_context": "CryptGPU reports no isolated local-product rate; derived from its Fig. 1 "
                          "(3 V100, LAN, whole protocol): about 6e9-1.1e10 effective ring MAC/s",
     }
