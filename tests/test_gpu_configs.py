@@ -53,6 +53,52 @@ def test_config_every_layer_bit_exact(env, cfg):
         check_layer(cg, ro, wl, cfg, li, L)
 
 
+def test_config4_step_replayed_from_a_hip_graph_is_bit_exact(env):
+    """A caller may capture the 16-layer step once and replay it (measured: no faster than host launches here,
+    the GPU is never idle between them); every replay must give the oracle's outputs, also with eager work and
+    fresh inputs between replays."""
+    cg, ro, wl = env
+    layers = wl.config_layers(4)
+    host = [list(wl.party_operands(L, wl.layer_seed(4, li))) for li, L in enumerate(layers)]
+    dev = [[cg.to_device(a) for a in ops] for ops in host]
+    outs = [torch.empty(L.z_shape, dtype=torch.int64, device="cuda") for L in layers]
+
+    def step():
+        for L, d, z in zip(layers, dev, outs):
+            if L.kind == "conv":
+                cg.cg_share_conv2d(*d, stride=(L.stride, L.stride), pad=(L.pad, L.pad), z_i=z)
+            else:
+                cg.cg_share_matmul(*d, z_i=z)
+
+    def oracle_outputs():
+        return [ro.party_conv2d(*ops, (L.stride, L.stride), (L.pad, L.pad)) if L.kind == "conv"
+                else ro.party_matmul(*ops) for L, ops in zip(layers, host)]
+
+    say("config 4: capture the step into a HIP graph")
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    want = oracle_outputs()
+    for rep in range(3):
+        say(f"config 4: graph replay {rep}")
+        for z in outs:
+            z.fill_(0x5A5A5A5A5A5A5A5A)          # eager work between replays; stale outputs would show
+        if rep == 2:
+            # new activations for the two largest layers, same buffers: the graph must read them afresh
+            for li in (1, 3):
+                for j in (0, 1):
+                    host[li][j] = wl.draw_ring(layers[li].x_shape, 4242 + 10 * li + j)
+                    dev[li][j].copy_(torch.from_numpy(host[li][j].view(np.int64)))
+            want = oracle_outputs()
+        graph.replay()
+        torch.cuda.synchronize()
+        for L, z, w in zip(layers, outs, want):
+            msg = first_mismatch(cg.to_host(z), w)
+            assert not msg, f"replay {rep} {L.name}: {msg}"
+
+
 def test_config3_alternate_reading_conv2_at_16x16(env):
     cg, ro, wl = env
     L = wl.config3(alt=True)[1]
