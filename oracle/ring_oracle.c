@@ -552,6 +552,38 @@ int oracle_trunc1_local(const u64 *z, const u64 *msg, const uint8_t key_self[16]
     return 0;
 }
 
+/* ---- binary replicated shares (Sec. III-B "Most significant bit") -------------------
+ * A 64-bit word holds 64 independent bits, each shared as v = v_0 ^ v_1 ^ v_2 with
+ * P_i holding (v_i, v_{i+1}).  XOR gates are local (share by share).  An AND gate is
+ * the multiplication protocol over Z_2: P_i computes
+ *   z_i = (x_i & y_i) ^ (x_{i+1} & y_i) ^ (x_i & y_{i+1}),
+ * an XOR-sharing of x & y among the three parties, blinds it with a zero share
+ *   beta_i[j] = F(k_i, j) ^ F(k_{i-1}, j)      (the three beta XOR to zero)
+ * and passes it on.  The addition circuit that turns the arithmetic shares into
+ * binary shares of their sum is a sequence of such gates on whole words. */
+void oracle_bshare_and(const u64 *x_i, const u64 *x_ip1, const u64 *y_i, const u64 *y_ip1,
+                       u64 *z_i, size_t n)
+{
+    for (size_t j = 0; j < n; ++j) {
+        const u64 t0 = x_i[j] & y_i[j];
+        const u64 t1 = x_ip1[j] & y_i[j];
+        const u64 t2 = x_i[j] & y_ip1[j];
+        z_i[j] = t0 ^ t1 ^ t2;
+    }
+}
+
+int oracle_bzero_share(const uint8_t key_self[16], const uint8_t key_prev[16], u64 nonce, u64 first,
+                       u64 *beta, size_t n)
+{
+    u64 *t = (u64 *)malloc((n ? n : 1) * sizeof(u64));
+    if (!t) return -1;
+    oracle_prf_words(key_self, nonce, first, beta, n);
+    oracle_prf_words(key_prev, nonce, first, t, n);
+    for (size_t j = 0; j < n; ++j) beta[j] ^= t[j];
+    free(t);
+    return 0;
+}
+
 /* =========================================================================
  * Other local linear-layer pieces on replicated shares.
  * ========================================================================= */

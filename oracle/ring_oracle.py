@@ -78,6 +78,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_zero_share.restype = ctypes.c_int
         L.oracle_reshare.argtypes = [_u64p, u8p, u8p, ctypes.c_uint64, ctypes.c_uint64, _u64p, _sz]
         L.oracle_reshare.restype = ctypes.c_int
+        L.oracle_bshare_and.argtypes = [_u64p] * 5 + [_sz]
+        L.oracle_bzero_share.argtypes = [u8p, u8p, ctypes.c_uint64, ctypes.c_uint64, _u64p, _sz]
+        L.oracle_bzero_share.restype = ctypes.c_int
         L.oracle_trunc1_local.argtypes = [_u64p, _u64p, u8p, u8p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int,
                                           u8p, ctypes.c_uint64, _u64p, _sz]
         L.oracle_trunc1_local.restype = ctypes.c_int
@@ -343,6 +346,87 @@ def trunc1_protocol(z, keys, nonce: int, first: int, d: int, mask_nonce: int):
     s2 = prf_words(k1, mask_nonce, first, _u(z[2]).size).reshape(_u(z[2]).shape)  # P_2 and P_1: the mask itself
     # round 2: P_1 -> P_0: s1, P_0 -> P_2: s0 (no arithmetic)
     return s0, s1, s2
+
+
+# ---- binary replicated shares and the adder circuit for the most significant bit ----------------
+def bshare_and(x_i, x_ip1, y_i, y_ip1) -> np.ndarray:
+    """One party's local step of an AND gate on binary shares (64 gates per word)."""
+    x_i, x_ip1, y_i, y_ip1 = _u(x_i), _u(x_ip1), _u(y_i), _u(y_ip1)
+    assert x_i.shape == x_ip1.shape == y_i.shape == y_ip1.shape
+    z = np.empty(x_i.shape, dtype=np.uint64)
+    lib().oracle_bshare_and(_p(x_i), _p(x_ip1), _p(y_i), _p(y_ip1), _p(z), x_i.size)
+    return z
+
+
+def bzero_share(key_self: bytes, key_prev: bytes, nonce: int, first: int, n: int) -> np.ndarray:
+    out = np.empty(n, dtype=np.uint64)
+    if lib().oracle_bzero_share(_key(key_self), _key(key_prev), nonce, first, _p(out), n):
+        raise MemoryError("oracle_bzero_share")
+    return out
+
+
+def breshare(z, key_self: bytes, key_prev: bytes, nonce: int, first: int) -> np.ndarray:
+    """z ^ beta: the blinded XOR share a party passes on after an AND gate."""
+    z = _u(z)
+    return z ^ bzero_share(key_self, key_prev, nonce, first, z.size).reshape(z.shape)
+
+
+def ks_stage_local(p_i, p_ip1, g_i, g_ip1, shift: int, last: bool = False):
+    """One party's local step of one stage of the parallel-prefix adder on (propagate, generate) words:
+    g' = g ^ (p & (g << shift)), p' = p & (p << shift), both AND gates by the three-term formula; the party
+    adds its own component g_i.  Returns (p', g') as this party's XOR shares (p' is None for the last stage)."""
+    p_i, p_ip1, g_i, g_ip1 = _u(p_i), _u(p_ip1), _u(g_i), _u(g_ip1)
+    sh = np.uint64(shift)
+    g_new = g_i ^ bshare_and(p_i, p_ip1, g_i << sh, g_ip1 << sh)
+    p_new = None if last else bshare_and(p_i, p_ip1, p_i << sh, p_ip1 << sh)
+    return p_new, g_new
+
+
+def msb_protocol(x, keys, nonce: int):
+    """All three parties' steps of the addition circuit on x = (x_0, x_1, x_2), the arithmetic shares of a
+    tensor (P_i holds x_i and x_{i+1}).  Each x_k is taken as a binary sharing with one non-zero component;
+    a carry-save step (one AND round) reduces the three addends to two, and a 64-bit parallel-prefix adder
+    (one AND round for the first generate word, six stages) adds those.  Messages are plain assignments.
+    Returns (sum, msb): binary sharings, as triples, of the 64-bit sum and of its top bit (in bit 0)."""
+    x = [_u(a) for a in x]
+    n, shape = x[0].size, x[0].shape
+    zero = np.zeros(shape, dtype=np.uint64)
+    pair = lambda v, i: (v[i], v[(i + 1) % 3])
+    counter = [0]
+
+    def and_gate(X, Y):
+        first = counter[0]
+        counter[0] += n
+        return tuple(breshare(bshare_and(*pair(X, i), *pair(Y, i)), keys[i], keys[(i - 1) % 3], nonce, first)
+                     for i in range(3))
+
+    xor = lambda X, Y: tuple(a ^ b for a, b in zip(X, Y))
+    A, B, C = (x[0], zero, zero), (zero, x[1], zero), (zero, zero, x[2])
+    # carry-save: S = A ^ B ^ C, carry = majority(A, B, C) = ((A ^ C) & (B ^ C)) ^ C
+    S = xor(xor(A, B), C)
+    carry = xor(and_gate(xor(A, C), xor(B, C)), C)
+    T = tuple(c << np.uint64(1) for c in carry)
+    # parallel-prefix adder of S and T
+    P0 = xor(S, T)
+    G = and_gate(S, T)
+    P = P0
+    for stage, shift in enumerate((1, 2, 4, 8, 16, 32)):
+        last = stage == 5
+        first = counter[0]
+        counter[0] += 2 * n
+        new_p, new_g = [], []
+        for i in range(3):
+            p_loc, g_loc = ks_stage_local(*pair(P, i), *pair(G, i), shift, last)
+            ks, kp = keys[i], keys[(i - 1) % 3]
+            new_g.append(breshare(g_loc, ks, kp, nonce, first))
+            if not last:
+                new_p.append(breshare(p_loc, ks, kp, nonce, first + n))
+        G = tuple(new_g)
+        if not last:
+            P = tuple(new_p)
+    total = xor(P0, tuple(g << np.uint64(1) for g in G))
+    msb = tuple(t >> np.uint64(63) for t in total)
+    return total, msb
 
 
 def party_mul(x_i, x_ip1, y_i, y_ip1) -> np.ndarray:

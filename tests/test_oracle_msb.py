@@ -1,0 +1,96 @@
+"""Pins for the oracle's binary-share gates and the addition circuit for the most significant bit (no GPU).
+
+Pinned by the plain definitions: the three parties' AND outputs XOR to x & y; zero shares XOR to zero and are
+the FIPS-pinned PRF words; and the whole circuit, run on arithmetic shares, opens to the 64-bit sum of the
+shares computed by ordinary integer addition (every bit, not only the top one), including inputs whose carries
+ripple through all 64 positions.
+"""
+import numpy as np
+import pytest
+
+from oracle import ring_oracle as ro
+from paper_2104_10949_amd import workloads as wl
+
+MOD = 1 << 64
+KEYS = (bytes(range(16)), bytes(range(16, 32)), bytes(range(32, 48)))
+
+
+def bshare(v, seed):
+    s0, s1 = wl.draw_ring(v.shape, seed), wl.draw_ring(v.shape, seed + 1)
+    return s0, s1, v ^ s0 ^ s1
+
+
+def test_and_gate_is_the_three_term_formula_and_opens_to_the_and():
+    x, y = wl.draw_ring((300,), 1), wl.draw_ring((300,), 2)
+    X, Y = bshare(x, 3), bshare(y, 5)
+    z = [ro.bshare_and(X[i], X[(i + 1) % 3], Y[i], Y[(i + 1) % 3]) for i in range(3)]
+    assert np.array_equal(z[0] ^ z[1] ^ z[2], x & y)
+    i = 1
+    want = [(int(X[1][j]) & int(Y[1][j])) ^ (int(X[2][j]) & int(Y[1][j])) ^ (int(X[1][j]) & int(Y[2][j]))
+            for j in range(300)]
+    assert [int(v) for v in z[i]] == want
+
+
+def test_binary_zero_shares_cancel_and_are_prf_words():
+    n, nonce, first = 101, 9, 7
+    b = [ro.bzero_share(KEYS[i], KEYS[(i - 1) % 3], nonce, first, n) for i in range(3)]
+    assert not (b[0] ^ b[1] ^ b[2]).any()
+    assert np.array_equal(b[1], ro.prf_words(KEYS[1], nonce, first, n) ^ ro.prf_words(KEYS[0], nonce, first, n))
+    z = wl.draw_ring((n,), 11)
+    assert np.array_equal(ro.breshare(z, KEYS[1], KEYS[0], nonce, first), z ^ b[1])
+
+
+def test_prefix_stage_matches_bit_level_definition():
+    # opened over the three parties, one stage computes g' = g | (p & g<<s), p' = p & p<<s when p & g = 0
+    p, g = wl.draw_ring((200,), 21), wl.draw_ring((200,), 22)
+    g = g & ~p
+    P, G = bshare(p, 23), bshare(g, 25)
+    for shift in (1, 4, 32):
+        outs = [ro.ks_stage_local(P[i], P[(i + 1) % 3], G[i], G[(i + 1) % 3], shift) for i in range(3)]
+        p_new = outs[0][0] ^ outs[1][0] ^ outs[2][0]
+        g_new = outs[0][1] ^ outs[1][1] ^ outs[2][1]
+        sh = np.uint64(shift)
+        assert np.array_equal(p_new, p & (p << sh))
+        assert np.array_equal(g_new, g ^ (p & (g << sh)))
+        assert np.array_equal(g_new, g | (p & (g << sh)))   # disjoint, so XOR is OR
+
+
+def open3(t):
+    return t[0] ^ t[1] ^ t[2]
+
+
+def test_circuit_opens_to_the_integer_sum_of_the_shares():
+    n = 4000
+    x = (wl.draw_ring((n,), 31), wl.draw_ring((n,), 32), wl.draw_ring((n,), 33))
+    total, msb = ro.msb_protocol(x, KEYS, nonce=3)
+    with np.errstate(over="ignore"):
+        want = x[0] + x[1] + x[2]
+    assert np.array_equal(open3(total), want)
+    assert np.array_equal(open3(msb), want >> np.uint64(63))
+
+
+def test_circuit_on_carry_chains_and_signs():
+    top = (1 << 63) - 1
+    cases = [
+        (top, 1, 0),                 # carry ripples through 63 positions into the sign bit
+        (MOD - 1, 1, 0),             # ripples through all 64 and out
+        (MOD - 1, MOD - 1, MOD - 1), # two carries per column
+        (0, 0, 0), (1 << 63, 0, 0), (1 << 63, 1 << 63, 0), (1 << 62, 1 << 62, 0),
+        (0x5555555555555555, 0xAAAAAAAAAAAAAAAA, 1), (0x8080808080808080, 0x8080808080808080, 0x8080808080808080),
+        (5, MOD - 7, 0),             # small negative secret
+        (MOD - 3, 2, 1),             # secret zero from wrapping shares
+    ]
+    x = tuple(np.array([c[k] for c in cases], dtype=np.uint64) for k in range(3))
+    total, msb = ro.msb_protocol(x, KEYS, nonce=4)
+    want = [(a + b + c) % MOD for a, b, c in cases]
+    assert [int(v) for v in open3(total)] == want
+    assert [int(v) for v in open3(msb)] == [w >> 63 for w in want]
+
+
+def test_sign_of_fixed_point_values():
+    rng = np.random.default_rng(41)
+    reals = rng.normal(0, 3, size=2000)
+    enc = ro.encode(reals, 16)
+    shares = ro.share(enc, wl.draw_ring(enc.shape, 42), wl.draw_ring(enc.shape, 43))
+    _, msb = ro.msb_protocol(shares, KEYS, nonce=5)
+    assert np.array_equal(open3(msb).astype(bool), np.rint(reals * 65536) < 0)
