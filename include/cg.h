@@ -327,6 +327,52 @@ CG_API cg_status cg_prf_words(const uint8_t *key, uint64_t nonce, uint64_t first
                        uint64_t *out, size_t n, void *stream);
 
 /*
+ * Gates on BINARY replicated shares (Sec. III-B "Most significant bit": the sign of
+ * a shared value is found by adding its three arithmetic shares in a Boolean addition
+ * circuit over binary shares, "a sequence of bitwise AND and XOR operations").  A
+ * 64-bit word carries 64 independent bits, each shared as v = v_0 ^ v_1 ^ v_2 with
+ * P_i holding the pair (v_i, v_{i+1}); n counts words.
+ *
+ *   cg_bshare_xor  : (za, zb) = (xa ^ ya, xb ^ yb)                      XOR gate, local
+ *   cg_bshare_and  : z_i = (x_i & y_i) ^ (x_ip1 & y_i) ^ (x_i & y_ip1)  local step of an AND
+ *                    gate: the multiplication protocol over Z_2; the three z_i XOR to x & y
+ *   cg_bshare_prefix_stage : one stage of a parallel-prefix adder on (propagate, generate)
+ *                    words, two AND gates fused with the word shifts:
+ *                      g_out = g_i ^ and3(p, g << shift),  p_out = and3(p, p << shift)
+ *                    with and3 the three-term formula of cg_bshare_and applied to the
+ *                    pairs; p_out may be NULL (last stage).  shift in [1, 63].
+ *   cg_bzero_share : beta[j] = F(k_i, first + j) ^ F(k_{i-1}, first + j): the three
+ *                    parties' beta XOR to zero (keys and F as for cg_zero_share)
+ *   cg_breshare    : out[j] = z_i[j] ^ beta[j], the blinded share passed on after an AND
+ *
+ * The paper gives no gate list for the circuit; the tests assemble this one from the
+ * calls above: the arithmetic shares x_0, x_1, x_2 are read as binary sharings
+ * (x_0,0,0), (0,x_1,0), (0,0,x_2); a carry-save step S = A^B^C,
+ * carry = ((A^C) & (B^C)) ^ C reduces them to two addends; a 64-bit parallel-prefix
+ * adder (first generate word S & (carry << 1), then stages with shifts 1..32) adds
+ * those: eight rounds of AND gates in all.  Bit 63 of the sum is the sign.
+ *
+ * Device pointers, 8-byte aligned; outputs may coincide with inputs element for
+ * element but not partially overlap, and two outputs must be disjoint (CG_ERR_ALIAS).
+ * n == 0 returns CG_OK.
+ */
+CG_API cg_status cg_bshare_xor(const uint64_t *xa, const uint64_t *xb, const uint64_t *ya,
+                        const uint64_t *yb, uint64_t *za, uint64_t *zb, size_t n, void *stream);
+
+CG_API cg_status cg_bshare_and(const uint64_t *x_i, const uint64_t *x_ip1, const uint64_t *y_i,
+                        const uint64_t *y_ip1, uint64_t *z_i, size_t n, void *stream);
+
+CG_API cg_status cg_bshare_prefix_stage(const uint64_t *p_i, const uint64_t *p_ip1,
+                                 const uint64_t *g_i, const uint64_t *g_ip1, int shift,
+                                 uint64_t *p_out, uint64_t *g_out, size_t n, void *stream);
+
+CG_API cg_status cg_bzero_share(const uint8_t *key_self, const uint8_t *key_prev, uint64_t nonce,
+                         uint64_t first, uint64_t *beta, size_t n, void *stream);
+
+CG_API cg_status cg_breshare(const uint64_t *z_i, const uint8_t *key_self, const uint8_t *key_prev,
+                      uint64_t nonce, uint64_t first, uint64_t *out, size_t n, void *stream);
+
+/*
  * out = s0 + s1 + s2 (mod 2^64), element-wise over n (Sec. III-B, "Secret
  * sharing").  Opens a replicated sharing (pass its three distinct shares) and
  * equally the three parties' additive outputs z_0, z_1, z_2 of

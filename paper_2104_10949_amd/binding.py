@@ -24,7 +24,8 @@ EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d
            "cg_share_mul_public", "cg_share_add_public", "cg_reconstruct",
            "cg_share_matmul_ws", "cg_share_conv2d_ws", "cg_zero_share", "cg_reshare", "cg_share_matmul_t",
            "cg_share_mul", "cg_share_sum_pool2d", "cg_share_conv2d_dgrad", "cg_share_conv2d_wgrad",
-           "cg_trunc1_local", "cg_prf_words",
+           "cg_trunc1_local", "cg_prf_words", "cg_bshare_xor", "cg_bshare_and", "cg_bshare_prefix_stage",
+           "cg_bzero_share", "cg_breshare",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -79,13 +80,18 @@ def lib() -> ctypes.CDLL:
         L.cg_share_matmul_t.argtypes = [vp] * 5 + [i64] * 3 + [ctypes.c_int] * 2 + [vp]
         L.cg_share_mul.argtypes = [vp] * 5 + [sz, sz, vp]
         L.cg_share_sum_pool2d.argtypes = [vp] * 4 + [ctypes.POINTER(PoolDesc), vp]
+        L.cg_bshare_xor.argtypes = [vp] * 6 + [sz, vp]
+        L.cg_bshare_and.argtypes = [vp] * 5 + [sz, vp]
+        L.cg_bshare_prefix_stage.argtypes = [vp] * 4 + [ctypes.c_int, vp, vp, sz, vp]
+        L.cg_bzero_share.argtypes = [key, key, u64, u64, vp, sz, vp]
+        L.cg_breshare.argtypes = [vp, key, key, u64, u64, vp, sz, vp]
         L.cg_trunc1_local.argtypes = [vp, vp, key, key, u64, u64, ctypes.c_int, key, u64, vp, sz, vp]
         L.cg_prf_words.argtypes = [key, u64, u64, vp, sz, vp]
         L.cg_share_conv2d_dgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
         L.cg_share_conv2d_wgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
-        for name in EXPORTS[2:19]:
+        for name in EXPORTS[2:24]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[19:]:
+        for name in EXPORTS[24:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -392,6 +398,61 @@ def cg_prf_words(key: bytes, nonce: int, first: int, n: int, out=None, stream=No
     elif out.numel() != n:
         raise ValueError("output size does not match")
     _check(lib().cg_prf_words(_key16(key), nonce, first, _ptr(out) if n else None, n, _stream(stream)), "cg_prf_words")
+    return out
+
+
+def cg_bshare_xor(xa, xb, ya, yb, za=None, zb=None, stream=None):
+    """XOR gate on binary replicated pairs: (xa ^ ya, xb ^ yb)."""
+    za = torch.empty_like(xa) if za is None else za
+    zb = torch.empty_like(xb) if zb is None else zb
+    n = xa.numel()
+    _check(lib().cg_bshare_xor(*(_ptr(t) if n else 0 for t in (xa, xb, ya, yb, za, zb)), n, _stream(stream)),
+           "cg_bshare_xor")
+    return za, zb
+
+
+def cg_bshare_and(x_i, x_ip1, y_i, y_ip1, z_i=None, stream=None) -> torch.Tensor:
+    """Local step of an AND gate on binary replicated pairs (64 gates per word)."""
+    if not (x_i.shape == x_ip1.shape == y_i.shape == y_ip1.shape):
+        raise ValueError("operand shapes do not match")
+    z_i = torch.empty_like(x_i) if z_i is None else z_i
+    n = x_i.numel()
+    _check(lib().cg_bshare_and(*(_ptr(t) if n else 0 for t in (x_i, x_ip1, y_i, y_ip1, z_i)), n, _stream(stream)),
+           "cg_bshare_and")
+    return z_i
+
+
+def cg_bshare_prefix_stage(p_i, p_ip1, g_i, g_ip1, shift: int, last: bool = False, p_out=None, g_out=None,
+                           stream=None):
+    """Local step of one parallel-prefix adder stage; returns (p_out or None, g_out)."""
+    if not (p_i.shape == p_ip1.shape == g_i.shape == g_ip1.shape):
+        raise ValueError("operand shapes do not match")
+    g_out = torch.empty_like(g_i) if g_out is None else g_out
+    if not last and p_out is None:
+        p_out = torch.empty_like(p_i)
+    n = p_i.numel()
+    _check(lib().cg_bshare_prefix_stage(*(_ptr(t) if n else 0 for t in (p_i, p_ip1, g_i, g_ip1)), shift,
+                                        None if last else (_ptr(p_out) if n else 0), _ptr(g_out) if n else 0, n,
+                                        _stream(stream)), "cg_bshare_prefix_stage")
+    return (None if last else p_out), g_out
+
+
+def cg_bzero_share(key_self: bytes, key_prev: bytes, nonce: int, first: int, n: int, out=None,
+                   stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((n,), dtype=torch.int64, device="cuda")
+    _check(lib().cg_bzero_share(_key16(key_self), _key16(key_prev), nonce, first, _ptr(out) if n else 0, n,
+                                _stream(stream)), "cg_bzero_share")
+    return out
+
+
+def cg_breshare(z_i, key_self: bytes, key_prev: bytes, nonce: int, first: int = 0, out=None,
+                stream=None) -> torch.Tensor:
+    """out = z_i ^ beta_i, the blinded XOR share passed on after an AND gate; out may be z_i."""
+    out = torch.empty_like(z_i) if out is None else out
+    n = z_i.numel()
+    _check(lib().cg_breshare(_ptr(z_i) if n else 0, _key16(key_self), _key16(key_prev), nonce, first,
+                             _ptr(out) if n else 0, n, _stream(stream)), "cg_breshare")
     return out
 
 

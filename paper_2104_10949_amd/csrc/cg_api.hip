@@ -181,6 +181,84 @@ struct PartyMulOp {
     }
 };
 
+// ---- binary (XOR) replicated shares: 64 independent bits per word ----------------
+struct BXorOp {  // (za, zb) = (xa ^ ya, xb ^ yb)
+    const u64 *xa, *xb, *ya, *yb;
+    u64 *za, *zb;
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 a[U], b[U], c[U], d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = ld2(xa, i + u * step); c[u] = ld2(ya, i + u * step);
+            b[u] = ld2(xb, i + u * step); d[u] = ld2(yb, i + u * step);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            st2(za, i + u * step, a[u] ^ c[u]);
+            st2(zb, i + u * step, b[u] ^ d[u]);
+        }
+    }
+    __device__ void one(size_t i) const {
+        const u64 a = xa[i] ^ ya[i], b = xb[i] ^ yb[i];
+        za[i] = a;
+        zb[i] = b;
+    }
+};
+
+// z = (x_a & y_a) ^ (x_b & y_a) ^ (x_a & y_b) = (x_a & (y_a ^ y_b)) ^ (x_b & y_a)
+struct BAndOp {
+    const u64 *xa, *xb, *ya, *yb;
+    u64* z;
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 a[U], b[U], c[U], d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = ld2(xa, i + u * step); c[u] = ld2(ya, i + u * step);
+            b[u] = ld2(xb, i + u * step); d[u] = ld2(yb, i + u * step);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) st2(z, i + u * step, (a[u] & (c[u] ^ d[u])) ^ (b[u] & c[u]));
+    }
+    __device__ void one(size_t i) const { z[i] = (xa[i] & (ya[i] ^ yb[i])) ^ (xb[i] & ya[i]); }
+};
+
+// One stage of the parallel-prefix adder on (propagate, generate) words:
+//   g' = g_a ^ and3(p, g << s),  p' = and3(p, p << s),  and3 = the three-term AND above.
+struct PrefixStageOp {
+    const u64 *pa, *pb, *ga, *gb;
+    u64 *p_out, *g_out;  // p_out may be null (last stage)
+    int s;
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 a[U], b[U], c[U], d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = ld2(pa, i + u * step); c[u] = ld2(ga, i + u * step);
+            b[u] = ld2(pb, i + u * step); d[u] = ld2(gb, i + u * step);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const ull2 gsa = c[u] << s, gsb = d[u] << s;
+            st2(g_out, i + u * step, c[u] ^ (a[u] & (gsa ^ gsb)) ^ (b[u] & gsa));
+            if (p_out) {
+                const ull2 psa = a[u] << s, psb = b[u] << s;
+                st2(p_out, i + u * step, (a[u] & (psa ^ psb)) ^ (b[u] & psa));
+            }
+        }
+    }
+    __device__ void one(size_t i) const {
+        const u64 a = pa[i], b = pb[i], c = ga[i], d = gb[i];
+        const u64 gsa = c << s, gsb = d << s;
+        g_out[i] = c ^ (a & (gsa ^ gsb)) ^ (b & gsa);
+        if (p_out) {
+            const u64 psa = a << s, psb = b << s;
+            p_out[i] = (a & (psa ^ psb)) ^ (b & psa);
+        }
+    }
+};
+
 // One thread per output pixel and channel pair: sums the window of both components.
 __global__ __launch_bounds__(256) void sum_pool_kernel(const u64* __restrict__ xa, const u64* __restrict__ xb,
                                                        u64* __restrict__ za, u64* __restrict__ zb,
@@ -772,6 +850,79 @@ cg_status cg_reshare(const uint64_t* z_i, const uint8_t* key_self, const uint8_t
     if (bad_overlap(out, z_i, (u64)n * 8)) return CG_ERR_ALIAS;
     const hipError_t e = cg::launch_zero_share(z_i, out, n, key_self, key_prev, nonce, first,
                                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+cg_status cg_bshare_xor(const uint64_t* xa, const uint64_t* xb, const uint64_t* ya, const uint64_t* yb,
+                        uint64_t* za, uint64_t* zb, size_t n, void* stream) {
+    if (n == 0) return CG_OK;
+    const void* ptrs[6] = {xa, xb, ya, yb, za, zb};
+    if (cg_status st = check_ptrs(ptrs, 6)) return st;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    for (int o = 4; o < 6; ++o)
+        for (int i = 0; i < 4; ++i)
+            if (bad_overlap(ptrs[o], ptrs[i], bytes)) return CG_ERR_ALIAS;
+    if (overlap(za, bytes, zb, bytes)) return CG_ERR_ALIAS;
+    BXorOp f = {xa, xb, ya, yb, za, zb};
+    return launch_ew(n, all_aligned16(ptrs, 6), f, stream);
+}
+
+cg_status cg_bshare_and(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i, const uint64_t* y_ip1,
+                        uint64_t* z_i, size_t n, void* stream) {
+    if (n == 0) return CG_OK;
+    const void* ptrs[5] = {x_i, x_ip1, y_i, y_ip1, z_i};
+    if (cg_status st = check_ptrs(ptrs, 5)) return st;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    for (int i = 0; i < 4; ++i)
+        if (bad_overlap(z_i, ptrs[i], bytes)) return CG_ERR_ALIAS;
+    BAndOp f = {x_i, x_ip1, y_i, y_ip1, z_i};
+    return launch_ew(n, all_aligned16(ptrs, 5), f, stream);
+}
+
+cg_status cg_bshare_prefix_stage(const uint64_t* p_i, const uint64_t* p_ip1, const uint64_t* g_i,
+                                 const uint64_t* g_ip1, int shift, uint64_t* p_out, uint64_t* g_out, size_t n,
+                                 void* stream) {
+    if (shift < 1 || shift > 63) return CG_ERR_SHAPE;
+    if (n == 0) return CG_OK;
+    const void* in[5] = {p_i, p_ip1, g_i, g_ip1, g_out};
+    if (cg_status st = check_ptrs(in, 5)) return st;
+    if (p_out && !aligned(p_out, 8)) return CG_ERR_ALIGN;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    // every output element depends only on the same element of the inputs, so in place is fine;
+    // partial overlaps and coinciding outputs are not
+    for (int i = 0; i < 4; ++i)
+        if (bad_overlap(g_out, in[i], bytes) || (p_out && bad_overlap(p_out, in[i], bytes))) return CG_ERR_ALIAS;
+    if (p_out && overlap(p_out, bytes, g_out, bytes)) return CG_ERR_ALIAS;
+    PrefixStageOp f = {p_i, p_ip1, g_i, g_ip1, p_out, g_out, shift};
+    const void* all[6] = {p_i, p_ip1, g_i, g_ip1, g_out, p_out ? p_out : g_out};
+    return launch_ew(n, all_aligned16(all, 6), f, stream);
+}
+
+cg_status cg_bzero_share(const uint8_t* key_self, const uint8_t* key_prev, uint64_t nonce, uint64_t first,
+                         uint64_t* beta, size_t n, void* stream) {
+    if (!key_self || !key_prev) return CG_ERR_NULL;
+    if (n == 0) return CG_OK;
+    if (!beta) return CG_ERR_NULL;
+    if (!aligned(beta, 8)) return CG_ERR_ALIGN;
+    if (n > (SIZE_MAX >> 4) || first + n < first) return CG_ERR_SHAPE;
+    const hipError_t e = cg::launch_prf_combine(nullptr, nullptr, beta, n, key_self, key_prev, nonce, first, 0, nullptr,
+                                                0, false, static_cast<hipStream_t>(stream), true);
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+cg_status cg_breshare(const uint64_t* z_i, const uint8_t* key_self, const uint8_t* key_prev, uint64_t nonce,
+                      uint64_t first, uint64_t* out, size_t n, void* stream) {
+    if (!key_self || !key_prev) return CG_ERR_NULL;
+    if (n == 0) return CG_OK;
+    if (!z_i || !out) return CG_ERR_NULL;
+    if (!aligned(z_i, 8) || !aligned(out, 8)) return CG_ERR_ALIGN;
+    if (n > (SIZE_MAX >> 4) || first + n < first) return CG_ERR_SHAPE;
+    if (bad_overlap(out, z_i, (u64)n * 8)) return CG_ERR_ALIAS;
+    const hipError_t e = cg::launch_prf_combine(z_i, nullptr, out, n, key_self, key_prev, nonce, first, 0, nullptr, 0,
+                                                false, static_cast<hipStream_t>(stream), true);
     return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
 

@@ -125,13 +125,14 @@ __device__ __forceinline__ u64 asr64(u64 v, int d) { return (u64)((int64_t)v >> 
 
 // For the words j = first .. first + n - 1 of the PRF streams:
 //   out = asr64((z ? z : 0) + (msg ? msg : 0) + [ALPHA] (F(self, j) - F(prev, j)), d)  -/+  [MASK] F(mask, j)
-// (alpha under `nonce`, the mask stream under `mask_nonce`; the mask is subtracted unless add_mask).
+// (alpha under `nonce`, the mask stream under `mask_nonce`; the mask is subtracted unless add_mask), or, for
+// binary shares (xor_mode, ALPHA only):  out = (z ? z : 0) ^ F(self, j) ^ F(prev, j).
 // One thread handles one AES block = two consecutive words of each stream.
 template <bool ALPHA, bool MASK>
 __global__ __launch_bounds__(256) void prf_combine_kernel(const u64* __restrict__ z, const u64* __restrict__ msg,
                                                           u64* __restrict__ out, size_t n, u64 first, u64 nonce,
-                                                          u64 mask_nonce, int d, bool add_mask, const PrfKeys keys,
-                                                          const T0Table table) {
+                                                          u64 mask_nonce, int d, bool add_mask, bool xor_mode,
+                                                          const PrfKeys keys, const T0Table table) {
     __shared__ u32 t0_all[256 * 64];
     {
         const u32 mine = table.v[threadIdx.x];
@@ -149,8 +150,10 @@ __global__ __launch_bounds__(256) void prf_combine_kernel(const u64* __restrict_
             u32 a[4], b[4];
             aes_block(t0, keys.self, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), a);
             aes_block(t0, keys.prev, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), b);
-            w0 = (((u64)a[1] << 32) | a[0]) - (((u64)b[1] << 32) | b[0]);
-            w1 = (((u64)a[3] << 32) | a[2]) - (((u64)b[3] << 32) | b[2]);
+            const u64 a0 = ((u64)a[1] << 32) | a[0], a1 = ((u64)a[3] << 32) | a[2];
+            const u64 b0 = ((u64)b[1] << 32) | b[0], b1 = ((u64)b[3] << 32) | b[2];
+            w0 = xor_mode ? a0 ^ b0 : a0 - b0;
+            w1 = xor_mode ? a1 ^ b1 : a1 - b1;
         }
         if constexpr (MASK) {
             u32 m[4];
@@ -162,11 +165,13 @@ __global__ __launch_bounds__(256) void prf_combine_kernel(const u64* __restrict_
         const u64 j0 = 2 * block, j1 = j0 + 1;  // word indices
         if (j0 >= first && j0 - first < n) {
             const size_t j = j0 - first;
-            out[j] = asr64((z ? z[j] : 0) + (msg ? msg[j] : 0) + w0, d) + r0;
+            const u64 zj = z ? z[j] : 0;
+            out[j] = xor_mode ? zj ^ w0 : asr64(zj + (msg ? msg[j] : 0) + w0, d) + r0;
         }
         if (j1 >= first && j1 - first < n) {
             const size_t j = j1 - first;
-            out[j] = asr64((z ? z[j] : 0) + (msg ? msg[j] : 0) + w1, d) + r1;
+            const u64 zj = z ? z[j] : 0;
+            out[j] = xor_mode ? zj ^ w1 : asr64(zj + (msg ? msg[j] : 0) + w1, d) + r1;
         }
     }
 }
@@ -175,10 +180,12 @@ __global__ __launch_bounds__(256) void prf_combine_kernel(const u64* __restrict_
 
 hipError_t launch_prf_combine(const uint64_t* z, const uint64_t* msg, uint64_t* out, size_t n,
                               const uint8_t* key_self, const uint8_t* key_prev, uint64_t nonce, uint64_t first, int d,
-                              const uint8_t* key_mask, uint64_t mask_nonce, bool add_mask, hipStream_t stream) {
+                              const uint8_t* key_mask, uint64_t mask_nonce, bool add_mask, hipStream_t stream,
+                              bool xor_mode) {
     if (n == 0) return hipSuccess;
     const bool alpha = key_self && key_prev, mask = key_mask != nullptr;
     if (!alpha && !mask) return hipErrorInvalidValue;
+    if (xor_mode && (mask || msg || d != 0)) return hipErrorInvalidValue;
     PrfKeys keys = {};
     if (alpha) {
         expand_key(key_self, keys.self);
@@ -193,19 +200,19 @@ hipError_t launch_prf_combine(const uint64_t* z, const uint64_t* msg, uint64_t* 
     const dim3 g((unsigned)grid), b(256);
     if (alpha && mask)
         hipLaunchKernelGGL((prf_combine_kernel<true, true>), g, b, 0, stream, z, msg, out, n, (u64)first, (u64)nonce,
-                           (u64)mask_nonce, d, add_mask, keys, table);
+                           (u64)mask_nonce, d, add_mask, xor_mode, keys, table);
     else if (alpha)
         hipLaunchKernelGGL((prf_combine_kernel<true, false>), g, b, 0, stream, z, msg, out, n, (u64)first, (u64)nonce,
-                           (u64)mask_nonce, d, add_mask, keys, table);
+                           (u64)mask_nonce, d, add_mask, xor_mode, keys, table);
     else
         hipLaunchKernelGGL((prf_combine_kernel<false, true>), g, b, 0, stream, z, msg, out, n, (u64)first, (u64)nonce,
-                           (u64)mask_nonce, d, add_mask, keys, table);
+                           (u64)mask_nonce, d, add_mask, xor_mode, keys, table);
     return hipGetLastError();
 }
 
 hipError_t launch_zero_share(const uint64_t* z, uint64_t* out, size_t n, const uint8_t key_self[16],
                              const uint8_t key_prev[16], uint64_t nonce, uint64_t first, hipStream_t stream) {
-    return launch_prf_combine(z, nullptr, out, n, key_self, key_prev, nonce, first, 0, nullptr, 0, false, stream);
+    return launch_prf_combine(z, nullptr, out, n, key_self, key_prev, nonce, first, 0, nullptr, 0, false, stream, false);
 }
 
 }  // namespace cg

@@ -1,0 +1,149 @@
+"""GPU parity of the binary-share gates and of the whole addition circuit for the most significant bit,
+every party's local steps through the C-ABI, messages as device-to-device assignments, against the CPU
+oracle bit for bit, and against plain integer addition of the shares."""
+import numpy as np
+import pytest
+
+from tests.gpu_util import first_mismatch, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+KEYS = (bytes(range(16)), bytes(range(16, 32)), bytes(range(32, 48)))
+
+
+@pytest.fixture(scope="module")
+def cg():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2104_10949_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ro():
+    from oracle import ring_oracle
+    return ring_oracle
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_2104_10949_amd import workloads
+    return workloads
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 255, 256, 257, 100003, (1 << 20) + 1])
+def test_gates_match_the_oracle(cg, ro, wl, n):
+    say(f"binary-share gates n={n}")
+    h = [wl.draw_ring((n,), 50 + k + n) for k in range(4)]
+    d = [cg.to_device(a) for a in h]
+    assert not first_mismatch(cg.to_host(cg.cg_bshare_and(*d)), ro.bshare_and(*h))
+    za, zb = cg.cg_bshare_xor(*d)
+    assert not first_mismatch(cg.to_host(za), h[0] ^ h[2]) and not first_mismatch(cg.to_host(zb), h[1] ^ h[3])
+    for shift, last in ((1, False), (8, False), (32, True), (63, False)):
+        p_out, g_out = cg.cg_bshare_prefix_stage(*d, shift, last)
+        want_p, want_g = ro.ks_stage_local(*h, shift, last)
+        assert not first_mismatch(cg.to_host(g_out), want_g)
+        assert (p_out is None) == last
+        if not last:
+            assert not first_mismatch(cg.to_host(p_out), want_p)
+    for first in (0, 1, 7):
+        got = cg.to_host(cg.cg_bzero_share(KEYS[1], KEYS[0], 9, first, n))
+        assert not first_mismatch(got, ro.bzero_share(KEYS[1], KEYS[0], 9, first, n))
+        got = cg.to_host(cg.cg_breshare(d[0], KEYS[1], KEYS[0], 9, first))
+        assert not first_mismatch(got, ro.breshare(h[0], KEYS[1], KEYS[0], 9, first))
+
+
+def test_gates_on_unaligned_views_and_in_place(cg, ro, wl):
+    n = 1001
+    h = [wl.draw_ring((n + 1,), 70 + k) for k in range(4)]
+    d = [cg.to_device(a)[1:] for a in h]          # 8-byte aligned only
+    hv = [a[1:] for a in h]
+    say("binary-share gates, 8-byte aligned views")
+    assert not first_mismatch(cg.to_host(cg.cg_bshare_and(*d).contiguous()), ro.bshare_and(*hv))
+    p_out, g_out = cg.cg_bshare_prefix_stage(*d, 4)
+    want_p, want_g = ro.ks_stage_local(*hv, 4)
+    assert not first_mismatch(cg.to_host(p_out.contiguous()), want_p)
+    assert not first_mismatch(cg.to_host(g_out.contiguous()), want_g)
+    # in place: outputs over the first components
+    dd = [cg.to_device(a) for a in h]
+    cg.cg_bshare_prefix_stage(*dd, 2, p_out=dd[0], g_out=dd[2])
+    want_p, want_g = ro.ks_stage_local(*h, 2)
+    assert not first_mismatch(cg.to_host(dd[0]), want_p) and not first_mismatch(cg.to_host(dd[2]), want_g)
+
+
+def gpu_msb_circuit(cg, x_dev, nonce):
+    """The circuit of the oracle's msb_protocol, every local step on the GPU through the C-ABI."""
+    n = x_dev[0].numel()
+    zero = torch.zeros_like(x_dev[0])
+    pair = lambda v, i: (v[i], v[(i + 1) % 3])
+    counter = [0]
+
+    def and_gate(X, Y):
+        first = counter[0]
+        counter[0] += n
+        return tuple(cg.cg_breshare(cg.cg_bshare_and(*pair(X, i), *pair(Y, i)), KEYS[i], KEYS[(i - 1) % 3], nonce, first)
+                     for i in range(3))
+
+    def xor(X, Y):
+        # share-wise XOR; run through the pair entry point party by party (component i is party i's first)
+        return tuple(cg.cg_bshare_xor(*pair(X, i), *pair(Y, i))[0] for i in range(3))
+
+    A, B, C = (x_dev[0], zero, zero), (zero, x_dev[1], zero), (zero, zero, x_dev[2])
+    S = xor(xor(A, B), C)
+    carry = xor(and_gate(xor(A, C), xor(B, C)), C)
+    T = tuple(c << 1 for c in carry)              # a word shift of a share is local
+    P0 = xor(S, T)
+    G = and_gate(S, T)
+    P = P0
+    for stage, shift in enumerate((1, 2, 4, 8, 16, 32)):
+        last = stage == 5
+        first = counter[0]
+        counter[0] += 2 * n
+        new_p, new_g = [], []
+        for i in range(3):
+            p_loc, g_loc = cg.cg_bshare_prefix_stage(*pair(P, i), *pair(G, i), shift, last)
+            new_g.append(cg.cg_breshare(g_loc, KEYS[i], KEYS[(i - 1) % 3], nonce, first, out=g_loc))
+            if not last:
+                new_p.append(cg.cg_breshare(p_loc, KEYS[i], KEYS[(i - 1) % 3], nonce, first + n, out=p_loc))
+        G = tuple(new_g)
+        if not last:
+            P = tuple(new_p)
+    total = xor(P0, tuple(g << 1 for g in G))
+    return total
+
+
+def test_addition_circuit_matches_the_oracle_and_plain_addition(cg, ro, wl):
+    n = 50000
+    say(f"addition circuit on binary shares, n={n}")
+    edge = [(1 << 63) - 1, 1, 0], [(1 << 64) - 1, 1, 0], [(1 << 64) - 1] * 3, [5, (1 << 64) - 7, 0]
+    x = [wl.draw_ring((n,), 80 + k) for k in range(3)]
+    for j, e in enumerate(edge):
+        for k in range(3):
+            x[k][j] = e[k]
+    total = gpu_msb_circuit(cg, [cg.to_device(a) for a in x], nonce=6)
+    torch.cuda.synchronize()
+    want_total, want_msb = ro.msb_protocol(x, KEYS, nonce=6)
+    for got, want in zip(total, want_total):
+        assert not first_mismatch(cg.to_host(got), want)
+    with np.errstate(over="ignore"):
+        plain = x[0] + x[1] + x[2]
+    opened = cg.to_host(total[0]) ^ cg.to_host(total[1]) ^ cg.to_host(total[2])
+    assert not first_mismatch(opened, plain)
+    assert np.array_equal(opened >> np.uint64(63), want_msb[0] ^ want_msb[1] ^ want_msb[2])
+
+
+def test_gate_argument_errors(cg):
+    z = torch.zeros(32, dtype=torch.int64, device="cuda")
+    for shift in (0, 64, -1):
+        with pytest.raises(cg.CgError) as e:
+            cg.cg_bshare_prefix_stage(z, z, z, z, shift)
+        assert e.value.status == cg.CG_ERR_SHAPE
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_bshare_and(z[:16], z[:16], z[:16], z[:16], z_i=z[8:24])
+    assert e.value.status == cg.CG_ERR_ALIAS
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_bshare_prefix_stage(z[:16], z[:16], z[:16], z[:16], 1, p_out=z[16:], g_out=z[16:])
+    assert e.value.status == cg.CG_ERR_ALIAS
