@@ -8,13 +8,16 @@
 // a little-endian integer.  One thread encrypts one block under both keys and
 // produces two consecutive words of alpha.
 //
-// AES rounds use the classic 32-bit table formulation of FIPS-197: one table
-// T0[x] = (2 S[x], S[x], S[x], 3 S[x]), the other three columns of the MixColumns
-// matrix being byte rotations of it; the last round uses the S-box byte of the same
-// table.  The table sits in LDS once per bank (64 copies, 64 KiB): lane i reads
-// entry x at dword 64*x + i, i.e. always from bank i, so the data-dependent
-// lookups of a wave never collide.  Round keys are expanded on the host and passed
-// by value.
+// AES rounds use the classic 32-bit table formulation of FIPS-197: the table
+// T0[x] = (2 S[x], S[x], S[x], 3 S[x]); the other three columns of the MixColumns
+// matrix are its byte rotations T1 = rotl8(T0), T2 = rotl16(T0), T3 = rotl8(T2).
+// Rotation distributes over XOR, so with T0 and T2 both in memory a column costs one
+// rotation: (T0[a] ^ T2[c]) ^ rotl8(T0[b] ^ T2[d]).  The last round uses the S-box
+// byte of T0.  Each table sits in LDS once per bank (64 copies, 64 KiB each, 128 KiB
+// per block of 16 waves): lane i reads entry x of table t at byte 65536 t + 256 x + 4 i,
+// always from bank i, so the data-dependent lookups of a wave never collide, and the
+// whole address is ONE byte permute of (state word, lane constant).  Round keys are
+// expanded on the host and passed by value.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
@@ -87,33 +90,48 @@ struct PrfKeys {
 };
 
 // ---- device ------------------------------------------------------------------
-__device__ __forceinline__ u32 rotl(u32 v, int s) { return (v << s) | (v >> (32 - s)); }
+constexpr int PRF_THREADS = 1024;
 
-// t0 points at this lane's column of the replicated table: entry x at t0[64 * x]
-__device__ __forceinline__ void aes_block(const u32* __restrict__ t0, const u32 (&rk)[44], u32 c0, u32 c1, u32 c2,
-                                          u32 c3, u32 out[4]) {
-#define T(x) (t0[(x) << 6])
+// LDS byte address of a table entry: byte 0 = 4 * (lane % 64) and byte 2 = table number
+// come from the lane constant `lc` = 4 * lane | 0x0100, byte 1 = byte `B` of the state word.
+// v_perm_b32(S0, S1, sel): selector values 0-3 pick bytes of S1, 4-7 bytes of S0, 0x0c gives 0.
+template <int B, int TABLE>
+__device__ __forceinline__ u32 lut(const char* __restrict__ tbl, u32 state, u32 lc) {
+    constexpr u32 sel = 0x0C000000u | (TABLE ? 0x00010000u : 0x000C0000u) | ((u32)(4 + B) << 8);
+    return *reinterpret_cast<const u32*>(tbl + __builtin_amdgcn_perm(state, lc, sel));
+}
+
+__device__ __forceinline__ u32 rotl8(u32 v) { return __builtin_amdgcn_alignbit(v, v, 24); }
+
+// one output column of a full round: bytes 0..3 taken from state words a, b, c, d
+__device__ __forceinline__ u32 column(const char* tbl, u32 lc, u32 a, u32 b, u32 c, u32 d, u32 rk) {
+    return (lut<0, 0>(tbl, a, lc) ^ lut<2, 1>(tbl, c, lc)) ^ rotl8(lut<1, 0>(tbl, b, lc) ^ lut<3, 1>(tbl, d, lc)) ^ rk;
+}
+
+// one output word of the last round: S-box bytes (byte 1 of T0) of byte 0 of a, 1 of b, 2 of c, 3 of d
+__device__ __forceinline__ u32 last_column(const char* tbl, u32 lc, u32 a, u32 b, u32 c, u32 d, u32 rk) {
+    const u32 ta = lut<0, 0>(tbl, a, lc), tb = lut<1, 0>(tbl, b, lc), tc = lut<2, 0>(tbl, c, lc),
+              td = lut<3, 0>(tbl, d, lc);
+    const u32 lo = __builtin_amdgcn_perm(tb, ta, 0x0C0C0501u);  // (ta.b1, tb.b1, 0, 0)
+    const u32 hi = __builtin_amdgcn_perm(td, tc, 0x0C0C0501u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u) ^ rk;
+}
+
+__device__ __forceinline__ void aes_block(const char* __restrict__ tbl, u32 lc, const u32 (&rk)[44], u32 c0, u32 c1,
+                                          u32 c2, u32 c3, u32 out[4]) {
     u32 s0 = c0 ^ rk[0], s1 = c1 ^ rk[1], s2 = c2 ^ rk[2], s3 = c3 ^ rk[3];
 #pragma unroll
     for (int r = 1; r < 10; ++r) {
-        const u32 n0 = T(s0 & 0xFF) ^ rotl(T((s1 >> 8) & 0xFF), 8) ^ rotl(T((s2 >> 16) & 0xFF), 16) ^
-                       rotl(T(s3 >> 24), 24) ^ rk[4 * r];
-        const u32 n1 = T(s1 & 0xFF) ^ rotl(T((s2 >> 8) & 0xFF), 8) ^ rotl(T((s3 >> 16) & 0xFF), 16) ^
-                       rotl(T(s0 >> 24), 24) ^ rk[4 * r + 1];
-        const u32 n2 = T(s2 & 0xFF) ^ rotl(T((s3 >> 8) & 0xFF), 8) ^ rotl(T((s0 >> 16) & 0xFF), 16) ^
-                       rotl(T(s1 >> 24), 24) ^ rk[4 * r + 2];
-        const u32 n3 = T(s3 & 0xFF) ^ rotl(T((s0 >> 8) & 0xFF), 8) ^ rotl(T((s1 >> 16) & 0xFF), 16) ^
-                       rotl(T(s2 >> 24), 24) ^ rk[4 * r + 3];
+        const u32 n0 = column(tbl, lc, s0, s1, s2, s3, rk[4 * r]);
+        const u32 n1 = column(tbl, lc, s1, s2, s3, s0, rk[4 * r + 1]);
+        const u32 n2 = column(tbl, lc, s2, s3, s0, s1, rk[4 * r + 2]);
+        const u32 n3 = column(tbl, lc, s3, s0, s1, s2, rk[4 * r + 3]);
         s0 = n0; s1 = n1; s2 = n2; s3 = n3;
     }
-    // last round: SubBytes + ShiftRows + AddRoundKey; S[x] is byte 1 of T0[x]
-#define SB(v) ((T((v)&0xFF) >> 8) & 0xFF)
-    out[0] = (SB(s0) | (SB(s1 >> 8) << 8) | (SB(s2 >> 16) << 16) | (SB(s3 >> 24) << 24)) ^ rk[40];
-    out[1] = (SB(s1) | (SB(s2 >> 8) << 8) | (SB(s3 >> 16) << 16) | (SB(s0 >> 24) << 24)) ^ rk[41];
-    out[2] = (SB(s2) | (SB(s3 >> 8) << 8) | (SB(s0 >> 16) << 16) | (SB(s1 >> 24) << 24)) ^ rk[42];
-    out[3] = (SB(s3) | (SB(s0 >> 8) << 8) | (SB(s1 >> 16) << 16) | (SB(s2 >> 24) << 24)) ^ rk[43];
-#undef SB
-#undef T
+    out[0] = last_column(tbl, lc, s0, s1, s2, s3, rk[40]);
+    out[1] = last_column(tbl, lc, s1, s2, s3, s0, rk[41]);
+    out[2] = last_column(tbl, lc, s2, s3, s0, s1, rk[42]);
+    out[3] = last_column(tbl, lc, s3, s0, s1, s2, rk[43]);
 }
 
 struct T0Table {
@@ -129,27 +147,35 @@ __device__ __forceinline__ u64 asr64(u64 v, int d) { return (u64)((int64_t)v >> 
 // binary shares (xor_mode, ALPHA only):  out = (z ? z : 0) ^ F(self, j) ^ F(prev, j).
 // One thread handles one AES block = two consecutive words of each stream.
 template <bool ALPHA, bool MASK>
-__global__ __launch_bounds__(256) void prf_combine_kernel(const u64* __restrict__ z, const u64* __restrict__ msg,
+__global__ __launch_bounds__(PRF_THREADS) void prf_combine_kernel(const u64* __restrict__ z, const u64* __restrict__ msg,
                                                           u64* __restrict__ out, size_t n, u64 first, u64 nonce,
                                                           u64 mask_nonce, int d, bool add_mask, bool xor_mode,
                                                           const PrfKeys keys, const T0Table table) {
-    __shared__ u32 t0_all[256 * 64];
+    __shared__ __attribute__((aligned(16))) u32 tables[2 * 256 * 64];  // T0 then T2, one copy per bank
     {
-        const u32 mine = table.v[threadIdx.x];
-#pragma unroll 8
-        for (int c = 0; c < 64; ++c) t0_all[threadIdx.x * 64 + ((c + threadIdx.x) & 63)] = mine;
+        // thread t fills 16 of the 64 copies of entry t % 256 in both tables; consecutive threads
+        // start at consecutive banks
+        const int e = threadIdx.x & 255, q = threadIdx.x >> 8;
+        const u32 v0 = table.v[e], v2 = (v0 << 16) | (v0 >> 16);
+#pragma unroll 4
+        for (int c = 0; c < 16; ++c) {
+            const int copy = q * 16 + ((c + e) & 15);
+            tables[e * 64 + copy] = v0;
+            tables[256 * 64 + e * 64 + copy] = v2;
+        }
     }
     __syncthreads();
-    const u32* t0 = t0_all + (threadIdx.x & 63);
+    const char* tbl = reinterpret_cast<const char*>(tables);
+    const u32 lc = ((threadIdx.x & 63) << 2) | 0x0100u;
     const u64 b_first = first >> 1, b_last = (first + n - 1) >> 1;  // n >= 1
     const u64 nblocks = b_last - b_first + 1;
-    for (u64 bi = (u64)blockIdx.x * 256 + threadIdx.x; bi < nblocks; bi += (u64)gridDim.x * 256) {
+    for (u64 bi = (u64)blockIdx.x * PRF_THREADS + threadIdx.x; bi < nblocks; bi += (u64)gridDim.x * PRF_THREADS) {
         const u64 block = b_first + bi;
         u64 w0 = 0, w1 = 0, r0 = 0, r1 = 0;
         if constexpr (ALPHA) {
             u32 a[4], b[4];
-            aes_block(t0, keys.self, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), a);
-            aes_block(t0, keys.prev, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), b);
+            aes_block(tbl, lc, keys.self, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), a);
+            aes_block(tbl, lc, keys.prev, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), b);
             const u64 a0 = ((u64)a[1] << 32) | a[0], a1 = ((u64)a[3] << 32) | a[2];
             const u64 b0 = ((u64)b[1] << 32) | b[0], b1 = ((u64)b[3] << 32) | b[2];
             w0 = xor_mode ? a0 ^ b0 : a0 - b0;
@@ -157,7 +183,7 @@ __global__ __launch_bounds__(256) void prf_combine_kernel(const u64* __restrict_
         }
         if constexpr (MASK) {
             u32 m[4];
-            aes_block(t0, keys.mask, (u32)block, (u32)(block >> 32), (u32)mask_nonce, (u32)(mask_nonce >> 32), m);
+            aes_block(tbl, lc, keys.mask, (u32)block, (u32)(block >> 32), (u32)mask_nonce, (u32)(mask_nonce >> 32), m);
             r0 = ((u64)m[1] << 32) | m[0];
             r1 = ((u64)m[3] << 32) | m[2];
             if (!add_mask) { r0 = 0 - r0; r1 = 0 - r1; }
@@ -194,10 +220,11 @@ hipError_t launch_prf_combine(const uint64_t* z, const uint64_t* msg, uint64_t* 
     if (mask) expand_key(key_mask, keys.mask);
     T0Table table;
     memcpy(table.v, tables().t0, sizeof(table.v));
+    // 128 KiB of tables per block: one block of 16 waves per compute unit, grid-stride beyond two rounds
     const size_t nblocks = (n + 1) / 2 + 1;
-    size_t grid = (nblocks + 255) / 256;
-    if (grid > 256 * 8) grid = 256 * 8;
-    const dim3 g((unsigned)grid), b(256);
+    size_t grid = (nblocks + PRF_THREADS - 1) / PRF_THREADS;
+    if (grid > 256 * 2) grid = 256 * 2;
+    const dim3 g((unsigned)grid), b(PRF_THREADS);
     if (alpha && mask)
         hipLaunchKernelGGL((prf_combine_kernel<true, true>), g, b, 0, stream, z, msg, out, n, (u64)first, (u64)nonce,
                            (u64)mask_nonce, d, add_mask, xor_mode, keys, table);
