@@ -190,6 +190,17 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / args.steps
 
+    # spread of single steps (separate pass, one event pair per step)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record()
+    for i in range(args.steps):
+        step()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    single = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    step_spread = {"median_ms": round(single[len(single) // 2], 5), "min_ms": round(single[0], 5),
+                   "max_ms": round(single[-1], 5)}
+
     total_mnk = sum(L.mnk * L.repeat for L in layers)
     launches = sum(L.repeat for L in layers)
     value = 3.0 * total_mnk / (ms_per_step * 1e-3)
@@ -291,6 +302,15 @@ def main() -> int:
                           "frac": round(big_tops / INT8_PEAK_TOPS, 4)},
         "traffic": PROFILED_TRAFFIC_CONFIG4 if args.config == WORKLOAD_CONFIG else None,
     }
+    # Per layer: measured time against t_roof = max(int8 ops / peak, algorithmic bytes / HBM peak) and the larger term.
+    per_layer = []
+    for L, ms in zip(layers, per_layer_ms):
+        t_mfma = 2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * L.mnk / (INT8_PEAK_TOPS * 1e12)
+        t_hbm = L.algorithmic_bytes / 8e12
+        per_layer.append({"name": L.name, "gemm": list(L.gemm), "repeat": L.repeat, "us": round(ms * 1e3, 2),
+                          "t_roof_us": round(max(t_mfma, t_hbm) * 1e6, 2), "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                          "frac_of_roof": round(max(t_mfma, t_hbm) / (ms * 1e-3), 4)})
+    roofline["layers"] = per_layer
     if not args.no_mfma_probe:
         # register-only MFMA loop on the same box: what the matrix cores sustain at the power limit
         peak_const, peak_random = mfma_ceiling(False), mfma_ceiling(True)
@@ -344,7 +364,7 @@ def main() -> int:
 
     out = {
         "metric": METRIC, "value": value, "unit": "ring MAC/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "step_spread": step_spread,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "dtype_note": "u64 ring elements as 8 signed-byte digits on int8 MFMA, i32 accumulate, exact",
         "data": "synthetic",
