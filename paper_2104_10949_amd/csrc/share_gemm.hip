@@ -1183,6 +1183,11 @@ hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStrea
     // full, a 64 x 128 block tile wastes fewer MFMAs.
     if (amode == A_TRANS && bmode == B_PATCH_T && T::BM == 128 && (p.M - 1) % 128 < 64 && p.M <= 448 && p.N > 64)
         return launch<Tile<2, 4, 1, 1>, A_TRANS, B_PATCH_T>(p, stream);
+    // Fully connected layers at small batch: one MFMA row block holds all of M, so a
+    // 32 x 128 tile of four waves does a quarter of the matrix work of the 128-row tile
+    // (measured: pays from K of a few thousand on; shorter products are launch-bound either way).
+    if (amode == A_LINEAR_VEC && bmode == B_VEC && T::BM == 128 && p.M <= 32 && p.N >= 128 && p.K >= 2048)
+        return launch<Tile<1, 4, 1, 1>, A_LINEAR_VEC, B_VEC>(p, stream);
 #define CG_CASE(A, B) if (amode == A && bmode == B) return launch<T, A, B>(p, stream)
     CG_CASE(A_LINEAR_VEC, B_VEC);
     CG_CASE(A_LINEAR_SCALAR, B_SCALAR);

@@ -65,6 +65,7 @@ MATMUL_SHAPES = [
     (1, 1, 1), (1, 1, 2), (3, 5, 7), (32, 32, 32), (33, 31, 34), (17, 63, 65), (128, 64, 32),
     (129, 65, 33), (130, 70, 100), (200, 100, 31), (256, 256, 256), (300, 129, 130), (64, 200, 512),
     (5, 1000, 96), (1000, 3, 40),
+    (32, 130, 2048), (7, 300, 4100), (1, 128, 2048),   # small batch, long K: the 32-row tile
 ]
 
 
