@@ -52,6 +52,12 @@
 #ifndef CG_TILE
 #define CG_TILE 4, 2, 1, 1
 #endif
+#ifndef CG_A_AHEAD
+#define CG_A_AHEAD 1   // how many digits ahead the left operand's fragments are fetched from LDS
+#endif
+#ifndef CG_B_AHEAD
+#define CG_B_AHEAD 2   // how many MFMA slots ahead the right operand's fragments are fetched
+#endif
 #ifndef CG_MINBLOCKS
 #define CG_MINBLOCKS 1
 #endif
@@ -731,7 +737,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     constexpr int LAST = NMFMA - 2 * SM * SN;  // the final slots only drain
     auto half_step = [&](const char* cur, char* nxt, auto even_c, auto&& issue_loads) {
         v4i bf[SN][8];
-        v4i af[2][SM];
+        v4i af[CG_A_AHEAD + 1][SM];
         auto read_b = [&](int m) {
 #pragma unroll
             for (int sn = 0; sn < SN; ++sn)
@@ -740,22 +746,26 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         auto read_a = [&](int l) {
 #pragma unroll
             for (int sm = 0; sm < SM; ++sm)
-                af[l & 1][sm] = *reinterpret_cast<const v4i*>(cur + a_frag + l * 2 * T::A_RS + sm * 512);
+                af[l % (CG_A_AHEAD + 1)][sm] = *reinterpret_cast<const v4i*>(cur + a_frag + l * 2 * T::A_RS + sm * 512);
         };
+        // fragments of the first MFMA first; the other initial reads are not waited for
         read_a(0);
         read_b(0);
-        read_b(1);
+        static_for<1, CG_B_AHEAD>([&](auto m_c) { read_b(decltype(m_c)::value); });
+        static_for<1, CG_A_AHEAD>([&](auto l_c) { read_a(decltype(l_c)::value); });
         __builtin_amdgcn_sched_barrier(0);
         static_for<0, NMFMA>([&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
             constexpr Slot sl = decode_slot(slot, SM, SN);
             constexpr int l = sl.l, m = sl.m, sm = sl.sm, sn = sl.sn;
             if constexpr (sm == 0 && sn == 0) {
-                if constexpr (l == 0 && m + 2 < 8) read_b(m + 2);
-                if constexpr (m == (l < 7 ? 1 : 0) && l < 7) read_a(l + 1);
+                if constexpr (l == 0 && m + CG_B_AHEAD < 8) read_b(m + CG_B_AHEAD);
+                // the register set of digit l + CG_A_AHEAD is free once digit l - 1 is done, i.e. from the
+                // first slot of digit l on; one slot later keeps it clear of the B reads of digit 0
+                if constexpr (m == (l < 7 ? 1 : 0) && l + CG_A_AHEAD < 8) read_a(l + CG_A_AHEAD);
             }
             acc[sm][sn][l + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                af[l & 1][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
+                af[l % (CG_A_AHEAD + 1)][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
             if constexpr (slot == 0) issue_loads();
             if constexpr (slot >= PRE && slot < LAST) {
                 constexpr int lo = (slot - PRE) * NOPS / (LAST - PRE);
