@@ -32,9 +32,11 @@
 // is exact padding in the ring), split into digit planes in registers
 // (4 integer ops + 4 byte permutes per word), written to LDS as
 // [digit][k-half][row][16 bytes] so that every MFMA operand is one conflict-free
-// ds_read_b128, and consumed by v_mfma_i32_32x32x32_i8.  Convolution uses the
-// same kernel: only the address generator of the left operand differs (patch
-// gather from NHWC with zero fill).  Nothing but z is written to HBM.
+// ds_read_b128, and consumed by v_mfma_i32_32x32x32_i8.  Convolution and the
+// backward products of both layer kinds (Sec. III-C) use the same kernel: only the
+// address generators of the operands differ (patch gather from NHWC with zero
+// fill, operands stored transposed, the filter read with its taps reversed, patch
+// entries gathered as the right operand).  Nothing but z is written to HBM.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
