@@ -606,6 +606,33 @@ void oracle_party_mul(const u64 *x_i, const u64 *x_ip1, const u64 *y_i, const u6
     }
 }
 
+/* Bias of a linear layer on shares (Sec. III-B "Linear operations": adding shared
+ * values is local).  Forward: every row of z [rows, cols] gets the bias share b [cols]
+ * added, component by component.  Backward: the bias gradient is the column sum of the
+ * incoming gradient, again component by component. */
+void oracle_share_bias_add(const u64 *xa, const u64 *xb, const u64 *ba, const u64 *bb,
+                           u64 *za, u64 *zb, size_t rows, size_t cols)
+{
+    for (size_t r = 0; r < rows; ++r)
+        for (size_t c = 0; c < cols; ++c) {
+            za[r * cols + c] = xa[r * cols + c] + ba[c];
+            zb[r * cols + c] = xb[r * cols + c] + bb[c];
+        }
+}
+
+void oracle_share_col_sum(const u64 *xa, const u64 *xb, u64 *za, u64 *zb, size_t rows, size_t cols)
+{
+    for (size_t c = 0; c < cols; ++c) {
+        u64 sa = 0, sb = 0;
+        for (size_t r = 0; r < rows; ++r) {
+            sa += xa[r * cols + c];
+            sb += xb[r * cols + c];
+        }
+        za[c] = sa;
+        zb[c] = sb;
+    }
+}
+
 /* Window sums of an NHWC tensor, zero padded: the linear part of average
  * pooling (Sec. V "Average pooling": pooling by averaging is linear, hence local
  * on shares).  Applied to each component of a replicated pair separately.  The

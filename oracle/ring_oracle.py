@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_party_conv2d_at.argtypes = [_u64p] * 4 + [_i64] * 13
         L.oracle_party_conv2d_at.restype = ctypes.c_uint64
         L.oracle_party_mul.argtypes = [_u64p] * 5 + [_sz, _sz]
+        L.oracle_share_bias_add.argtypes = [_u64p] * 6 + [_sz, _sz]
+        L.oracle_share_col_sum.argtypes = [_u64p] * 4 + [_sz, _sz]
         L.oracle_sum_pool2d.argtypes = [_u64p, _u64p] + [_i64] * 10
         u8p = ctypes.POINTER(ctypes.c_uint8)
         L.oracle_aes128_encrypt_block.argtypes = [u8p, u8p, u8p]
@@ -438,6 +440,25 @@ def party_mul(x_i, x_ip1, y_i, y_ip1) -> np.ndarray:
     if x_i.size:
         lib().oracle_party_mul(_p(x_i), _p(x_ip1), _p(y_i), _p(y_ip1), _p(z), x_i.size, y_i.size)
     return z
+
+
+def share_bias_add(xa, xb, ba, bb):
+    """(xa + ba, xb + bb) with the bias [cols] broadcast over the rows of x [..., cols]."""
+    xa, xb, ba, bb = _u(xa), _u(xb), _u(ba), _u(bb)
+    cols = ba.size
+    assert xa.shape == xb.shape and bb.size == cols and xa.shape[-1] == cols
+    za, zb = np.empty(xa.shape, dtype=np.uint64), np.empty(xa.shape, dtype=np.uint64)
+    lib().oracle_share_bias_add(_p(xa), _p(xb), _p(ba), _p(bb), _p(za), _p(zb), xa.size // cols, cols)
+    return za, zb
+
+
+def share_col_sum(xa, xb):
+    """Column sums of both components of x [..., cols] over all leading dimensions."""
+    xa, xb = _u(xa), _u(xb)
+    cols = xa.shape[-1]
+    za, zb = np.empty(cols, dtype=np.uint64), np.empty(cols, dtype=np.uint64)
+    lib().oracle_share_col_sum(_p(xa), _p(xb), _p(za), _p(zb), xa.size // cols, cols)
+    return za, zb
 
 
 def sum_pool2d(X, window, stride, pad=(0, 0)) -> np.ndarray:

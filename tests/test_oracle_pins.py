@@ -385,3 +385,32 @@ def test_sum_pool_closed_forms_and_paper_sizes():
     s = ro.share(X, ring(X.shape, 234), ring(X.shape, 235))
     pooled = [ro.sum_pool2d(v, (3, 3), (2, 2), (1, 1)) for v in s]
     assert np.array_equal(ro.reconstruct(*pooled), ro.sum_pool2d(X, (3, 3), (2, 2), (1, 1)))
+
+
+# ---------------------------------------------------------------- bias of a linear layer
+def test_bias_add_and_its_gradient():
+    rows, cols = 37, 11
+    x, b = ring((rows, cols), 501), ring((cols,), 502)
+    sx = ro.share(x, ring(x.shape, 503), ring(x.shape, 504))
+    sb = ro.share(b, ring(b.shape, 505), ring(b.shape, 506))
+    outs = [ro.share_bias_add(*ro.party_pair(sx, i), *ro.party_pair(sb, i)) for i in range(3)]
+    # party i's first component is share i: the three open to x + b, row by row, in Python integers
+    opened = ro.reconstruct(outs[0][0], outs[1][0], outs[2][0])
+    want = [[(int(x[r, c]) + int(b[c])) % MOD for c in range(cols)] for r in range(rows)]
+    assert opened.tolist() == want
+    # replicated form is kept: party i's second component is party i+1's first
+    for i in range(3):
+        assert np.array_equal(outs[i][1], outs[(i + 1) % 3][0])
+    sums = [ro.share_col_sum(*ro.party_pair(sx, i)) for i in range(3)]
+    opened = ro.reconstruct(sums[0][0], sums[1][0], sums[2][0])
+    assert opened.tolist() == [sum(int(x[r, c]) for r in range(rows)) % MOD for c in range(cols)]
+    # on a 4-d tensor the leading dimensions are all rows
+    x4 = ring((2, 3, 4, 5), 507)
+    za, _ = ro.share_col_sum(x4, x4)
+    assert za.tolist() == [sum(int(v) for v in x4[..., c].reshape(-1)) % MOD for c in range(5)]
+    # adjoint pair: <x + 1 b^T, g> - <x, g> = <b, colsum(g)>
+    g = ring((rows, cols), 508)
+    za, _ = ro.share_bias_add(x, x, b, b)
+    ga, _ = ro.share_col_sum(g, g)
+    dot = lambda u, v: sum(int(p) * int(q) for p, q in zip(u.reshape(-1).tolist(), v.reshape(-1).tolist())) % MOD
+    assert (dot(za, g) - dot(x, g)) % MOD == dot(b, ga)
