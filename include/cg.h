@@ -246,6 +246,28 @@ CG_API cg_status cg_share_mul(const uint64_t *x_i, const uint64_t *x_ip1,
                        uint64_t *z_i, size_t n, size_t period, void *stream);
 
 /*
+ * Bias of a linear layer on replicated pairs (Sec. III-B "Linear operations": sums
+ * of shared values are computed share by share, locally).
+ *
+ *   cg_share_bias_add : (za, zb)[j] = (xa[j] + ba[j mod period], xb[j] + bb[j mod period]),
+ *                       j < n: the bias pair [period] broadcast over the rows of a
+ *                       [n / period, period] tensor (FC output, or NHWC with period = C).
+ *                       period must divide n (CG_ERR_SHAPE).  za/zb may equal xa/xb.
+ *   cg_share_col_sum  : (za, zb)[c] = sum over r < rows of (xa, xb)[r * cols + c]: the bias
+ *                       gradient of the layer from the incoming gradient [rows, cols].
+ *                       Outputs [cols] must not overlap the inputs or each other.
+ *
+ * When the first operand is the party's additive product share z_i rather than a pair,
+ * pass it for both components and ignore zb.  n == 0 / cols == 0 return CG_OK.
+ */
+CG_API cg_status cg_share_bias_add(const uint64_t *xa, const uint64_t *xb, const uint64_t *ba,
+                            const uint64_t *bb, uint64_t *za, uint64_t *zb, size_t n, size_t period,
+                            void *stream);
+
+CG_API cg_status cg_share_col_sum(const uint64_t *xa, const uint64_t *xb, uint64_t *za, uint64_t *zb,
+                           size_t rows, size_t cols, void *stream);
+
+/*
  * Window sums of both components of a replicated pair, NHWC, zero padded: the
  * linear, hence local, part of average pooling (Sec. V "Average pooling").
  *   z[b][ho][wo][c] = sum over the kh x kw window at (ho*stride_h - pad_h, wo*stride_w - pad_w) of x[b][.][.][c]

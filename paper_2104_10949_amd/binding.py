@@ -25,7 +25,7 @@ EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d
            "cg_share_matmul_ws", "cg_share_conv2d_ws", "cg_zero_share", "cg_reshare", "cg_share_matmul_t",
            "cg_share_mul", "cg_share_sum_pool2d", "cg_share_conv2d_dgrad", "cg_share_conv2d_wgrad",
            "cg_trunc1_local", "cg_prf_words", "cg_bshare_xor", "cg_bshare_and", "cg_bshare_prefix_stage",
-           "cg_bzero_share", "cg_breshare",
+           "cg_bzero_share", "cg_breshare", "cg_share_bias_add", "cg_share_col_sum",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.cg_share_matmul_t.argtypes = [vp] * 5 + [i64] * 3 + [ctypes.c_int] * 2 + [vp]
         L.cg_share_mul.argtypes = [vp] * 5 + [sz, sz, vp]
         L.cg_share_sum_pool2d.argtypes = [vp] * 4 + [ctypes.POINTER(PoolDesc), vp]
+        L.cg_share_bias_add.argtypes = [vp] * 6 + [sz, sz, vp]
+        L.cg_share_col_sum.argtypes = [vp] * 4 + [sz, sz, vp]
         L.cg_bshare_xor.argtypes = [vp] * 6 + [sz, vp]
         L.cg_bshare_and.argtypes = [vp] * 5 + [sz, vp]
         L.cg_bshare_prefix_stage.argtypes = [vp] * 4 + [ctypes.c_int, vp, vp, sz, vp]
@@ -89,9 +91,9 @@ def lib() -> ctypes.CDLL:
         L.cg_prf_words.argtypes = [key, u64, u64, vp, sz, vp]
         L.cg_share_conv2d_dgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
         L.cg_share_conv2d_wgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
-        for name in EXPORTS[2:24]:
+        for name in EXPORTS[2:26]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[24:]:
+        for name in EXPORTS[26:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -399,6 +401,31 @@ def cg_prf_words(key: bytes, nonce: int, first: int, n: int, out=None, stream=No
         raise ValueError("output size does not match")
     _check(lib().cg_prf_words(_key16(key), nonce, first, _ptr(out) if n else None, n, _stream(stream)), "cg_prf_words")
     return out
+
+
+def cg_share_bias_add(xa, xb, ba, bb, za=None, zb=None, stream=None):
+    """(xa + ba, xb + bb) with the bias pair [cols] broadcast over the leading dimensions of x [..., cols]."""
+    if xa.shape != xb.shape or ba.shape != bb.shape or ba.dim() != 1 or xa.shape[-1] != ba.shape[0]:
+        raise ValueError("operand shapes do not match")
+    za = torch.empty_like(xa) if za is None else za
+    zb = torch.empty_like(xb) if zb is None else zb
+    n = xa.numel()
+    _check(lib().cg_share_bias_add(*(_ptr(t) if n else 0 for t in (xa, xb, ba, bb, za, zb)), n, ba.numel(),
+                                   _stream(stream)), "cg_share_bias_add")
+    return za, zb
+
+
+def cg_share_col_sum(xa, xb, za=None, zb=None, stream=None):
+    """Column sums of both components of x [..., cols] over all leading dimensions."""
+    if xa.shape != xb.shape:
+        raise ValueError("operand shapes do not match")
+    cols = xa.shape[-1]
+    rows = xa.numel() // cols if cols else 0
+    za = torch.empty((cols,), dtype=torch.int64, device=xa.device) if za is None else za
+    zb = torch.empty((cols,), dtype=torch.int64, device=xa.device) if zb is None else zb
+    _check(lib().cg_share_col_sum(_ptr(xa) if rows else 0, _ptr(xb) if rows else 0, _ptr(za) if cols else 0,
+                                  _ptr(zb) if cols else 0, rows, cols, _stream(stream)), "cg_share_col_sum")
+    return za, zb
 
 
 def cg_bshare_xor(xa, xb, ya, yb, za=None, zb=None, stream=None):

@@ -181,6 +181,81 @@ struct PartyMulOp {
     }
 };
 
+// (za, zb) = (xa + ba[j'], xb + bb[j']), j' = j mod period: a bias share broadcast over the rows
+struct BiasAddOp {
+    const u64 *xa, *xb, *ba, *bb;
+    u64 *za, *zb;
+    size_t period;   // in elements; the pair path requires it to be even
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        const size_t hp = period >> 1;
+        ull2 a[U], b[U], c[U], d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t k = i + u * step, kp = k % hp;
+            a[u] = ld2(xa, k); b[u] = ld2(xb, k);
+            c[u] = reinterpret_cast<const ull2*>(ba)[kp];
+            d[u] = reinterpret_cast<const ull2*>(bb)[kp];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            st2(za, i + u * step, a[u] + c[u]);
+            st2(zb, i + u * step, b[u] + d[u]);
+        }
+    }
+    __device__ void one(size_t i) const {
+        const size_t ip = i % period;
+        const u64 a = xa[i] + ba[ip], b = xb[i] + bb[ip];
+        za[i] = a;
+        zb[i] = b;
+    }
+};
+
+// Column sums of both components of x [rows, cols] into zero-filled za, zb [cols].  A block covers 64
+// columns (one per lane, so a wave reads 512 contiguous bytes of a row) and a slice of the rows; its
+// four waves take rows in turn, their partial sums meet in LDS and one wave adds them to the output
+// atomically (integer sums mod 2^64 do not depend on the order).
+__global__ __launch_bounds__(256) void col_sum_kernel(const u64* __restrict__ xa, const u64* __restrict__ xb,
+                                                      u64* __restrict__ za, u64* __restrict__ zb, size_t rows,
+                                                      size_t cols) {
+    __shared__ u64 part[2][4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t c = (size_t)blockIdx.x * 64 + lane;
+    u64 sa = 0, sb = 0;
+    if (c < cols) {
+        const size_t stride = (size_t)gridDim.y * 4;
+        size_t r = (size_t)blockIdx.y * 4 + wave;
+        for (; r + 3 * stride < rows; r += 4 * stride) {   // four independent loads per stream in flight
+            const u64 a0 = xa[r * cols + c], a1 = xa[(r + stride) * cols + c], a2 = xa[(r + 2 * stride) * cols + c],
+                      a3 = xa[(r + 3 * stride) * cols + c];
+            const u64 b0 = xb[r * cols + c], b1 = xb[(r + stride) * cols + c], b2 = xb[(r + 2 * stride) * cols + c],
+                      b3 = xb[(r + 3 * stride) * cols + c];
+            sa += (a0 + a1) + (a2 + a3);
+            sb += (b0 + b1) + (b2 + b3);
+        }
+        for (; r < rows; r += stride) {
+            sa += xa[r * cols + c];
+            sb += xb[r * cols + c];
+        }
+    }
+    part[0][wave][lane] = sa;
+    part[1][wave][lane] = sb;
+    __syncthreads();
+    if (wave == 0 && c < cols) {
+        sa = part[0][0][lane] + part[0][1][lane] + part[0][2][lane] + part[0][3][lane];
+        sb = part[1][0][lane] + part[1][1][lane] + part[1][2][lane] + part[1][3][lane];
+        atomicAdd(reinterpret_cast<unsigned long long*>(za + c), (unsigned long long)sa);
+        atomicAdd(reinterpret_cast<unsigned long long*>(zb + c), (unsigned long long)sb);
+    }
+}
+
+__global__ __launch_bounds__(256) void zero2_kernel(u64* a, u64* b, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        a[i] = 0;
+        b[i] = 0;
+    }
+}
+
 // ---- binary (XOR) replicated shares: 64 independent bits per word ----------------
 struct BXorOp {  // (za, zb) = (xa ^ ya, xb ^ yb)
     const u64 *xa, *xb, *ya, *yb;
@@ -792,6 +867,58 @@ cg_status cg_share_mul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_
     PartyMulOp f = {x_i, x_ip1, y_i, y_ip1, z_i, period};
     const bool vec = all_aligned16(ptrs, 5) && period % 2 == 0;
     return launch_ew(n, vec, f, stream);
+}
+
+cg_status cg_share_bias_add(const uint64_t* xa, const uint64_t* xb, const uint64_t* ba, const uint64_t* bb,
+                            uint64_t* za, uint64_t* zb, size_t n, size_t period, void* stream) {
+    if (n == 0) return CG_OK;
+    const void* ptrs[6] = {xa, xb, ba, bb, za, zb};
+    if (cg_status st = check_ptrs(ptrs, 6)) return st;
+    if (period == 0 || period > n || n % period != 0 || n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8, bbytes = (u64)period * 8;
+    if (bad_overlap(za, xa, bytes) || bad_overlap(za, xb, bytes) || bad_overlap(zb, xa, bytes) ||
+        bad_overlap(zb, xb, bytes) || overlap(za, bytes, zb, bytes))
+        return CG_ERR_ALIAS;
+    if (overlap(za, bytes, ba, bbytes) || overlap(za, bytes, bb, bbytes) || overlap(zb, bytes, ba, bbytes) ||
+        overlap(zb, bytes, bb, bbytes))
+        return CG_ERR_ALIAS;
+    BiasAddOp f = {xa, xb, ba, bb, za, zb, period};
+    return launch_ew(n, all_aligned16(ptrs, 6) && period % 2 == 0, f, stream);
+}
+
+cg_status cg_share_col_sum(const uint64_t* xa, const uint64_t* xb, uint64_t* za, uint64_t* zb, size_t rows,
+                           size_t cols, void* stream) {
+    if (cols == 0) return CG_OK;
+    if (!za || !zb) return CG_ERR_NULL;
+    if (!aligned(za, 8) || !aligned(zb, 8)) return CG_ERR_ALIGN;
+    size_t n;
+    if (__builtin_mul_overflow(rows, cols, &n) || n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    if (overlap(za, (u64)cols * 8, zb, (u64)cols * 8)) return CG_ERR_ALIAS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (rows > 0) {
+        if (!xa || !xb) return CG_ERR_NULL;
+        if (!aligned(xa, 8) || !aligned(xb, 8)) return CG_ERR_ALIGN;
+        const u64 xbytes = (u64)n * 8, zbytes = (u64)cols * 8;
+        if (overlap(za, zbytes, xa, xbytes) || overlap(za, zbytes, xb, xbytes) || overlap(zb, zbytes, xa, xbytes) ||
+            overlap(zb, zbytes, xb, xbytes))
+            return CG_ERR_ALIAS;
+    }
+    size_t zblocks = (cols + 255) / 256;
+    if (zblocks > 1024) zblocks = 1024;
+    hipLaunchKernelGGL(zero2_kernel, dim3((unsigned)zblocks), dim3(256), 0, s, za, zb, cols);
+    if (rows > 0) {
+        const size_t col_tiles = (cols + 63) / 64;
+        if (col_tiles > 0x7FFFFFFF) return CG_ERR_UNSUPPORTED;
+        // about eight blocks per compute unit, at least 16 rows per wave
+        size_t row_blocks = (2048 + col_tiles - 1) / col_tiles;
+        const size_t max_rb = (rows + 63) / 64;
+        if (row_blocks > max_rb) row_blocks = max_rb;
+        if (row_blocks < 1) row_blocks = 1;
+        if (row_blocks > 65535) row_blocks = 65535;
+        hipLaunchKernelGGL(col_sum_kernel, dim3((unsigned)col_tiles, (unsigned)row_blocks), dim3(256), 0, s, xa, xb, za,
+                           zb, rows, cols);
+    }
+    return hipGetLastError() == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
 
 cg_status cg_share_sum_pool2d(const uint64_t* xa, const uint64_t* xb, uint64_t* za, uint64_t* zb,

@@ -498,3 +498,23 @@ def test_sum_pool_matches_the_oracle(cg, ro, wl, shape, window, stride, pad):
     za, zb = cg.cg_share_sum_pool2d(cg.to_device(xa), cg.to_device(xb), window, stride, pad)
     assert not first_mismatch(cg.to_host(za), ro.sum_pool2d(xa, window, stride, pad))
     assert not first_mismatch(cg.to_host(zb), ro.sum_pool2d(xb, window, stride, pad))
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (3, 7), (37, 11), (128, 64), (1000, 10), (2, 9, 9, 3), (32, 16, 16, 256),
+                                   (5, 1000), (70000, 6)])
+def test_bias_add_and_bias_gradient(cg, ro, wl, shape):
+    say(f"cg_share_bias_add / cg_share_col_sum shape={shape}")
+    cols = shape[-1]
+    xa, xb = wl.draw_ring(shape, 610), wl.draw_ring(shape, 611)
+    ba, bb = wl.draw_ring((cols,), 612), wl.draw_ring((cols,), 613)
+    d = [cg.to_device(a) for a in (xa, xb, ba, bb)]
+    za, zb = cg.cg_share_bias_add(*d)
+    wa, wb = ro.share_bias_add(xa, xb, ba, bb)
+    assert not first_mismatch(cg.to_host(za), wa) and not first_mismatch(cg.to_host(zb), wb)
+    sa, sb = cg.cg_share_col_sum(d[0], d[1])
+    wa, wb = ro.share_col_sum(xa, xb)
+    assert not first_mismatch(cg.to_host(sa), wa) and not first_mismatch(cg.to_host(sb), wb)
+    # in place over x
+    cg.cg_share_bias_add(*d, za=d[0], zb=d[1])
+    wa, wb = ro.share_bias_add(xa, xb, ba, bb)
+    assert not first_mismatch(cg.to_host(d[0]), wa) and not first_mismatch(cg.to_host(d[1]), wb)
