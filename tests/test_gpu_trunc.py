@@ -110,3 +110,48 @@ def test_truncation_argument_errors(cg):
     with pytest.raises(cg.CgError) as e:
         cg.cg_trunc1_local(z[:8], None, K0, K2, 0, 0, 16, out=z[4:12])
     assert e.value.status == cg.CG_ERR_ALIAS
+
+
+def test_fc_stack_chained_through_the_truncation_protocol(cg, ro, wl):
+    """The FC stack of configuration 2 (784-128-128-10, batch 128) evaluated layer by layer on shares:
+    three parties' local products, bias add and the two-round truncation on the GPU, so that every layer's
+    output is back at scale 2^t in replicated form.  ReLU is not part of this library: between layers the
+    test opens the activations, clips them on the host and shares them again.  The decoded logits must match
+    a float64 network on the same grid-rounded parameters."""
+    t = wl.FRAC_BITS
+    layers = wl.config_layers(2)
+    rng = np.random.default_rng(2024)
+    keys = (K0, K1, K2)
+    x_real = np.rint(rng.uniform(0, 1, size=(layers[0].M, layers[0].K)) * 2 ** t) / 2 ** t
+    act_real = x_real
+    act = ro.encode(x_real, t)
+    nonce = 100
+    for li, L in enumerate(layers):
+        say(f"chained FC stack: layer {li} {L.gemm}")
+        w_real = np.rint(rng.normal(0, 0.05, size=(L.N, L.K)) * 2 ** t) / 2 ** t
+        b_real = np.rint(rng.normal(0, 0.1, size=(L.N,)) * 2 ** t) / 2 ** t
+        w, b = ro.encode(w_real, t), ro.encode(b_real, 2 * t)          # the bias joins the product at scale 2^2t
+        sx = ro.share(act, wl.draw_ring(act.shape, 10 * li + 1), wl.draw_ring(act.shape, 10 * li + 2))
+        sw = ro.share(w, wl.draw_ring(w.shape, 10 * li + 3), wl.draw_ring(w.shape, 10 * li + 4))
+        sb = ro.share(b, wl.draw_ring(b.shape, 10 * li + 5), wl.draw_ring(b.shape, 10 * li + 6))
+        dx, dw, db = ([cg.to_device(s) for s in sh] for sh in (sx, sw, sb))
+        z = []
+        for i in range(3):
+            zi = cg.cg_share_matmul(dx[i], dx[(i + 1) % 3], dw[i], dw[(i + 1) % 3])
+            # additive share of the bias: party i adds component i (passed for both slots, second result unused)
+            zi, _ = cg.cg_share_bias_add(zi, zi, db[i], db[i])
+            z.append(zi)
+        n = z[0].numel()
+        msg = cg.cg_reshare(z[2], keys[2], keys[1], nonce, 0)
+        s0 = cg.cg_trunc1_local(z[0], None, keys[0], keys[2], nonce, 0, t)
+        s1 = cg.cg_trunc1_local(z[1], msg, keys[1], keys[0], nonce, 0, t, keys[1], nonce + 1)
+        s2 = cg.cg_prf_words(keys[1], nonce + 1, 0, n).view_as(s0)
+        nonce += 2
+        opened = cg.to_host(cg.cg_reconstruct(s0, s1, s2)).astype(np.int64)
+        pre_real = act_real @ w_real.T + b_real
+        assert np.max(np.abs(opened / 2 ** t - pre_real)) < 5e-3, f"layer {li}"
+        if li + 1 < len(layers):
+            opened = np.maximum(opened, 0)                               # host-side ReLU between layers
+            act = opened.astype(np.uint64)
+            act_real = np.maximum(pre_real, 0)
+    assert opened.shape == (layers[-1].M, layers[-1].N)
