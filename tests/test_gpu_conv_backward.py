@@ -54,6 +54,8 @@ CASES = [
     (200, 1, 1, 32, 16, 3, 3, (1, 1), (1, 1)),         # many images per K slice and per row block
     (40, 2, 2, 8, 24, 2, 2, (1, 1), (1, 1)),
     (2, 20, 20, 200, 64, 3, 3, (1, 1), (1, 1)),        # ragged tails in every dimension
+    (1, 12, 12, 8, 32, 9, 9, (1, 1), (4, 4)),          # 81 taps: beyond the 64-bit tap mask of the gather
+    (2, 10, 11, 40, 64, 9, 8, (1, 1), (4, 3)),
 ]
 
 

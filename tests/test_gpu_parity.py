@@ -189,6 +189,8 @@ CONV_CASES = [
     (2, 7, 7, 6, 10, 1, 1, (1, 1), (0, 0)),
     (4, 5, 5, 7, 9, 1, 1, (1, 1), (0, 0)),
     (200, 1, 1, 32, 16, 3, 3, (1, 1), (1, 1)),
+    (1, 12, 12, 32, 40, 9, 9, (1, 1), (4, 4)),       # 81 taps: beyond the 64-bit tap mask, bounds tested per load
+    (2, 10, 11, 64, 70, 9, 8, (2, 1), (4, 3)),
 ]
 
 
