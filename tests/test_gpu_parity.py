@@ -66,6 +66,7 @@ MATMUL_SHAPES = [
     (129, 65, 33), (130, 70, 100), (200, 100, 31), (256, 256, 256), (300, 129, 130), (64, 200, 512),
     (5, 1000, 96), (1000, 3, 40),
     (32, 130, 2048), (7, 300, 4100), (1, 128, 2048),   # small batch, long K: the 32-row tile
+    (3, 70001, 40), (70001, 3, 40), (2, 2, 30000),      # very wide, very tall, very deep
 ]
 
 
