@@ -65,6 +65,7 @@ struct GemmParams {
     uint64_t xp_bytes;          // bytes of one left-operand plane tensor
     int group_m;                // tile-rows per launch-order group (set by the launcher)
     int ksplit;                 // number of K ranges the grid is replicated over (set by the launcher)
+    int64_t stream_per;         // > 0: (tile, slice) units per block of the streamed distribution (set by the launcher)
 };
 
 // Largest block-tile height any instantiation uses; the host checks 32-bit

@@ -487,22 +487,27 @@ __device__ __forceinline__ void recode2(u4& v) {
     v.x = a; v.y = b; v.z = c; v.w = d;
 }
 
-// block -> (K split, output tile).  The hardware deals consecutive block ids to the 8
-// XCDs in turn, and each XCD has an L2 cache of its own, so block ids are mapped such
-// that every XCD works through one contiguous run of the launch order
-// (split, group of group_m tile-rows, tile column, tile-row inside the group), split
-// slowest.  With 8 or more splits an XCD therefore sees only its own ranges of K and
-// reads its share of both operands once; with fewer, its run is a box of tile-rows
-// times tile columns whose shape the host picks through group_m.
-__device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int BN, int& split, int& tm, int& tn) {
-    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const int nb = tiles_m * tiles_n;
-    const int total = nb * p.ksplit;
+// Work distribution.  The work of a launch is the list of (output tile, K slice) units in the
+// launch order (group of group_m tile-rows, tile column, tile-row inside the group, slice), and
+// every block takes one contiguous range of it:
+//  * classic: the grid holds ksplit blocks per tile, block (split, tile) takes that tile's
+//    split-th range of slices;
+//  * streamed (p.stream_per > 0): one block per compute unit takes stream_per consecutive units,
+//    whatever tiles they belong to, so the units are spread evenly even when the tile count is
+//    just above a multiple of the number of compute units.
+// The hardware deals consecutive block ids to the 8 XCDs in turn, and each XCD has an L2 cache of
+// its own, so block ids are mapped such that every XCD works through one contiguous run of the
+// order above (K splits slowest in the classic scheme).  With 8 or more splits an XCD therefore
+// sees only its own ranges of K and reads its share of both operands once; with fewer, its run is
+// a box of tile-rows times tile columns whose shape the host picks through group_m.
+__device__ __forceinline__ int run_index(int total) {
     const int bid = blockIdx.x, xcd = bid & 7, idx = bid >> 3;
     const int per = total >> 3, rem = total & 7;
-    const int run = xcd * per + (xcd < rem ? xcd : rem) + idx;
-    split = run / nb;
-    const int logical = run - split * nb;
+    return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+
+__device__ __forceinline__ void logical_to_tile(const GemmParams& p, int tiles_m, int tiles_n, int logical, int& tm,
+                                                int& tn) {
     const int GM = p.group_m;
     const int per_group = GM * tiles_n;
     const int g = logical / per_group, in_g = logical - g * per_group;
@@ -510,6 +515,15 @@ __device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int B
     const int gsz = tiles_m - first < GM ? tiles_m - first : GM;
     tm = first + in_g % gsz;
     tn = in_g / gsz;
+}
+
+// classic distribution only: block -> (K split, output tile)
+__device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int BN, int& split, int& tm, int& tn) {
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    const int nb = tiles_m * tiles_n;
+    const int run = run_index(nb * p.ksplit);
+    split = run / nb;
+    logical_to_tile(p, tiles_m, tiles_n, run - split * nb, tm, tn);
 }
 
 // fold: z (+)= sum_s sext(P_s) << 8s for the wave's sub-tiles.  P_4..P_7 only
@@ -553,7 +567,9 @@ __device__ __forceinline__ void fold_tile(const GemmParams& p, v16i (&acc)[SM][S
 }
 
 // ---------------------------------------------------------------------------
-template <class T, int AMODE, int BMODE>
+// STREAM selects the streamed work distribution (see run_index); the classic instantiation runs
+// exactly one pass and compiles to straight-line set-up code.
+template <class T, int AMODE, int BMODE, bool STREAM>
 __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const GemmParams p) {
     constexpr int SM = T::SM, SN = T::SN, AU = T::A_UNITS, BU = T::B_UNITS;
     __shared__ __attribute__((aligned(16))) char lds[2 * T::STAGE];
@@ -562,8 +578,34 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     const int wm = wave % T::WM, wn = wave / T::WM;
     const int r32 = lane & 31, h = lane >> 5;
 
-    int split, tm, tn;
-    block_to_tile(p, T::BM, T::BN, split, tm, tn);
+    // ---- this block's range [u, u_end) of (tile, slice) units
+    const int tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
+    const int nb = tiles_m * tiles_n;
+    const int nk_all = (int)((p.K + 31) / 32);
+    int64_t u, u_end;
+    if constexpr (STREAM) {
+        const int64_t units = (int64_t)nb * nk_all;
+        u = (int64_t)run_index((int)gridDim.x) * p.stream_per;
+        u_end = u + p.stream_per < units ? u + p.stream_per : units;
+    } else {
+        const int run = run_index(nb * p.ksplit);
+        const int split = run / nb, logical = run - split * nb;
+        const int per_split = (nk_all + p.ksplit - 1) / p.ksplit;
+        const int kb = split * per_split;
+        u = (int64_t)logical * nk_all + kb;
+        u_end = (int64_t)logical * nk_all + (kb + per_split < nk_all ? kb + per_split : nk_all);
+    }
+
+    // One pass per tile the range touches (exactly one in the classic scheme).  Everything that
+    // depends on the tile is set up inside the pass.
+    if (u >= u_end) return;  // uniform over the block
+    do {
+    const int logical = (int)(u / nk_all);
+    const int k_begin = (int)(u - (int64_t)logical * nk_all);
+    const int nk = (int64_t)k_begin + (u_end - u) < nk_all ? k_begin + (int)(u_end - u) : nk_all;
+    u += nk - k_begin;
+    int tm, tn;
+    logical_to_tile(p, tiles_m, tiles_n, logical, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int rows_m = p.M - m0, rows_n = p.N - n0;
 
@@ -780,12 +822,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
 
     char* const st0 = lds;
     char* const st1 = lds + T::STAGE;
-    // this block's slices of K: [k_begin, k_end)
-    const int nk_all = (int)((p.K + 31) / 32);
-    const int per_split = (nk_all + p.ksplit - 1) / p.ksplit;
-    const int k_begin = split * per_split;
-    const int nk = k_begin + per_split < nk_all ? k_begin + per_split : nk_all;
-    if (k_begin >= nk) return;  // uniform over the block; only possible when ksplit does not divide evenly
+    // this pass covers the slices [k_begin, nk) of its tile
 
     auto clear_acc = [&]() {
 #pragma unroll
@@ -829,6 +866,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         }
         fold(ks0 > k_begin);
     }
+    } while (STREAM && u < u_end);  // next tile of the range
 }
 
 // ---------------------------------------------------------------------------
@@ -1088,6 +1126,10 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream);
 #ifndef CG_SPLIT_COST_ATOMIC
 #define CG_SPLIT_COST_ATOMIC 2.0
 #endif
+// The streamed distribution must beat the classic one by this factor of modelled time to be used.
+#ifndef CG_STREAM_MARGIN
+#define CG_STREAM_MARGIN 0.88
+#endif
 
 static int choose_ksplit(int64_t tiles, int nk) {
     // A block's 96 KB of LDS leaves room for one block per compute unit, so a grid runs
@@ -1177,15 +1219,51 @@ hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t 
     return hipGetLastError();
 }
 
+// Modelled time of the classic distribution with `ks` splits, in K slices (see choose_ksplit).
+static double classic_cost(int64_t tiles, int nk, int ks) {
+    const int64_t per = (nk + ks - 1) / ks;
+    const int64_t rounds = (tiles * ks + CG_SPLIT_TARGET - 1) / CG_SPLIT_TARGET;
+    return (double)rounds * ((double)per + (ks > 1 ? CG_SPLIT_COST_ATOMIC : CG_SPLIT_COST_PLAIN));
+}
+
+// The streamed distribution is compiled for the address generators of the large layers only.
+template <int AMODE, int BMODE>
+struct CanStream {
+    static constexpr bool value = (AMODE == A_LINEAR_VEC && BMODE == B_VEC) || (AMODE == A_CONV_C32 && BMODE == B_VEC) ||
+                                  (AMODE == A_CONV_C32 && BMODE == B_FLIP_C32) || (AMODE == A_TRANS && BMODE == B_PATCH_T);
+};
+
 template <class T, int AMODE, int BMODE>
 static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
+    const int64_t tiles = tiles_m * tiles_n;
+    const int nk = (p.K + 31) / 32;
     GemmParams q = p;
-    q.ksplit = choose_ksplit(tiles_m * tiles_n, (p.K + 31) / 32);
-    q.group_m = choose_group_m(p, tiles_m, tiles_n, q.ksplit);
+    q.ksplit = choose_ksplit(tiles, nk);
+    q.stream_per = 0;
+    unsigned grid = (unsigned)(tiles * q.ksplit);
+    // Streamed distribution: one block per compute unit, each taking an equal run of (tile, slice)
+    // units.  A block pays the fixed cost once per tile its run touches (about per/nk + 1 of them).
+    // Worth it when the classic grid leaves a round partly empty.
+    const int64_t units = tiles * nk;
+    if (CanStream<AMODE, BMODE>::value && units >= 3 * CG_SPLIT_TARGET && units < ((int64_t)1 << 40)) {
+        const int64_t per = (units + CG_SPLIT_TARGET - 1) / CG_SPLIT_TARGET;
+        const double streamed = (double)per + CG_SPLIT_COST_ATOMIC * ((double)per / nk + 1.0);
+        if (streamed < CG_STREAM_MARGIN * classic_cost(tiles, nk, q.ksplit)) {
+            q.stream_per = per;
+            q.ksplit = 2;  // any value above 1: the folds add atomically into a zero-filled z
+            grid = (unsigned)((units + per - 1) / per);
+        }
+    }
+    q.group_m = choose_group_m(p, tiles_m, tiles_n, q.stream_per > 0 ? 1 : q.ksplit);
     if (q.ksplit > 1) launch_zero_fill(q, stream);
-    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BMODE>), dim3((unsigned)(tiles_m * tiles_n * q.ksplit)),
-                       dim3(T::NT), 0, stream, q);
+    if constexpr (CanStream<AMODE, BMODE>::value) {
+        if (q.stream_per > 0) {
+            hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BMODE, true>), dim3(grid), dim3(T::NT), 0, stream, q);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BMODE, false>), dim3(grid), dim3(T::NT), 0, stream, q);
     return hipGetLastError();
 }
 

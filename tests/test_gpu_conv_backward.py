@@ -56,6 +56,8 @@ CASES = [
     (2, 20, 20, 200, 64, 3, 3, (1, 1), (1, 1)),        # ragged tails in every dimension
     (1, 12, 12, 8, 32, 9, 9, (1, 1), (4, 4)),          # 81 taps: beyond the 64-bit tap mask of the gather
     (2, 10, 11, 40, 64, 9, 8, (1, 1), (4, 3)),
+    (8, 14, 14, 256, 256, 3, 3, (1, 1), (1, 1)),       # tile counts that take the streamed distribution
+    (3, 21, 21, 96, 224, 3, 3, (1, 1), (1, 1)),
 ]
 
 

@@ -67,6 +67,7 @@ MATMUL_SHAPES = [
     (5, 1000, 96), (1000, 3, 40),
     (32, 130, 2048), (7, 300, 4100), (1, 128, 2048),   # small batch, long K: the 32-row tile
     (3, 70001, 40), (70001, 3, 40), (2, 2, 30000),      # very wide, very tall, very deep
+    (1568, 256, 2304), (700, 520, 3000), (1000, 136, 5000),   # tile counts that take the streamed distribution
 ]
 
 
@@ -192,6 +193,8 @@ CONV_CASES = [
     (200, 1, 1, 32, 16, 3, 3, (1, 1), (1, 1)),
     (1, 12, 12, 32, 40, 9, 9, (1, 1), (4, 4)),       # 81 taps: beyond the 64-bit tap mask, bounds tested per load
     (2, 10, 11, 64, 70, 9, 8, (2, 1), (4, 3)),
+    (8, 14, 14, 256, 256, 3, 3, (1, 1), (1, 1)),     # 13 x 4 tiles, 72 slices: streamed distribution
+    (3, 21, 21, 96, 200, 3, 3, (1, 1), (1, 1)),
 ]
 
 
