@@ -147,3 +147,61 @@ def test_gate_argument_errors(cg):
     with pytest.raises(cg.CgError) as e:
         cg.cg_bshare_prefix_stage(z[:16], z[:16], z[:16], z[:16], 1, p_out=z[16:], g_out=z[16:])
     assert e.value.status == cg.CG_ERR_ALIAS
+
+
+def test_relu_assembled_from_sign_bit_and_products(cg, ro, wl):
+    """ReLU on shares end to end, every local step on the GPU: the adder circuit for the sign bit, its three
+    binary shares read as arithmetic sharings, two integer XORs (u + v - 2uv) and the final (1 - b) x, each
+    product being cg_share_mul + cg_reshare.  The opened result equals max(x, 0) exactly, and every party's
+    shares equal the oracle's run of the same steps."""
+    n = 20000
+    say(f"ReLU from the sign bit and three products, n={n}")
+    rng = np.random.default_rng(61)
+    xs = rng.integers(-(1 << 40), 1 << 40, size=n, dtype=np.int64)
+    xs[:4] = [0, -1, 1, -(1 << 40)]
+    x = xs.astype(np.uint64)
+    X = ro.share(x, wl.draw_ring(x.shape, 62), wl.draw_ring(x.shape, 63))
+    Xd = [cg.to_device(a) for a in X]
+    total = gpu_msb_circuit(cg, Xd, nonce=7)
+    msb = [(t >> 63) & 1 for t in total]                       # a word shift of a share is local
+    zero = torch.zeros_like(Xd[0])
+    B = [tuple(msb[k] if j == k else zero for j in range(3)) for k in range(3)]
+
+    def mult(U, V, first):
+        out = []
+        for i in range(3):
+            zi = cg.cg_share_mul(U[i], U[(i + 1) % 3], V[i], V[(i + 1) % 3])
+            out.append(cg.cg_reshare(zi, KEYS[i], KEYS[(i - 1) % 3], 8, first, out=zi))
+        return tuple(out)
+
+    def xor_arith(U, V, first):
+        P = mult(U, V, first)
+        return tuple(u + v - 2 * p for u, v, p in zip(U, V, P))   # linear combination of shares: local
+
+    D = xor_arith(B[0], B[1], 0)
+    Bsum = xor_arith(D, B[2], n)
+    keep = tuple((1 if k == 0 else 0) - b for k, b in enumerate(Bsum))
+    R = mult(Xd, keep, 2 * n)
+    torch.cuda.synchronize()
+    opened = cg.to_host(cg.cg_reconstruct(*R)).astype(np.int64)
+    assert np.array_equal(opened, np.maximum(xs, 0))
+    # the oracle's run of the same steps, share by share
+    _, msb_o = ro.msb_protocol(X, KEYS, nonce=7)
+    zo = np.zeros_like(x)
+    Bo = [tuple(msb_o[k] if j == k else zo for j in range(3)) for k in range(3)]
+
+    def mult_o(U, V, first):
+        return tuple(ro.reshare(ro.party_mul(U[i], U[(i + 1) % 3], V[i], V[(i + 1) % 3]), KEYS[i], KEYS[(i - 1) % 3], 8, first)
+                     for i in range(3))
+
+    def xor_o(U, V, first):
+        P = mult_o(U, V, first)
+        with np.errstate(over="ignore"):
+            return tuple(u + v - np.uint64(2) * p for u, v, p in zip(U, V, P))
+
+    Bs_o = xor_o(xor_o(Bo[0], Bo[1], 0), Bo[2], n)
+    with np.errstate(over="ignore"):
+        keep_o = tuple((np.uint64(1) if k == 0 else np.uint64(0)) - b for k, b in enumerate(Bs_o))
+    Ro = mult_o(X, keep_o, 2 * n)
+    for got, want in zip(R, Ro):
+        assert not first_mismatch(cg.to_host(got), want)

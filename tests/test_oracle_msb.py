@@ -94,3 +94,42 @@ def test_sign_of_fixed_point_values():
     shares = ro.share(enc, wl.draw_ring(enc.shape, 42), wl.draw_ring(enc.shape, 43))
     _, msb = ro.msb_protocol(shares, KEYS, nonce=5)
     assert np.array_equal(open3(msb).astype(bool), np.rint(reals * 65536) < 0)
+
+
+def arithmetic_mult(X, Y, nonce, first):
+    """The multiplication protocol on replicated arithmetic sharings given as triples (oracle steps only)."""
+    z = []
+    for i in range(3):
+        zi = ro.party_mul(X[i], X[(i + 1) % 3], Y[i], Y[(i + 1) % 3])
+        z.append(ro.reshare(zi, KEYS[i], KEYS[(i - 1) % 3], nonce, first))
+    return tuple(z)
+
+
+def test_relu_from_the_sign_bit_and_three_products():
+    """ReLU assembled from the pieces: the sign bit b = b_0 ^ b_1 ^ b_2 from the adder circuit; each b_k read as
+    an arithmetic sharing with one non-zero component (the paper's re-interpretation trick in the other
+    direction); XOR over the integers, u ^ v = u + v - 2uv, costs one product each; relu(x) = (1 - b) x one
+    more.  (The paper uses the bit-injection protocol of ABY3 here, whose steps it does not list; this test
+    only needs the multiplication protocol.)  Multiplying by a bit needs no rescaling, so the result is exact."""
+    rng = np.random.default_rng(61)
+    xs = rng.integers(-(1 << 40), 1 << 40, size=3000, dtype=np.int64)
+    xs[:4] = [0, -1, 1, -(1 << 40)]
+    x = xs.astype(np.uint64)
+    X = ro.share(x, wl.draw_ring(x.shape, 62), wl.draw_ring(x.shape, 63))
+    _, msb = ro.msb_protocol(X, KEYS, nonce=7)
+    zero = np.zeros_like(x)
+    B = [tuple(msb[k] if j == k else zero for j in range(3)) for k in range(3)]   # arithmetic sharings of b_0, b_1, b_2
+    n = x.size
+
+    def xor_arith(U, V, first):
+        P = arithmetic_mult(U, V, 8, first)
+        with np.errstate(over="ignore"):
+            return tuple(u + v - np.uint64(2) * p for u, v, p in zip(U, V, P))
+
+    D = xor_arith(B[0], B[1], 0)
+    Bsum = xor_arith(D, B[2], n)
+    assert np.array_equal(ro.reconstruct(*Bsum), (xs < 0).astype(np.uint64))
+    with np.errstate(over="ignore"):
+        keep = tuple((np.uint64(1) if k == 0 else np.uint64(0)) - b for k, b in enumerate(Bsum))   # 1 - b: the constant joins share 0
+    R = arithmetic_mult(X, keep, 8, 2 * n)
+    assert np.array_equal(ro.reconstruct(*R).astype(np.int64), np.maximum(xs, 0))
