@@ -19,3 +19,75 @@ def first_mismatch(got: np.ndarray, want: np.ndarray) -> str:
     idx = tuple(int(v) for v in bad[0])
     return (f"{len(bad)} of {got.size} elements differ; first at {idx}: "
             f"got 0x{int(got[idx]):016x} want 0x{int(want[idx]):016x}")
+
+
+def gpu_msb_circuit(cg, x_dev, KEYS, nonce):
+    """The circuit of the oracle's msb_protocol, every local step on the GPU through the C-ABI."""
+    n = x_dev[0].numel()
+    import torch
+    zero = torch.zeros_like(x_dev[0])
+    pair = lambda v, i: (v[i], v[(i + 1) % 3])
+    counter = [0]
+
+    def and_gate(X, Y):
+        first = counter[0]
+        counter[0] += n
+        return tuple(cg.cg_breshare(cg.cg_bshare_and(*pair(X, i), *pair(Y, i)), KEYS[i], KEYS[(i - 1) % 3], nonce, first)
+                     for i in range(3))
+
+    def xor(X, Y):
+        # share-wise XOR; run through the pair entry point party by party (component i is party i's first)
+        return tuple(cg.cg_bshare_xor(*pair(X, i), *pair(Y, i))[0] for i in range(3))
+
+    A, B, C = (x_dev[0], zero, zero), (zero, x_dev[1], zero), (zero, zero, x_dev[2])
+    S = xor(xor(A, B), C)
+    carry = xor(and_gate(xor(A, C), xor(B, C)), C)
+    T = tuple(c << 1 for c in carry)              # a word shift of a share is local
+    P0 = xor(S, T)
+    G = and_gate(S, T)
+    P = P0
+    for stage, shift in enumerate((1, 2, 4, 8, 16, 32)):
+        last = stage == 5
+        first = counter[0]
+        counter[0] += 2 * n
+        new_p, new_g = [], []
+        for i in range(3):
+            p_loc, g_loc = cg.cg_bshare_prefix_stage(*pair(P, i), *pair(G, i), shift, last)
+            new_g.append(cg.cg_breshare(g_loc, KEYS[i], KEYS[(i - 1) % 3], nonce, first, out=g_loc))
+            if not last:
+                new_p.append(cg.cg_breshare(p_loc, KEYS[i], KEYS[(i - 1) % 3], nonce, first + n, out=p_loc))
+        G = tuple(new_g)
+        if not last:
+            P = tuple(new_p)
+    total = xor(P0, tuple(g << 1 for g in G))
+    return total
+
+
+def gpu_share_mult(cg, U, V, keys, nonce, first):
+    """The multiplication protocol on replicated arithmetic sharings held as triples of GPU tensors:
+    every party's three-term product and blinding on the GPU, the message a plain assignment."""
+    out = []
+    for i in range(3):
+        zi = cg.cg_share_mul(U[i], U[(i + 1) % 3], V[i], V[(i + 1) % 3])
+        out.append(cg.cg_reshare(zi, keys[i], keys[(i - 1) % 3], nonce, first, out=zi))
+    return tuple(out)
+
+
+def gpu_relu(cg, X, keys, nonce):
+    """ReLU of a replicated arithmetic sharing X = (x_0, x_1, x_2): sign bit from the adder circuit, its three
+    binary shares read as arithmetic sharings, two integer XORs (u + v - 2uv) and (1 - b) x.  Uses the PRF
+    streams `nonce` (binary gates) and `nonce + 1` (products)."""
+    import torch
+    n = X[0].numel()
+    total = gpu_msb_circuit(cg, list(X), keys, nonce)
+    msb = [(t >> 63) & 1 for t in total]
+    zero = torch.zeros_like(X[0])
+    B = [tuple(msb[k] if j == k else zero for j in range(3)) for k in range(3)]
+
+    def xor_arith(U, V, first):
+        P = gpu_share_mult(cg, U, V, keys, nonce + 1, first)
+        return tuple(u + v - 2 * p for u, v, p in zip(U, V, P))
+
+    b = xor_arith(xor_arith(B[0], B[1], 0), B[2], n)
+    keep = tuple((1 if k == 0 else 0) - s for k, s in enumerate(b))
+    return gpu_share_mult(cg, X, keep, keys, nonce + 1, 2 * n)

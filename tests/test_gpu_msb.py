@@ -4,7 +4,7 @@ oracle bit for bit, and against plain integer addition of the shares."""
 import numpy as np
 import pytest
 
-from tests.gpu_util import first_mismatch, say
+from tests.gpu_util import first_mismatch, gpu_msb_circuit, say
 
 pytestmark = pytest.mark.gpu
 
@@ -74,47 +74,6 @@ def test_gates_on_unaligned_views_and_in_place(cg, ro, wl):
     assert not first_mismatch(cg.to_host(dd[0]), want_p) and not first_mismatch(cg.to_host(dd[2]), want_g)
 
 
-def gpu_msb_circuit(cg, x_dev, nonce):
-    """The circuit of the oracle's msb_protocol, every local step on the GPU through the C-ABI."""
-    n = x_dev[0].numel()
-    zero = torch.zeros_like(x_dev[0])
-    pair = lambda v, i: (v[i], v[(i + 1) % 3])
-    counter = [0]
-
-    def and_gate(X, Y):
-        first = counter[0]
-        counter[0] += n
-        return tuple(cg.cg_breshare(cg.cg_bshare_and(*pair(X, i), *pair(Y, i)), KEYS[i], KEYS[(i - 1) % 3], nonce, first)
-                     for i in range(3))
-
-    def xor(X, Y):
-        # share-wise XOR; run through the pair entry point party by party (component i is party i's first)
-        return tuple(cg.cg_bshare_xor(*pair(X, i), *pair(Y, i))[0] for i in range(3))
-
-    A, B, C = (x_dev[0], zero, zero), (zero, x_dev[1], zero), (zero, zero, x_dev[2])
-    S = xor(xor(A, B), C)
-    carry = xor(and_gate(xor(A, C), xor(B, C)), C)
-    T = tuple(c << 1 for c in carry)              # a word shift of a share is local
-    P0 = xor(S, T)
-    G = and_gate(S, T)
-    P = P0
-    for stage, shift in enumerate((1, 2, 4, 8, 16, 32)):
-        last = stage == 5
-        first = counter[0]
-        counter[0] += 2 * n
-        new_p, new_g = [], []
-        for i in range(3):
-            p_loc, g_loc = cg.cg_bshare_prefix_stage(*pair(P, i), *pair(G, i), shift, last)
-            new_g.append(cg.cg_breshare(g_loc, KEYS[i], KEYS[(i - 1) % 3], nonce, first, out=g_loc))
-            if not last:
-                new_p.append(cg.cg_breshare(p_loc, KEYS[i], KEYS[(i - 1) % 3], nonce, first + n, out=p_loc))
-        G = tuple(new_g)
-        if not last:
-            P = tuple(new_p)
-    total = xor(P0, tuple(g << 1 for g in G))
-    return total
-
-
 def test_addition_circuit_matches_the_oracle_and_plain_addition(cg, ro, wl):
     n = 50000
     say(f"addition circuit on binary shares, n={n}")
@@ -123,7 +82,7 @@ def test_addition_circuit_matches_the_oracle_and_plain_addition(cg, ro, wl):
     for j, e in enumerate(edge):
         for k in range(3):
             x[k][j] = e[k]
-    total = gpu_msb_circuit(cg, [cg.to_device(a) for a in x], nonce=6)
+    total = gpu_msb_circuit(cg, [cg.to_device(a) for a in x], KEYS, nonce=6)
     torch.cuda.synchronize()
     want_total, want_msb = ro.msb_protocol(x, KEYS, nonce=6)
     for got, want in zip(total, want_total):
@@ -162,7 +121,7 @@ def test_relu_assembled_from_sign_bit_and_products(cg, ro, wl):
     x = xs.astype(np.uint64)
     X = ro.share(x, wl.draw_ring(x.shape, 62), wl.draw_ring(x.shape, 63))
     Xd = [cg.to_device(a) for a in X]
-    total = gpu_msb_circuit(cg, Xd, nonce=7)
+    total = gpu_msb_circuit(cg, Xd, KEYS, nonce=7)
     msb = [(t >> 63) & 1 for t in total]                       # a word shift of a share is local
     zero = torch.zeros_like(Xd[0])
     B = [tuple(msb[k] if j == k else zero for j in range(3)) for k in range(3)]

@@ -155,3 +155,51 @@ def test_fc_stack_chained_through_the_truncation_protocol(cg, ro, wl):
             act = opened.astype(np.uint64)
             act_real = np.maximum(pre_real, 0)
     assert opened.shape == (layers[-1].M, layers[-1].N)
+
+
+def test_fc_stack_evaluated_entirely_on_shares(cg, ro, wl):
+    """Configuration 2's FC stack with nothing opened between layers: product, bias, truncation protocol and
+    ReLU (sign-bit circuit + three share products) all on shares, every party's local step on the GPU.  Only the
+    logits are opened; they must match a float64 network on the same grid-rounded parameters."""
+    from tests.gpu_util import gpu_relu
+    t = wl.FRAC_BITS
+    layers = wl.config_layers(2)
+    rng = np.random.default_rng(2025)
+    keys = (K0, K1, K2)
+    x_real = np.rint(rng.uniform(0, 1, size=(layers[0].M, layers[0].K)) * 2 ** t) / 2 ** t
+    enc = ro.encode(x_real, t)
+    act = tuple(cg.to_device(s) for s in ro.share(enc, wl.draw_ring(enc.shape, 1), wl.draw_ring(enc.shape, 2)))
+    act_real = x_real
+    nonce = 1000
+    for li, L in enumerate(layers):
+        say(f"FC stack on shares: layer {li} {L.gemm}")
+        w_real = np.rint(rng.normal(0, 0.05, size=(L.N, L.K)) * 2 ** t) / 2 ** t
+        b_real = np.rint(rng.normal(0, 0.1, size=(L.N,)) * 2 ** t) / 2 ** t
+        w, b = ro.encode(w_real, t), ro.encode(b_real, 2 * t)
+        dw = [cg.to_device(s) for s in ro.share(w, wl.draw_ring(w.shape, 10 * li + 3), wl.draw_ring(w.shape, 10 * li + 4))]
+        db = [cg.to_device(s) for s in ro.share(b, wl.draw_ring(b.shape, 10 * li + 5), wl.draw_ring(b.shape, 10 * li + 6))]
+        z = []
+        for i in range(3):
+            zi = cg.cg_share_matmul(act[i], act[(i + 1) % 3], dw[i], dw[(i + 1) % 3])
+            zi, _ = cg.cg_share_bias_add(zi, zi, db[i], db[i])
+            z.append(zi)
+        n = z[0].numel()
+        msg = cg.cg_reshare(z[2], keys[2], keys[1], nonce, 0)
+        s0 = cg.cg_trunc1_local(z[0], None, keys[0], keys[2], nonce, 0, t)
+        s1 = cg.cg_trunc1_local(z[1], msg, keys[1], keys[0], nonce, 0, t, keys[1], nonce + 1)
+        s2 = cg.cg_prf_words(keys[1], nonce + 1, 0, n).view_as(s0)
+        pre = (s0, s1, s2)
+        pre_real = act_real @ w_real.T + b_real
+        if li + 1 < len(layers):
+            act = gpu_relu(cg, pre, keys, nonce + 2)
+            act_real = np.maximum(pre_real, 0)
+        nonce += 4
+    torch.cuda.synchronize()
+    logits = cg.to_host(cg.cg_reconstruct(*pre)).astype(np.int64) / 2 ** t
+    assert logits.shape == (layers[-1].M, layers[-1].N)
+    assert np.max(np.abs(logits - pre_real)) < 5e-3
+    # same predicted class wherever the reference's top two logits are further apart than the fixed-point error
+    top2 = np.sort(pre_real, axis=1)[:, -2:]
+    clear = top2[:, 1] - top2[:, 0] > 1e-3
+    assert clear.sum() > 100
+    assert np.array_equal(np.argmax(logits, axis=1)[clear], np.argmax(pre_real, axis=1)[clear])
