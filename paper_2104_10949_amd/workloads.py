@@ -162,7 +162,7 @@ def config5() -> List[Layer]:
 
 
 def config_layers(index: int) -> List[Layer]:
-    """Layers of benchmark configuration `index` (1-based, as listed in the benchmark spec)."""
+    """Layers of benchmark configuration `index` (1-based, in the order of the benchmark definition)."""
     return {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}[index]()
 
 
