@@ -138,6 +138,34 @@ def measure_extras(torch, cg, wl, config_layers):
         ms = timed(fn, warm=2, iters=5)
         out["streaming"].append({"name": name, "words": n, "ms": round(ms, 4), "words_per_s": n / (ms * 1e-3),
                                  "GB_per_s": round(nbytes * n / (ms * 1e-3) / 1e9, 1)})
+    # One party's local work for the sign bit of n words (carry-save step + 64-bit parallel-prefix adder on
+    # binary shares: 8 rounds of AND gates, each followed by the PRF blinding), message passing excluded.
+    n = 1 << 24
+    x0, x1, t0, t1, p0, p1, g0, g1 = (rnd((n,), s) for s in range(11, 19))
+    k0, k1 = bytes(range(16)), bytes(range(16, 32))
+
+    def msb_local():
+        cg.cg_bshare_xor(x0, x1, t0, t1, za=p0, zb=p1)              # A ^ C, B ^ C, S = A ^ B ^ C: three XOR gates
+        cg.cg_bshare_xor(x1, x0, t1, t0, za=g0, zb=g1)
+        cg.cg_bshare_xor(p0, p1, g0, g1, za=t0, zb=t1)
+        cg.cg_breshare(cg.cg_bshare_and(p0, p1, g0, g1, z_i=t0), k0, k1, 3, 0, out=t0)          # majority
+        cg.cg_bshare_xor(t0, t1, x0, x1, za=g0, zb=g1)              # ... ^ C, then P0 = S ^ T
+        cg.cg_bshare_xor(g0, g1, p0, p1, za=p0, zb=p1)
+        cg.cg_breshare(cg.cg_bshare_and(p0, p1, g0, g1, z_i=g0), k0, k1, 3, n, out=g0)          # G = S & T
+        first = 2 * n
+        for stage, shift in enumerate((1, 2, 4, 8, 16, 32)):
+            last = stage == 5
+            cg.cg_bshare_prefix_stage(p0, p1, g0, g1, shift, last, p_out=None if last else t0, g_out=t1)
+            cg.cg_breshare(t1, k0, k1, 3, first, out=g0)
+            if not last:
+                cg.cg_breshare(t0, k0, k1, 3, first + n, out=p0)
+            first += 2 * n
+        cg.cg_bshare_xor(p0, p1, g0, g1, za=t0, zb=t1)              # sum = P0 ^ (G << 1)
+
+    ms = timed(msb_local, warm=2, iters=5)
+    out["sign_bit_circuit_local"] = [{"name": "one party's local steps of the sign-bit addition circuit", "words": n,
+                                      "ms": round(ms, 4), "words_per_s": n / (ms * 1e-3),
+                                      "and_rounds": 8, "prf_blinded_words_per_input_word": 13}]
     return out
 
 

@@ -431,6 +431,84 @@ def msb_protocol(x, keys, nonce: int):
     return total, msb
 
 
+# ---- the same sign bit from a circuit pruned to it, on bit planes ---------------------------------
+def bit_planes(x) -> np.ndarray:
+    """64 x 64 bit transpose of a flat tensor of n = 64 m words: plane b (row b of the result, m words) holds
+    bit b of every element, element 64 w + e in bit e of word w.  Written with numpy's bit unpacking."""
+    x = _u(x).reshape(-1)
+    assert x.size % 64 == 0
+    m = x.size // 64
+    bits = np.unpackbits(x.view(np.uint8).reshape(x.size, 8), axis=1, bitorder="little")      # [n, 64]: bit b of element i
+    per_plane = bits.T.reshape(64, m, 64)                                                    # [b, w, e]
+    packed = np.packbits(per_plane, axis=2, bitorder="little")                               # [b, w, 8 bytes]
+    return np.ascontiguousarray(packed).view(np.uint64).reshape(64, m)
+
+
+def bits_unpack(plane, n: int) -> np.ndarray:
+    """Inverse for a single plane: word i of the result is bit i % 64 of plane[i // 64]."""
+    plane = _u(plane).reshape(-1)
+    bits = np.unpackbits(plane.view(np.uint8), bitorder="little")[:n]
+    return bits.astype(np.uint64)
+
+
+def carry_level_local(p_i, p_ip1, g_i, g_ip1, last: bool = False):
+    """One party's local step of one level of the carry tree on planes [2k, m] -> [k, m]: neighbouring
+    segments (hi = plane 2j+1, lo = plane 2j) are merged by g' = g_hi ^ (p_hi & g_lo), p' = p_hi & p_lo."""
+    p_i, p_ip1, g_i, g_ip1 = _u(p_i), _u(p_ip1), _u(g_i), _u(g_ip1)
+    hi, lo = slice(1, None, 2), slice(0, None, 2)
+    c = np.ascontiguousarray
+    g_new = g_i[hi] ^ bshare_and(c(p_i[hi]), c(p_ip1[hi]), c(g_i[lo]), c(g_ip1[lo]))
+    p_new = None if last else bshare_and(c(p_i[hi]), c(p_ip1[hi]), c(p_i[lo]), c(p_ip1[lo]))
+    return p_new, g_new
+
+
+def msb_protocol_sliced(x, keys, nonce: int):
+    """The sign bit of x_0 + x_1 + x_2 from a circuit pruned to that one output, evaluated on bit planes
+    (n = 64 m elements).  Local: every party transposes its two shares into planes.  Carry-save step on all 64
+    planes (one AND round), first generate word (one AND round), then a binary tree over the 64 positions
+    "below bit 63" (leaf q holds bit q - 1, leaf 0 is empty) that merges neighbouring segments, six AND rounds
+    on 32, 16, 8, 4, 2, 1 planes.  254 plane-sized AND gates instead of the 832 of the word-parallel adder.
+    Returns the binary sharing (triple of [m] words) of the packed sign bits."""
+    x = [_u(a).reshape(-1) for a in x]
+    n = x[0].size
+    m = n // 64
+    zero = np.zeros((64, m), dtype=np.uint64)
+    pair = lambda v, i: (v[i], v[(i + 1) % 3])
+    counter = [0]
+
+    def blind(z, i):
+        first = counter[0]
+        return breshare(z.reshape(-1), keys[i], keys[(i - 1) % 3], nonce, first).reshape(z.shape)
+
+    def and_gate(X, Y):
+        out = tuple(blind(bshare_and(*pair(X, i), *pair(Y, i)), i) for i in range(3))
+        counter[0] += X[0].size
+        return out
+
+    xor = lambda X, Y: tuple(a ^ b for a, b in zip(X, Y))
+    planes = [bit_planes(a) for a in x]
+    A, B, C = (planes[0], zero, zero), (zero, planes[1], zero), (zero, zero, planes[2])
+    S = xor(xor(A, B), C)
+    carry = xor(and_gate(xor(A, C), xor(B, C)), C)
+    up = lambda v: np.concatenate([np.zeros((1, m), dtype=np.uint64), v[:63]])       # one bit position up, plane-wise
+    T = tuple(up(c) for c in carry)
+    P0 = xor(S, T)
+    G0 = and_gate(S, T)
+    # leaves of the tree: position q = bit q - 1 (the carry into bit 63 is the generate of bits 0..62)
+    P, G = tuple(up(p) for p in P0), tuple(up(g) for g in G0)
+    while P[0].shape[0] > 1:
+        last = P[0].shape[0] == 2
+        loc = [carry_level_local(*pair(P, i), *pair(G, i), last) for i in range(3)]
+        G = tuple(blind(loc[i][1], i) for i in range(3))
+        counter[0] += G[0].size
+        if not last:
+            P = tuple(blind(loc[i][0], i) for i in range(3))
+            counter[0] += P[0].size
+        else:
+            P = tuple(g[:1] for g in G)   # only the shape is used from here on
+    return tuple(p0[63] ^ g[0] for p0, g in zip(P0, G))
+
+
 def party_mul(x_i, x_ip1, y_i, y_ip1) -> np.ndarray:
     """Element-wise local multiplication step; y is broadcast along the leading dimensions of x
     (y.size must divide x.size and match x's trailing elements)."""

@@ -133,3 +133,38 @@ def test_relu_from_the_sign_bit_and_three_products():
         keep = tuple((np.uint64(1) if k == 0 else np.uint64(0)) - b for k, b in enumerate(Bsum))   # 1 - b: the constant joins share 0
     R = arithmetic_mult(X, keep, 8, 2 * n)
     assert np.array_equal(ro.reconstruct(*R).astype(np.int64), np.maximum(xs, 0))
+
+
+# ---------------------------------------------------------------- the pruned circuit on bit planes
+def test_bit_planes_definition():
+    rng = np.random.default_rng(71)
+    x = rng.integers(0, 1 << 63, size=128, dtype=np.uint64) * np.uint64(2) + rng.integers(0, 2, size=128, dtype=np.uint64)
+    planes = ro.bit_planes(x)
+    assert planes.shape == (64, 2)
+    for b in (0, 1, 31, 32, 62, 63):
+        for w in range(2):
+            want = sum(((int(x[64 * w + e]) >> b) & 1) << e for e in range(64))
+            assert int(planes[b, w]) == want
+    assert np.array_equal(ro.bits_unpack(planes[63], 128), x >> np.uint64(63))
+    # transposing twice returns the words (a 64 x 64 bit transpose is an involution on each block of 64)
+    assert np.array_equal(ro.bit_planes(planes.T.reshape(-1)).T.reshape(-1), x)
+
+
+def test_pruned_circuit_gives_the_sign_of_the_integer_sum():
+    n = 64 * 50
+    x = [wl.draw_ring((n,), 81 + k) for k in range(3)]
+    top = (1 << 63) - 1
+    edge = [(top, 1, 0), (MOD - 1, 1, 0), (MOD - 1, MOD - 1, MOD - 1), (0, 0, 0), (1 << 63, 0, 0), (1 << 63, 1 << 63, 0),
+            (1 << 62, 1 << 62, 0), (0x5555555555555555, 0xAAAAAAAAAAAAAAAA, 1), (5, MOD - 7, 0), (MOD - 3, 2, 1),
+            (top, 0, 0), (1 << 62, (1 << 62) - 1, 1)]
+    for j, e in enumerate(edge):
+        for k in range(3):
+            x[k][j * 5] = e[k]
+    msb = ro.msb_protocol_sliced(x, KEYS, nonce=9)
+    with np.errstate(over="ignore"):
+        plain = x[0] + x[1] + x[2]
+    opened = msb[0] ^ msb[1] ^ msb[2]
+    assert np.array_equal(ro.bits_unpack(opened, n), plain >> np.uint64(63))
+    # and it agrees with the word-parallel adder's sign bit
+    _, msb_word = ro.msb_protocol(x, KEYS, nonce=10)
+    assert np.array_equal(ro.bits_unpack(opened, n), msb_word[0] ^ msb_word[1] ^ msb_word[2])
