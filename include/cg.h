@@ -388,6 +388,38 @@ CG_API cg_status cg_bshare_prefix_stage(const uint64_t *p_i, const uint64_t *p_i
                                  const uint64_t *g_i, const uint64_t *g_ip1, int shift,
                                  uint64_t *p_out, uint64_t *g_out, size_t n, void *stream);
 
+/*
+ * The same sign bit from a circuit pruned to that one output, on BIT PLANES: with 64 m
+ * elements, plane b is m words holding bit b of every element (element 64 w + e in bit e of
+ * word w).  Gates then cost in proportion to the bit positions they touch.
+ *
+ *   cg_bit_transpose64     : dst [64][m] = planes of src [64 m] (a 64 x 64 bit transpose per
+ *                            block of 64 words; local, applied by a party to each of its shares).
+ *                            n must be a multiple of 64 (CG_ERR_SHAPE); dst must not overlap src.
+ *   cg_bshare_carry_level  : one level of the carry tree: inputs [2 planes_out][m], outputs
+ *                            [planes_out][m]; output plane j merges the neighbouring segments
+ *                            hi = plane 2j+1 and lo = plane 2j,
+ *                              g_out = g_hi ^ and3(p_hi, g_lo),   p_out = and3(p_hi, p_lo)
+ *                            (and3 = the three-term AND of cg_bshare_and); p_out may be NULL at
+ *                            the root.  Outputs must not overlap the inputs or each other.
+ *   cg_bits_unpack         : out[i] = bit (i mod 64) of plane[i / 64], i < n: one word per element
+ *                            again, e.g. to read a share of the sign bit as an arithmetic share.
+ *
+ * Circuit assembled by the tests: transpose; carry-save step and first generate word on all 64
+ * planes (cg_bshare_and); the leaves of the tree are the (propagate, generate) planes moved up
+ * one bit position (the carry into bit 63 is the generate of bits 0..62); six levels on 32, 16,
+ * 8, 4, 2, 1 planes; sign = propagate plane 63 ^ root generate.  254 plane-sized AND gates
+ * instead of the 832 of the word-parallel adder, hence 3.3 times fewer PRF words.
+ */
+CG_API cg_status cg_bit_transpose64(const uint64_t *src, uint64_t *dst, size_t n, void *stream);
+
+CG_API cg_status cg_bshare_carry_level(const uint64_t *p_i, const uint64_t *p_ip1,
+                                const uint64_t *g_i, const uint64_t *g_ip1,
+                                uint64_t *p_out, uint64_t *g_out, size_t planes_out, size_t m,
+                                void *stream);
+
+CG_API cg_status cg_bits_unpack(const uint64_t *plane, uint64_t *out, size_t n, void *stream);
+
 CG_API cg_status cg_bzero_share(const uint8_t *key_self, const uint8_t *key_prev, uint64_t nonce,
                          uint64_t first, uint64_t *beta, size_t n, void *stream);
 

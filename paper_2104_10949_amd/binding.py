@@ -26,6 +26,7 @@ EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d
            "cg_share_mul", "cg_share_sum_pool2d", "cg_share_conv2d_dgrad", "cg_share_conv2d_wgrad",
            "cg_trunc1_local", "cg_prf_words", "cg_bshare_xor", "cg_bshare_and", "cg_bshare_prefix_stage",
            "cg_bzero_share", "cg_breshare", "cg_share_bias_add", "cg_share_col_sum",
+           "cg_bit_transpose64", "cg_bshare_carry_level", "cg_bits_unpack",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -82,6 +83,9 @@ def lib() -> ctypes.CDLL:
         L.cg_share_sum_pool2d.argtypes = [vp] * 4 + [ctypes.POINTER(PoolDesc), vp]
         L.cg_share_bias_add.argtypes = [vp] * 6 + [sz, sz, vp]
         L.cg_share_col_sum.argtypes = [vp] * 4 + [sz, sz, vp]
+        L.cg_bit_transpose64.argtypes = [vp, vp, sz, vp]
+        L.cg_bshare_carry_level.argtypes = [vp] * 6 + [sz, sz, vp]
+        L.cg_bits_unpack.argtypes = [vp, vp, sz, vp]
         L.cg_bshare_xor.argtypes = [vp] * 6 + [sz, vp]
         L.cg_bshare_and.argtypes = [vp] * 5 + [sz, vp]
         L.cg_bshare_prefix_stage.argtypes = [vp] * 4 + [ctypes.c_int, vp, vp, sz, vp]
@@ -91,9 +95,9 @@ def lib() -> ctypes.CDLL:
         L.cg_prf_words.argtypes = [key, u64, u64, vp, sz, vp]
         L.cg_share_conv2d_dgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
         L.cg_share_conv2d_wgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
-        for name in EXPORTS[2:26]:
+        for name in EXPORTS[2:29]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[26:]:
+        for name in EXPORTS[29:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -462,6 +466,38 @@ def cg_bshare_prefix_stage(p_i, p_ip1, g_i, g_ip1, shift: int, last: bool = Fals
                                         None if last else (_ptr(p_out) if n else 0), _ptr(g_out) if n else 0, n,
                                         _stream(stream)), "cg_bshare_prefix_stage")
     return (None if last else p_out), g_out
+
+
+def cg_bit_transpose64(x, out=None, stream=None) -> torch.Tensor:
+    """Bit planes [64, m] of a flat tensor of 64 m words."""
+    n = x.numel()
+    if n % 64:
+        _check(CG_ERR_SHAPE, "cg_bit_transpose64")
+    out = torch.empty((64, n // 64), dtype=torch.int64, device=x.device) if out is None else out
+    _check(lib().cg_bit_transpose64(_ptr(x) if n else 0, _ptr(out) if n else 0, n, _stream(stream)), "cg_bit_transpose64")
+    return out
+
+
+def cg_bshare_carry_level(p_i, p_ip1, g_i, g_ip1, last: bool = False, stream=None):
+    """Local step of one level of the carry tree on planes [2k, m]; returns (p_out or None, g_out), each [k, m]."""
+    if not (p_i.shape == p_ip1.shape == g_i.shape == g_ip1.shape) or p_i.dim() != 2 or p_i.shape[0] % 2:
+        raise ValueError("operands must be [2k, m] tensors of one shape")
+    k, m = p_i.shape[0] // 2, p_i.shape[1]
+    g_out = torch.empty((k, m), dtype=torch.int64, device=p_i.device)
+    p_out = None if last else torch.empty((k, m), dtype=torch.int64, device=p_i.device)
+    _check(lib().cg_bshare_carry_level(_ptr(p_i), _ptr(p_ip1), _ptr(g_i), _ptr(g_ip1),
+                                       None if last else _ptr(p_out), _ptr(g_out), k, m, _stream(stream)),
+           "cg_bshare_carry_level")
+    return p_out, g_out
+
+
+def cg_bits_unpack(plane, n: int, out=None, stream=None) -> torch.Tensor:
+    """One word per element (0 or 1) from a packed plane of at least ceil(n / 64) words."""
+    if plane.numel() * 64 < n:
+        raise ValueError("plane too short")
+    out = torch.empty((n,), dtype=torch.int64, device=plane.device) if out is None else out
+    _check(lib().cg_bits_unpack(_ptr(plane) if n else 0, _ptr(out) if n else 0, n, _stream(stream)), "cg_bits_unpack")
+    return out
 
 
 def cg_bzero_share(key_self: bytes, key_prev: bytes, nonce: int, first: int, n: int, out=None,

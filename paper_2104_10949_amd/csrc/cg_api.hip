@@ -334,6 +334,73 @@ struct PrefixStageOp {
     }
 };
 
+// One level of the carry tree on bit planes: inputs [2k, m] words, outputs [k, m]; output plane j merges the
+// neighbouring segments hi = plane 2j+1 and lo = plane 2j:
+//   g' = g_hi ^ and3(p_hi, g_lo),  p' = and3(p_hi, p_lo),  and3 = the three-term AND on the pairs.
+struct CarryLevelOp {
+    const u64 *pa, *pb, *ga, *gb;
+    u64 *p_out, *g_out;  // p_out may be null (root level)
+    size_t m;            // words per plane; the pair path requires it to be even
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        const size_t hm = m >> 1;
+        ull2 ph_a[U], ph_b[U], gh_a[U], pl_a[U], pl_b[U], gl_a[U], gl_b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t o = i + u * step, j = o / hm, w = o - j * hm;
+            const size_t hi = (2 * j + 1) * hm + w, lo = 2 * j * hm + w;
+            ph_a[u] = ld2(pa, hi); ph_b[u] = ld2(pb, hi); gh_a[u] = ld2(ga, hi);
+            gl_a[u] = ld2(ga, lo); gl_b[u] = ld2(gb, lo);
+            if (p_out) { pl_a[u] = ld2(pa, lo); pl_b[u] = ld2(pb, lo); }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            st2(g_out, i + u * step, gh_a[u] ^ (ph_a[u] & (gl_a[u] ^ gl_b[u])) ^ (ph_b[u] & gl_a[u]));
+            if (p_out) st2(p_out, i + u * step, (ph_a[u] & (pl_a[u] ^ pl_b[u])) ^ (ph_b[u] & pl_a[u]));
+        }
+    }
+    __device__ void one(size_t o) const {
+        const size_t j = o / m, w = o - j * m;
+        const size_t hi = (2 * j + 1) * m + w, lo = 2 * j * m + w;
+        const u64 a = pa[hi], b = pb[hi];
+        g_out[o] = ga[hi] ^ (a & (ga[lo] ^ gb[lo])) ^ (b & ga[lo]);
+        if (p_out) p_out[o] = (a & (pa[lo] ^ pb[lo])) ^ (b & pa[lo]);
+    }
+};
+
+// 64 x 64 bit transpose: plane b, word w, bit e = bit b of src[64 w + e].  A wave takes eight blocks of 64
+// words: lane e loads its word of each block (512 contiguous bytes per block), the 64 ballots of a block give
+// the 64 plane words, lane b keeps the one of plane b, and after eight blocks every lane stores 64 contiguous
+// bytes of its plane.
+__global__ __launch_bounds__(256) void bit_transpose_kernel(const u64* __restrict__ src, u64* __restrict__ dst, size_t m) {
+    const int lane = threadIdx.x & 63;
+    const size_t wave = ((size_t)blockIdx.x * 256 + threadIdx.x) >> 6, waves = ((size_t)gridDim.x * 256) >> 6;
+    for (size_t w0 = wave * 8; w0 < m; w0 += waves * 8) {
+        u64 mine[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const size_t w = w0 + k;
+            const u64 v = w < m ? src[64 * w + lane] : 0;   // uniform per k: whole blocks only
+            u64 keep = 0;
+#pragma unroll
+            for (int b = 0; b < 64; ++b) {
+                const u64 word = __ballot((v >> b) & 1);
+                if (lane == b) keep = word;
+            }
+            mine[k] = keep;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (w0 + k < m) dst[(size_t)lane * m + w0 + k] = mine[k];
+    }
+}
+
+// out[i] = bit (i % 64) of plane[i / 64]
+__global__ __launch_bounds__(256) void bits_unpack_kernel(const u64* __restrict__ plane, u64* __restrict__ out, size_t n) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) out[i] = (plane[i >> 6] >> (i & 63)) & 1;
+}
+
 // One thread per output pixel and channel pair: sums the window of both components.
 __global__ __launch_bounds__(256) void sum_pool_kernel(const u64* __restrict__ xa, const u64* __restrict__ xb,
                                                        u64* __restrict__ za, u64* __restrict__ zb,
@@ -1026,6 +1093,52 @@ cg_status cg_bshare_prefix_stage(const uint64_t* p_i, const uint64_t* p_ip1, con
     PrefixStageOp f = {p_i, p_ip1, g_i, g_ip1, p_out, g_out, shift};
     const void* all[6] = {p_i, p_ip1, g_i, g_ip1, g_out, p_out ? p_out : g_out};
     return launch_ew(n, all_aligned16(all, 6), f, stream);
+}
+
+cg_status cg_bshare_carry_level(const uint64_t* p_i, const uint64_t* p_ip1, const uint64_t* g_i, const uint64_t* g_ip1,
+                                uint64_t* p_out, uint64_t* g_out, size_t planes_out, size_t m, void* stream) {
+    size_t n;
+    if (__builtin_mul_overflow(planes_out, m, &n) || n > (SIZE_MAX >> 5)) return CG_ERR_SHAPE;
+    if (n == 0) return CG_OK;
+    const void* in[5] = {p_i, p_ip1, g_i, g_ip1, g_out};
+    if (cg_status st = check_ptrs(in, 5)) return st;
+    if (p_out && !aligned(p_out, 8)) return CG_ERR_ALIGN;
+    const u64 in_bytes = (u64)n * 16, out_bytes = (u64)n * 8;
+    // outputs are half the size of the inputs and indexed differently: no overlap with them at all
+    for (int i = 0; i < 4; ++i)
+        if (overlap(g_out, out_bytes, in[i], in_bytes) || (p_out && overlap(p_out, out_bytes, in[i], in_bytes)))
+            return CG_ERR_ALIAS;
+    if (p_out && overlap(p_out, out_bytes, g_out, out_bytes)) return CG_ERR_ALIAS;
+    CarryLevelOp f = {p_i, p_ip1, g_i, g_ip1, p_out, g_out, m};
+    const void* all[6] = {p_i, p_ip1, g_i, g_ip1, g_out, p_out ? p_out : g_out};
+    return launch_ew(n, all_aligned16(all, 6) && m % 2 == 0, f, stream);
+}
+
+cg_status cg_bit_transpose64(const uint64_t* src, uint64_t* dst, size_t n, void* stream) {
+    if (n == 0) return CG_OK;
+    if (!src || !dst) return CG_ERR_NULL;
+    if (!aligned(src, 8) || !aligned(dst, 8)) return CG_ERR_ALIGN;
+    if (n % 64 != 0 || n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    if (overlap(dst, (u64)n * 8, src, (u64)n * 8)) return CG_ERR_ALIAS;
+    const size_t m = n / 64;
+    size_t blocks = (m + 31) / 32;   // four waves per block, eight 64-word blocks per wave and trip
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), src,
+                       dst, m);
+    return hipGetLastError() == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
+cg_status cg_bits_unpack(const uint64_t* plane, uint64_t* out, size_t n, void* stream) {
+    if (n == 0) return CG_OK;
+    if (!plane || !out) return CG_ERR_NULL;
+    if (!aligned(plane, 8) || !aligned(out, 8)) return CG_ERR_ALIGN;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    if (overlap(out, (u64)n * 8, plane, (u64)((n + 63) / 64) * 8)) return CG_ERR_ALIAS;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(bits_unpack_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), plane,
+                       out, n);
+    return hipGetLastError() == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
 
 cg_status cg_bzero_share(const uint8_t* key_self, const uint8_t* key_prev, uint64_t nonce, uint64_t first,

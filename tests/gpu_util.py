@@ -91,3 +91,46 @@ def gpu_relu(cg, X, keys, nonce):
     b = xor_arith(xor_arith(B[0], B[1], 0), B[2], n)
     keep = tuple((1 if k == 0 else 0) - s for k, s in enumerate(b))
     return gpu_share_mult(cg, X, keep, keys, nonce + 1, 2 * n)
+
+
+def gpu_msb_sliced(cg, x_dev, KEYS, nonce):
+    """The oracle's msb_protocol_sliced with every local step on the GPU through the C-ABI: returns the
+    binary sharing (triple of [m] words) of the packed sign bits of x_0 + x_1 + x_2 (n = 64 m elements)."""
+    import torch
+    n = x_dev[0].numel()
+    m = n // 64
+    pair = lambda v, i: (v[i], v[(i + 1) % 3])
+    counter = [0]
+
+    def blind(z, i):
+        return cg.cg_breshare(z, KEYS[i], KEYS[(i - 1) % 3], nonce, counter[0], out=z)
+
+    def and_gate(X, Y):
+        out = tuple(blind(cg.cg_bshare_and(*pair(X, i), *pair(Y, i)), i) for i in range(3))
+        counter[0] += X[0].numel()
+        return out
+
+    def xor(X, Y):
+        return tuple(cg.cg_bshare_xor(*pair(X, i), *pair(Y, i))[0] for i in range(3))
+
+    planes = [cg.cg_bit_transpose64(a.reshape(-1)) for a in x_dev]
+    zero = torch.zeros_like(planes[0])
+    A, B, C = (planes[0], zero, zero), (zero, planes[1], zero), (zero, zero, planes[2])
+    S = xor(xor(A, B), C)
+    carry = xor(and_gate(xor(A, C), xor(B, C)), C)
+    up = lambda v: torch.cat([torch.zeros_like(v[:1]), v[:63]])        # one bit position up: a move of planes
+    T = tuple(up(c) for c in carry)
+    P0 = xor(S, T)
+    G0 = and_gate(S, T)
+    P, G = tuple(up(p) for p in P0), tuple(up(g) for g in G0)
+    while P[0].shape[0] > 1:
+        last = P[0].shape[0] == 2
+        loc = [cg.cg_bshare_carry_level(*pair(P, i), *pair(G, i), last) for i in range(3)]
+        G = tuple(blind(loc[i][1], i) for i in range(3))
+        counter[0] += G[0].numel()
+        if not last:
+            P = tuple(blind(loc[i][0], i) for i in range(3))
+            counter[0] += P[0].numel()
+        else:
+            P = G
+    return tuple(p0[63] ^ g[0] for p0, g in zip(P0, G))                # XOR of shares: local

@@ -164,3 +164,53 @@ def test_relu_assembled_from_sign_bit_and_products(cg, ro, wl):
     Ro = mult_o(X, keep_o, 2 * n)
     for got, want in zip(R, Ro):
         assert not first_mismatch(cg.to_host(got), want)
+
+
+@pytest.mark.parametrize("m", [1, 2, 7, 8, 9, 64, 1001])
+def test_bit_planes_and_unpack(cg, ro, wl, m):
+    from tests.gpu_util import first_mismatch as fm
+    n = 64 * m
+    say(f"cg_bit_transpose64 / cg_bits_unpack n={n}")
+    x = wl.draw_ring((n,), 900 + m)
+    planes = cg.cg_bit_transpose64(cg.to_device(x))
+    want = ro.bit_planes(x)
+    assert not fm(cg.to_host(planes), want)
+    for b in (0, 31, 63):
+        for nn in (n, n - 1, max(1, n - 63)):
+            got = cg.to_host(cg.cg_bits_unpack(planes[b], nn))
+            assert not fm(got, ro.bits_unpack(want[b], nn))
+
+
+@pytest.mark.parametrize("k,m", [(1, 1), (1, 6), (2, 5), (32, 40), (16, 1001), (4, 2)])
+def test_carry_level_matches_the_oracle(cg, ro, wl, k, m):
+    say(f"cg_bshare_carry_level k={k} m={m}")
+    h = [wl.draw_ring((2 * k, m), 950 + j + k + m) for j in range(4)]
+    d = [cg.to_device(a) for a in h]
+    for last in (False, True):
+        p_out, g_out = cg.cg_bshare_carry_level(*d, last)
+        want_p, want_g = ro.carry_level_local(*h, last)
+        assert not first_mismatch(cg.to_host(g_out), want_g)
+        assert (p_out is None) == last
+        if not last:
+            assert not first_mismatch(cg.to_host(p_out), want_p)
+
+
+def test_pruned_circuit_matches_the_oracle_and_the_sign_of_the_sum(cg, ro, wl):
+    from tests.gpu_util import gpu_msb_sliced
+    n = 64 * 700
+    say(f"sign bit from the pruned circuit on bit planes, n={n}")
+    x = [wl.draw_ring((n,), 980 + k) for k in range(3)]
+    edge = [((1 << 63) - 1, 1, 0), ((1 << 64) - 1, 1, 0), ((1 << 64) - 1,) * 3, (5, (1 << 64) - 7, 0), (0, 0, 0),
+            (1 << 62, (1 << 62) - 1, 1)]
+    for j, e in enumerate(edge):
+        for k in range(3):
+            x[k][j * 3] = e[k]
+    msb = gpu_msb_sliced(cg, [cg.to_device(a) for a in x], KEYS, nonce=9)
+    torch.cuda.synchronize()
+    want = ro.msb_protocol_sliced(x, KEYS, nonce=9)
+    for got, w in zip(msb, want):
+        assert not first_mismatch(cg.to_host(got), w)
+    opened = cg.to_host(msb[0]) ^ cg.to_host(msb[1]) ^ cg.to_host(msb[2])
+    with np.errstate(over="ignore"):
+        plain = x[0] + x[1] + x[2]
+    assert np.array_equal(ro.bits_unpack(opened, n), plain >> np.uint64(63))
