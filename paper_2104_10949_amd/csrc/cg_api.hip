@@ -368,29 +368,46 @@ struct CarryLevelOp {
     }
 };
 
-// 64 x 64 bit transpose: plane b, word w, bit e = bit b of src[64 w + e].  A wave takes eight blocks of 64
-// words: lane e loads its word of each block (512 contiguous bytes per block), the 64 ballots of a block give
-// the 64 plane words, lane b keeps the one of plane b, and after eight blocks every lane stores 64 contiguous
-// bytes of its plane.
+// 64 x 64 bit transpose: plane b, word w, bit e = bit b of src[64 w + e].  A wave takes sixteen blocks of 64
+// words.  Lane e loads its word of a block (512 contiguous bytes per block); the block is transposed in
+// registers by the recursive scheme (swap the off-diagonal j x j sub-blocks for j = 32, 16, .., 1, each step one
+// exchange with lane e ^ j and a masked merge), after which lane b holds the word of plane b; after eight
+// sixteen blocks every lane stores 128 contiguous bytes of its plane.
+template <int J>
+__device__ __forceinline__ u64 transpose_step(u64 x, int lane) {
+    // bits whose index has bit J clear
+    constexpr u64 mask = J == 32 ? 0x00000000FFFFFFFFull : J == 16 ? 0x0000FFFF0000FFFFull
+                       : J == 8 ? 0x00FF00FF00FF00FFull : J == 4 ? 0x0F0F0F0F0F0F0F0Full
+                       : J == 2 ? 0x3333333333333333ull : 0x5555555555555555ull;
+    const u64 y = (u64)__shfl_xor((unsigned long long)x, J, 64);
+    return (lane & J) ? (((y >> J) & mask) | (x & ~mask)) : ((x & mask) | ((y & mask) << J));
+}
+
+__device__ __forceinline__ u64 transpose64_lanes(u64 x, int lane) {
+    x = transpose_step<32>(x, lane);
+    x = transpose_step<16>(x, lane);
+    x = transpose_step<8>(x, lane);
+    x = transpose_step<4>(x, lane);
+    x = transpose_step<2>(x, lane);
+    return transpose_step<1>(x, lane);
+}
+
+constexpr int BT_BLOCKS = 16;  // 64-word blocks per wave and trip: 128 contiguous bytes per lane and plane
+
 __global__ __launch_bounds__(256) void bit_transpose_kernel(const u64* __restrict__ src, u64* __restrict__ dst, size_t m) {
     const int lane = threadIdx.x & 63;
     const size_t wave = ((size_t)blockIdx.x * 256 + threadIdx.x) >> 6, waves = ((size_t)gridDim.x * 256) >> 6;
-    for (size_t w0 = wave * 8; w0 < m; w0 += waves * 8) {
-        u64 mine[8];
+    for (size_t w0 = wave * BT_BLOCKS; w0 < m; w0 += waves * BT_BLOCKS) {
+        u64 mine[BT_BLOCKS];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < BT_BLOCKS; ++k) {
             const size_t w = w0 + k;
-            const u64 v = w < m ? src[64 * w + lane] : 0;   // uniform per k: whole blocks only
-            u64 keep = 0;
-#pragma unroll
-            for (int b = 0; b < 64; ++b) {
-                const u64 word = __ballot((v >> b) & 1);
-                if (lane == b) keep = word;
-            }
-            mine[k] = keep;
+            mine[k] = w < m ? src[64 * w + lane] : 0;       // uniform per k: whole blocks only
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
+        for (int k = 0; k < BT_BLOCKS; ++k) mine[k] = transpose64_lanes(mine[k], lane);
+#pragma unroll
+        for (int k = 0; k < BT_BLOCKS; ++k)
             if (w0 + k < m) dst[(size_t)lane * m + w0 + k] = mine[k];
     }
 }
@@ -1121,7 +1138,7 @@ cg_status cg_bit_transpose64(const uint64_t* src, uint64_t* dst, size_t n, void*
     if (n % 64 != 0 || n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
     if (overlap(dst, (u64)n * 8, src, (u64)n * 8)) return CG_ERR_ALIAS;
     const size_t m = n / 64;
-    size_t blocks = (m + 31) / 32;   // four waves per block, eight 64-word blocks per wave and trip
+    size_t blocks = (m + 63) / 64;   // four waves per block, sixteen 64-word blocks per wave and trip
     if (blocks > 256 * 16) blocks = 256 * 16;
     hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), src,
                        dst, m);
