@@ -176,13 +176,13 @@ def measure_extras(torch, cg, wl, config_layers):
     def msb_local_sliced():
         cg.cg_bit_transpose64(x0, out=a0)
         cg.cg_bit_transpose64(x1, out=a1)
-        cg.cg_bshare_xor(a0, a1, s0, s1, za=c0, zb=c1)              # the XOR gates of the carry-save step
-        cg.cg_bshare_xor(a1, a0, s1, s0, za=q0, zb=q1)
-        cg.cg_bshare_xor(c0, c1, q0, q1, za=s0, zb=s1)
-        cg.cg_breshare(cg.cg_bshare_and(c0, c1, q0, q1, z_i=s0), k0, k1, 4, 0, out=s0)          # majority
-        cg.cg_bshare_xor(s0, s1, a0, a1, za=q0, zb=q1)
-        cg.cg_bshare_xor(q0, q1, c0, c1, za=c0, zb=c1)                                          # P0
-        cg.cg_breshare(cg.cg_bshare_and(c0, c1, q0, q1, z_i=q0), k0, k1, 4, n, out=q0)          # G0
+        # carry-save cell on the three sharings (two of the six pair components of a party are its shares, the
+        # rest zero planes: the cell is timed in its general form), carry blinded
+        cg.cg_bshare_csa(a0, a1, s0, s1, c0, c1, s_i=q0, s_ip1=q1, carry_i=s0)
+        cg.cg_breshare(s0, k0, k1, 4, 0, out=s0)
+        # half-adder cell: propagate pair and generate share, generate blinded
+        cg.cg_bshare_half_adder(q0, q1, s0, s1, p_i=c0, p_ip1=c1, g_i=q0)
+        cg.cg_breshare(q0, k0, k1, 4, n, out=q0)
         first, P, G = 2 * n, (c0, c1), (q0, q1)
         while P[0].shape[0] > 1:
             last = P[0].shape[0] == 2

@@ -411,6 +411,28 @@ CG_API cg_status cg_bshare_prefix_stage(const uint64_t *p_i, const uint64_t *p_i
  * 8, 4, 2, 1 planes; sign = propagate plane 63 ^ root generate.  254 plane-sized AND gates
  * instead of the 832 of the word-parallel adder, hence 3.3 times fewer PRF words.
  */
+/*
+ * Adder cells on binary sharings, one party's local step each (fused forms of the gates above
+ * that read every operand once):
+ *
+ *   cg_bshare_csa        : carry-save (full) adder of three sharings A, B, C given as pairs:
+ *                          sum pair (s_i, s_ip1) = A ^ B ^ C, and the party's XOR share of the carry
+ *                          majority(A, B, C) = ((A ^ C) & (B ^ C)) ^ C before blinding, i.e.
+ *                          and3(A ^ C, B ^ C) ^ c_i.  Bit by bit a + b + c = sum + 2 carry.
+ *   cg_bshare_half_adder : propagate pair (p_i, p_ip1) = S ^ T and the party's XOR share of the
+ *                          generate word and3(S, T) before blinding.
+ *
+ * Outputs may coincide element for element with inputs but not partially overlap them, and must be
+ * disjoint from each other (CG_ERR_ALIAS).
+ */
+CG_API cg_status cg_bshare_csa(const uint64_t *a_i, const uint64_t *a_ip1, const uint64_t *b_i,
+                        const uint64_t *b_ip1, const uint64_t *c_i, const uint64_t *c_ip1,
+                        uint64_t *s_i, uint64_t *s_ip1, uint64_t *carry_i, size_t n, void *stream);
+
+CG_API cg_status cg_bshare_half_adder(const uint64_t *s_i, const uint64_t *s_ip1, const uint64_t *t_i,
+                               const uint64_t *t_ip1, uint64_t *p_i, uint64_t *p_ip1, uint64_t *g_i,
+                               size_t n, void *stream);
+
 CG_API cg_status cg_bit_transpose64(const uint64_t *src, uint64_t *dst, size_t n, void *stream);
 
 CG_API cg_status cg_bshare_carry_level(const uint64_t *p_i, const uint64_t *p_ip1,

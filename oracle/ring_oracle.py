@@ -373,6 +373,23 @@ def breshare(z, key_self: bytes, key_prev: bytes, nonce: int, first: int) -> np.
     return z ^ bzero_share(key_self, key_prev, nonce, first, z.size).reshape(z.shape)
 
 
+def csa_local(a_i, a_ip1, b_i, b_ip1, c_i, c_ip1):
+    """One party's local step of a carry-save (full) adder on three binary sharings: the sum S = A ^ B ^ C as a
+    pair (XOR gates only), and its XOR share of the carry majority(A, B, C) = ((A ^ C) & (B ^ C)) ^ C before
+    blinding (one AND gate by the three-term formula; the party adds its own component C_i)."""
+    a_i, a_ip1, b_i, b_ip1, c_i, c_ip1 = (_u(v) for v in (a_i, a_ip1, b_i, b_ip1, c_i, c_ip1))
+    s_i, s_ip1 = a_i ^ b_i ^ c_i, a_ip1 ^ b_ip1 ^ c_ip1
+    carry = bshare_and(a_i ^ c_i, a_ip1 ^ c_ip1, b_i ^ c_i, b_ip1 ^ c_ip1) ^ c_i
+    return s_i, s_ip1, carry
+
+
+def half_adder_local(s_i, s_ip1, t_i, t_ip1):
+    """One party's local step of a half adder on two binary sharings: propagate P = S ^ T as a pair and its
+    XOR share of generate G = S & T before blinding."""
+    s_i, s_ip1, t_i, t_ip1 = (_u(v) for v in (s_i, s_ip1, t_i, t_ip1))
+    return s_i ^ t_i, s_ip1 ^ t_ip1, bshare_and(s_i, s_ip1, t_i, t_ip1)
+
+
 def ks_stage_local(p_i, p_ip1, g_i, g_ip1, shift: int, last: bool = False):
     """One party's local step of one stage of the parallel-prefix adder on (propagate, generate) words:
     g' = g ^ (p & (g << shift)), p' = p & (p << shift), both AND gates by the three-term formula; the party

@@ -26,7 +26,7 @@ EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d
            "cg_share_mul", "cg_share_sum_pool2d", "cg_share_conv2d_dgrad", "cg_share_conv2d_wgrad",
            "cg_trunc1_local", "cg_prf_words", "cg_bshare_xor", "cg_bshare_and", "cg_bshare_prefix_stage",
            "cg_bzero_share", "cg_breshare", "cg_share_bias_add", "cg_share_col_sum",
-           "cg_bit_transpose64", "cg_bshare_carry_level", "cg_bits_unpack",
+           "cg_bit_transpose64", "cg_bshare_carry_level", "cg_bits_unpack", "cg_bshare_csa", "cg_bshare_half_adder",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 
 
@@ -83,6 +83,8 @@ def lib() -> ctypes.CDLL:
         L.cg_share_sum_pool2d.argtypes = [vp] * 4 + [ctypes.POINTER(PoolDesc), vp]
         L.cg_share_bias_add.argtypes = [vp] * 6 + [sz, sz, vp]
         L.cg_share_col_sum.argtypes = [vp] * 4 + [sz, sz, vp]
+        L.cg_bshare_csa.argtypes = [vp] * 9 + [sz, vp]
+        L.cg_bshare_half_adder.argtypes = [vp] * 7 + [sz, vp]
         L.cg_bit_transpose64.argtypes = [vp, vp, sz, vp]
         L.cg_bshare_carry_level.argtypes = [vp] * 6 + [sz, sz, vp]
         L.cg_bits_unpack.argtypes = [vp, vp, sz, vp]
@@ -95,9 +97,9 @@ def lib() -> ctypes.CDLL:
         L.cg_prf_words.argtypes = [key, u64, u64, vp, sz, vp]
         L.cg_share_conv2d_dgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
         L.cg_share_conv2d_wgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
-        for name in EXPORTS[2:29]:
+        for name in EXPORTS[2:31]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[29:]:
+        for name in EXPORTS[31:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -466,6 +468,34 @@ def cg_bshare_prefix_stage(p_i, p_ip1, g_i, g_ip1, shift: int, last: bool = Fals
                                         None if last else (_ptr(p_out) if n else 0), _ptr(g_out) if n else 0, n,
                                         _stream(stream)), "cg_bshare_prefix_stage")
     return (None if last else p_out), g_out
+
+
+def cg_bshare_csa(a_i, a_ip1, b_i, b_ip1, c_i, c_ip1, s_i=None, s_ip1=None, carry_i=None, stream=None):
+    """Local step of a carry-save adder: returns (s_i, s_ip1, carry_i)."""
+    ins = (a_i, a_ip1, b_i, b_ip1, c_i, c_ip1)
+    if any(t.shape != a_i.shape for t in ins):
+        raise ValueError("operand shapes do not match")
+    s_i = torch.empty_like(a_i) if s_i is None else s_i
+    s_ip1 = torch.empty_like(a_i) if s_ip1 is None else s_ip1
+    carry_i = torch.empty_like(a_i) if carry_i is None else carry_i
+    n = a_i.numel()
+    _check(lib().cg_bshare_csa(*(_ptr(t) if n else 0 for t in ins + (s_i, s_ip1, carry_i)), n, _stream(stream)),
+           "cg_bshare_csa")
+    return s_i, s_ip1, carry_i
+
+
+def cg_bshare_half_adder(s_i, s_ip1, t_i, t_ip1, p_i=None, p_ip1=None, g_i=None, stream=None):
+    """Local step of a half adder: returns (p_i, p_ip1, g_i)."""
+    ins = (s_i, s_ip1, t_i, t_ip1)
+    if any(t.shape != s_i.shape for t in ins):
+        raise ValueError("operand shapes do not match")
+    p_i = torch.empty_like(s_i) if p_i is None else p_i
+    p_ip1 = torch.empty_like(s_i) if p_ip1 is None else p_ip1
+    g_i = torch.empty_like(s_i) if g_i is None else g_i
+    n = s_i.numel()
+    _check(lib().cg_bshare_half_adder(*(_ptr(t) if n else 0 for t in ins + (p_i, p_ip1, g_i)), n, _stream(stream)),
+           "cg_bshare_half_adder")
+    return p_i, p_ip1, g_i
 
 
 def cg_bit_transpose64(x, out=None, stream=None) -> torch.Tensor:

@@ -334,6 +334,66 @@ struct PrefixStageOp {
     }
 };
 
+// Carry-save (full) adder on three binary sharings, one party's local step: sum pair S = A ^ B ^ C and the
+// party's XOR share of the carry ((A ^ C) & (B ^ C)) ^ C (three-term AND, own component of C added).
+struct CsaOp {
+    const u64 *aa, *ab, *ba, *bb, *ca, *cb;
+    u64 *sa, *sb, *carry;
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 a0[U], a1[U], b0[U], b1[U], c0[U], c1[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t k = i + u * step;
+            a0[u] = ld2(aa, k); a1[u] = ld2(ab, k); b0[u] = ld2(ba, k);
+            b1[u] = ld2(bb, k); c0[u] = ld2(ca, k); c1[u] = ld2(cb, k);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t k = i + u * step;
+            const ull2 x0 = a0[u] ^ c0[u], x1 = a1[u] ^ c1[u], y0 = b0[u] ^ c0[u], y1 = b1[u] ^ c1[u];
+            st2(sa, k, x0 ^ b0[u]);
+            st2(sb, k, x1 ^ b1[u]);
+            st2(carry, k, (x0 & (y0 ^ y1)) ^ (x1 & y0) ^ c0[u]);
+        }
+    }
+    __device__ void one(size_t k) const {
+        const u64 c0 = ca[k], c1 = cb[k], b0 = ba[k], b1 = bb[k];
+        const u64 x0 = aa[k] ^ c0, x1 = ab[k] ^ c1, y0 = b0 ^ c0, y1 = b1 ^ c1;
+        sa[k] = x0 ^ b0;
+        sb[k] = x1 ^ b1;
+        carry[k] = (x0 & (y0 ^ y1)) ^ (x1 & y0) ^ c0;
+    }
+};
+
+// Half adder on two binary sharings: propagate pair P = S ^ T and the party's XOR share of generate S & T.
+struct HalfAdderOp {
+    const u64 *sa, *sb, *ta, *tb;
+    u64 *pa, *pb, *g;
+    template <int U>
+    __device__ void pairs(size_t i, size_t step) const {
+        ull2 s0[U], s1[U], t0[U], t1[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t k = i + u * step;
+            s0[u] = ld2(sa, k); s1[u] = ld2(sb, k); t0[u] = ld2(ta, k); t1[u] = ld2(tb, k);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t k = i + u * step;
+            st2(pa, k, s0[u] ^ t0[u]);
+            st2(pb, k, s1[u] ^ t1[u]);
+            st2(g, k, (s0[u] & (t0[u] ^ t1[u])) ^ (s1[u] & t0[u]));
+        }
+    }
+    __device__ void one(size_t k) const {
+        const u64 s0 = sa[k], s1 = sb[k], t0 = ta[k], t1 = tb[k];
+        pa[k] = s0 ^ t0;
+        pb[k] = s1 ^ t1;
+        g[k] = (s0 & (t0 ^ t1)) ^ (s1 & t0);
+    }
+};
+
 // One level of the carry tree on bit planes: inputs [2k, m] words, outputs [k, m]; output plane j merges the
 // neighbouring segments hi = plane 2j+1 and lo = plane 2j:
 //   g' = g_hi ^ and3(p_hi, g_lo),  p' = and3(p_hi, p_lo),  and3 = the three-term AND on the pairs.
@@ -1110,6 +1170,41 @@ cg_status cg_bshare_prefix_stage(const uint64_t* p_i, const uint64_t* p_ip1, con
     PrefixStageOp f = {p_i, p_ip1, g_i, g_ip1, p_out, g_out, shift};
     const void* all[6] = {p_i, p_ip1, g_i, g_ip1, g_out, p_out ? p_out : g_out};
     return launch_ew(n, all_aligned16(all, 6), f, stream);
+}
+
+cg_status cg_bshare_csa(const uint64_t* a_i, const uint64_t* a_ip1, const uint64_t* b_i, const uint64_t* b_ip1,
+                        const uint64_t* c_i, const uint64_t* c_ip1, uint64_t* s_i, uint64_t* s_ip1, uint64_t* carry_i,
+                        size_t n, void* stream) {
+    if (n == 0) return CG_OK;
+    const void* ptrs[9] = {a_i, a_ip1, b_i, b_ip1, c_i, c_ip1, s_i, s_ip1, carry_i};
+    if (cg_status st = check_ptrs(ptrs, 9)) return st;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    for (int o = 6; o < 9; ++o) {
+        for (int i = 0; i < 6; ++i)
+            if (bad_overlap(ptrs[o], ptrs[i], bytes)) return CG_ERR_ALIAS;
+        for (int o2 = o + 1; o2 < 9; ++o2)
+            if (overlap(ptrs[o], bytes, ptrs[o2], bytes)) return CG_ERR_ALIAS;
+    }
+    CsaOp f = {a_i, a_ip1, b_i, b_ip1, c_i, c_ip1, s_i, s_ip1, carry_i};
+    return launch_ew(n, all_aligned16(ptrs, 9), f, stream);
+}
+
+cg_status cg_bshare_half_adder(const uint64_t* s_i, const uint64_t* s_ip1, const uint64_t* t_i, const uint64_t* t_ip1,
+                               uint64_t* p_i, uint64_t* p_ip1, uint64_t* g_i, size_t n, void* stream) {
+    if (n == 0) return CG_OK;
+    const void* ptrs[7] = {s_i, s_ip1, t_i, t_ip1, p_i, p_ip1, g_i};
+    if (cg_status st = check_ptrs(ptrs, 7)) return st;
+    if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
+    const u64 bytes = (u64)n * 8;
+    for (int o = 4; o < 7; ++o) {
+        for (int i = 0; i < 4; ++i)
+            if (bad_overlap(ptrs[o], ptrs[i], bytes)) return CG_ERR_ALIAS;
+        for (int o2 = o + 1; o2 < 7; ++o2)
+            if (overlap(ptrs[o], bytes, ptrs[o2], bytes)) return CG_ERR_ALIAS;
+    }
+    HalfAdderOp f = {s_i, s_ip1, t_i, t_ip1, p_i, p_ip1, g_i};
+    return launch_ew(n, all_aligned16(ptrs, 7), f, stream);
 }
 
 cg_status cg_bshare_carry_level(const uint64_t* p_i, const uint64_t* p_ip1, const uint64_t* g_i, const uint64_t* g_ip1,

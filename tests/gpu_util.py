@@ -93,9 +93,10 @@ def gpu_relu(cg, X, keys, nonce):
     return gpu_share_mult(cg, X, keep, keys, nonce + 1, 2 * n)
 
 
-def gpu_msb_sliced(cg, x_dev, KEYS, nonce):
+def gpu_msb_sliced(cg, x_dev, KEYS, nonce, cells=False):
     """The oracle's msb_protocol_sliced with every local step on the GPU through the C-ABI: returns the
-    binary sharing (triple of [m] words) of the packed sign bits of x_0 + x_1 + x_2 (n = 64 m elements)."""
+    binary sharing (triple of [m] words) of the packed sign bits of x_0 + x_1 + x_2 (n = 64 m elements).
+    cells=True takes the first two rounds with the fused adder cells instead of single gates."""
     import torch
     n = x_dev[0].numel()
     m = n // 64
@@ -116,12 +117,23 @@ def gpu_msb_sliced(cg, x_dev, KEYS, nonce):
     planes = [cg.cg_bit_transpose64(a.reshape(-1)) for a in x_dev]
     zero = torch.zeros_like(planes[0])
     A, B, C = (planes[0], zero, zero), (zero, planes[1], zero), (zero, zero, planes[2])
-    S = xor(xor(A, B), C)
-    carry = xor(and_gate(xor(A, C), xor(B, C)), C)
     up = lambda v: torch.cat([torch.zeros_like(v[:1]), v[:63]])        # one bit position up: a move of planes
-    T = tuple(up(c) for c in carry)
-    P0 = xor(S, T)
-    G0 = and_gate(S, T)
+    if cells:
+        loc = [cg.cg_bshare_csa(*pair(A, i), *pair(B, i), *pair(C, i)) for i in range(3)]
+        S = tuple(loc[i][0] for i in range(3))
+        carry = tuple(blind(loc[i][2], i) for i in range(3))
+        counter[0] += n
+        T = tuple(up(c) for c in carry)
+        loc = [cg.cg_bshare_half_adder(*pair(S, i), *pair(T, i)) for i in range(3)]
+        P0 = tuple(loc[i][0] for i in range(3))
+        G0 = tuple(blind(loc[i][2], i) for i in range(3))
+        counter[0] += n
+    else:
+        S = xor(xor(A, B), C)
+        carry = xor(and_gate(xor(A, C), xor(B, C)), C)
+        T = tuple(up(c) for c in carry)
+        P0 = xor(S, T)
+        G0 = and_gate(S, T)
     P, G = tuple(up(p) for p in P0), tuple(up(g) for g in G0)
     while P[0].shape[0] > 1:
         last = P[0].shape[0] == 2

@@ -168,3 +168,24 @@ def test_pruned_circuit_gives_the_sign_of_the_integer_sum():
     # and it agrees with the word-parallel adder's sign bit
     _, msb_word = ro.msb_protocol(x, KEYS, nonce=10)
     assert np.array_equal(ro.bits_unpack(opened, n), msb_word[0] ^ msb_word[1] ^ msb_word[2])
+
+
+def test_full_and_half_adder_steps_open_to_the_bitwise_definitions():
+    a, b, c = (wl.draw_ring((257,), 90 + k) for k in range(3))
+    A, B, C = bshare(a, 93), bshare(b, 95), bshare(c, 97)
+    outs = [ro.csa_local(A[i], A[(i + 1) % 3], B[i], B[(i + 1) % 3], C[i], C[(i + 1) % 3]) for i in range(3)]
+    assert np.array_equal(outs[0][0] ^ outs[1][0] ^ outs[2][0], a ^ b ^ c)
+    assert np.array_equal(outs[0][2] ^ outs[1][2] ^ outs[2][2], (a & b) | (a & c) | (b & c))
+    for i in range(3):                      # the sum keeps the replicated form
+        assert np.array_equal(outs[i][1], outs[(i + 1) % 3][0])
+    # one column of the adder: a + b + c = sum + 2 carry, bit by bit
+    for j in range(5):
+        for bit in (0, 17, 63):
+            abc = [(int(v[j]) >> bit) & 1 for v in (a, b, c)]
+            s_bit = (int(outs[0][0][j] ^ outs[1][0][j] ^ outs[2][0][j]) >> bit) & 1
+            c_bit = (int(outs[0][2][j] ^ outs[1][2][j] ^ outs[2][2][j]) >> bit) & 1
+            assert sum(abc) == s_bit + 2 * c_bit
+    S, T = bshare(a, 101), bshare(b, 103)
+    outs = [ro.half_adder_local(S[i], S[(i + 1) % 3], T[i], T[(i + 1) % 3]) for i in range(3)]
+    assert np.array_equal(outs[0][0] ^ outs[1][0] ^ outs[2][0], a ^ b)
+    assert np.array_equal(outs[0][2] ^ outs[1][2] ^ outs[2][2], a & b)
