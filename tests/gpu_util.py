@@ -73,14 +73,19 @@ def gpu_share_mult(cg, U, V, keys, nonce, first):
     return tuple(out)
 
 
-def gpu_relu(cg, X, keys, nonce):
+def gpu_relu(cg, X, keys, nonce, sliced=False):
     """ReLU of a replicated arithmetic sharing X = (x_0, x_1, x_2): sign bit from the adder circuit, its three
     binary shares read as arithmetic sharings, two integer XORs (u + v - 2uv) and (1 - b) x.  Uses the PRF
-    streams `nonce` (binary gates) and `nonce + 1` (products)."""
+    streams `nonce` (binary gates) and `nonce + 1` (products).  sliced=True takes the sign bit from the pruned
+    circuit on bit planes (the element count must then be a multiple of 64)."""
     import torch
     n = X[0].numel()
-    total = gpu_msb_circuit(cg, list(X), keys, nonce)
-    msb = [(t >> 63) & 1 for t in total]
+    if sliced:
+        planes = gpu_msb_sliced(cg, [x.reshape(-1) for x in X], keys, nonce, cells=True)
+        msb = [cg.cg_bits_unpack(p, n).view_as(X[0]) for p in planes]
+    else:
+        total = gpu_msb_circuit(cg, list(X), keys, nonce)
+        msb = [(t >> 63) & 1 for t in total]
     zero = torch.zeros_like(X[0])
     B = [tuple(msb[k] if j == k else zero for j in range(3)) for k in range(3)]
 

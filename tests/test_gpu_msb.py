@@ -252,3 +252,17 @@ def test_pruned_circuit_built_from_adder_cells_gives_the_same_shares(cg, ro, wl)
     want = ro.msb_protocol_sliced(x, KEYS, nonce=11)
     for g, w in zip(got, want):
         assert not first_mismatch(cg.to_host(g), w)
+
+
+def test_relu_is_the_same_with_either_sign_bit_circuit(cg, ro, wl):
+    from tests.gpu_util import gpu_relu
+    n = 64 * 100
+    say(f"ReLU with the word-parallel and the pruned sign-bit circuit, n={n}")
+    rng = np.random.default_rng(77)
+    xs = rng.integers(-(1 << 45), 1 << 45, size=n, dtype=np.int64)
+    x = xs.astype(np.uint64)
+    X = tuple(cg.to_device(s) for s in ro.share(x, wl.draw_ring(x.shape, 78), wl.draw_ring(x.shape, 79)))
+    for sliced in (False, True):
+        R = gpu_relu(cg, X, KEYS, nonce=20, sliced=sliced)
+        opened = cg.to_host(cg.cg_reconstruct(*R)).astype(np.int64)
+        assert np.array_equal(opened, np.maximum(xs, 0)), f"sliced={sliced}"

@@ -191,7 +191,8 @@ def test_fc_stack_evaluated_entirely_on_shares(cg, ro, wl):
         pre = (s0, s1, s2)
         pre_real = act_real @ w_real.T + b_real
         if li + 1 < len(layers):
-            act = gpu_relu(cg, pre, keys, nonce + 2)
+            # first hidden layer: sign bit from the word-parallel adder; second: from the pruned circuit on planes
+            act = gpu_relu(cg, pre, keys, nonce + 2, sliced=(li == 1))
             act_real = np.maximum(pre_real, 0)
         nonce += 4
     torch.cuda.synchronize()
