@@ -117,21 +117,48 @@ __device__ __forceinline__ u32 last_column(const char* tbl, u32 lc, u32 a, u32 b
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u) ^ rk;
 }
 
-__device__ __forceinline__ void aes_block(const char* __restrict__ tbl, u32 lc, const u32 (&rk)[44], u32 c0, u32 c1,
-                                          u32 c2, u32 c3, u32 out[4]) {
-    u32 s0 = c0 ^ rk[0], s1 = c1 ^ rk[1], s2 = c2 ^ rk[2], s3 = c3 ^ rk[3];
+// NS independent encryptions side by side, round by round.  The round loop is NOT unrolled and the round keys
+// are indexed by the loop counter, so that they are fetched by scalar loads as the rounds go (one round ahead):
+// keeping two or three whole key schedules in scalar registers does not fit and would be spilled into vector lanes.
+template <int NS>
+__device__ __forceinline__ void aes_blocks(const char* __restrict__ tbl, u32 lc, const u32* const (&rk)[NS],
+                                           const u32 (&in)[NS][4], u32 (&out)[NS][4]) {
+    u32 s[NS][4], k[NS][4];
 #pragma unroll
-    for (int r = 1; r < 10; ++r) {
-        const u32 n0 = column(tbl, lc, s0, s1, s2, s3, rk[4 * r]);
-        const u32 n1 = column(tbl, lc, s1, s2, s3, s0, rk[4 * r + 1]);
-        const u32 n2 = column(tbl, lc, s2, s3, s0, s1, rk[4 * r + 2]);
-        const u32 n3 = column(tbl, lc, s3, s0, s1, s2, rk[4 * r + 3]);
-        s0 = n0; s1 = n1; s2 = n2; s3 = n3;
+    for (int e = 0; e < NS; ++e) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            s[e][c] = in[e][c] ^ rk[e][c];
+            k[e][c] = rk[e][4 + c];
+        }
     }
-    out[0] = last_column(tbl, lc, s0, s1, s2, s3, rk[40]);
-    out[1] = last_column(tbl, lc, s1, s2, s3, s0, rk[41]);
-    out[2] = last_column(tbl, lc, s2, s3, s0, s1, rk[42]);
-    out[3] = last_column(tbl, lc, s3, s0, s1, s2, rk[43]);
+#pragma unroll 3
+    for (int r = 1; r < 10; ++r) {
+        u32 nk[NS][4];
+#pragma unroll
+        for (int e = 0; e < NS; ++e)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) nk[e][c] = rk[e][4 * (r + 1) + c];
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            const u32 n0 = column(tbl, lc, s[e][0], s[e][1], s[e][2], s[e][3], k[e][0]);
+            const u32 n1 = column(tbl, lc, s[e][1], s[e][2], s[e][3], s[e][0], k[e][1]);
+            const u32 n2 = column(tbl, lc, s[e][2], s[e][3], s[e][0], s[e][1], k[e][2]);
+            const u32 n3 = column(tbl, lc, s[e][3], s[e][0], s[e][1], s[e][2], k[e][3]);
+            s[e][0] = n0; s[e][1] = n1; s[e][2] = n2; s[e][3] = n3;
+        }
+#pragma unroll
+        for (int e = 0; e < NS; ++e)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) k[e][c] = nk[e][c];
+    }
+#pragma unroll
+    for (int e = 0; e < NS; ++e) {
+        out[e][0] = last_column(tbl, lc, s[e][0], s[e][1], s[e][2], s[e][3], k[e][0]);
+        out[e][1] = last_column(tbl, lc, s[e][1], s[e][2], s[e][3], s[e][0], k[e][1]);
+        out[e][2] = last_column(tbl, lc, s[e][2], s[e][3], s[e][0], s[e][1], k[e][2]);
+        out[e][3] = last_column(tbl, lc, s[e][3], s[e][0], s[e][1], s[e][2], k[e][3]);
+    }
 }
 
 struct T0Table {
@@ -172,20 +199,32 @@ __global__ __launch_bounds__(PRF_THREADS) void prf_combine_kernel(const u64* __r
     for (u64 bi = (u64)blockIdx.x * PRF_THREADS + threadIdx.x; bi < nblocks; bi += (u64)gridDim.x * PRF_THREADS) {
         const u64 block = b_first + bi;
         u64 w0 = 0, w1 = 0, r0 = 0, r1 = 0;
+        constexpr int NS = (ALPHA ? 2 : 0) + (MASK ? 1 : 0);
+        u32 in[NS][4], ct[NS][4];
+        const u32* rk[NS];
         if constexpr (ALPHA) {
-            u32 a[4], b[4];
-            aes_block(tbl, lc, keys.self, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), a);
-            aes_block(tbl, lc, keys.prev, (u32)block, (u32)(block >> 32), (u32)nonce, (u32)(nonce >> 32), b);
-            const u64 a0 = ((u64)a[1] << 32) | a[0], a1 = ((u64)a[3] << 32) | a[2];
-            const u64 b0 = ((u64)b[1] << 32) | b[0], b1 = ((u64)b[3] << 32) | b[2];
+            rk[0] = keys.self;
+            rk[1] = keys.prev;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                in[e][0] = (u32)block; in[e][1] = (u32)(block >> 32); in[e][2] = (u32)nonce; in[e][3] = (u32)(nonce >> 32);
+            }
+        }
+        if constexpr (MASK) {
+            rk[NS - 1] = keys.mask;
+            in[NS - 1][0] = (u32)block; in[NS - 1][1] = (u32)(block >> 32);
+            in[NS - 1][2] = (u32)mask_nonce; in[NS - 1][3] = (u32)(mask_nonce >> 32);
+        }
+        aes_blocks<NS>(tbl, lc, rk, in, ct);
+        if constexpr (ALPHA) {
+            const u64 a0 = ((u64)ct[0][1] << 32) | ct[0][0], a1 = ((u64)ct[0][3] << 32) | ct[0][2];
+            const u64 b0 = ((u64)ct[1][1] << 32) | ct[1][0], b1 = ((u64)ct[1][3] << 32) | ct[1][2];
             w0 = xor_mode ? a0 ^ b0 : a0 - b0;
             w1 = xor_mode ? a1 ^ b1 : a1 - b1;
         }
         if constexpr (MASK) {
-            u32 m[4];
-            aes_block(tbl, lc, keys.mask, (u32)block, (u32)(block >> 32), (u32)mask_nonce, (u32)(mask_nonce >> 32), m);
-            r0 = ((u64)m[1] << 32) | m[0];
-            r1 = ((u64)m[3] << 32) | m[2];
+            r0 = ((u64)ct[NS - 1][1] << 32) | ct[NS - 1][0];
+            r1 = ((u64)ct[NS - 1][3] << 32) | ct[NS - 1][2];
             if (!add_mask) { r0 = 0 - r0; r1 = 0 - r1; }
         }
         const u64 j0 = 2 * block, j1 = j0 + 1;  // word indices
