@@ -173,6 +173,75 @@ def test_prf_entry_points_validation(L):
     assert L.cg_reshare(0, k, k, 0, 0, 0, 0, None) == b.CG_OK
 
 
+def test_conv_backward_validation(L):
+    from paper_2104_10949_amd import binding as b
+    ok = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
+
+    def desc(**kw):
+        base = dict(B=2, H=8, W=8, Cin=4, Cout=6, kh=3, kw=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1)
+        base.update(kw)
+        return ctypes.byref(b.ConvDesc(**base))
+
+    for f in (L.cg_share_conv2d_dgrad, L.cg_share_conv2d_wgrad):
+        assert f(*ok, None, None) == b.CG_ERR_NULL
+        assert f(*ok[:4], 0, desc(), None) == b.CG_ERR_NULL
+        assert f(*ok, desc(Cout=0), None) == b.CG_ERR_SHAPE
+        assert f(*ok, desc(kh=11, pad_h=1), None) == b.CG_ERR_SHAPE
+        assert f(ok[0] + 4, *ok[1:], desc(), None) == b.CG_ERR_ALIGN
+        assert f(*ok[:4], ok[0] + 8, desc(), None) == b.CG_ERR_ALIAS          # output inside the gradient
+        assert f(*ok[:4], ok[2] + 8, desc(), None) == b.CG_ERR_ALIAS          # output inside the second operand
+    # documented limits: contraction of the input gradient, rows of the weight gradient's transposed operand
+    assert L.cg_share_conv2d_dgrad(*ok, desc(Cout=1 << 18, kh=3, kw=3), None) == b.CG_ERR_UNSUPPORTED
+    assert L.cg_share_conv2d_wgrad(*ok, desc(Cout=(1 << 22) + 1), None) == b.CG_ERR_UNSUPPORTED
+
+
+def test_truncation_and_binary_gate_validation(L):
+    from paper_2104_10949_amd import binding as b
+    k = bytes(16)
+    f = L.cg_trunc1_local
+    assert f(P, None, None, k, 0, 0, 16, None, 0, 2 * P, 8, None) == b.CG_ERR_NULL
+    assert f(P, None, k, k, 0, 0, 64, None, 0, 2 * P, 8, None) == b.CG_ERR_SHAPE
+    assert f(P, None, k, k, 0, 0, -1, None, 0, 2 * P, 8, None) == b.CG_ERR_SHAPE
+    assert f(0, None, k, k, 0, 0, 16, None, 0, 2 * P, 8, None) == b.CG_ERR_NULL
+    assert f(P, P + 4, k, k, 0, 0, 16, None, 0, 2 * P, 8, None) == b.CG_ERR_ALIGN
+    assert f(P, None, k, k, 0, 0, 16, None, 0, P + 8, 8, None) == b.CG_ERR_ALIAS
+    assert f(P, None, k, k, 0, (1 << 64) - 2, 16, None, 0, 2 * P, 8, None) == b.CG_ERR_SHAPE
+    assert f(0, None, k, k, 0, 0, 16, None, 0, 0, 0, None) == b.CG_OK
+    assert L.cg_prf_words(None, 0, 0, P, 8, None) == b.CG_ERR_NULL
+    assert L.cg_prf_words(k, 0, 0, P + 2, 8, None) == b.CG_ERR_ALIGN
+    assert L.cg_prf_words(k, 0, 0, 0, 0, None) == b.CG_OK
+    a = [P, 2 * P, 3 * P, 4 * P]
+    assert L.cg_bshare_and(*a, 0, 8, None) == b.CG_ERR_NULL
+    assert L.cg_bshare_and(*a, P + 8, 8, None) == b.CG_ERR_ALIAS
+    assert L.cg_bshare_xor(*a, 5 * P, 5 * P + 8, 8, None) == b.CG_ERR_ALIAS        # the two outputs overlap
+    assert L.cg_bshare_prefix_stage(*a, 0, 5 * P, 6 * P, 8, None) == b.CG_ERR_SHAPE
+    assert L.cg_bshare_prefix_stage(*a, 64, 5 * P, 6 * P, 8, None) == b.CG_ERR_SHAPE
+    assert L.cg_bshare_prefix_stage(*a, 1, None, 0, 8, None) == b.CG_ERR_NULL
+    assert L.cg_bshare_prefix_stage(*a, 1, None, 6 * P, 0, None) == b.CG_OK
+    assert L.cg_bshare_carry_level(*a, None, P + 64, 4, 4, None) == b.CG_ERR_ALIAS   # output inside an input
+    assert L.cg_bshare_carry_level(*a, None, 6 * P, 1 << 40, 1 << 40, None) == b.CG_ERR_SHAPE
+    assert L.cg_bit_transpose64(P, 2 * P, 65, None) == b.CG_ERR_SHAPE
+    assert L.cg_bit_transpose64(P, P + 64, 128, None) == b.CG_ERR_ALIAS
+    assert L.cg_bits_unpack(P, 0, 8, None) == b.CG_ERR_NULL
+    six = [P, 2 * P, 3 * P, 4 * P, 5 * P, 6 * P]
+    assert L.cg_bshare_csa(*six, 7 * P, 8 * P, 7 * P + 8, 8, None) == b.CG_ERR_ALIAS  # sum and carry overlap
+    assert L.cg_bshare_half_adder(*a, 5 * P, 6 * P, 0, 8, None) == b.CG_ERR_NULL
+
+
+def test_bias_entry_points_validation(L):
+    from paper_2104_10949_amd import binding as b
+    a = [P, 2 * P, 3 * P, 4 * P, 5 * P, 6 * P]
+    assert L.cg_share_bias_add(*a, 12, 5, None) == b.CG_ERR_SHAPE               # period does not divide n
+    assert L.cg_share_bias_add(*a, 12, 0, None) == b.CG_ERR_SHAPE
+    assert L.cg_share_bias_add(*a[:4], 3 * P, 6 * P, 12, 4, None) == b.CG_ERR_ALIAS   # output over the bias
+    assert L.cg_share_bias_add(*a, 0, 0, None) == b.CG_OK
+    assert L.cg_share_col_sum(P, 2 * P, 0, 4 * P, 8, 4, None) == b.CG_ERR_NULL
+    assert L.cg_share_col_sum(P, 2 * P, P + 8, 4 * P, 8, 4, None) == b.CG_ERR_ALIAS
+    assert L.cg_share_col_sum(P, 2 * P, 3 * P, 3 * P + 8, 8, 4, None) == b.CG_ERR_ALIAS
+    assert L.cg_share_col_sum(P, 2 * P, 3 * P, 4 * P, 1 << 62, 8, None) == b.CG_ERR_SHAPE
+    assert L.cg_share_col_sum(0, 0, 0, 0, 8, 0, None) == b.CG_OK
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     from paper_2104_10949_amd import binding as b
