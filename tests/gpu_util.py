@@ -151,3 +151,22 @@ def gpu_msb_sliced(cg, x_dev, KEYS, nonce, cells=False):
         else:
             P = G
     return tuple(p0[63] ^ g[0] for p0, g in zip(P0, G))                # XOR of shares: local
+
+
+def gpu_trunc(cg, z, keys, nonce, d):
+    """The two-round truncation protocol on a 3-out-of-3 additive sharing z = (z_0, z_1, z_2) of GPU tensors
+    (e.g. the outputs of the local products, or a replicated sharing read as its three shares): returns the
+    replicated sharing (s_0, s_1, s_2) of about z / 2^d.  PRF streams `nonce` and `nonce + 1`."""
+    n = z[0].numel()
+    msg = cg.cg_reshare(z[2], keys[2], keys[1], nonce, 0)
+    s0 = cg.cg_trunc1_local(z[0], None, keys[0], keys[2], nonce, 0, d)
+    s1 = cg.cg_trunc1_local(z[1], msg, keys[1], keys[0], nonce, 0, d, keys[1], nonce + 1)
+    s2 = cg.cg_prf_words(keys[1], nonce + 1, 0, n).view_as(s0)
+    return (s0, s1, s2)
+
+
+def gpu_mul_trunc(cg, U, V, keys, nonce, t):
+    """Fixed-point product of two replicated sharings at scale 2^t: every party's three-term product on the GPU,
+    then the truncation protocol on the three additive results (its first step blinds them)."""
+    z = tuple(cg.cg_share_mul(U[i], U[(i + 1) % 3], V[i], V[(i + 1) % 3]) for i in range(3))
+    return gpu_trunc(cg, z, keys, nonce, t)
