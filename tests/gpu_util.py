@@ -73,7 +73,7 @@ def gpu_share_mult(cg, U, V, keys, nonce, first):
     return tuple(out)
 
 
-def gpu_relu(cg, X, keys, nonce, sliced=False):
+def gpu_relu(cg, X, keys, nonce, sliced=False, with_mask=False):
     """ReLU of a replicated arithmetic sharing X = (x_0, x_1, x_2): sign bit from the adder circuit, its three
     binary shares read as arithmetic sharings, two integer XORs (u + v - 2uv) and (1 - b) x.  Uses the PRF
     streams `nonce` (binary gates) and `nonce + 1` (products).  sliced=True takes the sign bit from the pruned
@@ -95,7 +95,8 @@ def gpu_relu(cg, X, keys, nonce, sliced=False):
 
     b = xor_arith(xor_arith(B[0], B[1], 0), B[2], n)
     keep = tuple((1 if k == 0 else 0) - s for k, s in enumerate(b))
-    return gpu_share_mult(cg, X, keep, keys, nonce + 1, 2 * n)
+    out = gpu_share_mult(cg, X, keep, keys, nonce + 1, 2 * n)
+    return (out, keep) if with_mask else out          # keep = sharing of relu'(x) as an unscaled integer 0 / 1
 
 
 def gpu_msb_sliced(cg, x_dev, KEYS, nonce, cells=False):
@@ -170,3 +171,47 @@ def gpu_mul_trunc(cg, U, V, keys, nonce, t):
     then the truncation protocol on the three additive results (its first step blinds them)."""
     z = tuple(cg.cg_share_mul(U[i], U[(i + 1) % 3], V[i], V[(i + 1) % 3]) for i in range(3))
     return gpu_trunc(cg, z, keys, nonce, t)
+
+
+
+def softmax_float_model(x, log_m, newton):
+    """The approximations of gpu_softmax in float64, without shares or fixed point."""
+    y = x - x.max(axis=1, keepdims=True)
+    e = (1 + y / 2 ** log_m) ** (2 ** log_m)
+    s = e.sum(axis=1, keepdims=True)
+    z = np.full_like(s, 1 / x.shape[1])
+    for _ in range(newton):
+        z = 2 * z - s * z * z
+    return e * z
+
+
+def gpu_softmax(cg, X, keys, fresh, t, log_m, newton):
+    """Row-wise softmax of a replicated sharing X [batch, d] at scale 2^t, from local steps on the GPU: maximum by a
+    tree of comparisons, (1 + x/m)^m with m = 2^log_m by repeated squaring, reciprocal of the row sums by `newton`
+    Newton-Raphson iterations from the fixed start 1/d.  `fresh()` hands out unused PRF nonces (4 apart).
+    Returns (softmax sharing, sharing of the row maxima)."""
+    import torch
+    d = X[0].shape[1]
+    sub = lambda U, V: tuple(u - v for u, v in zip(U, V))        # linear combinations of shares are local
+    add = lambda U, V: tuple(u + v for u, v in zip(U, V))
+    const = lambda c, like: tuple(torch.full_like(like, int(round(c * 2 ** t))) if k == 0 else torch.zeros_like(like)
+                                  for k in range(3))             # a public constant lives in share 0
+    cols = [tuple(s[:, j].contiguous() for s in X) for j in range(d)]
+    while len(cols) > 1:
+        nxt = [add(b, gpu_relu(cg, sub(a, b), keys, fresh())) for a, b in zip(cols[0::2], cols[1::2])]   # max = b + relu(a - b)
+        if len(cols) % 2:
+            nxt.append(cols[-1])
+        cols = nxt
+    mx = cols[0]
+    Y = tuple((x - m[:, None]).contiguous() for x, m in zip(X, mx))
+    U = add(const(1.0, Y[0]), gpu_trunc(cg, Y, keys, fresh(), log_m))        # 1 + y / m
+    for _ in range(log_m):
+        U = gpu_mul_trunc(cg, U, U, keys, fresh(), t)
+    S = tuple(u.sum(dim=1, keepdim=True).contiguous() for u in U)            # sums of shares are local
+    Z = const(1.0 / d, S[0])
+    for _ in range(newton):
+        Z2 = gpu_mul_trunc(cg, Z, Z, keys, fresh(), t)
+        SZ2 = gpu_mul_trunc(cg, S, Z2, keys, fresh(), t)
+        Z = sub(add(Z, Z), SZ2)
+    Zb = tuple(z.expand(-1, d).contiguous() for z in Z)
+    return gpu_mul_trunc(cg, U, Zb, keys, fresh(), t), mx
