@@ -184,16 +184,22 @@ CG_API cg_status cg_share_conv2d_ws(const uint64_t *x_i, const uint64_t *x_ip1,
  *
  * All device pointers, 8-byte aligned, the output fully overwritten and disjoint
  * from the inputs (CG_ERR_ALIAS).  Nothing is written to memory besides the output:
- * the filter is read in place with its taps reversed, the gradient of a strided
- * layer is read as if zeros stood between its pixels, and the patch entries of the
- * weight gradient are gathered from the input.  Shape errors as cg_share_conv2d.
+ * the filter is read in place with its taps reversed, and the patch entries of the
+ * weight gradient are gathered from the input.  The input gradient of a strided
+ * layer runs one residue class (h mod stride_h, w mod stride_w) of the input
+ * pixels at a time, each a unit-stride product with the filter taps that reach the
+ * class (Cout a multiple of 32, 16-byte-aligned pointers, at most 64 classes; dx is
+ * cleared first, pixels no tap reaches stay zero); other strided layers read the
+ * gradient as if zeros stood between its pixels.  Shape errors as cg_share_conv2d.
  * CG_ERR_UNSUPPORTED: dgrad if kh*kw*Cout exceeds 2^20, B*H*W exceeds 2^31-1, the
  * gradient images one 256-row block can touch exceed 2^31-1 bytes, or (strided
  * layers, Cout not a multiple of 32, or 16-byte-unaligned pointers) the filter
  * exceeds 2^31-1 bytes; wgrad if B*Ho*Wo exceeds 2^30, Cout exceeds 2^22,
  * kh*kw*Cin exceeds 2^31-1 or the (31/(Ho*Wo) + 2) input images a run of 32
  * output pixels can touch exceed 2^31-1 bytes; either if a stride, padding or
- * window side exceeds 32767.
+ * window side exceeds 32767.  (A strided dgrad that runs class by class is held to
+ * these limits per class, with the class's own tap and pixel counts, and falls back
+ * to the other route when a class exceeds them.)
  */
 CG_API cg_status cg_share_conv2d_dgrad(const uint64_t *g_i, const uint64_t *g_ip1,
                                 const uint64_t *w_i, const uint64_t *w_ip1,

@@ -785,12 +785,90 @@ cg_status plan_conv2d_dgrad(const uint64_t* g_i, const uint64_t* g_ip1, const ui
     const bool c32 = !strided && all_aligned16(in, 4) && d->Cout % 32 == 0 && taps * d->Cin <= ((int64_t)1 << 22);
     if (c32) {
         pl.amode = cg::A_CONV_C32; pl.bmode = cg::B_FLIP_C32;
+        // the window covers every tap of the filter and the rows are the pixels in order
+        p.flt_kh = p.kh; p.flt_kw = p.kw; p.flt_r0 = 0; p.flt_s0 = 0; p.flt_sh = 1; p.flt_sw = 1;
+        p.out_H = (int)d->H; p.out_W = (int)d->W; p.out_h0 = 0; p.out_w0 = 0; p.out_sh = 1; p.out_sw = 1;
+        p.div_howo = cg::make_fast_div((uint32_t)hw);
+        p.div_wo = cg::make_fast_div((uint32_t)d->W);
     } else {
         // every word of the filter is addressed from one view
         if (cd.w_el * 8 > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;
         pl.amode = strided ? cg::A_CONV_DIL : cg::A_CONV_GEN;
         pl.bmode = cg::B_FLIP_GEN;
     }
+    pl.x_bytes = (u64)cd.z_el * 8; pl.w_bytes = (u64)cd.w_el * 8; pl.z_bytes = (u64)cd.x_el * 8;
+    *out = pl;
+    return CG_OK;
+}
+
+// Input gradient of a strided convolution, one phase.  Input pixel h = a + stride*i meets output
+// row ho through filter tap r only if h + pad - r = stride*ho, i.e. r = r0 + stride*t with
+// r0 = (a + pad) mod stride, and then ho = i + q0 - t with q0 = (a + pad) div stride.  The pixels of
+// one residue class (a, b) of (h, w) therefore see a unit-stride correlation of the gradient with
+// the sub-grid (r0 + stride_h*t, s0 + stride_w*u) of the filter's taps, so the phases together do
+// exactly the products of the forward pass, none of them with an inserted zero.
+struct Phase {
+    int64_t n;   // pixels of the class along this axis
+    int64_t t;   // taps of the class (0: these pixels receive no gradient)
+    int64_t r0;  // first tap
+    int64_t pad; // padding of the unit-stride gather, t - 1 - q0 (may be negative)
+};
+
+Phase make_phase(int64_t a, int64_t size, int64_t k, int64_t stride, int64_t pad) {
+    Phase f;
+    f.n = a < size ? (size - a + stride - 1) / stride : 0;
+    f.r0 = (a + pad) % stride;
+    f.t = f.r0 < k ? (k - f.r0 + stride - 1) / stride : 0;
+    f.pad = f.t - 1 - (a + pad) / stride;
+    return f;
+}
+
+const int64_t MAX_PHASES = 64;
+
+// True when the strided input gradient can run phase by phase on the 32-channel gather.
+bool dgrad_phased_ok(const cg_conv2d_desc* d, const void* const* in) {
+    return (d->stride_h != 1 || d->stride_w != 1) && d->stride_h * d->stride_w <= MAX_PHASES &&
+           all_aligned16(in, 4) && d->Cout % 32 == 0;
+}
+
+// Plan of phase (a, b); *empty is set when the class has no pixels or no taps.
+cg_status plan_conv2d_dgrad_phase(const uint64_t* g_i, const uint64_t* g_ip1, const uint64_t* w_i,
+                                  const uint64_t* w_ip1, uint64_t* dx_i, const cg_conv2d_desc* d,
+                                  const ConvDims& cd, int64_t a, int64_t b, Plan* out, bool* empty) {
+    const Phase fh = make_phase(a, d->H, d->kh, d->stride_h, d->pad_h);
+    const Phase fw = make_phase(b, d->W, d->kw, d->stride_w, d->pad_w);
+    *empty = fh.n == 0 || fw.n == 0 || fh.t == 0 || fw.t == 0;
+    if (*empty) return CG_OK;
+    const int64_t hw = fh.n * fw.n;
+    const int64_t Mg = d->B * hw, Kg = fh.t * fw.t * d->Cout;
+    const int64_t g_img = cd.howo * d->Cout;
+    if (Mg > MAX_DIM || d->Cin > MAX_DIM || Kg > MAX_ROW_WORDS || g_img > ((int64_t)1 << 27) ||
+        fh.pad > 32767 || fw.pad > 32767 || fh.pad < -32767 || fw.pad < -32767 || d->kh > 32767 || d->kw > 32767 ||
+        d->kh * d->kw * d->Cin > ((int64_t)1 << 22) || d->B * d->H * d->W > MAX_DIM)
+        return CG_ERR_UNSUPPORTED;
+    const int64_t span_imgs = (cg::MAX_TILE_ROWS - 1) / hw + 2;
+    if ((span_imgs < d->B ? span_imgs : d->B) * g_img * 8 > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;
+
+    Plan pl = {};
+    cg::GemmParams& p = pl.p;
+    p.x_a = g_i; p.x_b = g_ip1; p.w_a = w_i; p.w_b = w_ip1; p.z = dx_i;
+    p.M = (int)Mg; p.N = (int)d->Cin; p.K = (int)Kg;
+    p.x_elems = (u64)cd.z_el;
+    p.w_elems = (u64)cd.w_el;
+    p.img_elems = (u64)g_img;
+    p.H = (int)cd.Ho; p.W = (int)cd.Wo; p.Cin = (int)d->Cout; p.Ho = (int)fh.n; p.Wo = (int)fw.n;
+    p.kh = (int)fh.t; p.kw = (int)fw.t; p.sh = 1; p.sw = 1;
+    p.ph = (int)fh.pad; p.pw = (int)fw.pad;
+    p.div_cin = cg::make_fast_div((uint32_t)d->Cout);
+    p.div_kw = cg::make_fast_div((uint32_t)fw.t);
+    p.flt_kh = (int)d->kh; p.flt_kw = (int)d->kw; p.flt_r0 = (int)fh.r0; p.flt_s0 = (int)fw.r0;
+    p.flt_sh = (int)d->stride_h; p.flt_sw = (int)d->stride_w;
+    p.out_H = (int)d->H; p.out_W = (int)d->W; p.out_h0 = (int)a; p.out_w0 = (int)b;
+    p.out_sh = (int)d->stride_h; p.out_sw = (int)d->stride_w;
+    p.div_howo = cg::make_fast_div((uint32_t)hw);
+    p.div_wo = cg::make_fast_div((uint32_t)fw.n);
+    p.z_prezeroed = 1;
+    pl.amode = cg::A_CONV_C32; pl.bmode = cg::B_FLIP_C32;
     pl.x_bytes = (u64)cd.z_el * 8; pl.w_bytes = (u64)cd.w_el * 8; pl.z_bytes = (u64)cd.x_el * 8;
     *out = pl;
     return CG_OK;
@@ -937,8 +1015,30 @@ cg_status cg_share_conv2d_ws(const uint64_t* x_i, const uint64_t* x_ip1, const u
 cg_status cg_share_conv2d_dgrad(const uint64_t* g_i, const uint64_t* g_ip1, const uint64_t* w_i,
                                 const uint64_t* w_ip1, uint64_t* dx_i, const cg_conv2d_desc* d, void* stream) {
     Plan pl;
-    if (cg_status st = plan_conv2d_dgrad(g_i, g_ip1, w_i, w_ip1, dx_i, d, &pl)) return st;
-    return run_direct(pl, stream);
+    const cg_status generic = plan_conv2d_dgrad(g_i, g_ip1, w_i, w_ip1, dx_i, d, &pl);
+    if (generic != CG_OK && generic != CG_ERR_UNSUPPORTED) return generic;  // arguments are wrong either way
+    auto fallback = [&]() { return generic == CG_OK ? run_direct(pl, stream) : generic; };
+    const void* in[4] = {g_i, g_ip1, w_i, w_ip1};
+    if (!dgrad_phased_ok(d, in)) return fallback();
+    // strided, 32-channel gather: one unit-stride product per residue class of the input pixels.  All
+    // phases are planned before the first launch, so that an unsupported one leaves dx untouched and
+    // the whole call falls back to the zero-interleaved gather.
+    ConvDims cd;
+    if (cg_status st = conv_dims(d, &cd)) return st;
+    Plan phase[MAX_PHASES];
+    bool empty[MAX_PHASES];
+    int n = 0;
+    for (int64_t a = 0; a < d->stride_h; ++a)
+        for (int64_t b = 0; b < d->stride_w; ++b, ++n)
+            if (plan_conv2d_dgrad_phase(g_i, g_ip1, w_i, w_ip1, dx_i, d, cd, a, b, &phase[n], &empty[n]) != CG_OK)
+                return fallback();
+    // pixels of classes without taps keep the zeros; launches that split K add into them
+    if (cg::launch_zero_words(dx_i, (size_t)cd.x_el, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return CG_ERR_DEVICE;
+    for (int i = 0; i < n; ++i)
+        if (!empty[i])
+            if (cg_status st = run_direct(phase[i], stream)) return st;
+    return CG_OK;
 }
 
 cg_status cg_share_conv2d_wgrad(const uint64_t* g_i, const uint64_t* g_ip1, const uint64_t* x_i,

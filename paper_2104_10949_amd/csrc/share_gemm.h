@@ -40,7 +40,9 @@ enum BMode {
     B_TRANS = 2,   // stored transposed, [K, N] with N contiguous, 8-byte loads
     // Input gradient of a convolution: the right operand is the filter [Cout, kh, kw, N] read as
     // B[n, (r', s', co)] = W[co, kh-1-r', kw-1-s', n].
-    B_FLIP_C32 = 3,  // ... Cout % 32 == 0: a slice of K has one tap, rebased per slice
+    B_FLIP_C32 = 3,  // ... Cout % 32 == 0: a slice of K has one tap, rebased per slice; the window may
+                     // cover a regular sub-grid of the filter's taps and the output rows a regular
+                     // sub-grid of the pixels (see flt_* and out_* below)
     B_FLIP_GEN = 4,  // ... any Cout: every word finds its own tap
     // Weight gradient: the right operand is the layer input, B[(r, s, c), pixel] = patch entry
     B_PATCH_T = 5
@@ -59,7 +61,14 @@ struct GemmParams {
     FastDiv div_cin, div_kw;
     int dil_h, dil_w;           // A_CONV_DIL: spacing of the stored pixels inside the gathered image
     FastDiv div_dil_h, div_dil_w;
-    FastDiv div_howo, div_wo;   // B_PATCH_T: decomposition of a pixel index into (b, ho, wo)
+    FastDiv div_howo, div_wo;   // B_PATCH_T, B_FLIP_C32: decomposition of a pixel index into (b, ho, wo)
+    // B_FLIP_C32: the filter's own tap grid is flt_kh x flt_kw; tap (r', s') of the gathered kh x kw window
+    // reads filter tap (flt_r0 + flt_sh*(kh-1-r'), flt_s0 + flt_sw*(kw-1-s')).
+    int flt_kh, flt_kw, flt_r0, flt_s0, flt_sh, flt_sw;
+    // B_FLIP_C32: output row (b, i, j) of the [B, Ho, Wo] grid is pixel (out_h0 + out_sh*i, out_w0 + out_sw*j)
+    // of the stored tensor z [B, out_H, out_W, N].
+    int out_H, out_W, out_h0, out_w0, out_sh, out_sw;
+    int z_prezeroed;            // the caller has cleared z: launches that add into z do not clear it again
     // digit-plane route: planes of x_i, x_{i+1}, y_i + y_{i+1}, y_i (see to_planes_kernel)
     const char *xp_a, *xp_b, *wp_sum, *wp_a;
     uint64_t xp_bytes;          // bytes of one left-operand plane tensor
@@ -73,6 +82,9 @@ struct GemmParams {
 static const int MAX_TILE_ROWS = 256;
 
 hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream);
+
+// z[0..n) = 0 with a fill kernel (capturable).
+hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream);
 
 // Digit-plane route.  launch_to_planes converts a row-major [R, K] operand (K even,
 // 16-byte aligned), optionally summed with `add` first, into planes of

@@ -532,7 +532,8 @@ __device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int B
 // (split-K: integer sums mod 2^64 are exact in any order).  The lane index passes
 // through an empty asm so that none of the output addresses or bounds tests can be
 // computed ahead of the K loop, where they would sit in registers the loop needs.
-template <int SM, int SN>
+// REMAP: the rows are scattered over the pixels of a larger tensor (see GemmParams::out_*).
+template <int SM, int SN, bool REMAP = false>
 __device__ __forceinline__ void fold_tile(const GemmParams& p, v16i (&acc)[SM][SN][8], int row0, int col0,
                                           int lane, bool accumulate) {
     int lane_f = lane;
@@ -554,7 +555,15 @@ __device__ __forceinline__ void fold_tile(const GemmParams& p, v16i (&acc)[SM][S
                                ((u32)acc[sm][sn][6][i] << 16) + ((u32)acc[sm][sn][7][i] << 24);
                 v += (u64)hi << 32;
                 if (row < p.M && col < p.N) {
-                    u64* dst = p.z + (u64)row * (u64)p.N + (u64)col;
+                    u64 zrow = (u64)row;
+                    if constexpr (REMAP) {
+                        const u32 b = fast_div((u32)row, p.div_howo);
+                        const u32 rem = (u32)row - b * (u32)(p.Ho * p.Wo);
+                        const u32 i_ = fast_div(rem, p.div_wo), j_ = rem - i_ * (u32)p.Wo;
+                        zrow = ((u64)b * (u64)p.out_H + (u64)(p.out_h0 + p.out_sh * (int)i_)) * (u64)p.out_W +
+                               (u64)(p.out_w0 + p.out_sw * (int)j_);
+                    }
+                    u64* dst = p.z + zrow * (u64)p.N + (u64)col;
                     if (p.ksplit > 1) {
                         atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
                     } else {
@@ -646,9 +655,9 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             const u64 base = b_base_elems + (u64)ks * 32u * (u64)p.N;
             return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
         } else if constexpr (BMODE == B_FLIP_C32) {
-            const int taps = p.kh * p.kw;
             if (tap.c0 >= p.Cin) return make_rsrc(ptr, 0);  // past the end of K
-            const u64 base = b_base_elems + ((u64)tap.c0 * (u64)taps + (u64)(taps - 1 - tap.tap)) * (u64)p.N;
+            const int ftap = (p.flt_r0 + p.flt_sh * (p.kh - 1 - tap.r)) * p.flt_kw + p.flt_s0 + p.flt_sw * (p.kw - 1 - tap.s);
+            const u64 base = b_base_elems + ((u64)tap.c0 * (u64)(p.flt_kh * p.flt_kw) + (u64)ftap) * (u64)p.N;
             return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
         } else if constexpr (BMODE == B_PATCH_T) {
             const u64 base = (u64)fast_div(32u * (u32)ks, p.div_howo) * p.img_elems;
@@ -689,7 +698,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         const int jh = (u >> 2) / T::BN;
         // pitch between consecutive k of one row: N for a transposed matrix, one output
         // channel of the filter (kh*kw*N words) for the flipped filter
-        const u32 pitch = BMODE == B_FLIP_C32 ? (u32)(p.kh * p.kw) * (u32)p.N : (B_TR ? (u32)p.N : (u32)p.K);
+        const u32 pitch = BMODE == B_FLIP_C32 ? (u32)(p.flt_kh * p.flt_kw) * (u32)p.N : (B_TR ? (u32)p.N : (u32)p.K);
         bg[i].init(p, n0, row, rows_n, pitch, q, jh);
         b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
     }
@@ -836,7 +845,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     };
 
     auto fold = [&](bool accumulate) {
-        fold_tile<SM, SN>(p, acc, m0 + wm * SM * 32, n0 + wn * SN * 32, lane, accumulate);
+        fold_tile<SM, SN, BMODE == B_FLIP_C32>(p, acc, m0 + wm * SM * 32, n0 + wn * SN * 32, lane, accumulate);
     };
 
     // Prologue: the even half-step of the first slice goes to LDS.  Loads past the end of
@@ -1188,11 +1197,19 @@ static int choose_group_m(const GemmParams& p, int64_t tiles_m, int64_t tiles_n,
     return best;
 }
 
-static void launch_zero_fill(const GemmParams& p, hipStream_t stream) {
-    const size_t n = (size_t)p.M * (size_t)p.N;
+hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
     size_t blocks = (n + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p.z, n);
+    hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, z, n);
+    return hipGetLastError();
+}
+
+// z = 0 ahead of a launch whose blocks add into it (unless the caller has done so: a
+// scattered output is cleared by the caller, who knows its extent)
+static void launch_zero_fill(const GemmParams& p, hipStream_t stream) {
+    if (p.z_prezeroed) return;
+    launch_zero_words(p.z, (size_t)p.M * (size_t)p.N, stream);
 }
 
 hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,

@@ -58,6 +58,16 @@ CASES = [
     (2, 10, 11, 40, 64, 9, 8, (1, 1), (4, 3)),
     (8, 14, 14, 256, 256, 3, 3, (1, 1), (1, 1)),       # tile counts that take the streamed distribution
     (3, 21, 21, 96, 224, 3, 3, (1, 1), (1, 1)),
+    # strided with Cout % 32 == 0: one unit-stride product per residue class of the input pixels
+    (2, 9, 10, 24, 64, 3, 2, (2, 3), (1, 0)),          # different strides and window sides
+    (1, 7, 7, 8, 32, 2, 2, (3, 3), (0, 0)),            # classes that no tap reaches stay zero
+    (2, 5, 5, 8, 32, 1, 1, (2, 2), (2, 2)),            # padding beyond the window: negative gather padding
+    (3, 2, 9, 8, 32, 3, 3, (3, 2), (1, 1)),            # fewer rows than the stride: a class without pixels
+    (2, 16, 16, 40, 64, 5, 5, (4, 4), (2, 2)),
+    (2, 56, 56, 128, 128, 3, 3, (2, 2), (1, 1)),       # ResNet-shaped down-sampling layers
+    (2, 56, 56, 256, 512, 1, 1, (2, 2), (0, 0)),
+    (16, 14, 14, 256, 256, 3, 3, (2, 2), (1, 1)),      # few pixels per class: launches that split K
+    (1, 20, 20, 4, 32, 3, 3, (9, 9), (1, 1)),          # more classes than are run one by one: zero-interleaved gather
 ]
 
 
