@@ -104,24 +104,39 @@ def measure_extras(torch, cg, wl, config_layers):
         out["fig1_conv_shapes"].append(row(f"{name}, input {xs[0]}x{xs[1]}x{xs[2]}x{xs[3]}",
                                            zs[0] * zs[1] * zs[2] * ws[0] * ws[1] * ws[2] * ws[3], ms))
         del ops, z
-    # forward / input-gradient / weight-gradient products of the configuration's convolution layers
-    tot = {"forward": 0.0, "dgrad": 0.0, "wgrad": 0.0}
-    mnk = 0
-    for L in config_layers:
-        if L.kind != "conv":
-            continue
-        xs, ws, zs = L.x_shape, L.w_shape, L.z_shape
-        g, w, x = [rnd(zs, 1), rnd(zs, 2)], [rnd(ws, 3), rnd(ws, 4)], [rnd(xs, 5), rnd(xs, 6)]
-        dx, dw = torch.empty(xs, dtype=torch.int64, device="cuda"), torch.empty(ws, dtype=torch.int64, device="cuda")
-        z = torch.empty(zs, dtype=torch.int64, device="cuda")
-        st, pd = (L.stride, L.stride), (L.pad, L.pad)
-        tot["forward"] += timed(lambda: cg.cg_share_conv2d(*x, *w, stride=st, pad=pd, z_i=z)) * L.repeat
-        tot["dgrad"] += timed(lambda: cg.cg_share_conv2d_dgrad(*g, *w, xs, stride=st, pad=pd, dx_i=dx)) * L.repeat
-        tot["wgrad"] += timed(lambda: cg.cg_share_conv2d_wgrad(*g, *x, ws, stride=st, pad=pd, dw_i=dw)) * L.repeat
-        mnk += L.mnk * L.repeat
-        del g, w, x, dx, dw, z
-    for k, ms in tot.items():
-        out["backward_config4"].append(row(f"{k}, all convolution layers", mnk, ms))
+    # forward / input-gradient / weight-gradient products of a configuration's convolution layers
+    def backward_rows(layers, key):
+        tot = {"forward": 0.0, "dgrad": 0.0, "wgrad": 0.0}
+        strided = {"forward": 0.0, "dgrad": 0.0}
+        mnk = mnk_strided = 0
+        for li, L in enumerate(layers):
+            if L.kind != "conv":
+                continue
+            xs, ws, zs = L.x_shape, L.w_shape, L.z_shape
+            g, w, x = [rnd(zs, 1), rnd(zs, 2)], [rnd(ws, 3), rnd(ws, 4)], [rnd(xs, 5), rnd(xs, 6)]
+            dx, dw = torch.empty(xs, dtype=torch.int64, device="cuda"), torch.empty(ws, dtype=torch.int64, device="cuda")
+            z = torch.empty(zs, dtype=torch.int64, device="cuda")
+            st, pd = (L.stride, L.stride), (L.pad, L.pad)
+            fwd = timed(lambda: cg.cg_share_conv2d(*x, *w, stride=st, pad=pd, z_i=z)) * L.repeat
+            dg = timed(lambda: cg.cg_share_conv2d_dgrad(*g, *w, xs, stride=st, pad=pd, dx_i=dx)) * L.repeat
+            tot["forward"] += fwd
+            tot["dgrad"] += dg
+            tot["wgrad"] += timed(lambda: cg.cg_share_conv2d_wgrad(*g, *x, ws, stride=st, pad=pd, dw_i=dw)) * L.repeat
+            mnk += L.mnk * L.repeat
+            if L.stride > 1 and li > 0:      # the first layer's input gradient is never needed
+                strided["forward"] += fwd
+                strided["dgrad"] += dg
+                mnk_strided += L.mnk * L.repeat
+            del g, w, x, dx, dw, z
+        for k, ms in tot.items():
+            out[key].append(row(f"{k}, all convolution layers", mnk, ms))
+        if mnk_strided:
+            for k, ms in strided.items():
+                out[key].append(row(f"{k}, strided layers after the first", mnk_strided, ms))
+
+    backward_rows(config_layers, "backward_config4")
+    out["backward_config5"] = []
+    backward_rows(wl.config_layers(5), "backward_config5")
     # HBM- and ALU-bound kernels next to the products; n words per stream, beyond the 256 MB last-level cache
     n = 1 << 26
     a, b, c, d = (rnd((n,), s) for s in (1, 2, 3, 4))
