@@ -137,6 +137,24 @@ def measure_extras(torch, cg, wl, config_layers):
     backward_rows(config_layers, "backward_config4")
     out["backward_config5"] = []
     backward_rows(wl.config_layers(5), "backward_config5")
+    # The multiplication protocol's message z_i + alpha_i for one large convolution (32x32x128 -> 128, batch 32):
+    # product then reshare pass, against the product folded into an output that already holds alpha_i (which
+    # depends on no data and can be produced while the party waits for the previous round's messages).
+    xs, ws = (32, 32, 32, 128), (128, 3, 3, 128)
+    x, w = [rnd(xs, 1), rnd(xs, 2)], [rnd(ws, 3), rnd(ws, 4)]
+    z = torch.empty(cg.conv_out_shape(xs, ws, (1, 1), (1, 1)), dtype=torch.int64, device="cuda")
+    ka, kb = bytes(range(16)), bytes(range(16, 32))
+    nz = z.numel()
+    out["reshare_in_fold"] = [
+        {"name": "cg_share_conv2d", "ms": round(timed(lambda: cg.cg_share_conv2d(*x, *w, pad=(1, 1), z_i=z)), 4)},
+        {"name": "cg_share_conv2d + cg_reshare", "ms": round(timed(lambda: cg.cg_reshare(
+            cg.cg_share_conv2d(*x, *w, pad=(1, 1), z_i=z), ka, kb, 1, 0, out=z)), 4)},
+        {"name": "cg_zero_share + cg_share_conv2d_acc", "ms": round(timed(lambda: cg.cg_share_conv2d_acc(
+            *x, *w, cg.cg_zero_share(ka, kb, 1, 0, nz, out=z.view(-1)).view(z.shape), pad=(1, 1))), 4)},
+        {"name": "cg_share_conv2d_acc alone (alpha_i produced earlier)", "ms": round(timed(
+            lambda: cg.cg_share_conv2d_acc(*x, *w, z, pad=(1, 1))), 4)},
+    ]
+    del x, w, z
     # HBM- and ALU-bound kernels next to the products; n words per stream, beyond the 256 MB last-level cache
     n = 1 << 26
     a, b, c, d = (rnd((n,), s) for s in (1, 2, 3, 4))

@@ -163,6 +163,24 @@ CG_API cg_status cg_share_conv2d_ws(const uint64_t *x_i, const uint64_t *x_ip1,
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The products above added to what z_i holds on entry: z_i <- z_i + (local product)
+ * mod 2^64, everything else as cg_share_matmul / cg_share_conv2d (same argument
+ * meaning, validation and errors; z_i is read as well as written, and still may not
+ * overlap an input).  With z_i holding the party's zero share alpha_i (cg_zero_share:
+ * it depends on no data, so it can be produced before the operands exist) the result
+ * is z_i + alpha_i, the message of the multiplication protocol (Sec. III-B), formed
+ * in the product's own fold with no further pass over z.  Also sums the products of
+ * several operand pairs into one output.
+ */
+CG_API cg_status cg_share_matmul_acc(const uint64_t *x_i, const uint64_t *x_ip1,
+                              const uint64_t *y_i, const uint64_t *y_ip1,
+                              uint64_t *z_i, int64_t M, int64_t N, int64_t K, void *stream);
+
+CG_API cg_status cg_share_conv2d_acc(const uint64_t *x_i, const uint64_t *x_ip1,
+                              const uint64_t *w_i, const uint64_t *w_ip1,
+                              uint64_t *z_i, const cg_conv2d_desc *desc, void *stream);
+
+/*
  * Backward products of a convolution layer on shares (Sec. III-C: the gradients of
  * a linear / convolution layer are linear functions of the incoming gradient and
  * are evaluated with the protocols of Sec. III-B, i.e. with the same three-term

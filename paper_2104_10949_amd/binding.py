@@ -27,7 +27,9 @@ EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d
            "cg_trunc1_local", "cg_prf_words", "cg_bshare_xor", "cg_bshare_and", "cg_bshare_prefix_stage",
            "cg_bzero_share", "cg_breshare", "cg_share_bias_add", "cg_share_col_sum",
            "cg_bit_transpose64", "cg_bshare_carry_level", "cg_bits_unpack", "cg_bshare_csa", "cg_bshare_half_adder",
+           "cg_share_matmul_acc", "cg_share_conv2d_acc",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
+SIZE_EXPORTS = 2      # the last entries return size_t, the first two a string and an int, the rest cg_status
 
 
 class ConvDesc(ctypes.Structure):
@@ -67,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.cg_version.restype = ctypes.c_int
         L.cg_share_matmul.argtypes = [vp] * 5 + [i64] * 3 + [vp]
         L.cg_share_conv2d.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
+        L.cg_share_matmul_acc.argtypes = L.cg_share_matmul.argtypes
+        L.cg_share_conv2d_acc.argtypes = L.cg_share_conv2d.argtypes
         L.cg_share_add.argtypes = [vp] * 6 + [sz, vp]
         L.cg_share_mul_public.argtypes = [vp, vp, u64, vp, vp, sz, vp]
         L.cg_share_add_public.argtypes = [vp, vp, u64, ctypes.c_int, vp, vp, sz, vp]
@@ -97,9 +101,9 @@ def lib() -> ctypes.CDLL:
         L.cg_prf_words.argtypes = [key, u64, u64, vp, sz, vp]
         L.cg_share_conv2d_dgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
         L.cg_share_conv2d_wgrad.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
-        for name in EXPORTS[2:31]:
+        for name in EXPORTS[2:-SIZE_EXPORTS]:
             getattr(L, name).restype = ctypes.c_int
-        for name in EXPORTS[31:]:
+        for name in EXPORTS[-SIZE_EXPORTS:]:
             getattr(L, name).restype = sz
         _lib = L
     return _lib
@@ -169,6 +173,33 @@ def cg_share_matmul_t(x_i, x_ip1, y_i, y_ip1, trans_x: bool, trans_y: bool, z_i=
     _check(lib().cg_share_matmul_t(_ptr(x_i), _ptr(x_ip1), _ptr(y_i), _ptr(y_ip1), _ptr(z_i),
                                    M, N, K, int(bool(trans_x)), int(bool(trans_y)), _stream(stream)),
            "cg_share_matmul_t")
+    return z_i
+
+
+def cg_share_matmul_acc(x_i, x_ip1, y_i, y_ip1, z_i, stream=None) -> torch.Tensor:
+    """z_i += party-local product of x [M,K] and y [N,K]; z_i [M,N] holds a value on entry (e.g. the zero share)."""
+    M, K = x_i.shape
+    N = y_i.shape[0]
+    if x_ip1.shape != x_i.shape or y_ip1.shape != y_i.shape or y_i.shape[1] != K:
+        raise ValueError("operand shapes do not match")
+    if tuple(z_i.shape) != (M, N):
+        raise ValueError("output shape does not match")
+    _check(lib().cg_share_matmul_acc(_ptr(x_i), _ptr(x_ip1), _ptr(y_i), _ptr(y_ip1), _ptr(z_i), M, N, K,
+                                     _stream(stream)), "cg_share_matmul_acc")
+    return z_i
+
+
+def cg_share_conv2d_acc(x_i, x_ip1, w_i, w_ip1, z_i, stride=(1, 1), pad=(0, 0), stream=None) -> torch.Tensor:
+    """z_i += party-local convolution on shares; z_i NHWC holds a value on entry (e.g. the zero share)."""
+    B, H, W, Cin = x_i.shape
+    Cout, kh, kw, Cin2 = w_i.shape
+    if x_ip1.shape != x_i.shape or w_ip1.shape != w_i.shape or Cin2 != Cin:
+        raise ValueError("operand shapes do not match")
+    d = ConvDesc(B, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    if tuple(z_i.shape) != conv_out_shape(x_i.shape, w_i.shape, stride, pad):
+        raise ValueError("output shape does not match")
+    _check(lib().cg_share_conv2d_acc(_ptr(x_i), _ptr(x_ip1), _ptr(w_i), _ptr(w_ip1), _ptr(z_i),
+                                     ctypes.byref(d), _stream(stream)), "cg_share_conv2d_acc")
     return z_i
 
 

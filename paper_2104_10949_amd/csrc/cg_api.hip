@@ -966,6 +966,23 @@ cg_status cg_share_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint
     return run_direct(pl, stream);
 }
 
+cg_status cg_share_matmul_acc(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
+                              const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
+                              void* stream) {
+    Plan pl;
+    if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl)) return st;
+    pl.p.z_add = 1;
+    return run_direct(pl, stream);
+}
+
+cg_status cg_share_conv2d_acc(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i,
+                              const uint64_t* w_ip1, uint64_t* z_i, const cg_conv2d_desc* d, void* stream) {
+    Plan pl;
+    if (cg_status st = plan_conv2d(x_i, x_ip1, w_i, w_ip1, z_i, d, true, &pl)) return st;
+    pl.p.z_add = 1;
+    return run_direct(pl, stream);
+}
+
 cg_status cg_share_matmul_t(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
                             const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
                             int trans_x, int trans_y, void* stream) {

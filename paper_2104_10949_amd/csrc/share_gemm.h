@@ -69,6 +69,7 @@ struct GemmParams {
     // of the stored tensor z [B, out_H, out_W, N].
     int out_H, out_W, out_h0, out_w0, out_sh, out_sw;
     int z_prezeroed;            // the caller has cleared z: launches that add into z do not clear it again
+    int z_add;                  // z holds a value on entry and the product is added to it
     // digit-plane route: planes of x_i, x_{i+1}, y_i + y_{i+1}, y_i (see to_planes_kernel)
     const char *xp_a, *xp_b, *wp_sum, *wp_a;
     uint64_t xp_bytes;          // bytes of one left-operand plane tensor

@@ -873,7 +873,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             });
             __syncthreads();
         }
-        fold(ks0 > k_begin);
+        fold(ks0 > k_begin || p.z_add != 0);
     }
     } while (STREAM && u < u_end);  // next tile of the range
 }
@@ -1206,10 +1206,11 @@ hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream) {
 }
 
 // z = 0 ahead of a launch whose blocks add into it (unless the caller has done so: a
-// scattered output is cleared by the caller, who knows its extent)
+// scattered output is cleared by the caller, who knows its extent; or z holds a value
+// the product is to be added to)
 static void launch_zero_fill(const GemmParams& p, hipStream_t stream) {
-    if (p.z_prezeroed) return;
-    launch_zero_words(p.z, (size_t)p.M * (size_t)p.N, stream);
+    if (p.z_prezeroed || p.z_add) return;
+    (void)launch_zero_words(p.z, (size_t)p.M * (size_t)p.N, stream);  // a failed launch shows in the product's own launch status
 }
 
 hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,

@@ -37,6 +37,8 @@ def test_library_exports_every_declared_symbol(L):
     for name in header_symbols():
         assert hasattr(L, name), name
     assert sorted(binding.EXPORTS) == header_symbols()
+    for name in binding.EXPORTS:        # every entry point is called with declared argument types
+        assert getattr(L, name).argtypes is not None, name
     assert binding.version() >= 100
     assert binding.status_string(0) == "CG_OK"
     for s in range(1, 8):
@@ -62,6 +64,25 @@ def test_matmul_validation_happens_before_any_device_work(L):
     big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
     assert f(*big, 4, 4, (1 << 20) + 1, None) == b.CG_ERR_UNSUPPORTED
     assert f(*big, 1 << 31, 1, 1, None) == b.CG_ERR_UNSUPPORTED
+
+
+def test_accumulating_entry_points_validate_like_the_plain_ones(L):
+    from paper_2104_10949_amd import binding as b
+    ok = [P, 2 * P, 3 * P, 4 * P, 5 * P]
+    f = L.cg_share_matmul_acc
+    assert f(0, *ok[1:], 4, 4, 4, None) == b.CG_ERR_NULL
+    assert f(*ok[:4], 0, 4, 4, 4, None) == b.CG_ERR_NULL
+    assert f(*ok, 4, 0, 4, None) == b.CG_ERR_SHAPE
+    assert f(*ok[:4], 5 * P + 4, 4, 4, 4, None) == b.CG_ERR_ALIGN
+    assert f(*ok[:4], P + 8, 4, 4, 4, None) == b.CG_ERR_ALIAS              # z inside x_i
+    big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
+    assert f(*big, 4, 4, (1 << 20) + 1, None) == b.CG_ERR_UNSUPPORTED
+    g = L.cg_share_conv2d_acc
+    d = b.ConvDesc(1, 8, 8, 3, 4, 3, 3, 1, 1, 1, 1)
+    assert g(*big, None, None) == b.CG_ERR_NULL
+    assert g(*big[:4], 0, ctypes.byref(d), None) == b.CG_ERR_NULL
+    assert g(*big[:4], big[1] + 16, ctypes.byref(d), None) == b.CG_ERR_ALIAS
+    assert g(*big, ctypes.byref(b.ConvDesc(1, 8, 8, 3, 4, 11, 3, 1, 1, 1, 1)), None) == b.CG_ERR_SHAPE
 
 
 def test_workspace_entry_points_validate_like_the_plain_ones(L):

@@ -204,3 +204,50 @@ def test_fc_stack_evaluated_entirely_on_shares(cg, ro, wl):
     clear = top2[:, 1] - top2[:, 0] > 1e-3
     assert clear.sum() > 100
     assert np.array_equal(np.argmax(logits, axis=1)[clear], np.argmax(pre_real, axis=1)[clear])
+
+
+ACC_MATMUL = [
+    (100, 70, 90),          # one pass, plain read-add-write
+    (128, 64, 16384),       # K split over blocks: atomic adds into the value already there
+    (130, 70, 16400),       # ... with ragged tiles; more than one accumulator segment per block
+    (700, 700, 1100),       # tile counts that take the streamed distribution
+    (32, 512, 8192),        # the 32-row tile of the long fully connected layers
+]
+
+
+@pytest.mark.parametrize("M,N,K", ACC_MATMUL)
+def test_product_added_to_the_zero_share_is_the_reshared_product(cg, ro, wl, M, N, K):
+    """cg_share_matmul_acc on an output that holds alpha_i gives z_i + alpha_i: the oracle's reshare of its product."""
+    say(f"matmul_acc M={M} N={N} K={K}")
+    x_a, x_b = wl.draw_ring((M, K), 1), wl.draw_ring((M, K), 2)
+    y_a, y_b = wl.draw_ring((N, K), 3), wl.draw_ring((N, K), 4)
+    z = cg.cg_zero_share(K0, K2, 77, 5, M * N).view(M, N)
+    cg.cg_share_matmul_acc(*(cg.to_device(a) for a in (x_a, x_b, y_a, y_b)), z)
+    want = ro.reshare(ro.party_matmul(x_a, x_b, y_a, y_b), K0, K2, 77, 5)
+    assert not first_mismatch(cg.to_host(z), want)
+
+
+@pytest.mark.parametrize("case", [
+    (2, 12, 12, 64, 128, 3, 3, (1, 1), (1, 1)),        # 32-channel gather
+    (2, 9, 7, 3, 20, 5, 5, (2, 1), (2, 2)),            # per-word gather
+    (8, 14, 14, 256, 256, 3, 3, (1, 1), (1, 1)),       # streamed distribution
+    (2, 14, 14, 64, 96, 1, 1, (1, 1), (0, 0)),         # pointwise: the plain product
+])
+def test_convolution_added_to_the_zero_share(cg, ro, wl, case):
+    B, H, W, Cin, Cout, kh, kw, stride, pad = case
+    say(f"conv2d_acc {case}")
+    xs, ws = (B, H, W, Cin), (Cout, kh, kw, Cin)
+    x_a, x_b, w_a, w_b = wl.draw_ring(xs, 1), wl.draw_ring(xs, 2), wl.draw_ring(ws, 3), wl.draw_ring(ws, 4)
+    want = ro.party_conv2d(x_a, x_b, w_a, w_b, stride, pad)
+    z = cg.cg_zero_share(K1, K0, 78, 0, want.size).view(want.shape)
+    cg.cg_share_conv2d_acc(*(cg.to_device(a) for a in (x_a, x_b, w_a, w_b)), z, stride=stride, pad=pad)
+    assert not first_mismatch(cg.to_host(z), ro.reshare(want, K1, K0, 78, 0))
+
+
+def test_two_products_summed_into_one_output(cg, ro, wl):
+    M, N, K = 96, 80, 200
+    ops = [[wl.draw_ring((M, K) if j < 2 else (N, K), 10 * t + j) for j in range(4)] for t in range(2)]
+    z = cg.cg_share_matmul(*(cg.to_device(a) for a in ops[0]))
+    cg.cg_share_matmul_acc(*(cg.to_device(a) for a in ops[1]), z)
+    want = ro.party_matmul(*ops[0]) + ro.party_matmul(*ops[1])
+    assert not first_mismatch(cg.to_host(z), want)
