@@ -92,6 +92,19 @@ def measure_extras(torch, cg, wl, config_layers):
         z = torch.empty((M, N), dtype=torch.int64, device="cuda")
         out["square_products"].append(row(f"matmul {M}x{N}x{K}", M * N * K, timed(lambda: cg.cg_share_matmul(*ops, z_i=z))))
         del ops, z
+    # the paper's embedding (16-bit blocks in float64, float64 matrix instruction) against the int8 route, same product
+    out["limb_choice"] = []
+    for M, N, K in [(2048, 2048, 2048), (4096, 4096, 4096)]:
+        ops = [rnd((M, K), 1), rnd((M, K), 2), rnd((N, K), 3), rnd((N, K), 4)]
+        z = torch.empty((M, N), dtype=torch.int64, device="cuda")
+        ms8 = timed(lambda: cg.cg_share_matmul(*ops, z_i=z))
+        ms64 = timed(lambda: cg.cg_share_matmul_f64limb(*ops, z_i=z), warm=1, iters=3)
+        out["limb_choice"].append({
+            "name": f"matmul {M}x{N}x{K}", "int8_digits_ms": round(ms8, 4), "float64_blocks_ms": round(ms64, 4),
+            "float64_blocks_ring_macs_per_s": 3.0 * M * N * K / (ms64 * 1e-3),
+            "float64_blocks_tflops": round(2.0 * 20 * M * N * K / (ms64 * 1e-3) / 1e12, 1),
+            "int8_over_float64": round(ms64 / ms8, 2)})
+        del ops, z
     # shapes of the paper's Fig. 1 (its times are whole-protocol times on three V100s over a LAN: context only)
     fig1 = [("11x11 3->64 s4 p2", (1, n, n, 3), (64, 11, 11, 3), 4, 2) for n in (64, 128, 256, 512)]
     fig1 += [("11x11 3->64 s4 p2 on 32x32x3", (b, 32, 32, 3), (64, 11, 11, 3), 4, 2) for b in (32, 128, 512)]

@@ -181,6 +181,20 @@ CG_API cg_status cg_share_conv2d_acc(const uint64_t *x_i, const uint64_t *x_ip1,
                               uint64_t *z_i, const cg_conv2d_desc *desc, void *stream);
 
 /*
+ * cg_share_matmul computed the way the paper embeds ring products in floating point
+ * (Sec. II-B): every word as four unsigned 16-bit blocks held in float64, the ten
+ * block products whose weight stays below 2^64, on the float64 matrix instruction,
+ * accumulators folded into the 64-bit result before they leave the exact range.
+ * Same arguments, validation, errors and result (bit for bit) as cg_share_matmul;
+ * several times slower.  A comparator: it exists so that the choice of 8-bit digits
+ * on the integer matrix instruction is backed by a measurement, not to be called by
+ * applications.
+ */
+CG_API cg_status cg_share_matmul_f64limb(const uint64_t *x_i, const uint64_t *x_ip1,
+                                  const uint64_t *y_i, const uint64_t *y_ip1,
+                                  uint64_t *z_i, int64_t M, int64_t N, int64_t K, void *stream);
+
+/*
  * Backward products of a convolution layer on shares (Sec. III-C: the gradients of
  * a linear / convolution layer are linear functions of the incoming gradient and
  * are evaluated with the protocols of Sec. III-B, i.e. with the same three-term

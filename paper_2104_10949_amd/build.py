@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcg.so")
 PROBE_LIB = os.path.join(HERE, "libcg_probe.so")  # MFMA issue-rate microbenchmark for bench.py, not part of libcg
-SOURCES = ["cg_api.hip", "share_gemm.hip", "prf.hip"]
+SOURCES = ["cg_api.hip", "share_gemm.hip", "share_gemm_f64.hip", "prf.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

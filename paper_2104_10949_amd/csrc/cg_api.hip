@@ -983,6 +983,16 @@ cg_status cg_share_conv2d_acc(const uint64_t* x_i, const uint64_t* x_ip1, const 
     return run_direct(pl, stream);
 }
 
+cg_status cg_share_matmul_f64limb(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
+                                  const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
+                                  void* stream) {
+    Plan pl;  // validation and limits of the plain product
+    if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl)) return st;
+    const hipError_t e = cg::launch_share_gemm_f64limb(x_i, x_ip1, y_i, y_ip1, z_i, (int)M, (int)N, (int)K,
+                                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
+}
+
 cg_status cg_share_matmul_t(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
                             const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
                             int trans_x, int trans_y, void* stream) {

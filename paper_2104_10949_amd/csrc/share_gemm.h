@@ -84,6 +84,12 @@ static const int MAX_TILE_ROWS = 256;
 
 hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream);
 
+// The same product of row-major x [M, K] and w [N, K] on the float64 matrix instruction with
+// four 16-bit blocks per word (share_gemm_f64.hip); K below 2^31 / 8 words per row is the
+// caller's business, the kernel indexes with 64-bit offsets.
+hipError_t launch_share_gemm_f64limb(const uint64_t* x_a, const uint64_t* x_b, const uint64_t* w_a,
+                                     const uint64_t* w_b, uint64_t* z, int M, int N, int K, hipStream_t stream);
+
 // z[0..n) = 0 with a fill kernel (capturable).
 hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream);
 

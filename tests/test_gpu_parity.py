@@ -524,3 +524,27 @@ def test_bias_add_and_bias_gradient(cg, ro, wl, shape):
     cg.cg_share_bias_add(*d, za=d[0], zb=d[1])
     wa, wb = ro.share_bias_add(xa, xb, ba, bb)
     assert not first_mismatch(cg.to_host(d[0]), wa) and not first_mismatch(cg.to_host(d[1]), wb)
+
+
+F64LIMB_SHAPES = [(1, 1, 1), (16, 16, 4), (64, 64, 8), (65, 63, 9), (100, 130, 77), (200, 96, 1000),
+                  (33, 40, 40000)]          # the last folds its float64 accumulators more than once
+
+
+@pytest.mark.parametrize("M,N,K", F64LIMB_SHAPES)
+def test_float64_block_comparator_matches_the_oracle(cg, ro, wl, M, N, K):
+    """The product on 16-bit blocks in float64 (Sec. II-B) gives the same words as the definition."""
+    say(f"matmul_f64limb M={M} N={N} K={K}")
+    ops = [wl.draw_ring((M, K), 1), wl.draw_ring((M, K), 2), wl.draw_ring((N, K), 3), wl.draw_ring((N, K), 4)]
+    got = cg.to_host(cg.cg_share_matmul_f64limb(*(cg.to_device(a) for a in ops)))
+    assert not first_mismatch(got, ro.party_matmul(*ops))
+
+
+@pytest.mark.parametrize("word", [0xFFFFFFFFFFFFFFFF, 0xFFFF0000FFFF0000, 0x8000800080008000])
+def test_float64_block_comparator_stays_exact_on_extreme_blocks(cg, ro, word):
+    """Every block at its maximum for the longest accumulation the kernel allows between folds."""
+    M, N, K = 32, 32, 70000
+    say(f"matmul_f64limb constant words {word:#x}")
+    ops = [np.full((M, K), word, dtype=np.uint64), np.full((M, K), word, dtype=np.uint64),
+           np.full((N, K), word, dtype=np.uint64), np.full((N, K), word, dtype=np.uint64)]
+    got = cg.to_host(cg.cg_share_matmul_f64limb(*(cg.to_device(a) for a in ops)))
+    assert not first_mismatch(got, ro.party_matmul(*ops))
