@@ -77,6 +77,11 @@ def test_accumulating_entry_points_validate_like_the_plain_ones(L):
     assert f(*ok[:4], P + 8, 4, 4, 4, None) == b.CG_ERR_ALIAS              # z inside x_i
     big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
     assert f(*big, 4, 4, (1 << 20) + 1, None) == b.CG_ERR_UNSUPPORTED
+    h = L.cg_share_matmul_f64limb                                          # the float64 comparator: same checks
+    assert h(0, *ok[1:], 4, 4, 4, None) == b.CG_ERR_NULL
+    assert h(*ok, 4, 4, 0, None) == b.CG_ERR_SHAPE
+    assert h(*ok[:4], P + 8, 4, 4, 4, None) == b.CG_ERR_ALIAS
+    assert h(*big, 4, 4, (1 << 20) + 1, None) == b.CG_ERR_UNSUPPORTED
     g = L.cg_share_conv2d_acc
     d = b.ConvDesc(1, 8, 8, 3, 4, 3, 3, 1, 1, 1, 1)
     assert g(*big, None, None) == b.CG_ERR_NULL
