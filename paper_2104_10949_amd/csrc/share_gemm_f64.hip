@@ -50,14 +50,15 @@ __global__ __launch_bounds__(F_NT) void share_gemm_f64limb_kernel(const u64* __r
     const int tiles_n = (N + F_BN - 1) / F_BN;
     const int m0 = (int)(blockIdx.x / tiles_n) * F_BM, n0 = (int)(blockIdx.x % tiles_n) * F_BN;
 
-    // staging: thread t fetches contraction index t % 8 of rows t / 8 and t / 8 + 32 of every operand
-    const int kq = tid & (F_KS - 1), r0 = tid >> 3;
+    // staging: thread t fetches contraction indices t / 64 and t / 64 + 4 of row t % 64 of every operand, so that a
+    // wave's LDS stores of one block plane are consecutive doubles
+    const int kq = tid >> 6, r0 = tid & 63;
     u64 sx_a[2], sx_b[2], sw_s[2], sw_a[2];
     auto fetch = [&](int kc) {
-        const int k = kc + kq;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int row = m0 + r0 + 32 * h, col = n0 + r0 + 32 * h;
+            const int k = kc + kq + 4 * h;
+            const int row = m0 + r0, col = n0 + r0;
             const bool va = row < M && k < K, vb = col < N && k < K;
             const size_t ia = (size_t)row * (size_t)K + (size_t)k, ib = (size_t)col * (size_t)K + (size_t)k;
             sx_a[h] = va ? x_a[ia] : 0;
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(F_NT) void share_gemm_f64limb_kernel(const u64* __r
     auto stage = [&]() {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int o = kq * F_BM + r0 + 32 * h;
+            const int o = (kq + 4 * h) * F_BM + r0;
             split_store(lds + 0 * 4 * F_PLANE + o, sx_a[h]);
             split_store(lds + 1 * 4 * F_PLANE + o, sx_b[h]);
             split_store(lds + 2 * 4 * F_PLANE + o, sw_s[h]);
