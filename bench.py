@@ -222,9 +222,9 @@ def measure_extras(torch, cg, wl, config_layers):
     def msb_local_sliced():
         cg.cg_bit_transpose64(x0, out=a0)
         cg.cg_bit_transpose64(x1, out=a1)
-        # carry-save cell on the three sharings (two of the six pair components of a party are its shares, the
-        # rest zero planes: the cell is timed in its general form), carry blinded
-        cg.cg_bshare_csa(a0, a1, s0, s1, c0, c1, s_i=q0, s_ip1=q1, carry_i=s0)
+        # carry-save cell on the three sharings x_0, x_1, x_2, each with a single non-zero share: of the six pair
+        # components of party i only A's first (x_i) and B's second (x_{i+1}) are not zero; carry blinded
+        cg.cg_bshare_csa(a0, None, None, a1, None, None, s_i=q0, s_ip1=q1, carry_i=s0)
         cg.cg_breshare(s0, k0, k1, 4, 0, out=s0)
         # half-adder cell: propagate pair and generate share, generate blinded
         cg.cg_bshare_half_adder(q0, q1, s0, s1, p_i=c0, p_ip1=c1, g_i=q0)

@@ -456,7 +456,10 @@ CG_API cg_status cg_bshare_prefix_stage(const uint64_t *p_i, const uint64_t *p_i
  *   cg_bshare_csa        : carry-save (full) adder of three sharings A, B, C given as pairs:
  *                          sum pair (s_i, s_ip1) = A ^ B ^ C, and the party's XOR share of the carry
  *                          majority(A, B, C) = ((A ^ C) & (B ^ C)) ^ C before blinding, i.e.
- *                          and3(A ^ C, B ^ C) ^ c_i.  Bit by bit a + b + c = sum + 2 carry.
+ *                          and3(A ^ C, B ^ C) ^ c_i.  Bit by bit a + b + c = sum + 2 carry.  Any of the
+ *                          six input pointers may be NULL: that component is zero everywhere and is
+ *                          not read (the three summands of the sign-bit circuit are sharings with a
+ *                          single non-zero share, so a party holds two non-zero components of six).
  *   cg_bshare_half_adder : propagate pair (p_i, p_ip1) = S ^ T and the party's XOR share of the
  *                          generate word and3(S, T) before blinding.
  *

@@ -518,16 +518,21 @@ def cg_bshare_prefix_stage(p_i, p_ip1, g_i, g_ip1, shift: int, last: bool = Fals
 
 
 def cg_bshare_csa(a_i, a_ip1, b_i, b_ip1, c_i, c_ip1, s_i=None, s_ip1=None, carry_i=None, stream=None):
-    """Local step of a carry-save adder: returns (s_i, s_ip1, carry_i)."""
+    """Local step of a carry-save adder: returns (s_i, s_ip1, carry_i).  An input given as None is a component
+    that is zero everywhere (a party's view of a sharing whose only non-zero share it does not hold)."""
     ins = (a_i, a_ip1, b_i, b_ip1, c_i, c_ip1)
-    if any(t.shape != a_i.shape for t in ins):
+    given = [t for t in ins if t is not None]
+    if not given and s_i is None:
+        raise ValueError("no operand to take the shape from")
+    like = given[0] if given else s_i
+    if any(t.shape != like.shape for t in given):
         raise ValueError("operand shapes do not match")
-    s_i = torch.empty_like(a_i) if s_i is None else s_i
-    s_ip1 = torch.empty_like(a_i) if s_ip1 is None else s_ip1
-    carry_i = torch.empty_like(a_i) if carry_i is None else carry_i
-    n = a_i.numel()
-    _check(lib().cg_bshare_csa(*(_ptr(t) if n else 0 for t in ins + (s_i, s_ip1, carry_i)), n, _stream(stream)),
-           "cg_bshare_csa")
+    s_i = torch.empty_like(like) if s_i is None else s_i
+    s_ip1 = torch.empty_like(like) if s_ip1 is None else s_ip1
+    carry_i = torch.empty_like(like) if carry_i is None else carry_i
+    n = like.numel()
+    _check(lib().cg_bshare_csa(*(_ptr(t) if (n and t is not None) else 0 for t in ins + (s_i, s_ip1, carry_i)), n,
+                               _stream(stream)), "cg_bshare_csa")
     return s_i, s_ip1, carry_i
 
 

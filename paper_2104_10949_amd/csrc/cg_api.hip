@@ -337,16 +337,17 @@ struct PrefixStageOp {
 // Carry-save (full) adder on three binary sharings, one party's local step: sum pair S = A ^ B ^ C and the
 // party's XOR share of the carry ((A ^ C) & (B ^ C)) ^ C (three-term AND, own component of C added).
 struct CsaOp {
-    const u64 *aa, *ab, *ba, *bb, *ca, *cb;
+    const u64 *aa, *ab, *ba, *bb, *ca, *cb;  // a null input is a component that is zero everywhere
     u64 *sa, *sb, *carry;
+    static __device__ __forceinline__ ull2 in2(const u64* p, size_t k) { return p ? ld2(p, k) : ull2{0, 0}; }
     template <int U>
     __device__ void pairs(size_t i, size_t step) const {
         ull2 a0[U], a1[U], b0[U], b1[U], c0[U], c1[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t k = i + u * step;
-            a0[u] = ld2(aa, k); a1[u] = ld2(ab, k); b0[u] = ld2(ba, k);
-            b1[u] = ld2(bb, k); c0[u] = ld2(ca, k); c1[u] = ld2(cb, k);
+            a0[u] = in2(aa, k); a1[u] = in2(ab, k); b0[u] = in2(ba, k);
+            b1[u] = in2(bb, k); c0[u] = in2(ca, k); c1[u] = in2(cb, k);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -358,8 +359,8 @@ struct CsaOp {
         }
     }
     __device__ void one(size_t k) const {
-        const u64 c0 = ca[k], c1 = cb[k], b0 = ba[k], b1 = bb[k];
-        const u64 x0 = aa[k] ^ c0, x1 = ab[k] ^ c1, y0 = b0 ^ c0, y1 = b1 ^ c1;
+        const u64 c0 = ca ? ca[k] : 0, c1 = cb ? cb[k] : 0, b0 = ba ? ba[k] : 0, b1 = bb ? bb[k] : 0;
+        const u64 x0 = (aa ? aa[k] : 0) ^ c0, x1 = (ab ? ab[k] : 0) ^ c1, y0 = b0 ^ c0, y1 = b1 ^ c1;
         sa[k] = x0 ^ b0;
         sb[k] = x1 ^ b1;
         carry[k] = (x0 & (y0 ^ y1)) ^ (x1 & y0) ^ c0;
@@ -428,11 +429,12 @@ struct CarryLevelOp {
     }
 };
 
-// 64 x 64 bit transpose: plane b, word w, bit e = bit b of src[64 w + e].  A wave takes sixteen blocks of 64
-// words.  Lane e loads its word of a block (512 contiguous bytes per block); the block is transposed in
+// 64 x 64 bit transpose: plane b, word w, bit e = bit b of src[64 w + e].  A wave takes BT_BLOCKS blocks of 64
+// words per trip.  Lane e loads its word of a block (512 contiguous bytes per block); the block is transposed in
 // registers by the recursive scheme (swap the off-diagonal j x j sub-blocks for j = 32, 16, .., 1, each step one
-// exchange with lane e ^ j and a masked merge), after which lane b holds the word of plane b; after eight
-// sixteen blocks every lane stores 128 contiguous bytes of its plane.
+// exchange with lane e ^ j and a masked merge), after which lane b holds the word of plane b.  The words then
+// cross the wave's own LDS tile [plane][block], so that each half of the wave stores 256 contiguous bytes of
+// one plane instead of every lane 8 bytes of its own.
 template <int J>
 __device__ __forceinline__ u64 transpose_step(u64 x, int lane) {
     // bits whose index has bit J clear
@@ -452,11 +454,15 @@ __device__ __forceinline__ u64 transpose64_lanes(u64 x, int lane) {
     return transpose_step<1>(x, lane);
 }
 
-constexpr int BT_BLOCKS = 16;  // 64-word blocks per wave and trip: 128 contiguous bytes per lane and plane
+constexpr int BT_BLOCKS = 32;            // 64-word blocks per wave and trip
+constexpr int BT_PITCH = BT_BLOCKS + 1;  // words between planes in the LDS tile: consecutive lanes hit distinct banks
 
 __global__ __launch_bounds__(256) void bit_transpose_kernel(const u64* __restrict__ src, u64* __restrict__ dst, size_t m) {
+    __shared__ u64 tile_all[4][64 * BT_PITCH];
     const int lane = threadIdx.x & 63;
+    u64* tile = tile_all[threadIdx.x >> 6];  // private to the wave: no block barrier anywhere
     const size_t wave = ((size_t)blockIdx.x * 256 + threadIdx.x) >> 6, waves = ((size_t)gridDim.x * 256) >> 6;
+    const int half = lane >> 5, col = lane & 31;
     for (size_t w0 = wave * BT_BLOCKS; w0 < m; w0 += waves * BT_BLOCKS) {
         u64 mine[BT_BLOCKS];
 #pragma unroll
@@ -465,10 +471,19 @@ __global__ __launch_bounds__(256) void bit_transpose_kernel(const u64* __restric
             mine[k] = w < m ? src[64 * w + lane] : 0;       // uniform per k: whole blocks only
         }
 #pragma unroll
-        for (int k = 0; k < BT_BLOCKS; ++k) mine[k] = transpose64_lanes(mine[k], lane);
-#pragma unroll
-        for (int k = 0; k < BT_BLOCKS; ++k)
-            if (w0 + k < m) dst[(size_t)lane * m + w0 + k] = mine[k];
+        for (int k = 0; k < BT_BLOCKS; ++k) tile[lane * BT_PITCH + k] = transpose64_lanes(mine[k], lane);
+        // the tile is read by other lanes of the same wave: LDS operations of a wave complete in order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const bool in = w0 + col < m;
+#pragma unroll 8
+        for (int pl = 0; pl < 64; pl += 2) {
+            const u64 v = tile[(pl + half) * BT_PITCH + col];
+            if (in) dst[(size_t)(pl + half) * m + w0 + col] = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();    // the next trip overwrites the tile
     }
 }
 
@@ -1304,12 +1319,14 @@ cg_status cg_bshare_csa(const uint64_t* a_i, const uint64_t* a_ip1, const uint64
                         size_t n, void* stream) {
     if (n == 0) return CG_OK;
     const void* ptrs[9] = {a_i, a_ip1, b_i, b_ip1, c_i, c_ip1, s_i, s_ip1, carry_i};
-    if (cg_status st = check_ptrs(ptrs, 9)) return st;
+    if (cg_status st = check_ptrs(ptrs + 6, 3)) return st;  // outputs
+    for (int i = 0; i < 6; ++i)                               // inputs: null stands for an all-zero component
+        if (ptrs[i] && !aligned(ptrs[i], 8)) return CG_ERR_ALIGN;
     if (n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
     const u64 bytes = (u64)n * 8;
     for (int o = 6; o < 9; ++o) {
         for (int i = 0; i < 6; ++i)
-            if (bad_overlap(ptrs[o], ptrs[i], bytes)) return CG_ERR_ALIAS;
+            if (ptrs[i] && bad_overlap(ptrs[o], ptrs[i], bytes)) return CG_ERR_ALIAS;
         for (int o2 = o + 1; o2 < 9; ++o2)
             if (overlap(ptrs[o], bytes, ptrs[o2], bytes)) return CG_ERR_ALIAS;
     }
@@ -1360,7 +1377,7 @@ cg_status cg_bit_transpose64(const uint64_t* src, uint64_t* dst, size_t n, void*
     if (n % 64 != 0 || n > (SIZE_MAX >> 4)) return CG_ERR_SHAPE;
     if (overlap(dst, (u64)n * 8, src, (u64)n * 8)) return CG_ERR_ALIAS;
     const size_t m = n / 64;
-    size_t blocks = (m + 63) / 64;   // four waves per block, sixteen 64-word blocks per wave and trip
+    size_t blocks = (m + 4 * 32 - 1) / (4 * 32);   // four waves per block, 32 blocks of 64 words per wave and trip
     if (blocks > 256 * 16) blocks = 256 * 16;
     hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), src,
                        dst, m);

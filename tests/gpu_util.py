@@ -125,7 +125,9 @@ def gpu_msb_sliced(cg, x_dev, KEYS, nonce, cells=False):
     A, B, C = (planes[0], zero, zero), (zero, planes[1], zero), (zero, zero, planes[2])
     up = lambda v: torch.cat([torch.zeros_like(v[:1]), v[:63]])        # one bit position up: a move of planes
     if cells:
-        loc = [cg.cg_bshare_csa(*pair(A, i), *pair(B, i), *pair(C, i)) for i in range(3)]
+        # the three summands are sharings with a single non-zero share: zero components are passed as None
+        An, Bn, Cn = (planes[0], None, None), (None, planes[1], None), (None, None, planes[2])
+        loc = [cg.cg_bshare_csa(*pair(An, i), *pair(Bn, i), *pair(Cn, i)) for i in range(3)]
         S = tuple(loc[i][0] for i in range(3))
         carry = tuple(blind(loc[i][2], i) for i in range(3))
         counter[0] += n

@@ -251,6 +251,9 @@ def test_truncation_and_binary_gate_validation(L):
     assert L.cg_bits_unpack(P, 0, 8, None) == b.CG_ERR_NULL
     six = [P, 2 * P, 3 * P, 4 * P, 5 * P, 6 * P]
     assert L.cg_bshare_csa(*six, 7 * P, 8 * P, 7 * P + 8, 8, None) == b.CG_ERR_ALIAS  # sum and carry overlap
+    assert L.cg_bshare_csa(*six, 7 * P, 0, 9 * P, 8, None) == b.CG_ERR_NULL           # outputs are required
+    assert L.cg_bshare_csa(P, None, None, 4 * P + 4, None, None, 7 * P, 8 * P, 9 * P, 8, None) == b.CG_ERR_ALIGN
+    assert L.cg_bshare_csa(P, None, None, 4 * P, None, None, 7 * P, 8 * P, 4 * P + 8, 8, None) == b.CG_ERR_ALIAS
     assert L.cg_bshare_half_adder(*a, 5 * P, 6 * P, 0, 8, None) == b.CG_ERR_NULL
 
 
