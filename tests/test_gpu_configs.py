@@ -122,3 +122,60 @@ def test_config2_all_three_parties_open_to_the_fixed_point_product(env):
     opened = cg.to_host(cg.cg_reconstruct(*z))
     assert np.array_equal(opened, ro.matmul(ex, ew))
     assert np.max(np.abs(ro.decode(opened, 2 * t) - ro.decode(ex, t) @ ro.decode(ew, t).T)) <= 2.0 ** -12
+
+
+def test_protocol_steps_replayed_from_a_hip_graph_match_eager_runs(env):
+    """The entry points around the products (zero share, accumulating convolution, class-by-class strided input
+    gradient, weight gradient, truncation step, bit transpose, carry-save cell, binary reshare) captured into
+    one graph: every replay, with eager work and new inputs in between, must give what the eager calls give."""
+    cg, ro, wl = env
+    k0, k1 = bytes(range(16)), bytes(range(16, 32))
+    xs, ws, st, pd = (4, 14, 14, 64), (96, 3, 3, 64), (2, 2), (1, 1)
+    zs = cg.conv_out_shape(xs, ws, st, pd)
+    x = [cg.to_device(wl.draw_ring(xs, 70 + j)) for j in range(2)]
+    w = [cg.to_device(wl.draw_ring(ws, 72 + j)) for j in range(2)]
+    g = [cg.to_device(wl.draw_ring(zs, 74 + j)) for j in range(2)]
+    n = int(np.prod(zs))
+    assert n % 64 == 0
+    z = torch.empty(zs, dtype=torch.int64, device="cuda")
+    dx = torch.empty(xs, dtype=torch.int64, device="cuda")
+    dw = torch.empty(ws, dtype=torch.int64, device="cuda")
+    tr = torch.empty(zs, dtype=torch.int64, device="cuda")
+    planes = [torch.empty((64, n // 64), dtype=torch.int64, device="cuda") for _ in range(2)]
+    s0, s1, carry = (torch.empty((64, n // 64), dtype=torch.int64, device="cuda") for _ in range(3))
+    outs = [z, dx, dw, tr, s0, s1, carry]
+
+    def step():
+        cg.cg_zero_share(k0, k1, 9, 0, n, out=z.view(-1))
+        cg.cg_share_conv2d_acc(*x, *w, z, stride=st, pad=pd)                        # the reshared product
+        cg.cg_share_conv2d_dgrad(*g, *w, xs, stride=st, pad=pd, dx_i=dx)            # four launches after a fill
+        cg.cg_share_conv2d_wgrad(*g, *x, ws, stride=st, pad=pd, dw_i=dw)
+        cg.cg_trunc1_local(z, g[0], k1, k0, 10, 0, 16, k1, 11, out=tr)
+        cg.cg_bit_transpose64(z.view(-1), out=planes[0])
+        cg.cg_bit_transpose64(tr.view(-1), out=planes[1])
+        cg.cg_bshare_csa(planes[0], None, None, planes[1], None, None, s_i=s0, s_ip1=s1, carry_i=carry)
+        cg.cg_breshare(carry, k0, k1, 12, 0, out=carry)
+
+    say("protocol steps: eager run, then capture")
+    step()
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        say(f"protocol steps: graph replay {rep}")
+        for o in outs:
+            o.fill_(0x3C3C3C3C3C3C3C3C)
+        if rep == 2:                                   # new activations and gradient in the same buffers
+            x[0].copy_(cg.to_device(wl.draw_ring(xs, 170)))
+            g[1].copy_(cg.to_device(wl.draw_ring(zs, 171)))
+            step()
+            torch.cuda.synchronize()
+            want = [o.clone() for o in outs]
+            for o in outs:
+                o.fill_(0x3C3C3C3C3C3C3C3C)
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, o, w_ in zip(("z", "dx", "dw", "trunc", "sum", "sum'", "carry"), outs, want):
+            assert torch.equal(o, w_), f"replay {rep}: {name}"
