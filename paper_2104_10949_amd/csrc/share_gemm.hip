@@ -605,41 +605,80 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         u_end = (int64_t)logical * nk_all + (kb + per_split < nk_all ? kb + per_split : nk_all);
     }
 
-    // One pass per tile the range touches (exactly one in the classic scheme).  Everything that
-    // depends on the tile is set up inside the pass.
+    // One pass per tile the range touches (exactly one in the classic scheme).  Everything that depends
+    // on the tile lives in the variables below and is (re)computed by setup_tile(), which takes the
+    // next tile of the range: [k_begin, nk) are its slices, (m0, n0) its first row and column.
     if (u >= u_end) return;  // uniform over the block
-    do {
-    const int logical = (int)(u / nk_all);
-    const int k_begin = (int)(u - (int64_t)logical * nk_all);
-    const int nk = (int64_t)k_begin + (u_end - u) < nk_all ? k_begin + (int)(u_end - u) : nk_all;
-    u += nk - k_begin;
-    int tm, tn;
-    logical_to_tile(p, tiles_m, tiles_n, logical, tm, tn);
-    const int m0 = tm * T::BM, n0 = tn * T::BN;
-    const int rows_m = p.M - m0, rows_n = p.N - n0;
-
-    // ---- buffer views, rebased per block so that 32-bit offsets suffice
     constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
     constexpr bool A_TR = AMODE == A_TRANS;
     // right-operand modes whose memory is contiguous along n: consecutive lanes take consecutive rows
     constexpr bool B_TR = BMODE == B_TRANS || BMODE == B_FLIP_C32 || BMODE == B_FLIP_GEN || BMODE == B_PATCH_T;
-    u64 a_base_elems;
-    if (A_LINEAR) a_base_elems = (u64)m0 * (u64)p.lda;
-    else if (A_TR) a_base_elems = (u64)m0;
-    else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
-    const u64 b_base_elems = BMODE == B_PATCH_T ? 0 : (B_TR ? (u64)n0 : (u64)n0 * (u64)p.K);
+    // ---- per-thread units.  Row-major operands put the four 16-byte quarters of a
+    // 64-byte run on consecutive lanes; transposed operands put consecutive rows there.
+    typedef typename std::conditional<AMODE == A_LINEAR_VEC, LinearVec,
+            typename std::conditional<AMODE == A_LINEAR_SCALAR, LinearScalar,
+            typename std::conditional<AMODE == A_CONV_C32, ConvC32,
+            typename std::conditional<AMODE == A_TRANS, TransScalar,
+            typename std::conditional<AMODE == A_CONV_DIL, ConvDil, ConvGen>::type>::type>::type>::type>::type AGen;
+    typedef typename std::conditional<BMODE == B_VEC, LinearVec,
+            typename std::conditional<BMODE == B_SCALAR, LinearScalar,
+            typename std::conditional<BMODE == B_FLIP_GEN, FlipGen,
+            typename std::conditional<BMODE == B_PATCH_T, PatchTrans, TransScalar>::type>::type>::type>::type BGen;
+    int k_begin, nk, m0, n0;
+    u64 a_base_elems, b_base_elems;
     const u64 w_elems = p.w_elems;
     TapCursor tap;
-    tap.reset();
-    // view on `elems_total` words starting `base` words in, advanced by `adv` words
+    __amdgpu_buffer_rsrc_t rs_xa, rs_xb, rs_wa, rs_wb;  // views, rebased per tile so that 32-bit offsets suffice
+    AGen ag[AU];
+    BGen bg[BU];
+    int a_dst[AU], b_dst[BU];  // LDS byte offset of digit 0 inside a stage
+    // view on `elems_total` words starting `base` words in
     auto view = [&](const u64* ptr, u64 elems_total, u64 base) {
         const u64 left = (elems_total - base) * 8u;
         return make_rsrc(ptr + base, left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left);
     };
-    const __amdgpu_buffer_rsrc_t rs_xa = view(p.x_a, p.x_elems, a_base_elems);
-    const __amdgpu_buffer_rsrc_t rs_xb = view(p.x_b, p.x_elems, a_base_elems);
-    const __amdgpu_buffer_rsrc_t rs_wa = view(p.w_a, w_elems, b_base_elems);
-    const __amdgpu_buffer_rsrc_t rs_wb = view(p.w_b, w_elems, b_base_elems);
+    auto setup_tile = [&]() {
+        const int logical = (int)(u / nk_all);
+        k_begin = (int)(u - (int64_t)logical * nk_all);
+        nk = (int64_t)k_begin + (u_end - u) < nk_all ? k_begin + (int)(u_end - u) : nk_all;
+        u += nk - k_begin;
+        int tm, tn;
+        logical_to_tile(p, tiles_m, tiles_n, logical, tm, tn);
+        m0 = tm * T::BM;
+        n0 = tn * T::BN;
+        const int rows_m = p.M - m0, rows_n = p.N - n0;
+        if (A_LINEAR) a_base_elems = (u64)m0 * (u64)p.lda;
+        else if (A_TR) a_base_elems = (u64)m0;
+        else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
+        b_base_elems = BMODE == B_PATCH_T ? 0 : (B_TR ? (u64)n0 : (u64)n0 * (u64)p.K);
+        tap.reset();
+        rs_xa = view(p.x_a, p.x_elems, a_base_elems);
+        rs_xb = view(p.x_b, p.x_elems, a_base_elems);
+        rs_wa = view(p.w_a, w_elems, b_base_elems);
+        rs_wb = view(p.w_b, w_elems, b_base_elems);
+#pragma unroll
+        for (int i = 0; i < AU; ++i) {
+            const int t = tid + i * T::NT;
+            const int q = A_TR ? (t / T::BM) & 3 : t & 3;
+            const int row = A_TR ? t % T::BM : (t >> 2) % T::BM;
+            const int jh = (t >> 2) / T::BM;
+            ag[i].init(p, m0, row, rows_m, A_TR ? (u32)p.M : (u32)p.lda, q, jh);
+            a_dst[i] = jh * T::A_RS + row * 16 + q * 4;
+        }
+#pragma unroll
+        for (int i = 0; i < BU; ++i) {
+            const int t = tid + i * T::NT;
+            const int q = B_TR ? (t / T::BN) & 3 : t & 3;
+            const int row = B_TR ? t % T::BN : (t >> 2) % T::BN;
+            const int jh = (t >> 2) / T::BN;
+            // pitch between consecutive k of one row: N for a transposed matrix, one output
+            // channel of the filter (kh*kw*N words) for the flipped filter
+            const u32 pitch = BMODE == B_FLIP_C32 ? (u32)(p.flt_kh * p.flt_kw) * (u32)p.N : (B_TR ? (u32)p.N : (u32)p.K);
+            bg[i].init(p, n0, row, rows_n, pitch, q, jh);
+            b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
+        }
+    };
+    setup_tile();
     // transposed operands: one view per K slice
     auto a_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
         if constexpr (A_TR) {
@@ -666,42 +705,6 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             return fixed;
         }
     };
-
-    // ---- per-thread units.  Row-major operands put the four 16-byte quarters of a
-    // 64-byte run on consecutive lanes; transposed operands put consecutive rows there.
-    typedef typename std::conditional<AMODE == A_LINEAR_VEC, LinearVec,
-            typename std::conditional<AMODE == A_LINEAR_SCALAR, LinearScalar,
-            typename std::conditional<AMODE == A_CONV_C32, ConvC32,
-            typename std::conditional<AMODE == A_TRANS, TransScalar,
-            typename std::conditional<AMODE == A_CONV_DIL, ConvDil, ConvGen>::type>::type>::type>::type>::type AGen;
-    typedef typename std::conditional<BMODE == B_VEC, LinearVec,
-            typename std::conditional<BMODE == B_SCALAR, LinearScalar,
-            typename std::conditional<BMODE == B_FLIP_GEN, FlipGen,
-            typename std::conditional<BMODE == B_PATCH_T, PatchTrans, TransScalar>::type>::type>::type>::type BGen;
-    AGen ag[AU];
-    BGen bg[BU];
-    int a_dst[AU], b_dst[BU];  // LDS byte offset of digit 0 inside a stage
-#pragma unroll
-    for (int i = 0; i < AU; ++i) {
-        const int u = tid + i * T::NT;
-        const int q = A_TR ? (u / T::BM) & 3 : u & 3;
-        const int row = A_TR ? u % T::BM : (u >> 2) % T::BM;
-        const int jh = (u >> 2) / T::BM;
-        ag[i].init(p, m0, row, rows_m, A_TR ? (u32)p.M : (u32)p.lda, q, jh);
-        a_dst[i] = jh * T::A_RS + row * 16 + q * 4;
-    }
-#pragma unroll
-    for (int i = 0; i < BU; ++i) {
-        const int u = tid + i * T::NT;
-        const int q = B_TR ? (u / T::BN) & 3 : u & 3;
-        const int row = B_TR ? u % T::BN : (u >> 2) % T::BN;
-        const int jh = (u >> 2) / T::BN;
-        // pitch between consecutive k of one row: N for a transposed matrix, one output
-        // channel of the filter (kh*kw*N words) for the flipped filter
-        const u32 pitch = BMODE == B_FLIP_C32 ? (u32)(p.flt_kh * p.flt_kw) * (u32)p.N : (B_TR ? (u32)p.N : (u32)p.K);
-        bg[i].init(p, n0, row, rows_n, pitch, q, jh);
-        b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
-    }
 
     // Two sets of staging registers.  E feeds an even half-step (x_a against
     // w_a + w_b), O an odd one (x_b against w_a).
@@ -844,38 +847,54 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
                     for (int i = 0; i < 16; ++i) acc[sm][sn][s][i] = 0;
     };
 
-    auto fold = [&](bool accumulate) {
-        fold_tile<SM, SN, BMODE == B_FLIP_C32>(p, acc, m0 + wm * SM * 32, n0 + wn * SN * 32, lane, accumulate);
+    auto fold = [&](int fm0, int fn0, bool accumulate) {
+        fold_tile<SM, SN, BMODE == B_FLIP_C32>(p, acc, fm0 + wm * SM * 32, fn0 + wn * SN * 32, lane, accumulate);
     };
 
     // Prologue: the even half-step of the first slice goes to LDS.  Loads past the end of
     // K are out of range and return zeros that are never used, so the loop body
     // needs no "is there a next slice" branch.
+    static_assert(CG_PIPE == 1 || !STREAM, "the tile switch below is written for the one-half-step pipeline");
     load_even(k_begin);
     split_all(std::true_type{}, st0);
     if (CG_PIPE == 2) load_odd(k_begin);
     __syncthreads();
 
-    // Outer loop: one pass per segment of at most SEG_KSTEPS slices (a single pass
-    // unless K > 32*SEG_KSTEPS); the LDS pipeline runs straight through.
-    for (int ks0 = k_begin; ks0 < nk; ks0 += SEG_KSTEPS) {
-        const int ke = ks0 + SEG_KSTEPS < nk ? ks0 + SEG_KSTEPS : nk;
-        clear_acc();
-        for (int ks = ks0; ks < ke; ++ks) {
-            // even half-step: x_a against w_a + w_b from st0; odd words are split into st1
-            half_step(st0, st1, std::false_type{}, [&]() {
-                if (CG_PIPE == 2) load_even(ks + 1); else load_odd(ks);
-            });
-            __syncthreads();
-            // odd half-step: x_b against w_a from st1; the next slice's even words go to st0
-            half_step(st1, st0, std::true_type{}, [&]() {
-                if (CG_PIPE == 2) load_odd(ks + 1); else load_even(ks + 1);
-            });
-            __syncthreads();
+    // One pass of the outer loop per tile.  In the streamed scheme the LDS pipeline runs straight on
+    // into the next tile of the range: the last odd half-step of a tile already loads and splits
+    // the first even slice of the next one (whose address generators are set up just before it, when
+    // the current tile has issued its last load), so only the fold separates two tiles.
+    bool more;
+    do {
+        more = false;
+        const int fm0 = m0, fn0 = n0, k0 = k_begin, nk_c = nk;  // the tile being computed
+        // one pass per segment of at most SEG_KSTEPS slices (a single pass unless K > 32*SEG_KSTEPS)
+        for (int ks0 = k0; ks0 < nk_c; ks0 += SEG_KSTEPS) {
+            const int ke = ks0 + SEG_KSTEPS < nk_c ? ks0 + SEG_KSTEPS : nk_c;
+            clear_acc();
+            for (int ks = ks0; ks < ke; ++ks) {
+                // even half-step: x_a against w_a + w_b from st0; odd words are split into st1
+                half_step(st0, st1, std::false_type{}, [&]() {
+                    if (CG_PIPE == 2) load_even(ks + 1); else load_odd(ks);
+                });
+                __syncthreads();
+                int next_ks = ks + 1;
+                if constexpr (STREAM) {
+                    if (next_ks == nk_c && u < u_end) {  // uniform: the range goes on with another tile
+                        setup_tile();
+                        next_ks = k_begin;
+                        more = true;
+                    }
+                }
+                // odd half-step: x_b against w_a from st1; the next even words go to st0
+                half_step(st1, st0, std::true_type{}, [&]() {
+                    if (CG_PIPE == 2) load_odd(next_ks); else load_even(next_ks);
+                });
+                __syncthreads();
+            }
+            fold(fm0, fn0, ks0 > k0 || p.z_add != 0);
         }
-        fold(ks0 > k_begin || p.z_add != 0);
-    }
-    } while (STREAM && u < u_end);  // next tile of the range
+    } while (more);
 }
 
 // ---------------------------------------------------------------------------
