@@ -854,7 +854,6 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     // Prologue: the even half-step of the first slice goes to LDS.  Loads past the end of
     // K are out of range and return zeros that are never used, so the loop body
     // needs no "is there a next slice" branch.
-    static_assert(CG_PIPE == 1 || !STREAM, "the tile switch below is written for the one-half-step pipeline");
     load_even(k_begin);
     split_all(std::true_type{}, st0);
     if (CG_PIPE == 2) load_odd(k_begin);
@@ -873,19 +872,24 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             const int ke = ks0 + SEG_KSTEPS < nk_c ? ks0 + SEG_KSTEPS : nk_c;
             clear_acc();
             for (int ks = ks0; ks < ke; ++ks) {
+                int next_ks = ks + 1;
+                // at the tile's last slice, once its last load has been issued, the loads turn to the next tile
+                auto switch_tile = [&]() {
+                    if constexpr (STREAM) {
+                        if (ks + 1 == nk_c && u < u_end) {  // uniform: the range goes on with another tile
+                            setup_tile();
+                            next_ks = k_begin;
+                            more = true;
+                        }
+                    }
+                };
+                if (CG_PIPE == 2) switch_tile();
                 // even half-step: x_a against w_a + w_b from st0; odd words are split into st1
                 half_step(st0, st1, std::false_type{}, [&]() {
-                    if (CG_PIPE == 2) load_even(ks + 1); else load_odd(ks);
+                    if (CG_PIPE == 2) load_even(next_ks); else load_odd(ks);
                 });
                 __syncthreads();
-                int next_ks = ks + 1;
-                if constexpr (STREAM) {
-                    if (next_ks == nk_c && u < u_end) {  // uniform: the range goes on with another tile
-                        setup_tile();
-                        next_ks = k_begin;
-                        more = true;
-                    }
-                }
+                if (CG_PIPE != 2) switch_tile();
                 // odd half-step: x_b against w_a from st1; the next even words go to st0
                 half_step(st1, st0, std::true_type{}, [&]() {
                     if (CG_PIPE == 2) load_odd(next_ks); else load_even(next_ks);
