@@ -1309,8 +1309,11 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     // plainly.  Measured: 3-9 % on layers of up to 16 slices; with a long K the fixed part of a tile does not
     // matter and the classic order, which keeps the tiles an XCD runs at one time next to each other, is
     // 1-2 % faster.
-    if (CG_PERSIST && CanStream<AMODE, BMODE>::value && q.stream_per == 0 && q.ksplit == 1 && tiles > CG_SPLIT_TARGET &&
-        nk <= CG_PERSIST_MAX_SLICES) {
+    // Row-major left operands only: a patch gather re-reads the rows of neighbouring tiles, which hit in L2
+    // when the neighbours run at the same time and miss when one block takes them one after the other
+    // (measured on the 3x3 layers of the VGG-shaped step: twice the memory reads for 1-3 % of time).
+    if (CG_PERSIST && CanStream<AMODE, BMODE>::value && AMODE == A_LINEAR_VEC && q.stream_per == 0 && q.ksplit == 1 &&
+        tiles > CG_SPLIT_TARGET && nk <= CG_PERSIST_MAX_SLICES) {
         const int64_t tiles_per_block = (tiles + CG_SPLIT_TARGET - 1) / CG_SPLIT_TARGET;
         q.stream_per = tiles_per_block * nk;
         grid = (unsigned)((tiles + tiles_per_block - 1) / tiles_per_block);
