@@ -637,6 +637,19 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         const u64 left = (elems_total - base) * 8u;
         return make_rsrc(ptr + base, left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left);
     };
+    // where a thread's units go inside a stage does not depend on the tile
+#pragma unroll
+    for (int i = 0; i < AU; ++i) {
+        const int t = tid + i * T::NT;
+        const int q = A_TR ? (t / T::BM) & 3 : t & 3, row = A_TR ? t % T::BM : (t >> 2) % T::BM, jh = (t >> 2) / T::BM;
+        a_dst[i] = jh * T::A_RS + row * 16 + q * 4;
+    }
+#pragma unroll
+    for (int i = 0; i < BU; ++i) {
+        const int t = tid + i * T::NT;
+        const int q = B_TR ? (t / T::BN) & 3 : t & 3, row = B_TR ? t % T::BN : (t >> 2) % T::BN, jh = (t >> 2) / T::BN;
+        b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
+    }
     auto setup_tile = [&]() {
         const int logical = (int)(u / nk_all);
         k_begin = (int)(u - (int64_t)logical * nk_all);
@@ -663,7 +676,6 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             const int row = A_TR ? t % T::BM : (t >> 2) % T::BM;
             const int jh = (t >> 2) / T::BM;
             ag[i].init(p, m0, row, rows_m, A_TR ? (u32)p.M : (u32)p.lda, q, jh);
-            a_dst[i] = jh * T::A_RS + row * 16 + q * 4;
         }
 #pragma unroll
         for (int i = 0; i < BU; ++i) {
@@ -675,7 +687,6 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
             // channel of the filter (kh*kw*N words) for the flipped filter
             const u32 pitch = BMODE == B_FLIP_C32 ? (u32)(p.flt_kh * p.flt_kw) * (u32)p.N : (B_TR ? (u32)p.N : (u32)p.K);
             bg[i].init(p, n0, row, rows_n, pitch, q, jh);
-            b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
         }
     };
     setup_tile();
