@@ -494,7 +494,10 @@ __device__ __forceinline__ void recode2(u4& v) {
 //    split-th range of slices;
 //  * streamed (p.stream_per > 0): one block per compute unit takes stream_per consecutive units,
 //    whatever tiles they belong to, so the units are spread evenly even when the tile count is
-//    just above a multiple of the number of compute units.
+//    just above a multiple of the number of compute units.  Partial tiles add into a cleared
+//    output (ksplit > 1); when stream_per is a multiple of the slices of a tile every block
+//    holds whole tiles and stores them plainly (ksplit == 1).  Either way the LDS pipeline of
+//    a block runs on from one tile of its range into the next.
 // The hardware deals consecutive block ids to the 8 XCDs in turn, and each XCD has an L2 cache of
 // its own, so block ids are mapped such that every XCD works through one contiguous run of the
 // order above (K splits slowest in the classic scheme).  With 8 or more splits an XCD therefore
