@@ -2,7 +2,7 @@
 // given operand bytes, with no memory traffic in the loop.  Used by bench.py to
 // report the share-product kernel against a MEASURED ceiling next to the
 // published one: operand bit patterns change the power drawn and with it the
-// clock, and secret shares are uniformly random bytes.  Not part of libcg.so.
+// clock, and secret shares are uniformly random bytes.  Built next to bench.py; not part of libcg.so.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

@@ -370,7 +370,8 @@ CG_API cg_status cg_reshare(const uint64_t *z_i, const uint8_t *key_self, const 
  *                              - (key_mask ? F(key_mask, first + j) : 0),   j < n
  *       alpha as in cg_zero_share under `nonce`; the mask stream uses the same
  *       indices under `mask_nonce`, which must differ from `nonce` when key_mask is
- *       one of the two alpha keys.  msg and key_mask may be NULL.  d in [0, 63]
+ *       one of the two alpha keys (the mask would be a term of alpha itself and blind
+ *       nothing: CG_ERR_SHAPE).  msg and key_mask may be NULL.  d in [0, 63]
  *       (CG_ERR_SHAPE otherwise).  out may equal z_i or msg; partial overlap is
  *       CG_ERR_ALIAS.
  *   cg_prf_words    : out[j] = F(key, first + j), j < n: the raw PRF stream.
@@ -389,7 +390,7 @@ CG_API cg_status cg_prf_words(const uint8_t *key, uint64_t nonce, uint64_t first
 /*
  * Gates on BINARY replicated shares (Sec. III-B "Most significant bit": the sign of
  * a shared value is found by adding its three arithmetic shares in a Boolean addition
- * circuit over binary shares, "a sequence of bitwise AND and XOR operations").  A
+ * circuit over binary shares built from bitwise AND and XOR gates).  A
  * 64-bit word carries 64 independent bits, each shared as v = v_0 ^ v_1 ^ v_2 with
  * P_i holding the pair (v_i, v_{i+1}); n counts words.
  *

@@ -14,8 +14,7 @@ from typing import Optional, Sequence, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# CG_LIBRARY may name another build of the same library (tuning experiments)
-LIB_PATH = os.environ.get("CG_LIBRARY") or os.path.join(_HERE, "libcg.so")
+LIB_PATH = os.path.join(_HERE, "libcg.so")
 
 (CG_OK, CG_ERR_NULL, CG_ERR_SHAPE, CG_ERR_ALIGN, CG_ERR_ALIAS, CG_ERR_UNSUPPORTED, CG_ERR_DEVICE,
  CG_ERR_WORKSPACE) = range(8)

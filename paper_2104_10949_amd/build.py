@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcg.so")
-PROBE_LIB = os.path.join(HERE, "libcg_probe.so")  # MFMA issue-rate microbenchmark for bench.py, not part of libcg
+PROBE_SRC = os.path.join(ROOT, "bench_mfma_probe.hip")  # MFMA issue-rate microbenchmark of bench.py, not part of libcg
+PROBE_LIB = os.path.join(ROOT, "libbench_mfma_probe.so")
 SOURCES = ["cg_api.hip", "share_gemm.hip", "share_gemm_f64.hip", "prf.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -30,7 +31,7 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
-    cmd = ["hipcc", *FLAGS, "-shared", "-o", PROBE_LIB, os.path.join(CSRC, "mfma_probe.hip")]
+    cmd = ["hipcc", *FLAGS, "-shared", "-o", PROBE_LIB, PROBE_SRC]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

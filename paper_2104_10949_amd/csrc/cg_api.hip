@@ -2,6 +2,7 @@
 // the address generator, and the element-wise share operations.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "cg.h"
 #include "prf.h"
@@ -1189,12 +1190,12 @@ cg_status cg_share_col_sum(const uint64_t* xa, const uint64_t* xb, uint64_t* za,
             overlap(zb, zbytes, xb, xbytes))
             return CG_ERR_ALIAS;
     }
+    const size_t col_tiles = (cols + 63) / 64;
+    if (rows > 0 && col_tiles > 0x7FFFFFFF) return CG_ERR_UNSUPPORTED;  // before anything is launched
     size_t zblocks = (cols + 255) / 256;
     if (zblocks > 1024) zblocks = 1024;
     hipLaunchKernelGGL(zero2_kernel, dim3((unsigned)zblocks), dim3(256), 0, s, za, zb, cols);
     if (rows > 0) {
-        const size_t col_tiles = (cols + 63) / 64;
-        if (col_tiles > 0x7FFFFFFF) return CG_ERR_UNSUPPORTED;
         // about eight blocks per compute unit, at least 16 rows per wave
         size_t row_blocks = (2048 + col_tiles - 1) / col_tiles;
         const size_t max_rb = (rows + 63) / 64;
@@ -1438,6 +1439,10 @@ cg_status cg_trunc1_local(const uint64_t* z_i, const uint64_t* msg, const uint8_
                           uint64_t* out, size_t n, void* stream) {
     if (!key_self || !key_prev) return CG_ERR_NULL;
     if (d < 0 || d > 63) return CG_ERR_SHAPE;
+    // a mask drawn from one of the alpha streams themselves would cancel against alpha instead of blinding
+    if (key_mask && mask_nonce == nonce &&
+        (memcmp(key_mask, key_self, 16) == 0 || memcmp(key_mask, key_prev, 16) == 0))
+        return CG_ERR_SHAPE;
     if (n == 0) return CG_OK;
     if (!z_i || !out) return CG_ERR_NULL;
     if (!aligned(z_i, 8) || !aligned(out, 8) || (msg && !aligned(msg, 8))) return CG_ERR_ALIGN;

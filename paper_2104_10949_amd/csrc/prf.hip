@@ -174,8 +174,8 @@ __device__ __forceinline__ u64 asr64(u64 v, int d) { return (u64)((int64_t)v >> 
 // binary shares (xor_mode, ALPHA only):  out = (z ? z : 0) ^ F(self, j) ^ F(prev, j).
 // One thread handles one AES block = two consecutive words of each stream.
 template <bool ALPHA, bool MASK>
-__global__ __launch_bounds__(PRF_THREADS) void prf_combine_kernel(const u64* __restrict__ z, const u64* __restrict__ msg,
-                                                          u64* __restrict__ out, size_t n, u64 first, u64 nonce,
+__global__ __launch_bounds__(PRF_THREADS) void prf_combine_kernel(const u64* z, const u64* msg,
+                                                          u64* out, size_t n, u64 first, u64 nonce,
                                                           u64 mask_nonce, int d, bool add_mask, bool xor_mode,
                                                           const PrfKeys keys, const T0Table table) {
     __shared__ __attribute__((aligned(16))) u32 tables[2 * 256 * 64];  // T0 then T2, one copy per bank

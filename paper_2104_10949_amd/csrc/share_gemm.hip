@@ -44,26 +44,6 @@
 
 #include "share_gemm.h"
 
-// tuning knobs of the hand-placed issue order (see half_step() in the kernel)
-#ifndef CG_PRE_NUM
-#define CG_PRE_NUM 3   // eighths of a half-step's MFMAs issued before the split work starts
-#endif
-#ifndef CG_PIPE
-#define CG_PIPE 1      // 1: words are split in the half-step that loads them; 2: one half-step later
-#endif
-#ifndef CG_TILE
-#define CG_TILE 4, 2, 1, 1
-#endif
-#ifndef CG_A_AHEAD
-#define CG_A_AHEAD 1   // how many digits ahead the left operand's fragments are fetched from LDS
-#endif
-#ifndef CG_B_AHEAD
-#define CG_B_AHEAD 2   // how many MFMA slots ahead the right operand's fragments are fetched
-#endif
-#ifndef CG_MINBLOCKS
-#define CG_MINBLOCKS 1
-#endif
-
 namespace cg {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -81,6 +61,14 @@ static constexpr u32 OOB = 0x80000000u;
 // 2*511 = 1022 half-steps <= 1023.
 static constexpr int SEG_KSTEPS = 511;
 
+// Hand-placed issue order of a half-step (see half_step() in the kernel): the split work of the
+// next half-step starts after PRE_EIGHTHS/8 of the MFMAs; fragments of the left operand are fetched
+// from LDS one digit ahead, those of the right operand two MFMA slots ahead.
+static constexpr int PRE_EIGHTHS = 3;
+static constexpr int A_AHEAD = 1;
+static constexpr int B_AHEAD = 2;
+
+
 template <int WM_, int WN_, int SM_, int SN_>
 struct Tile {
     static constexpr int WM = WM_, WN = WN_, SM = SM_, SN = SN_;
@@ -94,6 +82,8 @@ struct Tile {
     static constexpr int STAGE = A_BYTES + B_BYTES;
     static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
 };
+// Default block tile: 4 x 2 waves, one 32x32 sub-tile per wave = 128 x 64.
+typedef Tile<4, 2, 1, 1> DefaultTile;
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, u32 bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
@@ -582,7 +572,7 @@ __device__ __forceinline__ void fold_tile(const GemmParams& p, v16i (&acc)[SM][S
 // STREAM selects the streamed work distribution (see run_index); the classic instantiation runs
 // exactly one pass and compiles to straight-line set-up code.
 template <class T, int AMODE, int BMODE, bool STREAM>
-__global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const GemmParams p) {
+__global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p) {
     constexpr int SM = T::SM, SN = T::SN, AU = T::A_UNITS, BU = T::B_UNITS;
     __shared__ __attribute__((aligned(16))) char lds[2 * T::STAGE];
 
@@ -803,11 +793,11 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     // keeps the compiler from regrouping them.  Every index is a compile-time
     // constant.
     constexpr int NMFMA = 36 * SM * SN;
-    constexpr int PRE = NMFMA * CG_PRE_NUM / 8;
+    constexpr int PRE = NMFMA * PRE_EIGHTHS / 8;
     constexpr int LAST = NMFMA - 2 * SM * SN;  // the final slots only drain
     auto half_step = [&](const char* cur, char* nxt, auto even_c, auto&& issue_loads) {
         v4i bf[SN][8];
-        v4i af[CG_A_AHEAD + 1][SM];
+        v4i af[A_AHEAD + 1][SM];
         auto read_b = [&](int m) {
 #pragma unroll
             for (int sn = 0; sn < SN; ++sn)
@@ -816,26 +806,26 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
         auto read_a = [&](int l) {
 #pragma unroll
             for (int sm = 0; sm < SM; ++sm)
-                af[l % (CG_A_AHEAD + 1)][sm] = *reinterpret_cast<const v4i*>(cur + a_frag + l * 2 * T::A_RS + sm * 512);
+                af[l % (A_AHEAD + 1)][sm] = *reinterpret_cast<const v4i*>(cur + a_frag + l * 2 * T::A_RS + sm * 512);
         };
         // fragments of the first MFMA first; the other initial reads are not waited for
         read_a(0);
         read_b(0);
-        static_for<1, CG_B_AHEAD>([&](auto m_c) { read_b(decltype(m_c)::value); });
-        static_for<1, CG_A_AHEAD>([&](auto l_c) { read_a(decltype(l_c)::value); });
+        static_for<1, B_AHEAD>([&](auto m_c) { read_b(decltype(m_c)::value); });
+        static_for<1, A_AHEAD>([&](auto l_c) { read_a(decltype(l_c)::value); });
         __builtin_amdgcn_sched_barrier(0);
         static_for<0, NMFMA>([&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
             constexpr Slot sl = decode_slot(slot, SM, SN);
             constexpr int l = sl.l, m = sl.m, sm = sl.sm, sn = sl.sn;
             if constexpr (sm == 0 && sn == 0) {
-                if constexpr (l == 0 && m + CG_B_AHEAD < 8) read_b(m + CG_B_AHEAD);
-                // the register set of digit l + CG_A_AHEAD is free once digit l - 1 is done, i.e. from the
+                if constexpr (l == 0 && m + B_AHEAD < 8) read_b(m + B_AHEAD);
+                // the register set of digit l + A_AHEAD is free once digit l - 1 is done, i.e. from the
                 // first slot of digit l on; one slot later keeps it clear of the B reads of digit 0
-                if constexpr (m == (l < 7 ? 1 : 0) && l + CG_A_AHEAD < 8) read_a(l + CG_A_AHEAD);
+                if constexpr (m == (l < 7 ? 1 : 0) && l + A_AHEAD < 8) read_a(l + A_AHEAD);
             }
             acc[sm][sn][l + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                af[l % (CG_A_AHEAD + 1)][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
+                af[l % (A_AHEAD + 1)][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
             if constexpr (slot == 0) issue_loads();
             if constexpr (slot >= PRE && slot < LAST) {
                 constexpr int lo = (slot - PRE) * NOPS / (LAST - PRE);
@@ -870,7 +860,6 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
     // needs no "is there a next slice" branch.
     load_even(k_begin);
     split_all(std::true_type{}, st0);
-    if (CG_PIPE == 2) load_odd(k_begin);
     __syncthreads();
 
     // One pass of the outer loop per tile.  In the streamed scheme the LDS pipeline runs straight on
@@ -897,17 +886,12 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_kernel(const G
                         }
                     }
                 };
-                if (CG_PIPE == 2) switch_tile();
                 // even half-step: x_a against w_a + w_b from st0; odd words are split into st1
-                half_step(st0, st1, std::false_type{}, [&]() {
-                    if (CG_PIPE == 2) load_even(next_ks); else load_odd(ks);
-                });
+                half_step(st0, st1, std::false_type{}, [&]() { load_odd(ks); });
                 __syncthreads();
-                if (CG_PIPE != 2) switch_tile();
+                switch_tile();
                 // odd half-step: x_b against w_a from st1; the next even words go to st0
-                half_step(st1, st0, std::true_type{}, [&]() {
-                    if (CG_PIPE == 2) load_odd(next_ks); else load_even(next_ks);
-                });
+                half_step(st1, st0, std::true_type{}, [&]() { load_even(next_ks); });
                 __syncthreads();
             }
             fold(fm0, fn0, ks0 > k0 || p.z_add != 0);
@@ -991,7 +975,7 @@ struct PlanesConv {
 };
 
 template <class T, bool CONV>
-__global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_planes_kernel(const GemmParams p) {
+__global__ __launch_bounds__(T::NT, 1) void share_gemm_planes_kernel(const GemmParams p) {
     constexpr int SM = T::SM, SN = T::SN;
     constexpr int AP = T::BM * 16 / T::NT, BP = T::BN * 16 / T::NT;  // 16-byte pieces per thread and half-step
     static_assert(T::BM * 16 % T::NT == 0 && T::BN * 16 % T::NT == 0, "tile does not divide over the threads");
@@ -1078,7 +1062,7 @@ __global__ __launch_bounds__(T::NT, CG_MINBLOCKS) void share_gemm_planes_kernel(
 
     v16i acc[SM][SN][8];
     constexpr int NMFMA = 36 * SM * SN;
-    constexpr int PRE = NMFMA * CG_PRE_NUM / 8;
+    constexpr int PRE = NMFMA * PRE_EIGHTHS / 8;
     constexpr int LAST = NMFMA - 2 * SM * SN;
     auto half_step = [&](const char* cur, char* nxt, auto even_c, auto&& issue_loads) {
         v4i bf[SN][8];
@@ -1157,32 +1141,18 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(u64* z, size_t n) {
 template <class T, int AMODE, int BMODE>
 static hipError_t launch(const GemmParams& p, hipStream_t stream);
 
-#ifndef CG_SPLIT_TARGET
-#define CG_SPLIT_TARGET 256
-#endif
-#ifndef CG_SPLIT_MIN_SLICES
-#define CG_SPLIT_MIN_SLICES 2
-#endif
-
+// Blocks that run at one time: a block's LDS leaves room for one block per compute unit.
+static constexpr int ROUND_BLOCKS = 256;
+// A K range of a split holds at least this many slices.
+static constexpr int SPLIT_MIN_SLICES = 2;
 // Cost of the fixed part of a block (prologue, fold of the accumulators into z), in
 // units of one K slice of the main loop, with a plain store and with atomic adds.
-#ifndef CG_SPLIT_COST_PLAIN
-#define CG_SPLIT_COST_PLAIN 1.0
-#endif
-#ifndef CG_SPLIT_COST_ATOMIC
-#define CG_SPLIT_COST_ATOMIC 2.0
-#endif
+static constexpr double SPLIT_COST_PLAIN = 1.0, SPLIT_COST_ATOMIC = 2.0;
 // The streamed distribution must beat the classic one by this factor of modelled time to be used.
-#ifndef CG_STREAM_MARGIN
-#define CG_STREAM_MARGIN 0.88
-#endif
-// 1: several rounds of unsplit tiles are run as one round of blocks that each walk through whole tiles
-#ifndef CG_PERSIST
-#define CG_PERSIST 1
-#endif
-#ifndef CG_PERSIST_MAX_SLICES
-#define CG_PERSIST_MAX_SLICES 32
-#endif
+static constexpr double STREAM_MARGIN = 0.88;
+// Several rounds of unsplit tiles of at most this many slices are run as one round of blocks that
+// each walk through whole tiles.
+static constexpr int PERSIST_MAX_SLICES = 32;
 
 static int choose_ksplit(int64_t tiles, int nk) {
     // A block's 96 KB of LDS leaves room for one block per compute unit, so a grid runs
@@ -1190,9 +1160,9 @@ static int choose_ksplit(int64_t tiles, int nk) {
     // K makes the blocks shorter, which fills the chip when the tiles alone cannot and
     // shrinks the idle part of the last round otherwise.  The split count with the least
     // modelled time wins: rounds * (slices per block + fixed cost per block).
-    const int units = CG_SPLIT_TARGET;
+    const int units = ROUND_BLOCKS;
     int64_t max_split = 8 * units / tiles;  // at most eight rounds' worth of blocks
-    if (max_split > nk / CG_SPLIT_MIN_SLICES) max_split = nk / CG_SPLIT_MIN_SLICES;
+    if (max_split > nk / SPLIT_MIN_SLICES) max_split = nk / SPLIT_MIN_SLICES;
     int best = 1;
     double best_cost = 0;
     for (int64_t ks = 1; ks <= (max_split < 1 ? 1 : max_split); ++ks) {
@@ -1200,7 +1170,7 @@ static int choose_ksplit(int64_t tiles, int nk) {
         const int64_t eff = (nk + per - 1) / per;  // no empty splits
         if (eff != ks) continue;
         const int64_t rounds = (tiles * eff + units - 1) / units;
-        const double cost = (double)rounds * ((double)per + (eff > 1 ? CG_SPLIT_COST_ATOMIC : CG_SPLIT_COST_PLAIN));
+        const double cost = (double)rounds * ((double)per + (eff > 1 ? SPLIT_COST_ATOMIC : SPLIT_COST_PLAIN));
         if (ks == 1 || cost < best_cost * 0.97) {  // a split must pay for itself by a margin
             best = (int)eff;
             best_cost = cost;
@@ -1252,9 +1222,9 @@ hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream) {
 // z = 0 ahead of a launch whose blocks add into it (unless the caller has done so: a
 // scattered output is cleared by the caller, who knows its extent; or z holds a value
 // the product is to be added to)
-static void launch_zero_fill(const GemmParams& p, hipStream_t stream) {
-    if (p.z_prezeroed || p.z_add) return;
-    (void)launch_zero_words(p.z, (size_t)p.M * (size_t)p.N, stream);  // a failed launch shows in the product's own launch status
+static hipError_t launch_zero_fill(const GemmParams& p, hipStream_t stream) {
+    if (p.z_prezeroed || p.z_add) return hipSuccess;
+    return launch_zero_words(p.z, (size_t)p.M * (size_t)p.N, stream);
 }
 
 hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,
@@ -1269,12 +1239,13 @@ hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst,
 }
 
 hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t stream) {
-    typedef Tile<CG_TILE> T;
+    typedef DefaultTile T;
     const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
     GemmParams q = p;
     q.ksplit = choose_ksplit(tiles_m * tiles_n, (p.K + 31) / 32);
     q.group_m = choose_group_m(p, tiles_m, tiles_n, q.ksplit);
-    if (q.ksplit > 1) launch_zero_fill(q, stream);
+    if (q.ksplit > 1)
+        if (hipError_t e = launch_zero_fill(q, stream)) return e;
     const dim3 grid((unsigned)(tiles_m * tiles_n * q.ksplit));
     if (conv) hipLaunchKernelGGL((share_gemm_planes_kernel<T, true>), grid, dim3(T::NT), 0, stream, q);
     else hipLaunchKernelGGL((share_gemm_planes_kernel<T, false>), grid, dim3(T::NT), 0, stream, q);
@@ -1284,8 +1255,8 @@ hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t 
 // Modelled time of the classic distribution with `ks` splits, in K slices (see choose_ksplit).
 static double classic_cost(int64_t tiles, int nk, int ks) {
     const int64_t per = (nk + ks - 1) / ks;
-    const int64_t rounds = (tiles * ks + CG_SPLIT_TARGET - 1) / CG_SPLIT_TARGET;
-    return (double)rounds * ((double)per + (ks > 1 ? CG_SPLIT_COST_ATOMIC : CG_SPLIT_COST_PLAIN));
+    const int64_t rounds = (tiles * ks + ROUND_BLOCKS - 1) / ROUND_BLOCKS;
+    return (double)rounds * ((double)per + (ks > 1 ? SPLIT_COST_ATOMIC : SPLIT_COST_PLAIN));
 }
 
 // The streamed distribution is compiled for the address generators of the large layers only.
@@ -1308,10 +1279,10 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     // units.  A block pays the fixed cost once per tile its run touches (about per/nk + 1 of them).
     // Worth it when the classic grid leaves a round partly empty.
     const int64_t units = tiles * nk;
-    if (CanStream<AMODE, BMODE>::value && units >= 3 * CG_SPLIT_TARGET && units < ((int64_t)1 << 40)) {
-        const int64_t per = (units + CG_SPLIT_TARGET - 1) / CG_SPLIT_TARGET;
-        const double streamed = (double)per + CG_SPLIT_COST_ATOMIC * ((double)per / nk + 1.0);
-        if (streamed < CG_STREAM_MARGIN * classic_cost(tiles, nk, q.ksplit)) {
+    if (CanStream<AMODE, BMODE>::value && units >= 3 * ROUND_BLOCKS && units < ((int64_t)1 << 40)) {
+        const int64_t per = (units + ROUND_BLOCKS - 1) / ROUND_BLOCKS;
+        const double streamed = (double)per + SPLIT_COST_ATOMIC * ((double)per / nk + 1.0);
+        if (streamed < STREAM_MARGIN * classic_cost(tiles, nk, q.ksplit)) {
             q.stream_per = per;
             q.ksplit = 2;  // any value above 1: the folds add atomically into a zero-filled z
             grid = (unsigned)((units + per - 1) / per);
@@ -1326,14 +1297,15 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     // Row-major left operands only: a patch gather re-reads the rows of neighbouring tiles, which hit in L2
     // when the neighbours run at the same time and miss when one block takes them one after the other
     // (measured on the 3x3 layers of the VGG-shaped step: twice the memory reads for 1-3 % of time).
-    if (CG_PERSIST && CanStream<AMODE, BMODE>::value && AMODE == A_LINEAR_VEC && q.stream_per == 0 && q.ksplit == 1 &&
-        tiles > CG_SPLIT_TARGET && nk <= CG_PERSIST_MAX_SLICES) {
-        const int64_t tiles_per_block = (tiles + CG_SPLIT_TARGET - 1) / CG_SPLIT_TARGET;
+    if (CanStream<AMODE, BMODE>::value && AMODE == A_LINEAR_VEC && q.stream_per == 0 && q.ksplit == 1 &&
+        tiles > ROUND_BLOCKS && nk <= PERSIST_MAX_SLICES) {
+        const int64_t tiles_per_block = (tiles + ROUND_BLOCKS - 1) / ROUND_BLOCKS;
         q.stream_per = tiles_per_block * nk;
         grid = (unsigned)((tiles + tiles_per_block - 1) / tiles_per_block);
     }
     q.group_m = choose_group_m(p, tiles_m, tiles_n, q.stream_per > 0 ? 1 : q.ksplit);
-    if (q.ksplit > 1) launch_zero_fill(q, stream);
+    if (q.ksplit > 1)
+        if (hipError_t e = launch_zero_fill(q, stream)) return e;
     if constexpr (CanStream<AMODE, BMODE>::value) {
         if (q.stream_per > 0) {
             hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BMODE, true>), dim3(grid), dim3(T::NT), 0, stream, q);
@@ -1345,7 +1317,7 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
 }
 
 hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream) {
-    typedef Tile<CG_TILE> T;  // waves along M, waves along N, 32x32 sub-tiles per wave along M, along N
+    typedef DefaultTile T;  // waves along M, waves along N, 32x32 sub-tiles per wave along M, along N
     // Weight gradients have M = Cout: when the last 128-row tile would be at most half
     // full, a 64 x 128 block tile wastes fewer MFMAs.
     if (amode == A_TRANS && bmode == B_PATCH_T && T::BM == 128 && (p.M - 1) % 128 < 64 && p.M <= 448 && p.N > 64)

@@ -154,66 +154,3 @@ def gpu_msb_sliced(cg, x_dev, KEYS, nonce, cells=False):
         else:
             P = G
     return tuple(p0[63] ^ g[0] for p0, g in zip(P0, G))                # XOR of shares: local
-
-
-def gpu_trunc(cg, z, keys, nonce, d):
-    """The two-round truncation protocol on a 3-out-of-3 additive sharing z = (z_0, z_1, z_2) of GPU tensors
-    (e.g. the outputs of the local products, or a replicated sharing read as its three shares): returns the
-    replicated sharing (s_0, s_1, s_2) of about z / 2^d.  PRF streams `nonce` and `nonce + 1`."""
-    n = z[0].numel()
-    msg = cg.cg_reshare(z[2], keys[2], keys[1], nonce, 0)
-    s0 = cg.cg_trunc1_local(z[0], None, keys[0], keys[2], nonce, 0, d)
-    s1 = cg.cg_trunc1_local(z[1], msg, keys[1], keys[0], nonce, 0, d, keys[1], nonce + 1)
-    s2 = cg.cg_prf_words(keys[1], nonce + 1, 0, n).view_as(s0)
-    return (s0, s1, s2)
-
-
-def gpu_mul_trunc(cg, U, V, keys, nonce, t):
-    """Fixed-point product of two replicated sharings at scale 2^t: every party's three-term product on the GPU,
-    then the truncation protocol on the three additive results (its first step blinds them)."""
-    z = tuple(cg.cg_share_mul(U[i], U[(i + 1) % 3], V[i], V[(i + 1) % 3]) for i in range(3))
-    return gpu_trunc(cg, z, keys, nonce, t)
-
-
-
-def softmax_float_model(x, log_m, newton):
-    """The approximations of gpu_softmax in float64, without shares or fixed point."""
-    y = x - x.max(axis=1, keepdims=True)
-    e = (1 + y / 2 ** log_m) ** (2 ** log_m)
-    s = e.sum(axis=1, keepdims=True)
-    z = np.full_like(s, 1 / x.shape[1])
-    for _ in range(newton):
-        z = 2 * z - s * z * z
-    return e * z
-
-
-def gpu_softmax(cg, X, keys, fresh, t, log_m, newton):
-    """Row-wise softmax of a replicated sharing X [batch, d] at scale 2^t, from local steps on the GPU: maximum by a
-    tree of comparisons, (1 + x/m)^m with m = 2^log_m by repeated squaring, reciprocal of the row sums by `newton`
-    Newton-Raphson iterations from the fixed start 1/d.  `fresh()` hands out unused PRF nonces (4 apart).
-    Returns (softmax sharing, sharing of the row maxima)."""
-    import torch
-    d = X[0].shape[1]
-    sub = lambda U, V: tuple(u - v for u, v in zip(U, V))        # linear combinations of shares are local
-    add = lambda U, V: tuple(u + v for u, v in zip(U, V))
-    const = lambda c, like: tuple(torch.full_like(like, int(round(c * 2 ** t))) if k == 0 else torch.zeros_like(like)
-                                  for k in range(3))             # a public constant lives in share 0
-    cols = [tuple(s[:, j].contiguous() for s in X) for j in range(d)]
-    while len(cols) > 1:
-        nxt = [add(b, gpu_relu(cg, sub(a, b), keys, fresh())) for a, b in zip(cols[0::2], cols[1::2])]   # max = b + relu(a - b)
-        if len(cols) % 2:
-            nxt.append(cols[-1])
-        cols = nxt
-    mx = cols[0]
-    Y = tuple((x - m[:, None]).contiguous() for x, m in zip(X, mx))
-    U = add(const(1.0, Y[0]), gpu_trunc(cg, Y, keys, fresh(), log_m))        # 1 + y / m
-    for _ in range(log_m):
-        U = gpu_mul_trunc(cg, U, U, keys, fresh(), t)
-    S = tuple(u.sum(dim=1, keepdim=True).contiguous() for u in U)            # sums of shares are local
-    Z = const(1.0 / d, S[0])
-    for _ in range(newton):
-        Z2 = gpu_mul_trunc(cg, Z, Z, keys, fresh(), t)
-        SZ2 = gpu_mul_trunc(cg, S, Z2, keys, fresh(), t)
-        Z = sub(add(Z, Z), SZ2)
-    Zb = tuple(z.expand(-1, d).contiguous() for z in Z)
-    return gpu_mul_trunc(cg, U, Zb, keys, fresh(), t), mx

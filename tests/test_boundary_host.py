@@ -233,6 +233,13 @@ def test_truncation_and_binary_gate_validation(L):
     assert f(P, None, k, k, 0, 0, 16, None, 0, P + 8, 8, None) == b.CG_ERR_ALIAS
     assert f(P, None, k, k, 0, (1 << 64) - 2, 16, None, 0, 2 * P, 8, None) == b.CG_ERR_SHAPE
     assert f(0, None, k, k, 0, 0, 16, None, 0, 0, 0, None) == b.CG_OK
+    # a mask stream that coincides with one of the two alpha streams (same key AND same nonce) blinds nothing
+    k1, k2, k3 = bytes(range(16)), bytes(range(16, 32)), bytes(range(32, 48))
+    assert f(P, None, k1, k2, 5, 0, 16, bytes(k1), 5, 2 * P, 8, None) == b.CG_ERR_SHAPE
+    assert f(P, None, k1, k2, 5, 0, 16, bytes(k2), 5, 2 * P, 8, None) == b.CG_ERR_SHAPE
+    assert f(0, None, k1, k2, 5, 0, 16, k1, 5, 0, 0, None) == b.CG_ERR_SHAPE       # checked even for n == 0
+    assert f(0, None, k1, k2, 5, 0, 16, k1, 6, 0, 0, None) == b.CG_OK              # another nonce is fine
+    assert f(0, None, k1, k2, 5, 0, 16, k3, 5, 0, 0, None) == b.CG_OK              # another key is fine
     assert L.cg_prf_words(None, 0, 0, P, 8, None) == b.CG_ERR_NULL
     assert L.cg_prf_words(k, 0, 0, P + 2, 8, None) == b.CG_ERR_ALIGN
     assert L.cg_prf_words(k, 0, 0, 0, 0, None) == b.CG_OK
