@@ -121,6 +121,29 @@ CG_API cg_status cg_share_matmul_ws(const uint64_t *x_i, const uint64_t *x_ip1,
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * cg_share_matmul for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  The digit planes of cg_share_matmul_ws go to a fixed
+ * array of CG_STATIC_SCRATCH_BYTES bytes inside the library's device image
+ * (one copy per GPU, held until the process ends); the call itself allocates and
+ * frees nothing.  Result and argument rules are those of cg_share_matmul, bit
+ * for bit.  CG_ERR_WORKSPACE when cg_share_matmul_workspace_bytes(M, N, K)
+ * exceeds CG_STATIC_SCRATCH_BYTES (nothing is launched then); products the digit
+ * route does not apply to (odd K, 8-byte-aligned pointers) run as
+ * cg_share_matmul, whatever their size.  The array's address is looked up on the
+ * first call on each device, which must be the current device, as for every
+ * call here.  All calls on one GPU share the array and every call overwrites the part
+ * it uses: calls that overlap in time on one GPU (different streams, or
+ * threads) race and must be ordered by the caller.
+ */
+#define CG_STATIC_SCRATCH_BYTES (64u << 20)
+
+CG_API cg_status cg_share_matmul_static(const uint64_t *x_i, const uint64_t *x_ip1,
+                                 const uint64_t *y_i, const uint64_t *y_ip1,
+                                 uint64_t *z_i, int64_t M, int64_t N, int64_t K,
+                                 void *stream);
+
+/*
  * Same local step for a 2-D convolution (Sec. III-B, "Convolutions and matrix
  * multiplication"), evaluated as an implicit matrix product: no patch matrix
  * is ever written to memory.  Convolution means cross-correlation with zero

@@ -26,7 +26,7 @@ EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d
            "cg_trunc1_local", "cg_prf_words", "cg_bshare_xor", "cg_bshare_and", "cg_bshare_prefix_stage",
            "cg_bzero_share", "cg_breshare", "cg_share_bias_add", "cg_share_col_sum",
            "cg_bit_transpose64", "cg_bshare_carry_level", "cg_bits_unpack", "cg_bshare_csa", "cg_bshare_half_adder",
-           "cg_share_matmul_acc", "cg_share_conv2d_acc", "cg_share_matmul_f64limb",
+           "cg_share_matmul_acc", "cg_share_conv2d_acc", "cg_share_matmul_f64limb", "cg_share_matmul_static",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 SIZE_EXPORTS = 2      # the last entries return size_t, the first two a string and an int, the rest cg_status
 
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.cg_share_conv2d.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp]
         L.cg_share_matmul_acc.argtypes = L.cg_share_matmul.argtypes
         L.cg_share_matmul_f64limb.argtypes = L.cg_share_matmul.argtypes
+        L.cg_share_matmul_static.argtypes = L.cg_share_matmul.argtypes
         L.cg_share_conv2d_acc.argtypes = L.cg_share_conv2d.argtypes
         L.cg_share_add.argtypes = [vp] * 6 + [sz, vp]
         L.cg_share_mul_public.argtypes = [vp, vp, u64, vp, vp, sz, vp]
@@ -243,6 +244,24 @@ def cg_share_matmul_ws(x_i, x_ip1, y_i, y_ip1, workspace, z_i=None, stream=None)
     wp, wb = _ws(workspace)
     _check(lib().cg_share_matmul_ws(_ptr(x_i), _ptr(x_ip1), _ptr(y_i), _ptr(y_ip1), _ptr(z_i),
                                     M, N, K, wp, wb, _stream(stream)), "cg_share_matmul_ws")
+    return z_i
+
+
+STATIC_SCRATCH_BYTES = 64 << 20   # CG_STATIC_SCRATCH_BYTES of include/cg.h
+
+
+def cg_share_matmul_static(x_i, x_ip1, y_i, y_ip1, z_i=None, stream=None) -> torch.Tensor:
+    """cg_share_matmul on the library's own fixed scratch array: the call allocates nothing."""
+    M, K = x_i.shape
+    N = y_i.shape[0]
+    if x_ip1.shape != x_i.shape or y_ip1.shape != y_i.shape or y_i.shape[1] != K:
+        raise ValueError("operand shapes do not match")
+    if z_i is None:
+        z_i = torch.empty((M, N), dtype=torch.int64, device=x_i.device)
+    elif tuple(z_i.shape) != (M, N):
+        raise ValueError("output shape does not match")
+    _check(lib().cg_share_matmul_static(_ptr(x_i), _ptr(x_ip1), _ptr(y_i), _ptr(y_ip1), _ptr(z_i),
+                                        M, N, K, _stream(stream)), "cg_share_matmul_static")
     return z_i
 
 

@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "cg.h"
 #include "prf.h"
 #include "share_gemm.h"
@@ -585,7 +587,7 @@ const char* cg_status_string(cg_status s) {
         case CG_ERR_ALIAS: return "CG_ERR_ALIAS: output overlaps an input";
         case CG_ERR_UNSUPPORTED: return "CG_ERR_UNSUPPORTED: shape outside the kernels' addressing range";
         case CG_ERR_DEVICE: return "CG_ERR_DEVICE: HIP launch error";
-        case CG_ERR_WORKSPACE: return "CG_ERR_WORKSPACE: scratch memory smaller than cg_*_workspace_bytes()";
+        case CG_ERR_WORKSPACE: return "CG_ERR_WORKSPACE: scratch memory smaller than the product needs (cg_*_workspace_bytes())";
     }
     return "unknown cg_status";
 }
@@ -1031,6 +1033,49 @@ cg_status cg_share_matmul_ws(const uint64_t* x_i, const uint64_t* x_ip1, const u
     if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl)) return st;
     if (!pl.planes_ok) return run_direct(pl, stream);
     return run_planes(pl, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+// Scratch memory of cg_share_matmul_static: a fixed array in the library's own device image, so that
+// the call never allocates.  Every GPU that loads the library holds its own copy at its own address;
+// on the host the array's name is only a handle for hipGetSymbolAddress, never an address to pass on.
+static __device__ __align__(256) unsigned char scratch[CG_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+const int MAX_DEVICES = 64;
+void* scratch_ptr[MAX_DEVICES];   // device address of `scratch` on device d, once looked up
+std::mutex scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up on the first call per device).
+cg_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return CG_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CG_ERR_DEVICE;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return CG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+cg_status cg_share_matmul_static(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
+                                 const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
+                                 void* stream) {
+    Plan pl;
+    if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl)) return st;
+    if (!pl.planes_ok) return run_direct(pl, stream);
+    if (plan_workspace_bytes(pl) > (u64)CG_STATIC_SCRATCH_BYTES) return CG_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    if (cg_status st = static_scratch(&ptr)) return st;
+    return run_planes(pl, ptr, (size_t)CG_STATIC_SCRATCH_BYTES, stream);
 }
 
 cg_status cg_share_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* w_i,

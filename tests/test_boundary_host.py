@@ -221,6 +221,21 @@ def test_conv_backward_validation(L):
     assert L.cg_share_conv2d_wgrad(*ok, desc(Cout=(1 << 22) + 1), None) == b.CG_ERR_UNSUPPORTED
 
 
+def test_static_scratch_entry_point_validates_and_bounds_its_size(L):
+    from paper_2104_10949_amd import binding as b
+    f = L.cg_share_matmul_static
+    G = 1 << 32   # fake pointers far enough apart for 128 MB operands
+    far = [G, 2 * G, 3 * G, 4 * G, 5 * G]
+    assert f(0, *far[1:], 4, 4, 4, None) == b.CG_ERR_NULL
+    assert f(*far, 4, 0, 4, None) == b.CG_ERR_SHAPE
+    assert f(*far[:4], far[0] + 8, 4, 4, 4, None) == b.CG_ERR_ALIAS
+    # 2 * (4096 + 4096) rows of 4096 words as digit planes are 512 MiB: beyond the fixed array, refused on the host
+    assert L.cg_share_matmul_workspace_bytes(4096, 4096, 4096) > b.STATIC_SCRATCH_BYTES
+    assert f(*far, 4096, 4096, 4096, None) == b.CG_ERR_WORKSPACE
+    text = open(os.path.join(ROOT, "include", "cg.h")).read()
+    assert re.search(r"#define\s+CG_STATIC_SCRATCH_BYTES\s+\(64u << 20\)", text) and b.STATIC_SCRATCH_BYTES == 64 << 20
+
+
 def test_truncation_and_binary_gate_validation(L):
     from paper_2104_10949_amd import binding as b
     k = bytes(16)
