@@ -85,6 +85,31 @@ struct Tile {
 // Default block tile: 4 x 2 waves, one 32x32 sub-tile per wave = 128 x 64.
 typedef Tile<4, 2, 1, 1> DefaultTile;
 
+// Block tile of the fused kernel: WM x WN waves, each computing a 32 x 32 sub-tile as 2 x 2 blocks of
+// v_mfma_i32_16x16x64_i8.  One step covers a 32-word slice of K for BOTH shares of each operand:
+// the 64 contraction bytes of an instruction are [x_a | x_b] against [w_a + w_b | w_a], 16 bytes per
+// "k-group" (two halves of the slice times two shares).  LDS holds digit planes
+//     [digit][k-group 4][row][16 bytes]
+// for the left operand in two parts, digits 0-3 (two buffers) and digits 4-7 (one buffer), and for
+// the right operand in two buffers of all eight digits: 3*A_HALF + 2*B_ALL bytes (160 KB at 128 x 64).
+template <int WM_, int WN_>
+struct StepTile {
+    static constexpr int WM = WM_, WN = WN_;
+    static constexpr int BM = WM * 32, BN = WN * 32;
+    static constexpr int NT = WM * WN * 64;
+    // A "unit" is 4 words of one row of one share: two 16-byte loads, eight 4-byte LDS writes.
+    static constexpr int A_UNITS = BM * 8 / NT, B_UNITS = BN * 8 / NT;
+    static constexpr int A_RS = BM * 16, B_RS = BN * 16;      // one [digit][k-group] slab
+    static constexpr int A_DIG = 4 * A_RS, B_DIG = 4 * B_RS;  // one digit
+    static constexpr int A_HALF = 4 * A_DIG, B_ALL = 8 * B_DIG;
+    static constexpr int OFF_AHI = 2 * A_HALF, OFF_B = 3 * A_HALF;
+    static constexpr int LDS_BYTES = 3 * A_HALF + 2 * B_ALL;
+    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
+    static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the LDS of a compute unit");
+    static_assert(3 * A_DIG + 256 < 65536 && 7 * B_DIG + 256 < 65536, "fragment offsets must fit an LDS immediate");
+};
+typedef StepTile<4, 2> DefaultStepTile;
+
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, u32 bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
@@ -568,40 +593,140 @@ __device__ __forceinline__ void fold_tile(const GemmParams& p, v16i (&acc)[SM][S
         }
 }
 
+// fold of the fused kernel's accumulators: the wave's 32 x 32 sub-tile is 2 x 2 blocks of 16 x 16, and
+// lane i holds rows 4*(i/16) .. +3 of column i%16 of each block.  Modes as in fold_tile.
+template <bool REMAP>
+__device__ __forceinline__ void fold_blocks(const GemmParams& p, v4i (&acc)[2][2][8], int row0, int col0, int lane,
+                                            bool accumulate) {
+    int lane_f = lane;
+    asm volatile("" : "+v"(lane_f));
+    const int c16 = lane_f & 15, g4 = lane_f >> 4;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const int col = col0 + cb * 16 + c16;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = row0 + rb * 16 + 4 * g4 + i;
+                u64 v = (u64)(int64_t)acc[rb][cb][0][i];
+                v += (u64)(int64_t)acc[rb][cb][1][i] << 8;
+                v += (u64)(int64_t)acc[rb][cb][2][i] << 16;
+                v += (u64)(int64_t)acc[rb][cb][3][i] << 24;
+                const u32 hi = (u32)acc[rb][cb][4][i] + ((u32)acc[rb][cb][5][i] << 8) +
+                               ((u32)acc[rb][cb][6][i] << 16) + ((u32)acc[rb][cb][7][i] << 24);
+                v += (u64)hi << 32;
+                if (row < p.M && col < p.N) {
+                    u64 zrow = (u64)row;
+                    if constexpr (REMAP) {
+                        const u32 b = fast_div((u32)row, p.div_howo);
+                        const u32 rem = (u32)row - b * (u32)(p.Ho * p.Wo);
+                        const u32 i_ = fast_div(rem, p.div_wo), j_ = rem - i_ * (u32)p.Wo;
+                        zrow = ((u64)b * (u64)p.out_H + (u64)(p.out_h0 + p.out_sh * (int)i_)) * (u64)p.out_W +
+                               (u64)(p.out_w0 + p.out_sw * (int)j_);
+                    }
+                    u64* dst = p.z + zrow * (u64)p.N + (u64)col;
+                    if (p.ksplit > 1) {
+                        atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
+                    } else {
+                        if (accumulate) v += *dst;
+                        *dst = v;
+                    }
+                }
+            }
+        }
+}
+
+// The digit pairs (l, m), l + m <= 7, of one step in issue order, in two phases.
+//   Phase 1: the ten pairs with l >= 4, grouped by m = 0, 1, 2, 3, l descending inside a group (they read
+//            digits 4-7 of the left operand, whose single LDS buffer the next slice overwrites in phase 2).
+//   Phase 2: the 26 pairs with l <= 3, grouped by m = 2, 3, 0, 1, 4, 5, 6, 7, l descending inside a group.
+// A wave keeps four left-operand digits in registers (4-7 in phase 1; digits 3, 2, 1, 0 take the places of
+// 7, 6, 5, 4 as those retire) and two right-operand digits (digit m lives in set m & 1 and is fetched when
+// the previous holder's group is done; the groups of m = 2, 3 come first in phase 2 because these digits are
+// the ones left in registers by phase 1).
+struct Pair {
+    int l, m;
+};
+constexpr Pair phase1_pair(int i) {
+    int m = 0, cnt = 4;
+    while (i >= cnt) { i -= cnt; ++m; --cnt; }
+    return Pair{7 - m - i, m};
+}
+constexpr int phase2_group(int g) { return g < 2 ? g + 2 : (g < 4 ? g - 2 : g); }  // m of the g-th group
+constexpr Pair phase2_pair(int i) {
+    int g = 0;
+    while (true) {
+        const int m = phase2_group(g);
+        const int cnt = m <= 4 ? 4 : 8 - m;  // digits l = cnt-1 .. 0
+        if (i < cnt) return Pair{cnt - 1 - i, m};
+        i -= cnt;
+        ++g;
+    }
+}
+// first slot after the last MFMA that uses right-operand digit m in its phase
+constexpr int phase1_group_end(int m) {
+    int slots = 0;
+    for (int mm = 0; mm <= m; ++mm) slots += 4 * (4 - mm);
+    return slots;
+}
+constexpr int phase2_group_end(int g) {
+    int slots = 0;
+    for (int gg = 0; gg <= g; ++gg) {
+        const int m = phase2_group(gg);
+        slots += 4 * (m <= 4 ? 4 : 8 - m);
+    }
+    return slots;
+}
+
 // ---------------------------------------------------------------------------
-// STREAM selects the streamed work distribution (see run_index); the classic instantiation runs
-// exactly one pass and compiles to straight-line set-up code.
+// A block's range of (tile, slice) units, walked one slice at a time.  Three walkers go over the same
+// range at different distances: the MFMA loop, the loads of the left operand one slice ahead of it and
+// the loads of the right operand up to two slices ahead.  All members are uniform over the block.
+struct Walker {
+    int64_t u, u_end;   // first unit after the current tile's share of the range; end of the range
+    int logical;        // current tile in launch order
+    int ks, nk;         // current slice; end of the current tile's slices
+};
+
+// STREAM selects the streamed work distribution (see run_index); the classic instantiation has exactly
+// one tile per block and compiles to straight-line set-up code.
 template <class T, int AMODE, int BMODE, bool STREAM>
 __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p) {
-    constexpr int SM = T::SM, SN = T::SN, AU = T::A_UNITS, BU = T::B_UNITS;
-    __shared__ __attribute__((aligned(16))) char lds[2 * T::STAGE];
+    constexpr int AU = T::A_UNITS, BU = T::B_UNITS;
+    __shared__ __attribute__((aligned(16))) char lds[T::LDS_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % T::WM, wn = wave / T::WM;
-    const int r32 = lane & 31, h = lane >> 5;
+    const int r16 = lane & 15, kg = lane >> 4;
 
-    // ---- this block's range [u, u_end) of (tile, slice) units
+    // ---- this block's range [u0, u_end) of (tile, slice) units
     const int tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
     const int nb = tiles_m * tiles_n;
     const int nk_all = (int)((p.K + 31) / 32);
-    int64_t u, u_end;
+    int64_t u0, u_end;
     if constexpr (STREAM) {
         const int64_t units = (int64_t)nb * nk_all;
-        u = (int64_t)run_index((int)gridDim.x) * p.stream_per;
-        u_end = u + p.stream_per < units ? u + p.stream_per : units;
+        u0 = (int64_t)run_index((int)gridDim.x) * p.stream_per;
+        u_end = u0 + p.stream_per < units ? u0 + p.stream_per : units;
     } else {
         const int run = run_index(nb * p.ksplit);
         const int split = run / nb, logical = run - split * nb;
         const int per_split = (nk_all + p.ksplit - 1) / p.ksplit;
         const int kb = split * per_split;
-        u = (int64_t)logical * nk_all + kb;
+        u0 = (int64_t)logical * nk_all + kb;
         u_end = (int64_t)logical * nk_all + (kb + per_split < nk_all ? kb + per_split : nk_all);
     }
+    if (u0 >= u_end) return;  // uniform over the block
 
-    // One pass per tile the range touches (exactly one in the classic scheme).  Everything that depends
-    // on the tile lives in the variables below and is (re)computed by setup_tile(), which takes the
-    // next tile of the range: [k_begin, nk) are its slices, (m0, n0) its first row and column.
-    if (u >= u_end) return;  // uniform over the block
+    // take the tile that starts at unit w.u: its slices [w.ks, w.nk)
+    auto enter_tile = [&](Walker& w) {
+        w.logical = (int)(w.u / nk_all);
+        w.ks = (int)(w.u - (int64_t)w.logical * nk_all);
+        w.nk = (int64_t)w.ks + (w.u_end - w.u) < nk_all ? w.ks + (int)(w.u_end - w.u) : nk_all;
+        w.u += w.nk - w.ks;
+    };
+
     constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
     constexpr bool A_TR = AMODE == A_TRANS;
     // right-operand modes whose memory is contiguous along n: consecutive lanes take consecutive rows
@@ -617,51 +742,37 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             typename std::conditional<BMODE == B_SCALAR, LinearScalar,
             typename std::conditional<BMODE == B_FLIP_GEN, FlipGen,
             typename std::conditional<BMODE == B_PATCH_T, PatchTrans, TransScalar>::type>::type>::type>::type BGen;
-    int k_begin, nk, m0, n0;
-    u64 a_base_elems, b_base_elems;
     const u64 w_elems = p.w_elems;
-    TapCursor tap;
-    __amdgpu_buffer_rsrc_t rs_xa, rs_xb, rs_wa, rs_wb;  // views, rebased per tile so that 32-bit offsets suffice
-    AGen ag[AU];
-    BGen bg[BU];
-    int a_dst[AU], b_dst[BU];  // LDS byte offset of digit 0 inside a stage
     // view on `elems_total` words starting `base` words in
     auto view = [&](const u64* ptr, u64 elems_total, u64 base) {
         const u64 left = (elems_total - base) * 8u;
         return make_rsrc(ptr + base, left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left);
     };
-    // where a thread's units go inside a stage does not depend on the tile
+
+    // ---- loader of the left operand: walker, views rebased per tile so that 32-bit offsets suffice,
+    // address generators, tap cursor of the patch gather
+    Walker wa_;
+    u64 a_base_elems;
+    TapCursor tap_a;
+    __amdgpu_buffer_rsrc_t rs_xa, rs_xb;
+    AGen ag[AU];
+    int a_dst[AU];  // LDS byte offset of a unit inside the slab set of digit 0, first share
 #pragma unroll
-    for (int i = 0; i < AU; ++i) {
+    for (int i = 0; i < AU; ++i) {   // where a thread's units go does not depend on the tile
         const int t = tid + i * T::NT;
         const int q = A_TR ? (t / T::BM) & 3 : t & 3, row = A_TR ? t % T::BM : (t >> 2) % T::BM, jh = (t >> 2) / T::BM;
         a_dst[i] = jh * T::A_RS + row * 16 + q * 4;
     }
-#pragma unroll
-    for (int i = 0; i < BU; ++i) {
-        const int t = tid + i * T::NT;
-        const int q = B_TR ? (t / T::BN) & 3 : t & 3, row = B_TR ? t % T::BN : (t >> 2) % T::BN, jh = (t >> 2) / T::BN;
-        b_dst[i] = T::A_BYTES + jh * T::B_RS + row * 16 + q * 4;
-    }
-    auto setup_tile = [&]() {
-        const int logical = (int)(u / nk_all);
-        k_begin = (int)(u - (int64_t)logical * nk_all);
-        nk = (int64_t)k_begin + (u_end - u) < nk_all ? k_begin + (int)(u_end - u) : nk_all;
-        u += nk - k_begin;
+    auto setup_a = [&]() {
         int tm, tn;
-        logical_to_tile(p, tiles_m, tiles_n, logical, tm, tn);
-        m0 = tm * T::BM;
-        n0 = tn * T::BN;
-        const int rows_m = p.M - m0, rows_n = p.N - n0;
+        logical_to_tile(p, tiles_m, tiles_n, wa_.logical, tm, tn);
+        const int m0 = tm * T::BM, rows_m = p.M - m0;
         if (A_LINEAR) a_base_elems = (u64)m0 * (u64)p.lda;
         else if (A_TR) a_base_elems = (u64)m0;
         else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
-        b_base_elems = BMODE == B_PATCH_T ? 0 : (B_TR ? (u64)n0 : (u64)n0 * (u64)p.K);
-        tap.reset();
+        tap_a.reset();
         rs_xa = view(p.x_a, p.x_elems, a_base_elems);
         rs_xb = view(p.x_b, p.x_elems, a_base_elems);
-        rs_wa = view(p.w_a, w_elems, b_base_elems);
-        rs_wb = view(p.w_b, w_elems, b_base_elems);
 #pragma unroll
         for (int i = 0; i < AU; ++i) {
             const int t = tid + i * T::NT;
@@ -670,6 +781,28 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             const int jh = (t >> 2) / T::BM;
             ag[i].init(p, m0, row, rows_m, A_TR ? (u32)p.M : (u32)p.lda, q, jh);
         }
+    };
+    // ---- loader of the right operand
+    Walker wb_;
+    u64 b_base_elems;
+    TapCursor tap_b;   // B_FLIP_C32 and the slice order of the patch gather follow the left operand's taps
+    __amdgpu_buffer_rsrc_t rs_wa, rs_wb;
+    BGen bg[BU];
+    int b_dst[BU];
+#pragma unroll
+    for (int i = 0; i < BU; ++i) {
+        const int t = tid + i * T::NT;
+        const int q = B_TR ? (t / T::BN) & 3 : t & 3, row = B_TR ? t % T::BN : (t >> 2) % T::BN, jh = (t >> 2) / T::BN;
+        b_dst[i] = jh * T::B_RS + row * 16 + q * 4;
+    }
+    auto setup_b = [&]() {
+        int tm, tn;
+        logical_to_tile(p, tiles_m, tiles_n, wb_.logical, tm, tn);
+        const int n0 = tn * T::BN, rows_n = p.N - n0;
+        b_base_elems = BMODE == B_PATCH_T ? 0 : (B_TR ? (u64)n0 : (u64)n0 * (u64)p.K);
+        tap_b.reset();
+        rs_wa = view(p.w_a, w_elems, b_base_elems);
+        rs_wb = view(p.w_b, w_elems, b_base_elems);
 #pragma unroll
         for (int i = 0; i < BU; ++i) {
             const int t = tid + i * T::NT;
@@ -682,7 +815,24 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             bg[i].init(p, n0, row, rows_n, pitch, q, jh);
         }
     };
-    setup_tile();
+    // next slice of a loader: the next tile of the range when the current one is used up (streamed
+    // distribution only); past the end of the range the slice index just runs on, and what is loaded
+    // there (zeros beyond K, or words of the next K range) is never used
+    auto advance = [&](Walker& w, auto&& setup) {
+        ++w.ks;
+        if constexpr (STREAM) {
+            if (w.ks == w.nk && w.u < w.u_end) {  // uniform
+                enter_tile(w);
+                setup();
+            }
+        }
+    };
+    wa_.u = u0; wa_.u_end = u_end;
+    enter_tile(wa_);
+    setup_a();
+    wb_ = wa_;
+    setup_b();
+
     // transposed operands: one view per K slice
     auto a_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
         if constexpr (A_TR) {
@@ -692,15 +842,15 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             return fixed;
         }
     };
-    // (B_FLIP_C32 reads the tap cursor, which load_a has moved to slice ks before this is called)
+    // (B_FLIP_C32 reads the right operand's tap cursor, which load_w moves to slice ks first)
     auto b_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
         if constexpr (BMODE == B_TRANS) {
             const u64 base = b_base_elems + (u64)ks * 32u * (u64)p.N;
             return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
         } else if constexpr (BMODE == B_FLIP_C32) {
-            if (tap.c0 >= p.Cin) return make_rsrc(ptr, 0);  // past the end of K
-            const int ftap = (p.flt_r0 + p.flt_sh * (p.kh - 1 - tap.r)) * p.flt_kw + p.flt_s0 + p.flt_sw * (p.kw - 1 - tap.s);
-            const u64 base = b_base_elems + ((u64)tap.c0 * (u64)(p.flt_kh * p.flt_kw) + (u64)ftap) * (u64)p.N;
+            if (tap_b.c0 >= p.Cin) return make_rsrc(ptr, 0);  // past the end of K
+            const int ftap = (p.flt_r0 + p.flt_sh * (p.kh - 1 - tap_b.r)) * p.flt_kw + p.flt_s0 + p.flt_sw * (p.kw - 1 - tap_b.s);
+            const u64 base = b_base_elems + ((u64)tap_b.c0 * (u64)(p.flt_kh * p.flt_kw) + (u64)ftap) * (u64)p.N;
             return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
         } else if constexpr (BMODE == B_PATCH_T) {
             const u64 base = (u64)fast_div(32u * (u32)ks, p.div_howo) * p.img_elems;
@@ -710,193 +860,223 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         }
     };
 
-    // Two sets of staging registers.  E feeds an even half-step (x_a against
-    // w_a + w_b), O an odd one (x_b against w_a).
-    u4 eA[AU][2], eB[BU][2], eB2[BU][2], oA[AU][2], oB[BU][2];
+    // Staging registers: the raw words of one slice of the four share tensors.  They are filled in three
+    // batches (first share of the left operand, second share, right operand), each about a third of a step
+    // ahead of its split, so that only two batches are ever alive at one time.
+    u4 xa[AU][2], xb[AU][2], wa[BU][2], wb[BU][2];
 
     auto load_a = [&](__amdgpu_buffer_rsrc_t rs, int ks, u4 (*dst)[2]) {
         if constexpr (AMODE == A_CONV_C32) {
-            tap.advance_to(p, ks);
+            tap_a.advance_to(p, ks);
 #pragma unroll
-            for (int i = 0; i < AU; ++i) ag[i].load(p, rs, tap, dst[i]);
+            for (int i = 0; i < AU; ++i) ag[i].load(p, rs, tap_a, dst[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < AU; ++i) ag[i].load(p, rs, ks, (u32)p.K, dst[i]);
         }
     };
-    auto load_b = [&](__amdgpu_buffer_rsrc_t rs, int ks, u4 (*dst)[2]) {
+    auto load_xa = [&]() { load_a(a_view(p.x_a, rs_xa, wa_.ks), wa_.ks, xa); };
+    auto load_xb = [&]() { load_a(a_view(p.x_b, rs_xb, wa_.ks), wa_.ks, xb); };
+    auto load_w = [&]() {
+        const int ks = wb_.ks;
+        int kb = ks;
+        if constexpr (AMODE == A_CONV_C32) {  // the right operand follows the left operand's slice order (see TapCursor)
+            tap_b.advance_to(p, ks);
+            kb = tap_b.pks;
+        }
+        const __amdgpu_buffer_rsrc_t ra = b_view(p.w_a, rs_wa, ks), rb = b_view(p.w_b, rs_wb, ks);
 #pragma unroll
-        for (int i = 0; i < BU; ++i) bg[i].load(p, rs, ks, (u32)p.K, dst[i]);
+        for (int i = 0; i < BU; ++i) bg[i].load(p, ra, kb, (u32)p.K, wa[i]);
+#pragma unroll
+        for (int i = 0; i < BU; ++i) bg[i].load(p, rb, kb, (u32)p.K, wb[i]);
     };
-    auto load_even = [&](int ks) {
-        load_a(a_view(p.x_a, rs_xa, ks), ks, eA);
-        // the right operand follows the left operand's slice order (see TapCursor)
-        const int kb = AMODE == A_CONV_C32 ? tap.pks : ks;
-        load_b(b_view(p.w_a, rs_wa, ks), kb, eB);
-        load_b(b_view(p.w_b, rs_wb, ks), kb, eB2);
-    };
-    // w_a of a slice is fetched once, with the even set; the odd set's copy is
-    // taken from there before the even set is summed and recoded.
-    auto load_odd = [&](int ks) { load_a(a_view(p.x_b, rs_xb, ks), ks, oA); };
 
     // The split of one unit in four pieces, so that they can be placed between MFMAs:
     // 0: recode the first two words, 1: the last two, 2: digits 0-3 to LDS, 3: digits 4-7.
-    // `add` (the second share of the right operand) is summed in before recoding.
-    auto unit_op = [&](u4 (&v)[2], const u4 (*add)[2], u4 (*keep)[2], char* dst, auto rs_c, auto phase_c) {
-        constexpr int RS = decltype(rs_c)::value, phase = decltype(phase_c)::value;
+    // `add` (the first share of the right operand) is summed in before recoding.
+    auto unit_op = [&](u4 (&v)[2], const u4 (*add)[2], char* lo, char* hi, auto dig_c, auto phase_c) {
+        constexpr int DIG = decltype(dig_c)::value, phase = decltype(phase_c)::value;
         if constexpr (phase < 2) {
-            if (keep) (*keep)[phase] = v[phase];
             if (add) v[phase] = add64x2(v[phase], (*add)[phase]);
             recode2(v[phase]);
         } else {
             u32 d[4];
             if constexpr (phase == 2) transpose4(v[0].x, v[0].z, v[1].x, v[1].z, d);
             else transpose4(v[0].y, v[0].w, v[1].y, v[1].w, d);
-            constexpr int l0 = phase == 2 ? 0 : 4;
+            char* dst = phase == 2 ? lo : hi;
 #pragma unroll
-            for (int l = 0; l < 4; ++l) *reinterpret_cast<u32*>(dst + (l0 + l) * 2 * RS) = d[l];
+            for (int l = 0; l < 4; ++l) *reinterpret_cast<u32*>(dst + l * DIG) = d[l];
         }
     };
-    constexpr int NOPS = 4 * (AU + BU);
-    // op index -> (unit, piece); A units first, then B units
-    auto split_op = [&](auto op_c, auto even_c, char* stage) {
+    // Pieces of the three batches.  Right operand: the units of w_a + w_b (formed in the registers of w_b,
+    // which must happen before w_a is recoded in place), then those of w_a.
+    constexpr int NOPS_X = 4 * AU, NOPS_W = 8 * BU;
+    auto split_x = [&](auto op_c, u4 (*x)[2], int share_off, char* a_lo, char* a_hi) {
         constexpr int op = decltype(op_c)::value, unit = op / 4;
-        constexpr bool even_set = decltype(even_c)::value;
+        unit_op(x[unit], nullptr, a_lo + share_off + a_dst[unit], a_hi + share_off + a_dst[unit],
+                std::integral_constant<int, T::A_DIG>{}, std::integral_constant<int, op % 4>{});
+    };
+    auto split_w = [&](auto op_c, char* b_all) {
+        constexpr int op = decltype(op_c)::value, unit = op / 4;
+        const std::integral_constant<int, T::B_DIG> bdig;
         const std::integral_constant<int, op % 4> phase;
-        if constexpr (unit < AU) {
-            const std::integral_constant<int, T::A_RS> rs;
-            if constexpr (even_set) unit_op(eA[unit], nullptr, nullptr, stage + a_dst[unit], rs, phase);
-            else unit_op(oA[unit], nullptr, nullptr, stage + a_dst[unit], rs, phase);
+        if constexpr (unit < BU) {
+            unit_op(wb[unit], &wa[unit], b_all + b_dst[unit], b_all + 4 * T::B_DIG + b_dst[unit], bdig, phase);
         } else {
-            constexpr int b = unit - AU;
-            const std::integral_constant<int, T::B_RS> rs;
-            if constexpr (even_set) unit_op(eB[b], &eB2[b], &oB[b], stage + b_dst[b], rs, phase);
-            else unit_op(oB[b], nullptr, nullptr, stage + b_dst[b], rs, phase);
+            constexpr int i = unit - BU;
+            unit_op(wa[i], nullptr, b_all + 2 * T::B_RS + b_dst[i], b_all + 4 * T::B_DIG + 2 * T::B_RS + b_dst[i], bdig,
+                    phase);
         }
     };
-    auto split_all = [&](auto even_c, char* stage) {
-        static_for<0, NOPS>([&](auto op_c) { split_op(op_c, even_c, stage); });
-    };
 
-    const int a_frag = h * T::A_RS + (wm * SM * 32 + r32) * 16;
-    const int b_frag = T::A_BYTES + h * T::B_RS + (wn * SN * 32 + r32) * 16;
+    // fragment addresses of this lane: row r16 of a 16-row block, k-group kg
+    const int a_frag = kg * T::A_RS + (wm * 32 + r16) * 16;
+    const int b_frag = kg * T::B_RS + (wn * 32 + r16) * 16;
+    const char* const a_hi_rd = lds + T::OFF_AHI + a_frag;
 
-    v16i acc[SM][SN][8];
+    v4i acc[2][2][8];
+    v4i af[4][2], bf[2][2];  // four digits of the left operand, two of the right one; two 16-row blocks each
 
-    // One half-step with a hand-placed issue order.  MFMAs go digit l of the left
-    // operand outermost.  Only the fragments of the first MFMA are awaited after
-    // the barrier; every other fragment is fetched a slot or two ahead of its
-    // first use, and the global loads for a later half-step (`issue_loads`) go out
-    // in the shadow of the first MFMA.  From slot PRE on, the NOPS split pieces
-    // are spread evenly over the MFMA slots up to LAST, so the vector ALU works
-    // while the matrix pipe is busy.  A full scheduling fence after every slot
-    // keeps the compiler from regrouping them.  Every index is a compile-time
-    // constant.
-    constexpr int NMFMA = 36 * SM * SN;
-    constexpr int PRE = NMFMA * PRE_EIGHTHS / 8;
-    constexpr int LAST = NMFMA - 2 * SM * SN;  // the final slots only drain
-    auto half_step = [&](const char* cur, char* nxt, auto even_c, auto&& issue_loads) {
-        v4i bf[SN][8];
-        v4i af[A_AHEAD + 1][SM];
-        auto read_b = [&](int m) {
+    // One step: the 144 MFMAs of a slice with a hand-placed issue order (every index is a compile-time
+    // constant, a full scheduling fence after every slot keeps the compiler from regrouping them).
+    //   a_lo, b_rd : buffers of this step (digits 0-3 of the left operand, all digits of the right one)
+    //   a_lo_wr, b_wr : the other buffers, which receive the next slice; digits 4-7 of the left operand have
+    //                   one buffer, read in phase 1 and rewritten in phase 2, hence the barrier between them
+    // Between the MFMAs the next slice is prepared, spread evenly over the step (slots counted over both
+    // phases): the right operand's words, loaded late in the step before, are split in slots W0..W1; the
+    // left operand's first share is loaded at XA_LOAD and split in XA0..XA1 (its digits 4-7 can only be
+    // written in phase 2), the second share at XB_LOAD (into the registers the right operand has left) and
+    // split in XB0..XB1; W_LOAD then fetches the right operand of the slice after the next.
+    constexpr int N1 = 40, N2 = 104;
+    constexpr int W0 = 3, W1 = 39, XA_LOAD = 1, XA0 = 42, XA1 = 92, XB_LOAD = 41, XB0 = 94, XB1 = 142, W_LOAD = 93;
+    auto step = [&](const char* a_lo, const char* b_rd, char* a_lo_wr, char* b_wr) {
+        auto read_a_hi = [&](int l) {   // digit l in 4..7 -> register set l - 4
 #pragma unroll
-            for (int sn = 0; sn < SN; ++sn)
-                bf[sn][m] = *reinterpret_cast<const v4i*>(cur + b_frag + m * 2 * T::B_RS + sn * 512);
+            for (int rb = 0; rb < 2; ++rb)
+                af[l - 4][rb] = *reinterpret_cast<const v4i*>(a_hi_rd + (l - 4) * T::A_DIG + rb * 256);
         };
-        auto read_a = [&](int l) {
+        auto read_a_lo = [&](int l) {   // digit l in 0..3 -> register set l
 #pragma unroll
-            for (int sm = 0; sm < SM; ++sm)
-                af[l % (A_AHEAD + 1)][sm] = *reinterpret_cast<const v4i*>(cur + a_frag + l * 2 * T::A_RS + sm * 512);
+            for (int rb = 0; rb < 2; ++rb)
+                af[l][rb] = *reinterpret_cast<const v4i*>(a_lo + a_frag + l * T::A_DIG + rb * 256);
         };
-        // fragments of the first MFMA first; the other initial reads are not waited for
-        read_a(0);
-        read_b(0);
-        static_for<1, B_AHEAD>([&](auto m_c) { read_b(decltype(m_c)::value); });
-        static_for<1, A_AHEAD>([&](auto l_c) { read_a(decltype(l_c)::value); });
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<0, NMFMA>([&](auto slot_c) {
+        auto read_b = [&](int m) {      // digit m -> register set m & 1
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+                bf[m & 1][cb] = *reinterpret_cast<const v4i*>(b_rd + b_frag + m * T::B_DIG + cb * 256);
+        };
+        // what goes between the MFMAs of slot `slot` (0..143 over both phases)
+        auto between = [&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
-            constexpr Slot sl = decode_slot(slot, SM, SN);
-            constexpr int l = sl.l, m = sl.m, sm = sl.sm, sn = sl.sn;
-            if constexpr (sm == 0 && sn == 0) {
-                if constexpr (l == 0 && m + B_AHEAD < 8) read_b(m + B_AHEAD);
-                // the register set of digit l + A_AHEAD is free once digit l - 1 is done, i.e. from the
-                // first slot of digit l on; one slot later keeps it clear of the B reads of digit 0
-                if constexpr (m == (l < 7 ? 1 : 0) && l + A_AHEAD < 8) read_a(l + A_AHEAD);
+            if constexpr (slot == XA_LOAD) load_xa();
+            if constexpr (slot == XB_LOAD) {
+                load_xb();
+                advance(wa_, setup_a);
             }
-            acc[sm][sn][l + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                af[l % (A_AHEAD + 1)][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
-            if constexpr (slot == 0) issue_loads();
-            if constexpr (slot >= PRE && slot < LAST) {
-                constexpr int lo = (slot - PRE) * NOPS / (LAST - PRE);
-                constexpr int hi = (slot - PRE + 1) * NOPS / (LAST - PRE);
-                static_for<lo, hi>([&](auto op_c) { split_op(op_c, even_c, nxt); });
+            if constexpr (slot == W_LOAD) {
+                load_w();
+                advance(wb_, setup_b);
             }
+            if constexpr (slot >= W0 && slot < W1) {
+                constexpr int lo = (slot - W0) * NOPS_W / (W1 - W0), hi = (slot - W0 + 1) * NOPS_W / (W1 - W0);
+                static_for<lo, hi>([&](auto op_c) { split_w(op_c, b_wr); });
+            }
+            if constexpr (slot >= XA0 && slot < XA1) {
+                constexpr int lo = (slot - XA0) * NOPS_X / (XA1 - XA0), hi = (slot - XA0 + 1) * NOPS_X / (XA1 - XA0);
+                static_for<lo, hi>([&](auto op_c) { split_x(op_c, xa, 0, a_lo_wr, lds + T::OFF_AHI); });
+            }
+            if constexpr (slot >= XB0 && slot < XB1) {
+                constexpr int lo = (slot - XB0) * NOPS_X / (XB1 - XB0), hi = (slot - XB0 + 1) * NOPS_X / (XB1 - XB0);
+                static_for<lo, hi>([&](auto op_c) { split_x(op_c, xb, 2 * T::A_RS, a_lo_wr, lds + T::OFF_AHI); });
+            }
+        };
+        // ---- phase 1: fragments in the order of first use; only the first pair's are awaited before the first MFMA
+        read_a_hi(7); read_b(0);
+        read_a_hi(6); read_a_hi(5); read_a_hi(4); read_b(1);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, N1>([&](auto slot_c) {
+            constexpr int slot = decltype(slot_c)::value;
+            constexpr Pair pr = phase1_pair(slot / 4);
+            constexpr int rb = (slot >> 1) & 1, cb = slot & 1;
+            acc[rb][cb][pr.l + pr.m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                af[pr.l - 4][rb], bf[pr.m & 1][cb], acc[rb][cb][pr.l + pr.m], 0, 0, 0);
+            if constexpr (slot + 1 == phase1_group_end(0)) read_b(2);
+            if constexpr (slot + 1 == phase1_group_end(1)) read_b(3);
+            // a retired high digit hands its registers to a low digit of the same slice (already in LDS):
+            // digit 7 is last used by pair 0, digit 6 by pair 4, digit 5 by pair 7
+            if constexpr (slot == 3) read_a_lo(3);
+            else if constexpr (slot == 19) read_a_lo(2);
+            else if constexpr (slot == 31) read_a_lo(1);
+            between(slot_c);
             __builtin_amdgcn_sched_barrier(0);
         });
+        __syncthreads();   // every wave has read digits 4-7: their buffer may be rewritten
+        read_a_lo(0);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, N2>([&](auto slot_c) {
+            constexpr int slot = decltype(slot_c)::value;
+            constexpr Pair pr = phase2_pair(slot / 4);
+            constexpr int rb = (slot >> 1) & 1, cb = slot & 1;
+            acc[rb][cb][pr.l + pr.m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                af[pr.l][rb], bf[pr.m & 1][cb], acc[rb][cb][pr.l + pr.m], 0, 0, 0);
+            // when the g-th group is done its digit's registers take the digit of group g + 2
+            static_for<0, 6>([&](auto g_c) {
+                constexpr int g = decltype(g_c)::value;
+                if constexpr (slot + 1 == phase2_group_end(g)) read_b(phase2_group(g + 2));
+            });
+            between(std::integral_constant<int, N1 + slot>{});
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        __syncthreads();   // the next slice is in LDS
     };
-
-    char* const st0 = lds;
-    char* const st1 = lds + T::STAGE;
-    // this pass covers the slices [k_begin, nk) of its tile
 
     auto clear_acc = [&]() {
 #pragma unroll
-        for (int sm = 0; sm < SM; ++sm)
+        for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int sn = 0; sn < SN; ++sn)
+            for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-                for (int s = 0; s < 8; ++s)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[sm][sn][s][i] = 0;
+                for (int s = 0; s < 8; ++s) acc[rb][cb][s] = v4i{0, 0, 0, 0};
     };
 
-    auto fold = [&](int fm0, int fn0, bool accumulate) {
-        fold_tile<SM, SN, BMODE == B_FLIP_C32>(p, acc, fm0 + wm * SM * 32, fn0 + wn * SN * 32, lane, accumulate);
-    };
-
-    // Prologue: the even half-step of the first slice goes to LDS.  Loads past the end of
-    // K are out of range and return zeros that are never used, so the loop body
+    // Prologue: the first slice goes to buffer 0 and the right operand of the second slice is requested.
+    // Loads past the end of K are out of range and return zeros that are never used, so the loop body
     // needs no "is there a next slice" branch.
-    load_even(k_begin);
-    split_all(std::true_type{}, st0);
+    load_xa();
+    load_xb();
+    advance(wa_, setup_a);
+    load_w();
+    advance(wb_, setup_b);
+    static_for<0, NOPS_X>([&](auto op_c) { split_x(op_c, xa, 0, lds, lds + T::OFF_AHI); });
+    static_for<0, NOPS_X>([&](auto op_c) { split_x(op_c, xb, 2 * T::A_RS, lds, lds + T::OFF_AHI); });
+    static_for<0, NOPS_W>([&](auto op_c) { split_w(op_c, lds + T::OFF_B); });
+    load_w();
+    advance(wb_, setup_b);
     __syncthreads();
+    int par = 0;   // buffer holding the current slice
 
-    // One pass of the outer loop per tile.  In the streamed scheme the LDS pipeline runs straight on
-    // into the next tile of the range: the last odd half-step of a tile already loads and splits
-    // the first even slice of the next one (whose address generators are set up just before it, when
-    // the current tile has issued its last load), so only the fold separates two tiles.
-    bool more;
-    do {
-        more = false;
-        const int fm0 = m0, fn0 = n0, k0 = k_begin, nk_c = nk;  // the tile being computed
+    // One pass of the outer loop per tile.  In the streamed scheme the loaders run straight on into the
+    // next tile of the range, so that only the fold separates two tiles.
+    Walker wc;
+    wc.u = u0; wc.u_end = u_end;
+    while (true) {
+        enter_tile(wc);
+        int tm, tn;
+        logical_to_tile(p, tiles_m, tiles_n, wc.logical, tm, tn);
+        const int fm0 = tm * T::BM + wm * 32, fn0 = tn * T::BN + wn * 32;   // the wave's sub-tile
         // one pass per segment of at most SEG_KSTEPS slices (a single pass unless K > 32*SEG_KSTEPS)
-        for (int ks0 = k0; ks0 < nk_c; ks0 += SEG_KSTEPS) {
-            const int ke = ks0 + SEG_KSTEPS < nk_c ? ks0 + SEG_KSTEPS : nk_c;
+        for (int ks0 = wc.ks; ks0 < wc.nk; ks0 += SEG_KSTEPS) {
+            const int ke = ks0 + SEG_KSTEPS < wc.nk ? ks0 + SEG_KSTEPS : wc.nk;
             clear_acc();
             for (int ks = ks0; ks < ke; ++ks) {
-                int next_ks = ks + 1;
-                // at the tile's last slice, once its last load has been issued, the loads turn to the next tile
-                auto switch_tile = [&]() {
-                    if constexpr (STREAM) {
-                        if (ks + 1 == nk_c && u < u_end) {  // uniform: the range goes on with another tile
-                            setup_tile();
-                            next_ks = k_begin;
-                            more = true;
-                        }
-                    }
-                };
-                // even half-step: x_a against w_a + w_b from st0; odd words are split into st1
-                half_step(st0, st1, std::false_type{}, [&]() { load_odd(ks); });
-                __syncthreads();
-                switch_tile();
-                // odd half-step: x_b against w_a from st1; the next even words go to st0
-                half_step(st1, st0, std::true_type{}, [&]() { load_even(next_ks); });
-                __syncthreads();
+                step(lds + par * T::A_HALF, lds + T::OFF_B + par * T::B_ALL, lds + (par ^ 1) * T::A_HALF,
+                     lds + T::OFF_B + (par ^ 1) * T::B_ALL);
+                par ^= 1;
             }
-            fold(fm0, fn0, ks0 > k0 || p.z_add != 0);
+            fold_blocks<BMODE == B_FLIP_C32>(p, acc, fm0, fn0, lane, ks0 > wc.ks || p.z_add != 0);
         }
-    } while (more);
+        if (!STREAM || wc.u >= wc.u_end) break;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1317,16 +1497,12 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
 }
 
 hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream) {
-    typedef DefaultTile T;  // waves along M, waves along N, 32x32 sub-tiles per wave along M, along N
-    // Weight gradients have M = Cout: when the last 128-row tile would be at most half
-    // full, a 64 x 128 block tile wastes fewer MFMAs.
-    if (amode == A_TRANS && bmode == B_PATCH_T && T::BM == 128 && (p.M - 1) % 128 < 64 && p.M <= 448 && p.N > 64)
-        return launch<Tile<2, 4, 1, 1>, A_TRANS, B_PATCH_T>(p, stream);
-    // Fully connected layers at small batch: one MFMA row block holds all of M, so a
+    typedef DefaultStepTile T;  // 4 waves along M, 2 along N
+    // Fully connected layers at small batch: one 32-row wave tile holds all of M, so a
     // 32 x 128 tile of four waves does a quarter of the matrix work of the 128-row tile
     // (measured: pays from K of a few thousand on; shorter products are launch-bound either way).
-    if (amode == A_LINEAR_VEC && bmode == B_VEC && T::BM == 128 && p.M <= 32 && p.N >= 128 && p.K >= 2048)
-        return launch<Tile<1, 4, 1, 1>, A_LINEAR_VEC, B_VEC>(p, stream);
+    if (amode == A_LINEAR_VEC && bmode == B_VEC && p.M <= 32 && p.N >= 128 && p.K >= 2048)
+        return launch<StepTile<1, 4>, A_LINEAR_VEC, B_VEC>(p, stream);
 #define CG_CASE(A, B) if (amode == A && bmode == B) return launch<T, A, B>(p, stream)
     CG_CASE(A_LINEAR_VEC, B_VEC);
     CG_CASE(A_LINEAR_SCALAR, B_SCALAR);
