@@ -27,6 +27,8 @@ if ROOT not in sys.path:
 
 METRIC = "Z_2^64 share-GEMM effective 64-bit MAC/s (1 party) + % MFMA peak"
 INT8_PEAK_TOPS = 5000.0  # MI355X dense int8 MFMA, published: 5.0 POP/s (2 ops per MAC)
+HBM_PEAK_GBS = 8000.0    # MI355X HBM3E, published: 8 TB/s
+LAST_LEVEL_CACHE_BYTES = 256 << 20
 DIGIT_MACS_PER_RING_MAC_TRIPLE = 72  # 2 ring products x 36 signed-byte digit pairs per (m, n, k)
 WORKLOAD_CONFIG = 4
 # HBM bytes per share_gemm_kernel launch on the config-4 step, from the two rocprofv3 --pmc runs summarised in
@@ -39,7 +41,7 @@ PROFILED_TRAFFIC_CONFIG4 = {"read_bytes_per_launch": 67.8e6, "write_bytes_per_la
 def parse_args():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=WORKLOAD_CONFIG, choices=[1, 2, 3, 4, 5],
                     help="benchmark configuration (default: the VGG16-shaped one)")
@@ -51,6 +53,9 @@ def parse_args():
     ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the register-only MFMA issue-rate measurement")
+    ap.add_argument("--no-rows", action="store_true",
+                    help="skip the rows printed beside the step by default (largest share-GEMM shapes, totals of the "
+                         "other configurations, streaming kernels, warm/cold fully connected layers)")
     ap.add_argument("--extras", action="store_true",
                     help="after the step, also time the rows outside the five configurations (square share products, "
                          "the paper's Fig. 1 convolution shapes, backward products, element-wise and PRF kernels) and "
@@ -59,6 +64,118 @@ def parse_args():
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of "
                          "known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
+
+
+def _rnd(torch, shape, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return torch.randint(-2 ** 63, 2 ** 63 - 1, tuple(shape), dtype=torch.int64, device="cuda", generator=g)
+
+
+def _timed(torch, fn, warm=3, iters=10):
+    """Mean duration in ms of `iters` calls after `warm` untimed ones, HIP events on the launch stream."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def measure_rows(torch, cg, wl, headline_config):
+    """Rows reported beside the timed step in every run (not part of `value`): the largest share-GEMM shapes,
+    the totals of the other convolution configurations, the streaming kernels against the HBM peak, and the
+    HBM-bound fully connected layers with warm and cold operands."""
+    out = {}
+    # ---- largest GEMM shapes: plain entry point and the digit-plane route with caller scratch
+    rows = []
+    for M, N, K in [(4096, 4096, 4096), (8192, 8192, 2048)]:
+        ops = [_rnd(torch, (M, K), 1), _rnd(torch, (M, K), 2), _rnd(torch, (N, K), 3), _rnd(torch, (N, K), 4)]
+        z = torch.empty((M, N), dtype=torch.int64, device="cuda")
+        ws = torch.empty(cg.cg_share_matmul_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+        ops_per = 2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * M * N * K
+        ms = _timed(torch, lambda: cg.cg_share_matmul(*ops, z_i=z), warm=2, iters=8)
+        ms_ws = _timed(torch, lambda: cg.cg_share_matmul_ws(*ops, ws, z_i=z), warm=2, iters=8)
+        rows.append({"gemm": [M, N, K], "cg_share_matmul_ms": round(ms, 4),
+                     "ring_macs_per_s": 3.0 * M * N * K / (ms * 1e-3),
+                     "int8_tops": round(ops_per / (ms * 1e-3) / 1e12, 1),
+                     "frac_of_peak": round(ops_per / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4),
+                     "cg_share_matmul_ws_ms": round(ms_ws, 4),
+                     "ws_frac_of_peak": round(ops_per / (ms_ws * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4)})
+        del ops, z, ws
+    out["largest_gemm_shapes"] = rows
+    # ---- the other convolution configurations: one step = all their layers, same method as the headline step
+    rows = []
+    for cfg in (3, 5):
+        if cfg == headline_config:
+            continue
+        layers = wl.config_layers(cfg)
+        dev, outs = [], []
+        for li, L in enumerate(layers):
+            dev.append([_rnd(torch, L.x_shape, 7 * li + 1), _rnd(torch, L.x_shape, 7 * li + 2),
+                        _rnd(torch, L.w_shape, 7 * li + 3), _rnd(torch, L.w_shape, 7 * li + 4)])
+            outs.append(torch.empty(L.z_shape, dtype=torch.int64, device="cuda"))
+
+        def step():
+            for L, ops, z in zip(layers, dev, outs):
+                for _ in range(L.repeat):
+                    if L.kind == "conv":
+                        cg.cg_share_conv2d(*ops, stride=(L.stride, L.stride), pad=(L.pad, L.pad), z_i=z)
+                    else:
+                        cg.cg_share_matmul(*ops, z_i=z)
+        ms = _timed(torch, step, warm=3, iters=20)
+        mnk = sum(L.mnk * L.repeat for L in layers)
+        tops = 2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * mnk / (ms * 1e-3) / 1e12
+        rows.append({"config": cfg, "layers": sum(L.repeat for L in layers), "ms_per_step": round(ms, 4),
+                     "ring_macs_per_s": 3.0 * mnk / (ms * 1e-3), "int8_tops": round(tops, 1),
+                     "frac_of_peak": round(tops / INT8_PEAK_TOPS, 4)})
+        del dev, outs
+    out["other_configs"] = rows
+    # ---- element-wise share operations: HBM-bound, 2^26 words per stream (beyond the 256 MB last-level cache)
+    n = 1 << 26
+    a, b, c, d = (_rnd(torch, (n,), s) for s in (1, 2, 3, 4))
+    o1, o2 = torch.empty_like(a), torch.empty_like(a)
+    rows = []
+    for name, nbytes, fn in [
+        ("cg_share_add", 48, lambda: cg.cg_share_add(a, b, c, d, za=o1, zb=o2)),
+        ("cg_share_mul_public", 32, lambda: cg.cg_share_mul_public(a, b, 12345, za=o1, zb=o2)),
+        ("cg_reconstruct", 32, lambda: cg.cg_reconstruct(a, b, c, out=o1)),
+    ]:
+        ms = _timed(torch, fn, warm=2, iters=5)
+        gbs = nbytes * n / (ms * 1e-3) / 1e9
+        rows.append({"name": name, "words": n, "ms": round(ms, 4), "GB_per_s": round(gbs, 1),
+                     "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)})
+    out["streaming"] = rows
+    del a, b, c, d, o1, o2
+    # ---- HBM-bound fully connected layers: warm = the same operands every launch (they stay in the last-level
+    # cache), cold = rotating through enough distinct operand sets to exceed it
+    rows = []
+    fcs = [L for L in wl.config_layers(4) if L.kind == "matmul"] + [L for L in wl.config_layers(5) if L.kind == "matmul"]
+    for L in fcs:
+        nbytes = L.algorithmic_bytes
+        sets = max(2, int(2 * LAST_LEVEL_CACHE_BYTES // nbytes) + 1)
+        sets = min(sets, 160)
+        pool = [[_rnd(torch, L.x_shape, 10 * i + 1), _rnd(torch, L.x_shape, 10 * i + 2),
+                 _rnd(torch, L.w_shape, 10 * i + 3), _rnd(torch, L.w_shape, 10 * i + 4)] for i in range(sets)]
+        z = torch.empty(L.z_shape, dtype=torch.int64, device="cuda")
+        warm_ms = _timed(torch, lambda: cg.cg_share_matmul(*pool[0], z_i=z), warm=3, iters=20)
+        it = [0]
+
+        def cold():
+            cg.cg_share_matmul(*pool[it[0] % sets], z_i=z)
+            it[0] += 1
+        cold_ms = _timed(torch, cold, warm=sets, iters=sets)
+        rows.append({"name": L.name, "gemm": list(L.gemm), "algorithmic_bytes": nbytes, "operand_sets": sets,
+                     "warm_us": round(warm_ms * 1e3, 2), "cold_us": round(cold_ms * 1e3, 2),
+                     "hbm_time_us": round(nbytes / (HBM_PEAK_GBS * 1e9) * 1e6, 2),
+                     "cold_GB_per_s": round(nbytes / (cold_ms * 1e-3) / 1e9, 1)})
+        del pool, z
+    out["fc_warm_cold"] = rows
+    return out
 
 
 def measure_extras(torch, cg, wl, config_layers):
@@ -299,13 +416,14 @@ def main() -> int:
     ms_per_step = e0.elapsed_time(e1) / args.steps
 
     # spread of single steps (separate pass, one event pair per step)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    n_single = min(args.steps, 50)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_single + 1)]
     marks[0].record()
-    for i in range(args.steps):
+    for i in range(n_single):
         step()
         marks[i + 1].record()
     torch.cuda.synchronize()
-    single = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    single = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(n_single))
     step_spread = {"median_ms": round(single[len(single) // 2], 5), "min_ms": round(single[0], 5),
                    "max_ms": round(single[-1], 5)}
 
@@ -408,6 +526,11 @@ def main() -> int:
         "largest_layer": {"name": layers[big].name, "gemm": list(layers[big].gemm),
                           "ms": round(per_layer_ms[big], 5), "achieved": round(big_tops, 2),
                           "frac": round(big_tops / INT8_PEAK_TOPS, 4)},
+        # every layer whose M*N*K equals the largest one's (several layers of the VGG-shaped stack tie)
+        "largest_layers": [{"name": L.name, "gemm": list(L.gemm), "ms": round(ms, 5),
+                            "frac": round(2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * L.mnk / (ms * 1e-3) / 1e12
+                                          / INT8_PEAK_TOPS, 4)}
+                           for L, ms in zip(layers, per_layer_ms) if L.mnk == layers[big].mnk],
         "traffic": PROFILED_TRAFFIC_CONFIG4 if args.config == WORKLOAD_CONFIG else None,
     }
     # Per layer: measured time against t_roof = max(int8 ops / peak, algorithmic bytes / HBM peak) and the larger term.
@@ -463,11 +586,26 @@ def main() -> int:
                 if passes == 0:
                     covered.append(L.name)
             passes += 1
+        # the same oracle on ONE thread, on configuration 1 (256^3, the three parties' products)
+        c1 = wl.config_layers(1)[0]
+        ops1 = wl.party_operands(c1, wl.layer_seed(1, 0))
+        all_threads = ro.num_threads()
+        ro.set_num_threads(1)
+        t0, n1 = time.perf_counter(), 0
+        while time.perf_counter() - t0 < 1.0:
+            ro.party_matmul(*ops1)
+            n1 += 1
+        t_one = time.perf_counter() - t0
+        ro.set_num_threads(all_threads)
+        single_thread = {"value": 3.0 * c1.mnk * n1 / t_one, "unit": "ring MAC/s", "cores": 1,
+                         "sample": f"{n1} party products of config 1 (matmul 256^3) on one thread"}
         cpu = {"value": 3.0 * done_mnk / t_cpu, "unit": "ring MAC/s", "cores": ro.num_threads(),
+               "single_thread_config1": single_thread,
                "kind": "oracle", "seconds": round(t_cpu, 2),
                "sample": (f"{passes} pass(es) over {len(covered)} of {len(layers)} layers of config {args.config} at "
                           f"full size, one party ({covered[0]} .. {covered[-1]}), {3 * done_mnk:.3e} ring MACs")}
 
+    rows = None if args.no_rows else measure_rows(torch, cg, wl, args.config)
     extras = measure_extras(torch, cg, wl, layers) if args.extras else None
 
     out = {
@@ -485,6 +623,7 @@ def main() -> int:
                    "parties_timed": 1, "fixed_point_bits": wl.FRAC_BITS},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "rows": rows,
         "extras": extras,
         "paper_context": "CryptGPU reports no isolated local-product rate; derived from its Fig. 1 "
                          "(3 V100, LAN, whole protocol): about 6e9-1.1e10 effective ring MAC/s",

@@ -45,6 +45,17 @@ int oracle_num_threads(void)
 #endif
 }
 
+/* Number of threads the loops below may use from now on (benchmark reporting only: no result
+ * depends on it). */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* ---- fixed-point encoding (Sec. III-B "Fixed point representation") -------
  * A real x with t fractional bits is the integer nearest to x*2^t, embedded in
  * the ring as a two's-complement 64-bit word.  Ties go to even (the paper does

@@ -44,6 +44,8 @@ def lib() -> ctypes.CDLL:
         build()
         L = ctypes.CDLL(_LIB)
         L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_set_num_threads.argtypes = [ctypes.c_int]
+        L.oracle_set_num_threads.restype = None
         L.oracle_encode.argtypes = [_f64p, _u64p, _sz, ctypes.c_int]
         L.oracle_decode.argtypes = [_u64p, _f64p, _sz, ctypes.c_int]
         L.oracle_share.argtypes = [_u64p] * 6 + [_sz]
@@ -92,6 +94,11 @@ def lib() -> ctypes.CDLL:
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the C loops may use from now on (timing reports only; results do not depend on it)."""
+    lib().oracle_set_num_threads(int(n))
 
 
 def _u(a) -> np.ndarray:

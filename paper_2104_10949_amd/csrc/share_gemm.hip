@@ -875,8 +875,12 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             for (int i = 0; i < AU; ++i) ag[i].load(p, rs, ks, (u32)p.K, dst[i]);
         }
     };
-    auto load_xa = [&]() { load_a(a_view(p.x_a, rs_xa, wa_.ks), wa_.ks, xa); };
-    auto load_xb = [&]() { load_a(a_view(p.x_b, rs_xb, wa_.ks), wa_.ks, xb); };
+    // A loader that has run past the last slice of the block's range loads through empty views: every offset is
+    // out of range there, so the loads return zeros without touching memory (no branch around them: a branch
+    // would make the compiler wait for all outstanding loads where the paths join).
+    auto dead_view = [&](__amdgpu_buffer_rsrc_t r, const u64* ptr, bool live) { return live ? r : make_rsrc(ptr, 0); };
+    auto load_xa = [&]() { load_a(dead_view(a_view(p.x_a, rs_xa, wa_.ks), p.x_a, wa_.ks < wa_.nk), wa_.ks, xa); };
+    auto load_xb = [&]() { load_a(dead_view(a_view(p.x_b, rs_xb, wa_.ks), p.x_b, wa_.ks < wa_.nk), wa_.ks, xb); };
     auto load_w = [&]() {
         const int ks = wb_.ks;
         int kb = ks;
@@ -884,7 +888,9 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             tap_b.advance_to(p, ks);
             kb = tap_b.pks;
         }
-        const __amdgpu_buffer_rsrc_t ra = b_view(p.w_a, rs_wa, ks), rb = b_view(p.w_b, rs_wb, ks);
+        const bool live = ks < wb_.nk;
+        const __amdgpu_buffer_rsrc_t ra = dead_view(b_view(p.w_a, rs_wa, ks), p.w_a, live),
+                                     rb = dead_view(b_view(p.w_b, rs_wb, ks), p.w_b, live);
 #pragma unroll
         for (int i = 0; i < BU; ++i) bg[i].load(p, ra, kb, (u32)p.K, wa[i]);
 #pragma unroll
