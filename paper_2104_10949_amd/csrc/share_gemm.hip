@@ -275,18 +275,21 @@ struct PatchRow {
 // (tap, channel) order.  (r, s), c0 are uniform over the block and advance by scalar
 // increments.
 struct TapCursor {
-    int ks, r, s, c0, tap, pks;
-    u32 off;  // ((r*W + s)*Cin + c0) * 8: byte offset of the slice relative to the row's pixel (hi0, wi0)
-    __device__ __forceinline__ void reset() { ks = 0; r = 0; s = 0; c0 = 0; tap = 0; pks = 0; off = 0; }
+    int ks, r, s, c0;   // the cursor proper; everything else is derived on use, to keep few values alive
+    __device__ __forceinline__ void reset() { ks = 0; r = 0; s = 0; c0 = 0; }
     __device__ __forceinline__ void advance_to(const GemmParams& p, int want) {
         while (ks < want) {  // zero or one step per call in the kernel's load order
             ++ks;
-            ++tap;
             if (++s == p.kw) { s = 0; ++r; }
-            if (r == p.kh) { r = 0; tap = 0; c0 += 32; }  // past the end of K: c0 == Cin
-            off = (((u32)r * (u32)p.W + (u32)s) * (u32)p.Cin + (u32)c0) * 8u;
-            pks = (tap * p.Cin + c0) >> 5;
+            if (r == p.kh) { r = 0; c0 += 32; }  // past the end of K: c0 == Cin
         }
+    }
+    __device__ __forceinline__ int tap(const GemmParams& p) const { return r * p.kw + s; }
+    // slice index in the filter's own (tap, channel) order
+    __device__ __forceinline__ int pks(const GemmParams& p) const { return (tap(p) * p.Cin + c0) >> 5; }
+    // ((r*W + s)*Cin + c0) * 8: byte offset of the slice relative to the row's pixel (hi0, wi0)
+    __device__ __forceinline__ u32 off(const GemmParams& p) const {
+        return (((u32)r * (u32)p.W + (u32)s) * (u32)p.Cin + (u32)c0) * 8u;
     }
 };
 
@@ -314,11 +317,11 @@ struct ConvC32 {
                                          u4 out[2]) const {
         bool v;
         if (p.kh * p.kw <= 64) {  // uniform
-            v = t.c0 < p.Cin && ((inside >> t.tap) & 1);
+            v = t.c0 < p.Cin && ((inside >> t.tap(p)) & 1);
         } else {
             v = pr.ok && t.c0 < p.Cin && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
         }
-        const u32 off = v ? base_kq + t.off : OOB;
+        const u32 off = v ? base_kq + t.off(p) : OOB;
         out[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off, 0, 0);
         out[1] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off + 64u, 0, 0);
     }
@@ -680,11 +683,28 @@ constexpr int phase2_group_end(int g) {
 }
 
 // ---------------------------------------------------------------------------
+// LDS byte offset, inside the slab set of one digit and share, of the unit that thread-slot t (thread id plus a
+// multiple of the block size) handles in a tile of `rows` rows: k-group jh, row, 16-byte quarter q.  Row-major
+// operands put the four quarters of a 64-byte run on consecutive lanes, transposed ones consecutive rows.
+__host__ __device__ constexpr int unit_dst(int t, int rows, bool transposed) {
+    const int q = transposed ? (t / rows) & 3 : t & 3;
+    const int row = transposed ? t % rows : (t >> 2) % rows;
+    const int jh = (t >> 2) / rows;
+    return jh * rows * 16 + row * 16 + q * 4;
+}
+// Distance of unit i from unit 0 of the same thread.  The block size is a multiple of four and either a
+// multiple of 4*rows (then row and quarter repeat and only the k-group moves) or a divisor of it whose
+// multiples stay inside one k-group per pair of units; both cases make the distance the same for every
+// thread, so it is evaluated for thread 0.
+__host__ __device__ constexpr int unit_delta(int i, int nt, int rows, bool transposed) {
+    return unit_dst(i * nt, rows, transposed) - unit_dst(0, rows, transposed);
+}
+
 // A block's range of (tile, slice) units, walked one slice at a time.  Three walkers go over the same
 // range at different distances: the MFMA loop, the loads of the left operand one slice ahead of it and
 // the loads of the right operand up to two slices ahead.  All members are uniform over the block.
 struct Walker {
-    int64_t u, u_end;   // first unit after the current tile's share of the range; end of the range
+    int64_t u;          // first unit of the range after the current tile's share of it
     int logical;        // current tile in launch order
     int ks, nk;         // current slice; end of the current tile's slices
 };
@@ -723,7 +743,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     auto enter_tile = [&](Walker& w) {
         w.logical = (int)(w.u / nk_all);
         w.ks = (int)(w.u - (int64_t)w.logical * nk_all);
-        w.nk = (int64_t)w.ks + (w.u_end - w.u) < nk_all ? w.ks + (int)(w.u_end - w.u) : nk_all;
+        w.nk = (int64_t)w.ks + (u_end - w.u) < nk_all ? w.ks + (int)(u_end - w.u) : nk_all;
         w.u += w.nk - w.ks;
     };
 
@@ -756,14 +776,14 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     TapCursor tap_a;
     __amdgpu_buffer_rsrc_t rs_xa, rs_xb;
     AGen ag[AU];
-    int a_dst[AU];  // LDS byte offset of a unit inside the slab set of digit 0, first share
-#pragma unroll
-    for (int i = 0; i < AU; ++i) {   // where a thread's units go does not depend on the tile
-        const int t = tid + i * T::NT;
-        const int q = A_TR ? (t / T::BM) & 3 : t & 3, row = A_TR ? t % T::BM : (t >> 2) % T::BM, jh = (t >> 2) / T::BM;
-        a_dst[i] = jh * T::A_RS + row * 16 + q * 4;
-    }
+    // LDS byte offset of unit 0 inside the slab set of digit 0, first share; where a thread's units go does
+    // not depend on the tile, and unit i lies a compile-time distance from unit 0 (see unit_delta)
+    const int a_dst0 = unit_dst(tid, T::BM, A_TR);
     auto setup_a = [&]() {
+        // (the thread id passes through an empty asm so that nothing below is computed ahead of the K loop and
+        // kept in registers across it: a new tile is entered rarely, the registers are needed all the time)
+        int tid_s = tid;
+        if constexpr (STREAM) asm volatile("" : "+v"(tid_s));
         int tm, tn;
         logical_to_tile(p, tiles_m, tiles_n, wa_.logical, tm, tn);
         const int m0 = tm * T::BM, rows_m = p.M - m0;
@@ -775,7 +795,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         rs_xb = view(p.x_b, p.x_elems, a_base_elems);
 #pragma unroll
         for (int i = 0; i < AU; ++i) {
-            const int t = tid + i * T::NT;
+            const int t = tid_s + i * T::NT;
             const int q = A_TR ? (t / T::BM) & 3 : t & 3;
             const int row = A_TR ? t % T::BM : (t >> 2) % T::BM;
             const int jh = (t >> 2) / T::BM;
@@ -788,14 +808,10 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     TapCursor tap_b;   // B_FLIP_C32 and the slice order of the patch gather follow the left operand's taps
     __amdgpu_buffer_rsrc_t rs_wa, rs_wb;
     BGen bg[BU];
-    int b_dst[BU];
-#pragma unroll
-    for (int i = 0; i < BU; ++i) {
-        const int t = tid + i * T::NT;
-        const int q = B_TR ? (t / T::BN) & 3 : t & 3, row = B_TR ? t % T::BN : (t >> 2) % T::BN, jh = (t >> 2) / T::BN;
-        b_dst[i] = jh * T::B_RS + row * 16 + q * 4;
-    }
+    const int b_dst0 = unit_dst(tid, T::BN, B_TR);
     auto setup_b = [&]() {
+        int tid_s = tid;
+        if constexpr (STREAM) asm volatile("" : "+v"(tid_s));
         int tm, tn;
         logical_to_tile(p, tiles_m, tiles_n, wb_.logical, tm, tn);
         const int n0 = tn * T::BN, rows_n = p.N - n0;
@@ -805,7 +821,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         rs_wb = view(p.w_b, w_elems, b_base_elems);
 #pragma unroll
         for (int i = 0; i < BU; ++i) {
-            const int t = tid + i * T::NT;
+            const int t = tid_s + i * T::NT;
             const int q = B_TR ? (t / T::BN) & 3 : t & 3;
             const int row = B_TR ? t % T::BN : (t >> 2) % T::BN;
             const int jh = (t >> 2) / T::BN;
@@ -821,13 +837,13 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     auto advance = [&](Walker& w, auto&& setup) {
         ++w.ks;
         if constexpr (STREAM) {
-            if (w.ks == w.nk && w.u < w.u_end) {  // uniform
+            if (w.ks == w.nk && w.u < u_end) {  // uniform
                 enter_tile(w);
                 setup();
             }
         }
     };
-    wa_.u = u0; wa_.u_end = u_end;
+    wa_.u = u0;
     enter_tile(wa_);
     setup_a();
     wb_ = wa_;
@@ -886,7 +902,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         int kb = ks;
         if constexpr (AMODE == A_CONV_C32) {  // the right operand follows the left operand's slice order (see TapCursor)
             tap_b.advance_to(p, ks);
-            kb = tap_b.pks;
+            kb = tap_b.pks(p);
         }
         const bool live = ks < wb_.nk;
         const __amdgpu_buffer_rsrc_t ra = dead_view(b_view(p.w_a, rs_wa, ks), p.w_a, live),
@@ -917,37 +933,47 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     // Pieces of the three batches.  Right operand: the units of w_a + w_b (formed in the registers of w_b,
     // which must happen before w_a is recoded in place), then those of w_a.
     constexpr int NOPS_X = 4 * AU, NOPS_W = 8 * BU;
-    auto split_x = [&](auto op_c, u4 (*x)[2], int share_off, char* a_lo, char* a_hi) {
+    // a_lo / a_hi / b_all: LDS byte addresses of this thread's unit 0 in the buffers written (digit 0, first share)
+    auto split_x = [&](auto op_c, u4 (*x)[2], auto share_c, int a_lo, int a_hi) {
         constexpr int op = decltype(op_c)::value, unit = op / 4;
-        unit_op(x[unit], nullptr, a_lo + share_off + a_dst[unit], a_hi + share_off + a_dst[unit],
-                std::integral_constant<int, T::A_DIG>{}, std::integral_constant<int, op % 4>{});
+        constexpr int off = decltype(share_c)::value * 2 * T::A_RS + unit_delta(unit, T::NT, T::BM, A_TR);
+        unit_op(x[unit], nullptr, lds + a_lo + off, lds + a_hi + off, std::integral_constant<int, T::A_DIG>{},
+                std::integral_constant<int, op % 4>{});
     };
-    auto split_w = [&](auto op_c, char* b_all) {
+    auto split_w = [&](auto op_c, int b_all) {
         constexpr int op = decltype(op_c)::value, unit = op / 4;
         const std::integral_constant<int, T::B_DIG> bdig;
         const std::integral_constant<int, op % 4> phase;
         if constexpr (unit < BU) {
-            unit_op(wb[unit], &wa[unit], b_all + b_dst[unit], b_all + 4 * T::B_DIG + b_dst[unit], bdig, phase);
+            constexpr int off = unit_delta(unit, T::NT, T::BN, B_TR);
+            unit_op(wb[unit], &wa[unit], lds + b_all + off, lds + b_all + 4 * T::B_DIG + off, bdig, phase);
         } else {
-            constexpr int i = unit - BU;
-            unit_op(wa[i], nullptr, b_all + 2 * T::B_RS + b_dst[i], b_all + 4 * T::B_DIG + 2 * T::B_RS + b_dst[i], bdig,
-                    phase);
+            constexpr int off = 2 * T::B_RS + unit_delta(unit - BU, T::NT, T::BN, B_TR);
+            unit_op(wa[unit - BU], nullptr, lds + b_all + off, lds + b_all + 4 * T::B_DIG + off, bdig, phase);
         }
+    };
+    // A byte address in LDS kept in a register of its own: every access then is this register plus a 16-bit
+    // immediate.  (Left to itself the compiler folds all addresses onto one base and spends an instruction
+    // per access on offsets beyond the immediate's range.)
+    auto pin = [](int v) {
+        asm volatile("" : "+v"(v));
+        return v;
     };
 
     // fragment addresses of this lane: row r16 of a 16-row block, k-group kg
     const int a_frag = kg * T::A_RS + (wm * 32 + r16) * 16;
     const int b_frag = kg * T::B_RS + (wn * 32 + r16) * 16;
-    const char* const a_hi_rd = lds + T::OFF_AHI + a_frag;
+    const int a_hi_rd = pin(T::OFF_AHI + a_frag);   // the two addresses that do not change from step to step
+    const int a_hi_wr = pin(T::OFF_AHI + a_dst0);
 
     v4i acc[2][2][8];
     v4i af[4][2], bf[2][2];  // four digits of the left operand, two of the right one; two 16-row blocks each
 
     // One step: the 144 MFMAs of a slice with a hand-placed issue order (every index is a compile-time
     // constant, a full scheduling fence after every slot keeps the compiler from regrouping them).
-    //   a_lo, b_rd : buffers of this step (digits 0-3 of the left operand, all digits of the right one)
-    //   a_lo_wr, b_wr : the other buffers, which receive the next slice; digits 4-7 of the left operand have
-    //                   one buffer, read in phase 1 and rewritten in phase 2, hence the barrier between them
+    // Buffers `par` hold this step's slice (digits 0-3 of the left operand, all digits of the right one), the
+    // other buffers receive the next slice; digits 4-7 of the left operand have one buffer, read in phase 1 and
+    // rewritten in phase 2, hence the barrier between them.
     // Between the MFMAs the next slice is prepared, spread evenly over the step (slots counted over both
     // phases): the right operand's words, loaded late in the step before, are split in slots W0..W1; the
     // left operand's first share is loaded at XA_LOAD and split in XA0..XA1 (its digits 4-7 can only be
@@ -955,45 +981,41 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     // split in XB0..XB1; W_LOAD then fetches the right operand of the slice after the next.
     constexpr int N1 = 40, N2 = 104;
     constexpr int W0 = 3, W1 = 39, XA_LOAD = 1, XA0 = 42, XA1 = 92, XB_LOAD = 41, XB0 = 94, XB1 = 142, W_LOAD = 93;
-    auto step = [&](const char* a_lo, const char* b_rd, char* a_lo_wr, char* b_wr) {
+    auto step = [&](int par) {
+        const int a_lo_rd = pin(par * T::A_HALF + a_frag), b_rd = pin(T::OFF_B + par * T::B_ALL + b_frag);
+        const int a_lo_wr = pin((par ^ 1) * T::A_HALF + a_dst0), b_wr = pin(T::OFF_B + (par ^ 1) * T::B_ALL + b_dst0);
         auto read_a_hi = [&](int l) {   // digit l in 4..7 -> register set l - 4
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
-                af[l - 4][rb] = *reinterpret_cast<const v4i*>(a_hi_rd + (l - 4) * T::A_DIG + rb * 256);
+                af[l - 4][rb] = *reinterpret_cast<const v4i*>(lds + a_hi_rd + (l - 4) * T::A_DIG + rb * 256);
         };
         auto read_a_lo = [&](int l) {   // digit l in 0..3 -> register set l
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
-                af[l][rb] = *reinterpret_cast<const v4i*>(a_lo + a_frag + l * T::A_DIG + rb * 256);
+                af[l][rb] = *reinterpret_cast<const v4i*>(lds + a_lo_rd + l * T::A_DIG + rb * 256);
         };
         auto read_b = [&](int m) {      // digit m -> register set m & 1
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb)
-                bf[m & 1][cb] = *reinterpret_cast<const v4i*>(b_rd + b_frag + m * T::B_DIG + cb * 256);
+                bf[m & 1][cb] = *reinterpret_cast<const v4i*>(lds + b_rd + m * T::B_DIG + cb * 256);
         };
         // what goes between the MFMAs of slot `slot` (0..143 over both phases)
         auto between = [&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
             if constexpr (slot == XA_LOAD) load_xa();
-            if constexpr (slot == XB_LOAD) {
-                load_xb();
-                advance(wa_, setup_a);
-            }
-            if constexpr (slot == W_LOAD) {
-                load_w();
-                advance(wb_, setup_b);
-            }
+            if constexpr (slot == XB_LOAD) load_xb();
+            if constexpr (slot == W_LOAD) load_w();
             if constexpr (slot >= W0 && slot < W1) {
                 constexpr int lo = (slot - W0) * NOPS_W / (W1 - W0), hi = (slot - W0 + 1) * NOPS_W / (W1 - W0);
                 static_for<lo, hi>([&](auto op_c) { split_w(op_c, b_wr); });
             }
             if constexpr (slot >= XA0 && slot < XA1) {
                 constexpr int lo = (slot - XA0) * NOPS_X / (XA1 - XA0), hi = (slot - XA0 + 1) * NOPS_X / (XA1 - XA0);
-                static_for<lo, hi>([&](auto op_c) { split_x(op_c, xa, 0, a_lo_wr, lds + T::OFF_AHI); });
+                static_for<lo, hi>([&](auto op_c) { split_x(op_c, xa, std::integral_constant<int, 0>{}, a_lo_wr, a_hi_wr); });
             }
             if constexpr (slot >= XB0 && slot < XB1) {
                 constexpr int lo = (slot - XB0) * NOPS_X / (XB1 - XB0), hi = (slot - XB0 + 1) * NOPS_X / (XB1 - XB0);
-                static_for<lo, hi>([&](auto op_c) { split_x(op_c, xb, 2 * T::A_RS, a_lo_wr, lds + T::OFF_AHI); });
+                static_for<lo, hi>([&](auto op_c) { split_x(op_c, xb, std::integral_constant<int, 1>{}, a_lo_wr, a_hi_wr); });
             }
         };
         // ---- phase 1: fragments in the order of first use; only the first pair's are awaited before the first MFMA
@@ -1053,9 +1075,9 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     advance(wa_, setup_a);
     load_w();
     advance(wb_, setup_b);
-    static_for<0, NOPS_X>([&](auto op_c) { split_x(op_c, xa, 0, lds, lds + T::OFF_AHI); });
-    static_for<0, NOPS_X>([&](auto op_c) { split_x(op_c, xb, 2 * T::A_RS, lds, lds + T::OFF_AHI); });
-    static_for<0, NOPS_W>([&](auto op_c) { split_w(op_c, lds + T::OFF_B); });
+    static_for<0, NOPS_X>([&](auto op_c) { split_x(op_c, xa, std::integral_constant<int, 0>{}, a_dst0, a_hi_wr); });
+    static_for<0, NOPS_X>([&](auto op_c) { split_x(op_c, xb, std::integral_constant<int, 1>{}, a_dst0, a_hi_wr); });
+    static_for<0, NOPS_W>([&](auto op_c) { split_w(op_c, T::OFF_B + b_dst0); });
     load_w();
     advance(wb_, setup_b);
     __syncthreads();
@@ -1064,7 +1086,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     // One pass of the outer loop per tile.  In the streamed scheme the loaders run straight on into the
     // next tile of the range, so that only the fold separates two tiles.
     Walker wc;
-    wc.u = u0; wc.u_end = u_end;
+    wc.u = u0;
     while (true) {
         enter_tile(wc);
         int tm, tn;
@@ -1075,13 +1097,16 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             const int ke = ks0 + SEG_KSTEPS < wc.nk ? ks0 + SEG_KSTEPS : wc.nk;
             clear_acc();
             for (int ks = ks0; ks < ke; ++ks) {
-                step(lds + par * T::A_HALF, lds + T::OFF_B + par * T::B_ALL, lds + (par ^ 1) * T::A_HALF,
-                     lds + T::OFF_B + (par ^ 1) * T::B_ALL);
+                step(par);
+                // the loaders move on between two steps, where no fragment registers are alive (entering a
+                // new tile computes many addresses)
+                advance(wa_, setup_a);
+                advance(wb_, setup_b);
                 par ^= 1;
             }
             fold_blocks<BMODE == B_FLIP_C32>(p, acc, fm0, fn0, lane, ks0 > wc.ks || p.z_add != 0);
         }
-        if (!STREAM || wc.u >= wc.u_end) break;
+        if (!STREAM || wc.u >= u_end) break;
     }
 }
 
@@ -1156,7 +1181,7 @@ struct PlanesConv {
     __device__ __forceinline__ u4 load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int, const TapCursor& t) const {
         const bool v = pr.ok && t.c0 < p.Cin && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
         // a pixel's Cin words occupy Cin*8 bytes of planes; slice c0/32 starts at c0*8 bytes
-        return __builtin_amdgcn_raw_buffer_load_b128(rs_, v ? pr.base + t.off + c16 : OOB, 0, 0);
+        return __builtin_amdgcn_raw_buffer_load_b128(rs_, v ? pr.base + t.off(p) + c16 : OOB, 0, 0);
     }
 };
 
@@ -1220,7 +1245,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_planes_kernel(const GemmP
     u4 eA[AP], eB[BP], oA[AP], oB[BP];
     auto load_set = [&](__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, int ks, u4* da, u4* db) {
         if (CONV) tap.advance_to(p, ks);
-        const int kb = CONV ? tap.pks : ks;  // the right operand follows the left operand's slice order
+        const int kb = CONV ? tap.pks(p) : ks;  // the right operand follows the left operand's slice order
 #pragma unroll
         for (int i = 0; i < AP; ++i) da[i] = ag[i].load(p, ra, ks, tap);
 #pragma unroll
