@@ -4,9 +4,14 @@ TEST INFRASTRUCTURE ONLY: tests, the smoke check and the benchmark's
 ``cpu_baseline`` leg may import this module; the product package never does.
 
 All functions take and return numpy arrays of dtype uint64 (ring elements of
-Z_{2^64}) or float64 (reals before encoding / after decoding).  No function
-here does arithmetic of its own: each one forwards to the C routine of the
-same name, which writes the paper's definition out as plain loops.
+Z_{2^64}) or float64 (reals before encoding / after decoding).  The ring
+products, convolutions, element-wise share operations, the PRF and the
+truncation steps forward to the C routine of the same name, which writes the
+paper's definition out as plain loops.  The binary-share section further down
+(the adder circuits for the most significant bit, their gates and the bit-plane
+helpers) is numpy arithmetic of this module's own: XOR / AND / shifts on whole
+arrays, written gate by gate, and pinned by the plain integer sum of the shares
+in ``tests/test_oracle_msb.py``.
 """
 from __future__ import annotations
 

@@ -645,11 +645,10 @@ cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     if (!trans_x && trans_y) pl.amode = vec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR;
     // a transposed operand is addressed slice by slice: 32 rows of its pitch must fit a 2^31-byte view
     if ((trans_x && M > (1 << 22)) || (trans_y && N > (1 << 22))) return CG_ERR_UNSUPPORTED;
-    const int64_t KS = (K + 31) / 32;
     pl.planes_ok = vec && !trans_x && !trans_y;
     pl.planes_conv = false;
     pl.x_rows = M; pl.x_k = K;
-    pl.xp_bytes = (u64)M * (u64)KS * 256; pl.wp_bytes = (u64)N * (u64)KS * 256;
+    pl.xp_bytes = cg::planes_bytes(M, K); pl.wp_bytes = cg::planes_bytes(N, K);
     pl.x_bytes = (u64)mk * 8; pl.w_bytes = (u64)nk * 8; pl.z_bytes = (u64)mn * 8;
     *out = pl;
     return CG_OK;
@@ -732,19 +731,20 @@ cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     }
     pl.amode = amode;
     pl.bmode = bvec ? cg::B_VEC : cg::B_SCALAR;
-    const int64_t KS = (K + 31) / 32;
     if (pointwise) {
         pl.planes_ok = bvec;
         pl.planes_conv = false;
         pl.x_rows = M; pl.x_k = d->Cin;
-        pl.xp_bytes = (u64)M * (u64)KS * 256;
     } else {
-        pl.planes_ok = amode == cg::A_CONV_C32;
+        // (the plane view of a block starts up to 15 pixels ahead of its first image)
+        const int64_t span_imgs = (cg::MAX_TILE_ROWS - 1) / howo + 2;
+        const int64_t view = (span_imgs < d->B ? span_imgs : d->B) * img * 8 + 16 * d->Cin * 8;
+        pl.planes_ok = amode == cg::A_CONV_C32 && view <= MAX_VIEW_BYTES;
         pl.planes_conv = true;
         pl.x_rows = d->B * d->H * d->W; pl.x_k = d->Cin;
-        pl.xp_bytes = (u64)x_el * 8;
     }
-    pl.wp_bytes = (u64)d->Cout * (u64)KS * 256;
+    pl.xp_bytes = cg::planes_bytes(pl.x_rows, pl.x_k);
+    pl.wp_bytes = cg::planes_bytes(d->Cout, K);
     pl.x_bytes = (u64)x_el * 8; pl.w_bytes = (u64)w_el * 8; pl.z_bytes = (u64)z_el * 8;
     *out = pl;
     return CG_OK;
@@ -968,7 +968,8 @@ cg_status run_planes(Plan& pl, void* workspace, size_t workspace_bytes, void* st
     if (e != hipSuccess) return CG_ERR_DEVICE;
     pl.p.xp_a = xp_a; pl.p.xp_b = xp_b; pl.p.wp_sum = wp_sum; pl.p.wp_a = wp_a;
     pl.p.xp_bytes = pl.xp_bytes;
-    e = cg::launch_share_gemm_planes(pl.p, pl.planes_conv, s);
+    pl.p.wp_bytes = pl.wp_bytes;
+    e = cg::launch_share_gemm(pl.p, pl.planes_conv ? cg::A_PLANES_CONV : cg::A_PLANES, cg::B_PLANES, s);
     return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
 

@@ -29,8 +29,10 @@ enum AMode {
     A_CONV_C32 = 2,       // NHWC patch gather, Cin % 32 == 0, 16-byte loads
     A_CONV_GEN = 3,       // NHWC patch gather, any Cin, 8-byte loads
     A_TRANS = 4,          // stored transposed, [K, M] with M contiguous, 8-byte loads
-    A_CONV_DIL = 5        // NHWC patch gather from an image whose pixels sit dil_h, dil_w apart
+    A_CONV_DIL = 5,       // NHWC patch gather from an image whose pixels sit dil_h, dil_w apart
                           // with zeros between them (input gradient of a strided convolution)
+    A_PLANES = 6,         // row-major [M, K] kept as digit planes (xp_a, xp_b; see to_planes_kernel)
+    A_PLANES_CONV = 7     // NHWC patch gather, Cin % 32 == 0, from the digit planes of the [pixels, Cin] matrix
 };
 
 // How the right operand's words are addressed.
@@ -45,7 +47,8 @@ enum BMode {
                      // sub-grid of the pixels (see flt_* and out_* below)
     B_FLIP_GEN = 4,  // ... any Cout: every word finds its own tap
     // Weight gradient: the right operand is the layer input, B[(r, s, c), pixel] = patch entry
-    B_PATCH_T = 5
+    B_PATCH_T = 5,
+    B_PLANES = 6     // row-major [N, K] kept as digit planes (wp_sum, wp_a)
 };
 
 struct GemmParams {
@@ -73,6 +76,7 @@ struct GemmParams {
     // digit-plane route: planes of x_i, x_{i+1}, y_i + y_{i+1}, y_i (see to_planes_kernel)
     const char *xp_a, *xp_b, *wp_sum, *wp_a;
     uint64_t xp_bytes;          // bytes of one left-operand plane tensor
+    uint64_t wp_bytes;          // bytes of one right-operand plane tensor
     int group_m;                // tile-rows per launch-order group (set by the launcher)
     int ksplit;                 // number of K ranges the grid is replicated over (set by the launcher)
     int64_t stream_per;         // > 0: (tile, slice) units per block of the streamed distribution (set by the launcher)
@@ -95,10 +99,13 @@ hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream);
 
 // Digit-plane route.  launch_to_planes converts a row-major [R, K] operand (K even,
 // 16-byte aligned), optionally summed with `add` first, into planes of
-// R * ceil(K/32) * 256 bytes; launch_share_gemm_planes contracts four plane tensors.
+// planes_bytes(R, K) bytes; launch_share_gemm with the modes A_PLANES / A_PLANES_CONV and
+// B_PLANES contracts four plane tensors.
 hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,
                             hipStream_t stream);
-hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t stream);
+inline uint64_t planes_bytes(int64_t R, int64_t K) {
+    return (uint64_t)((R + 15) / 16 * 16) * (uint64_t)((K + 31) / 32) * 256u;
+}
 
 }  // namespace cg
 #endif

@@ -47,7 +47,6 @@
 namespace cg {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32;
@@ -57,33 +56,9 @@ typedef uint64_t u64;
 // the hardware then returns zeros instead of reading memory.
 static constexpr u32 OOB = 0x80000000u;
 
-// Slices of K (32 elements each) between two folds of the i32 accumulators:
-// 2*511 = 1022 half-steps <= 1023.
+// Slices of K (32 words of each share) between two folds of the i32 accumulators: a slice adds
+// (s + 1) * 64 digit products of at most 2^14 to P_s, so P_0..P_3 stay exact for 511 slices.
 static constexpr int SEG_KSTEPS = 511;
-
-// Hand-placed issue order of a half-step (see half_step() in the kernel): the split work of the
-// next half-step starts after PRE_EIGHTHS/8 of the MFMAs; fragments of the left operand are fetched
-// from LDS one digit ahead, those of the right operand two MFMA slots ahead.
-static constexpr int PRE_EIGHTHS = 3;
-static constexpr int A_AHEAD = 1;
-static constexpr int B_AHEAD = 2;
-
-
-template <int WM_, int WN_, int SM_, int SN_>
-struct Tile {
-    static constexpr int WM = WM_, WN = WN_, SM = SM_, SN = SN_;
-    static constexpr int BM = WM * SM * 32, BN = WN * SN * 32;
-    static constexpr int NT = WM * WN * 64;
-    // A "unit" is 4 words of one row: two 16-byte loads, one 4x4 byte transpose
-    // per 32-bit half, eight 4-byte LDS writes.
-    static constexpr int A_UNITS = BM * 8 / NT, B_UNITS = BN * 8 / NT;
-    static constexpr int A_RS = BM * 16, B_RS = BN * 16;  // bytes of one [digit][k-half] slab
-    static constexpr int A_BYTES = 16 * A_RS, B_BYTES = 16 * B_RS;
-    static constexpr int STAGE = A_BYTES + B_BYTES;
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile does not divide over the threads");
-};
-// Default block tile: 4 x 2 waves, one 32x32 sub-tile per wave = 128 x 64.
-typedef Tile<4, 2, 1, 1> DefaultTile;
 
 // Block tile of the fused kernel: WM x WN waves, each computing a 32 x 32 sub-tile as 2 x 2 blocks of
 // v_mfma_i32_16x16x64_i8.  One step covers a 32-word slice of K for BOTH shares of each operand:
@@ -474,6 +449,57 @@ struct PatchTrans {
     }
 };
 
+// Digit planes (see to_planes_kernel): this thread's row of a tile and its first piece.  The thread moves the
+// pieces of ONE row: for the left operand those of digits cq and cq + 4 in both k-halves, for the right operand
+// those of digit cq in both k-halves.
+struct PlanesRow {
+    u32 off0;  // byte offset, relative to the view, of piece cq of slice 0 of the row's 16-row block; or OOB
+    __device__ __forceinline__ void init(int row_local, int rows_left, u32 KS, int cq) {
+        off0 = row_local < rows_left
+                   ? ((u32)(row_local >> 4) * KS * 16u + (u32)cq) * 256u + (u32)(row_local & 15) * 16u
+                   : OOB;
+    }
+};
+
+// Patch gather from the digit planes of the activations seen as a [pixels, Cin] matrix, Cin % 32 == 0.
+struct PlanesPatch {
+    u32 pix0;     // pixel index of (hi0, wi0) relative to the view's first 16-pixel block (mod 2^32)
+    int hi0, wi0;
+    bool ok;
+    u64 inside;   // bit t: tap t = r*kw + s reads a pixel inside the image
+    u32 cq256;
+    __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, int cq) {
+        ok = row_local < rows_left;
+        const u32 m = (u32)(m0 + (ok ? row_local : 0));
+        const u32 HoWo = (u32)(p.Ho * p.Wo), HW = (u32)(p.H * p.W);
+        const u32 b = m / HoWo, b0 = (u32)m0 / HoWo;
+        const u32 rem = m - b * HoWo;
+        const u32 ho = rem / (u32)p.Wo, wo = rem - ho * (u32)p.Wo;
+        hi0 = (int)ho * p.sh - p.ph;
+        wi0 = (int)wo * p.sw - p.pw;
+        // the view starts at the 16-pixel block that holds the first pixel of image b0
+        pix0 = ((b0 * HW) & 15u) + (b - b0) * HW + (u32)hi0 * (u32)p.W + (u32)wi0;
+        cq256 = (u32)cq * 256u;
+        inside = 0;
+        const int taps = p.kh * p.kw;
+        if (ok && taps <= 64) {
+            int t = 0;
+            for (int r = 0; r < p.kh; ++r)
+                for (int s_ = 0; s_ < p.kw; ++s_, ++t)
+                    if ((u32)(hi0 + r) < (u32)p.H && (u32)(wi0 + s_) < (u32)p.W) inside |= 1ull << t;
+        }
+    }
+    // byte offset of piece cq of the slice the cursor points at, or OOB
+    __device__ __forceinline__ u32 offset(const GemmParams& p, const TapCursor& t) const {
+        bool v;
+        if (p.kh * p.kw <= 64) v = t.c0 < p.Cin && ((inside >> t.tap(p)) & 1);
+        else v = ok && t.c0 < p.Cin && (u32)(hi0 + t.r) < (u32)p.H && (u32)(wi0 + t.s) < (u32)p.W;
+        const u32 pix = pix0 + (u32)t.r * (u32)p.W + (u32)t.s;
+        const u32 KS = (u32)p.Cin >> 5;
+        return v ? ((pix >> 4) * KS + ((u32)t.c0 >> 5)) * 4096u + cq256 + (pix & 15u) * 16u : OOB;
+    }
+};
+
 // compile-time loop: f(integral_constant<int, I>) for I in [I0, N)
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -481,21 +507,6 @@ __device__ __forceinline__ void static_for(F&& f) {
         f(std::integral_constant<int, I>{});
         static_for<I + 1, N>(f);
     }
-}
-
-// The MFMAs of one half-step in issue order: digit l of the left operand
-// outermost, digit m of the right operand (l + m <= 7) next, then the wave's
-// 32x32 sub-tiles.
-struct Slot {
-    int l, m, sm, sn;
-};
-constexpr Slot decode_slot(int slot, int SM, int SN) {
-    const int per = SM * SN;
-    int pair = slot / per;
-    const int in = slot % per;
-    int l = 0, cnt = 8;
-    while (pair >= cnt) { pair -= cnt; ++l; --cnt; }
-    return Slot{l, pair, in / SN, in % SN};
 }
 
 __device__ __forceinline__ void recode2(u4& v) {
@@ -547,57 +558,13 @@ __device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int B
     logical_to_tile(p, tiles_m, tiles_n, run - split * nb, tm, tn);
 }
 
-// fold: z (+)= sum_s sext(P_s) << 8s for the wave's sub-tiles.  P_4..P_7 only
-// reach bits 32..63.  Modes: plain store (one fold, one split), read-add-write by
-// the owning lane (later folds of a single split), atomic add into a zero-filled z
-// (split-K: integer sums mod 2^64 are exact in any order).  The lane index passes
-// through an empty asm so that none of the output addresses or bounds tests can be
-// computed ahead of the K loop, where they would sit in registers the loop needs.
-// REMAP: the rows are scattered over the pixels of a larger tensor (see GemmParams::out_*).
-template <int SM, int SN, bool REMAP = false>
-__device__ __forceinline__ void fold_tile(const GemmParams& p, v16i (&acc)[SM][SN][8], int row0, int col0,
-                                          int lane, bool accumulate) {
-    int lane_f = lane;
-    asm volatile("" : "+v"(lane_f));
-    const int r32f = lane_f & 31, hf = lane_f >> 5;
-#pragma unroll
-    for (int sm = 0; sm < SM; ++sm)
-#pragma unroll
-        for (int sn = 0; sn < SN; ++sn) {
-            const int col = col0 + sn * 32 + r32f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = row0 + sm * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
-                u64 v = (u64)(int64_t)acc[sm][sn][0][i];
-                v += (u64)(int64_t)acc[sm][sn][1][i] << 8;
-                v += (u64)(int64_t)acc[sm][sn][2][i] << 16;
-                v += (u64)(int64_t)acc[sm][sn][3][i] << 24;
-                const u32 hi = (u32)acc[sm][sn][4][i] + ((u32)acc[sm][sn][5][i] << 8) +
-                               ((u32)acc[sm][sn][6][i] << 16) + ((u32)acc[sm][sn][7][i] << 24);
-                v += (u64)hi << 32;
-                if (row < p.M && col < p.N) {
-                    u64 zrow = (u64)row;
-                    if constexpr (REMAP) {
-                        const u32 b = fast_div((u32)row, p.div_howo);
-                        const u32 rem = (u32)row - b * (u32)(p.Ho * p.Wo);
-                        const u32 i_ = fast_div(rem, p.div_wo), j_ = rem - i_ * (u32)p.Wo;
-                        zrow = ((u64)b * (u64)p.out_H + (u64)(p.out_h0 + p.out_sh * (int)i_)) * (u64)p.out_W +
-                               (u64)(p.out_w0 + p.out_sw * (int)j_);
-                    }
-                    u64* dst = p.z + zrow * (u64)p.N + (u64)col;
-                    if (p.ksplit > 1) {
-                        atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
-                    } else {
-                        if (accumulate) v += *dst;
-                        *dst = v;
-                    }
-                }
-            }
-        }
-}
-
-// fold of the fused kernel's accumulators: the wave's 32 x 32 sub-tile is 2 x 2 blocks of 16 x 16, and
-// lane i holds rows 4*(i/16) .. +3 of column i%16 of each block.  Modes as in fold_tile.
+// fold: z (+)= sum_s sext(P_s) << 8s for the wave's 32 x 32 sub-tile, which is 2 x 2 blocks of 16 x 16; lane i
+// holds rows 4*(i/16) .. +3 of column i%16 of each block.  P_4..P_7 only reach bits 32..63.  Modes: plain store
+// (one fold, one split), read-add-write by the owning lane (later folds of a single split), atomic add into a
+// zero-filled z (split-K: integer sums mod 2^64 are exact in any order).  The lane index passes through an empty
+// asm so that none of the output addresses or bounds tests can be computed ahead of the K loop, where they would
+// sit in registers the loop needs.  REMAP: the rows are scattered over the pixels of a larger tensor (see
+// GemmParams::out_*).
 template <bool REMAP>
 __device__ __forceinline__ void fold_blocks(const GemmParams& p, v4i (&acc)[2][2][8], int row0, int col0, int lane,
                                             bool accumulate) {
@@ -749,6 +716,13 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
 
     constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
     constexpr bool A_TR = AMODE == A_TRANS;
+    // digit-plane route: both operands arrive split; a thread moves the pieces of one row of each tile
+    constexpr bool PLANES = AMODE == A_PLANES || AMODE == A_PLANES_CONV;
+    static_assert(PLANES == (BMODE == B_PLANES), "plane operands come in pairs");
+    static_assert(!PLANES || (T::NT == 4 * T::BM && T::NT == 8 * T::BN && AU == 2 && BU == 1),
+                  "the plane route's piece distribution assumes the 128 x 64 tile");
+    // the slices follow the taps of a patch gather (see TapCursor)
+    constexpr bool A_TAPS = AMODE == A_CONV_C32 || AMODE == A_PLANES_CONV;
     // right-operand modes whose memory is contiguous along n: consecutive lanes take consecutive rows
     constexpr bool B_TR = BMODE == B_TRANS || BMODE == B_FLIP_C32 || BMODE == B_FLIP_GEN || BMODE == B_PATCH_T;
     // ---- per-thread units.  Row-major operands put the four 16-byte quarters of a
@@ -762,6 +736,8 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             typename std::conditional<BMODE == B_SCALAR, LinearScalar,
             typename std::conditional<BMODE == B_FLIP_GEN, FlipGen,
             typename std::conditional<BMODE == B_PATCH_T, PatchTrans, TransScalar>::type>::type>::type>::type BGen;
+    PlanesRow pa_row, pb_row;   // plane route: this thread's row of the left and of the right tile
+    PlanesPatch pa_patch;
     const u64 w_elems = p.w_elems;
     // view on `elems_total` words starting `base` words in
     auto view = [&](const u64* ptr, u64 elems_total, u64 base) {
@@ -778,7 +754,8 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     AGen ag[AU];
     // LDS byte offset of unit 0 inside the slab set of digit 0, first share; where a thread's units go does
     // not depend on the tile, and unit i lies a compile-time distance from unit 0 (see unit_delta)
-    const int a_dst0 = unit_dst(tid, T::BM, A_TR);
+    // (plane route: row tid % BM, digit tid / BM of the low half; the k-half is the unit)
+    const int a_dst0 = PLANES ? (tid % T::BM) * 16 + (tid / T::BM) * T::A_DIG : unit_dst(tid, T::BM, A_TR);
     auto setup_a = [&]() {
         // (the thread id passes through an empty asm so that nothing below is computed ahead of the K loop and
         // kept in registers across it: a new tile is entered rarely, the registers are needed all the time)
@@ -787,6 +764,23 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         int tm, tn;
         logical_to_tile(p, tiles_m, tiles_n, wa_.logical, tm, tn);
         const int m0 = tm * T::BM, rows_m = p.M - m0;
+        if constexpr (PLANES) {
+            const u32 KS = (u32)((AMODE == A_PLANES ? p.K : p.Cin) + 31) >> 5;
+            u64 base;   // bytes: the 16-row block of the tile's first row / of its first image's first pixel
+            if constexpr (AMODE == A_PLANES) {
+                base = (u64)(m0 >> 4) * KS * 4096u;
+                pa_row.init(tid_s % T::BM, rows_m, KS, tid_s / T::BM);
+            } else {
+                base = (((u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)(p.H * p.W)) >> 4) * KS * 4096u;
+                pa_patch.init(p, m0, tid_s % T::BM, rows_m, tid_s / T::BM);
+            }
+            tap_a.reset();
+            const u64 left = p.xp_bytes - base;
+            const u32 bytes = left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left;
+            rs_xa = make_rsrc(p.xp_a + base, bytes);
+            rs_xb = make_rsrc(p.xp_b + base, bytes);
+            return;
+        }
         if (A_LINEAR) a_base_elems = (u64)m0 * (u64)p.lda;
         else if (A_TR) a_base_elems = (u64)m0;
         else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
@@ -808,13 +802,24 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     TapCursor tap_b;   // B_FLIP_C32 and the slice order of the patch gather follow the left operand's taps
     __amdgpu_buffer_rsrc_t rs_wa, rs_wb;
     BGen bg[BU];
-    const int b_dst0 = unit_dst(tid, T::BN, B_TR);
+    const int b_dst0 = PLANES ? (tid % T::BN) * 16 + (tid / T::BN) * T::B_DIG : unit_dst(tid, T::BN, B_TR);
     auto setup_b = [&]() {
         int tid_s = tid;
         if constexpr (STREAM) asm volatile("" : "+v"(tid_s));
         int tm, tn;
         logical_to_tile(p, tiles_m, tiles_n, wb_.logical, tm, tn);
         const int n0 = tn * T::BN, rows_n = p.N - n0;
+        if constexpr (PLANES) {
+            const u32 KS = (u32)(p.K + 31) >> 5;
+            const u64 base = (u64)(n0 >> 4) * KS * 4096u;
+            pb_row.init(tid_s % T::BN, rows_n, KS, tid_s / T::BN);
+            tap_b.reset();
+            const u64 left = p.wp_bytes - base;
+            const u32 bytes = left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left;
+            rs_wa = make_rsrc(p.wp_a + base, bytes);
+            rs_wb = make_rsrc(p.wp_sum + base, bytes);   // the registers of w_b hold w_a + w_b on this route
+            return;
+        }
         b_base_elems = BMODE == B_PATCH_T ? 0 : (B_TR ? (u64)n0 : (u64)n0 * (u64)p.K);
         tap_b.reset();
         rs_wa = view(p.w_a, w_elems, b_base_elems);
@@ -882,7 +887,21 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     u4 xa[AU][2], xb[AU][2], wa[BU][2], wb[BU][2];
 
     auto load_a = [&](__amdgpu_buffer_rsrc_t rs, int ks, u4 (*dst)[2]) {
-        if constexpr (AMODE == A_CONV_C32) {
+        if constexpr (PLANES) {
+            // unit g = k-half: its low-digit piece (cq) and its high-digit piece (cq + 4)
+            u32 off;
+            if constexpr (AMODE == A_PLANES) {
+                off = pa_row.off0 + (u32)ks * 4096u;
+            } else {
+                tap_a.advance_to(p, ks);
+                off = pa_patch.offset(p, tap_a);
+            }
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                dst[g][0] = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 2048u * g, 0, 0);
+                dst[g][1] = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 2048u * g + 1024u, 0, 0);
+            }
+        } else if constexpr (AMODE == A_CONV_C32) {
             tap_a.advance_to(p, ks);
 #pragma unroll
             for (int i = 0; i < AU; ++i) ag[i].load(p, rs, tap_a, dst[i]);
@@ -900,17 +919,27 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     auto load_w = [&]() {
         const int ks = wb_.ks;
         int kb = ks;
-        if constexpr (AMODE == A_CONV_C32) {  // the right operand follows the left operand's slice order (see TapCursor)
+        if constexpr (A_TAPS) {  // the right operand follows the left operand's slice order (see TapCursor)
             tap_b.advance_to(p, ks);
             kb = tap_b.pks(p);
         }
         const bool live = ks < wb_.nk;
         const __amdgpu_buffer_rsrc_t ra = dead_view(b_view(p.w_a, rs_wa, ks), p.w_a, live),
                                      rb = dead_view(b_view(p.w_b, rs_wb, ks), p.w_b, live);
+        if constexpr (PLANES) {
+            // digit cq of both k-halves, from the planes of w_a and of w_a + w_b
+            const u32 off = pb_row.off0 + (u32)kb * 4096u;
 #pragma unroll
-        for (int i = 0; i < BU; ++i) bg[i].load(p, ra, kb, (u32)p.K, wa[i]);
+            for (int g = 0; g < 2; ++g) {
+                wa[0][g] = __builtin_amdgcn_raw_buffer_load_b128(ra, off + 2048u * g, 0, 0);
+                wb[0][g] = __builtin_amdgcn_raw_buffer_load_b128(rb, off + 2048u * g, 0, 0);
+            }
+        } else {
 #pragma unroll
-        for (int i = 0; i < BU; ++i) bg[i].load(p, rb, kb, (u32)p.K, wb[i]);
+            for (int i = 0; i < BU; ++i) bg[i].load(p, ra, kb, (u32)p.K, wa[i]);
+#pragma unroll
+            for (int i = 0; i < BU; ++i) bg[i].load(p, rb, kb, (u32)p.K, wb[i]);
+        }
     };
 
     // The split of one unit in four pieces, so that they can be placed between MFMAs:
@@ -936,12 +965,25 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     // a_lo / a_hi / b_all: LDS byte addresses of this thread's unit 0 in the buffers written (digit 0, first share)
     auto split_x = [&](auto op_c, u4 (*x)[2], auto share_c, int a_lo, int a_hi) {
         constexpr int op = decltype(op_c)::value, unit = op / 4;
+        if constexpr (PLANES) {   // the pieces are stored as they are: the low-digit one, then the high-digit one
+            constexpr int poff = decltype(share_c)::value * 2 * T::A_RS + unit * T::A_RS;
+            if constexpr (op % 4 == 2) *reinterpret_cast<u4*>(lds + a_lo + poff) = x[unit][0];
+            if constexpr (op % 4 == 3) *reinterpret_cast<u4*>(lds + a_hi + poff) = x[unit][1];
+            return;
+        }
         constexpr int off = decltype(share_c)::value * 2 * T::A_RS + unit_delta(unit, T::NT, T::BM, A_TR);
         unit_op(x[unit], nullptr, lds + a_lo + off, lds + a_hi + off, std::integral_constant<int, T::A_DIG>{},
                 std::integral_constant<int, op % 4>{});
     };
     auto split_w = [&](auto op_c, int b_all) {
         constexpr int op = decltype(op_c)::value, unit = op / 4;
+        if constexpr (PLANES) {   // unit 0: pieces of w_a + w_b (k-groups 0, 1); unit 1: pieces of w_a (k-groups 2, 3)
+            if constexpr (op % 4 >= 2) {
+                constexpr int g = op % 4 - 2;
+                *reinterpret_cast<u4*>(lds + b_all + (2 * unit + g) * T::B_RS) = unit == 0 ? wb[0][g] : wa[0][g];
+            }
+            return;
+        }
         const std::integral_constant<int, T::B_DIG> bdig;
         const std::integral_constant<int, op % 4> phase;
         if constexpr (unit < BU) {
@@ -1110,235 +1152,62 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     }
 }
 
-// ---------------------------------------------------------------------------
 // ===========================================================================
 // Digit-plane route.  The split of a word into digits is the same whoever uses
 // the word, yet a tile of the left operand is needed by every block column and,
 // in a convolution, by every filter tap.  With caller-supplied scratch memory
 // the split is therefore done ONCE per operand by to_planes_kernel, which writes
-// the digits as int8 "planes", and the contraction kernel below only moves
-// 16-byte pieces from HBM to LDS: no vector-ALU work per MFMA.
+// the digits as int8 "planes", and the product kernel (address modes A_PLANES,
+// A_PLANES_CONV, B_PLANES) only moves 16-byte pieces from memory to LDS: no
+// vector-ALU work per MFMA.
 //
-// Plane format of a row-major [R, K] operand, KS = ceil(K/32) slices per row:
-//     byte (row, ks, c, j) at ((row*KS + ks)*16 + c)*16 + j,  c = 8*g + l,
-// holds digit l of word k = 32*ks + 16*g + j (zero beyond K): per row and slice
-// 256 bytes = 16 pieces of 16 bytes, a piece being one MFMA operand register set
-// for one k-half g.  The format has the size of the raw operand (rows padded to
-// whole slices).
+// Plane format of a row-major [R, K] operand, KS = ceil(K/32) slices per row, rows in
+// blocks of 16:
+//     byte (row, ks, c, j) at (((row/16)*KS + ks)*16 + c)*256 + (row%16)*16 + j,  c = 8*g + l,
+// holds digit l of word k = 32*ks + 16*g + j (zero beyond K and beyond R): a piece of 16
+// bytes is one MFMA operand register set for one k-half g, and the sixteen rows of a
+// block lie next to each other piece by piece, which is the order the product kernel's
+// LDS planes have.  The format has the size of the raw operand (rows padded to a
+// multiple of 16, K to whole slices).
 // ===========================================================================
 
-// One thread converts four consecutive words of a row: the four lanes of a quad
-// read 128 contiguous bytes and write, digit by digit, 16 contiguous bytes.
+// One thread converts four consecutive words of a row; the 64 lanes of a wave take the four
+// 4-word quarters of one k-half of sixteen rows, so that each of their eight stores (one per
+// digit) writes 256 contiguous bytes.
 __global__ __launch_bounds__(256) void to_planes_kernel(const u64* __restrict__ src, const u64* __restrict__ add,
                                                         char* __restrict__ dst, u32 R, u32 K, u32 KS) {
-    const u64 units = (u64)R * KS * 8;  // 8 four-word units per 32-word slice
+    const u64 rb_count = (R + 15) / 16;
+    const u64 units = rb_count * KS * 2 * 64;  // per row block, slice and k-half: 16 rows x 4 quarters
     for (u64 ui = (u64)blockIdx.x * 256 + threadIdx.x; ui < units; ui += (u64)gridDim.x * 256) {
-        const u32 row = (u32)(ui / (8 * KS)), in_row = (u32)(ui - (u64)row * 8 * KS);
-        const u32 k0 = 4 * in_row;  // first word of the unit
-        const u64* s = src + (u64)row * K + k0;
-        const u64* a = add ? add + (u64)row * K + k0 : nullptr;
+        const u32 lane = (u32)(ui & 63), q = lane & 3, r16 = lane >> 2;
+        const u64 grp = ui >> 6;
+        const u32 g = (u32)(grp & 1);
+        const u64 bs = grp >> 1;                 // (row block, slice)
+        const u32 ks = (u32)(bs % KS);
+        const u64 rb = bs / KS;
+        const u64 row = rb * 16 + r16;
+        const u32 k0 = 32 * ks + 16 * g + 4 * q;  // first word of the unit
         u4 v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
-        if (k0 < K) {  // K is even: words come in valid pairs
-            v0 = *reinterpret_cast<const u4*>(s);
-            if (a) v0 = add64x2(v0, *reinterpret_cast<const u4*>(a));
-        }
-        if (k0 + 2 < K) {
-            v1 = *reinterpret_cast<const u4*>(s + 2);
-            if (a) v1 = add64x2(v1, *reinterpret_cast<const u4*>(a + 2));
+        if (row < R) {
+            const u64* s_ = src + row * K + k0;
+            const u64* a = add ? add + row * K + k0 : nullptr;
+            if (k0 < K) {  // K is even: words come in valid pairs
+                v0 = *reinterpret_cast<const u4*>(s_);
+                if (a) v0 = add64x2(v0, *reinterpret_cast<const u4*>(a));
+            }
+            if (k0 + 2 < K) {
+                v1 = *reinterpret_cast<const u4*>(s_ + 2);
+                if (a) v1 = add64x2(v1, *reinterpret_cast<const u4*>(a + 2));
+            }
         }
         recode2(v0);
         recode2(v1);
         u32 d[8];
         transpose4(v0.x, v0.z, v1.x, v1.z, d);
         transpose4(v0.y, v0.w, v1.y, v1.w, d + 4);
-        // slice ks = in_row / 8, k-half g = (in_row / 4) & 1, dword q = in_row & 3 of each piece
-        char* o = dst + ((u64)row * KS + in_row / 8) * 256 + ((in_row >> 2) & 1) * 128 + (in_row & 3) * 4;
+        char* o = dst + ((bs * 16 + 8 * g) * 256) + r16 * 16 + q * 4;
 #pragma unroll
-        for (int l = 0; l < 8; ++l) *reinterpret_cast<u32*>(o + l * 16) = d[l];
-    }
-}
-
-// Piece addressing of the contraction kernel: piece (row, c) of slice ks.
-struct PlanesLinear {
-    u32 off0;  // byte offset of piece c of slice 0 of the row inside the view, or OOB
-    __device__ __forceinline__ void init(const GemmParams&, int, int row_local, int rows_left, u32 row_bytes,
-                                         int c) {
-        off0 = row_local < rows_left ? (u32)row_local * row_bytes + (u32)c * 16u : OOB;
-    }
-    __device__ __forceinline__ u4 load(const GemmParams&, __amdgpu_buffer_rsrc_t r, int ks, const TapCursor&) const {
-        return __builtin_amdgcn_raw_buffer_load_b128(r, off0 + 256u * ks, 0, 0);
-    }
-};
-
-// Patch gather from activation planes [pixel][Cin/32][256 bytes], Cin % 32 == 0.
-struct PlanesConv {
-    PatchRow pr;  // pr.base in units of pixels*Cin*8 bytes, as for raw words: planes have the same pitch
-    u32 c16;
-    __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, u32, int c) {
-        pr.init(p, m0, row_local, rows_left);
-        c16 = (u32)c * 16u;
-    }
-    __device__ __forceinline__ u4 load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, int, const TapCursor& t) const {
-        const bool v = pr.ok && t.c0 < p.Cin && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
-        // a pixel's Cin words occupy Cin*8 bytes of planes; slice c0/32 starts at c0*8 bytes
-        return __builtin_amdgcn_raw_buffer_load_b128(rs_, v ? pr.base + t.off(p) + c16 : OOB, 0, 0);
-    }
-};
-
-template <class T, bool CONV>
-__global__ __launch_bounds__(T::NT, 1) void share_gemm_planes_kernel(const GemmParams p) {
-    constexpr int SM = T::SM, SN = T::SN;
-    constexpr int AP = T::BM * 16 / T::NT, BP = T::BN * 16 / T::NT;  // 16-byte pieces per thread and half-step
-    static_assert(T::BM * 16 % T::NT == 0 && T::BN * 16 % T::NT == 0, "tile does not divide over the threads");
-    constexpr int A_BYTES = T::BM * 256, STAGE = (T::BM + T::BN) * 256;
-    __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % T::WM, wn = wave / T::WM;
-    const int r32 = lane & 31, h = lane >> 5;
-
-    int split, tm, tn;
-    block_to_tile(p, T::BM, T::BN, split, tm, tn);
-    const int m0 = tm * T::BM, n0 = tn * T::BN;
-    const int rows_m = p.M - m0, rows_n = p.N - n0;
-
-    // ---- buffer views on the four plane tensors, rebased per block
-    const int KS = (p.K + 31) / 32;
-    const u32 b_row_bytes = (u32)KS * 256u;
-    const u32 a_row_bytes = CONV ? 0u : b_row_bytes;
-    u64 a_base;
-    if (CONV) a_base = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems * 8u;
-    else a_base = (u64)m0 * a_row_bytes;
-    const u64 a_left = p.xp_bytes - a_base;
-    const u32 a_bytes = a_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)a_left;
-    const __amdgpu_buffer_rsrc_t rs_a0 = make_rsrc(p.xp_a + a_base, a_bytes);
-    const __amdgpu_buffer_rsrc_t rs_a1 = make_rsrc(p.xp_b + a_base, a_bytes);
-    const u64 b_base = (u64)n0 * b_row_bytes;
-    const u64 b_left = (u64)p.N * b_row_bytes - b_base;
-    const u32 b_bytes = b_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)b_left;
-    const __amdgpu_buffer_rsrc_t rs_b0 = make_rsrc(p.wp_sum + b_base, b_bytes);
-    const __amdgpu_buffer_rsrc_t rs_b1 = make_rsrc(p.wp_a + b_base, b_bytes);
-
-    // ---- per-thread pieces.  LDS keeps a tile row-major, 256 bytes per row, with
-    // the piece index XOR-ed by the row's low four bits: 16 consecutive lanes then
-    // hit 16 different piece slots both when a row is written (16 pieces of one row)
-    // and when fragments are read (one piece of 16 rows).
-    typedef typename std::conditional<CONV, PlanesConv, PlanesLinear>::type AGen;
-    AGen ag[AP];
-    PlanesLinear bg[BP];
-    int a_dst[AP], b_dst[BP];
-#pragma unroll
-    for (int i = 0; i < AP; ++i) {
-        const int u = tid + i * T::NT, c = u & 15, row = u >> 4;
-        ag[i].init(p, m0, row, rows_m, a_row_bytes, c);
-        a_dst[i] = row * 256 + ((c ^ (row & 15)) << 4);
-    }
-#pragma unroll
-    for (int i = 0; i < BP; ++i) {
-        const int u = tid + i * T::NT, c = u & 15, row = u >> 4;
-        bg[i].init(p, n0, row, rows_n, b_row_bytes, c);
-        b_dst[i] = A_BYTES + row * 256 + ((c ^ (row & 15)) << 4);
-    }
-    TapCursor tap;
-    tap.reset();
-
-    u4 eA[AP], eB[BP], oA[AP], oB[BP];
-    auto load_set = [&](__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, int ks, u4* da, u4* db) {
-        if (CONV) tap.advance_to(p, ks);
-        const int kb = CONV ? tap.pks(p) : ks;  // the right operand follows the left operand's slice order
-#pragma unroll
-        for (int i = 0; i < AP; ++i) da[i] = ag[i].load(p, ra, ks, tap);
-#pragma unroll
-        for (int i = 0; i < BP; ++i) db[i] = bg[i].load(p, rb, kb, tap);
-    };
-    auto load_even = [&](int ks) { load_set(rs_a0, rs_b0, ks, eA, eB); };
-    auto load_odd = [&](int ks) { load_set(rs_a1, rs_b1, ks, oA, oB); };
-    constexpr int NOPS = AP + BP;
-    auto store_op = [&](auto op_c, auto even_c, char* stage) {
-        constexpr int op = decltype(op_c)::value;
-        constexpr bool even_set = decltype(even_c)::value;
-        if constexpr (op < AP) *reinterpret_cast<u4*>(stage + a_dst[op]) = even_set ? eA[op] : oA[op];
-        else *reinterpret_cast<u4*>(stage + b_dst[op - AP]) = even_set ? eB[op - AP] : oB[op - AP];
-    };
-
-    // fragment addresses: row part and, per digit, the swizzled piece slot
-    const int x16 = r32 & 15;
-    int a_frag[8], b_frag[8];
-#pragma unroll
-    for (int l = 0; l < 8; ++l) {
-        const int slot = ((h * 8 + l) ^ x16) << 4;
-        a_frag[l] = (wm * SM * 32 + r32) * 256 + slot;
-        b_frag[l] = A_BYTES + (wn * SN * 32 + r32) * 256 + slot;
-    }
-
-    v16i acc[SM][SN][8];
-    constexpr int NMFMA = 36 * SM * SN;
-    constexpr int PRE = NMFMA * PRE_EIGHTHS / 8;
-    constexpr int LAST = NMFMA - 2 * SM * SN;
-    auto half_step = [&](const char* cur, char* nxt, auto even_c, auto&& issue_loads) {
-        v4i bf[SN][8];
-        v4i af[2][SM];
-        auto read_b = [&](int m) {
-#pragma unroll
-            for (int sn = 0; sn < SN; ++sn)
-                bf[sn][m] = *reinterpret_cast<const v4i*>(cur + b_frag[m] + sn * 8192);
-        };
-        auto read_a = [&](int l) {
-#pragma unroll
-            for (int sm = 0; sm < SM; ++sm)
-                af[l & 1][sm] = *reinterpret_cast<const v4i*>(cur + a_frag[l] + sm * 8192);
-        };
-        read_a(0);
-        read_b(0);
-        read_b(1);
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<0, NMFMA>([&](auto slot_c) {
-            constexpr int slot = decltype(slot_c)::value;
-            constexpr Slot sl = decode_slot(slot, SM, SN);
-            constexpr int l = sl.l, m = sl.m, sm = sl.sm, sn = sl.sn;
-            if constexpr (sm == 0 && sn == 0) {
-                if constexpr (l == 0 && m + 2 < 8) read_b(m + 2);
-                if constexpr (m == 1 && l < 7) read_a(l + 1);
-            }
-            acc[sm][sn][l + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                af[l & 1][sm], bf[sn][m], acc[sm][sn][l + m], 0, 0, 0);
-            if constexpr (slot == 0) issue_loads();
-            if constexpr (slot >= PRE && slot < LAST) {
-                constexpr int lo = (slot - PRE) * NOPS / (LAST - PRE);
-                constexpr int hi = (slot - PRE + 1) * NOPS / (LAST - PRE);
-                static_for<lo, hi>([&](auto op_c) { store_op(op_c, even_c, nxt); });
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
-    };
-
-    char* const st0 = lds;
-    char* const st1 = lds + STAGE;
-    const int per_split = (KS + p.ksplit - 1) / p.ksplit;
-    const int k_begin = split * per_split;
-    const int nk = k_begin + per_split < KS ? k_begin + per_split : KS;
-    if (k_begin >= nk) return;
-
-    load_even(k_begin);
-    static_for<0, NOPS>([&](auto op_c) { store_op(op_c, std::true_type{}, st0); });
-    __syncthreads();
-    for (int ks0 = k_begin; ks0 < nk; ks0 += SEG_KSTEPS) {
-        const int ke = ks0 + SEG_KSTEPS < nk ? ks0 + SEG_KSTEPS : nk;
-#pragma unroll
-        for (int sm = 0; sm < SM; ++sm)
-#pragma unroll
-            for (int sn = 0; sn < SN; ++sn)
-#pragma unroll
-                for (int s_ = 0; s_ < 8; ++s_)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[sm][sn][s_][i] = 0;
-        for (int ks = ks0; ks < ke; ++ks) {
-            half_step(st0, st1, std::false_type{}, [&]() { load_odd(ks); });
-            __syncthreads();
-            half_step(st1, st0, std::true_type{}, [&]() { load_even(ks + 1); });
-            __syncthreads();
-        }
-        fold_tile<SM, SN>(p, acc, m0 + wm * SM * 32, n0 + wn * SN * 32, lane, ks0 > k_begin);
+        for (int l = 0; l < 8; ++l) *reinterpret_cast<u32*>(o + l * 256) = d[l];
     }
 }
 
@@ -1441,25 +1310,11 @@ static hipError_t launch_zero_fill(const GemmParams& p, hipStream_t stream) {
 hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,
                             hipStream_t stream) {
     const int64_t KS = (K + 31) / 32;
-    const int64_t units = R * KS * 8;
+    const int64_t units = (R + 15) / 16 * KS * 128;
     int64_t blocks = (units + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
     hipLaunchKernelGGL(to_planes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, add,
                        static_cast<char*>(dst), (u32)R, (u32)K, (u32)KS);
-    return hipGetLastError();
-}
-
-hipError_t launch_share_gemm_planes(const GemmParams& p, bool conv, hipStream_t stream) {
-    typedef DefaultTile T;
-    const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
-    GemmParams q = p;
-    q.ksplit = choose_ksplit(tiles_m * tiles_n, (p.K + 31) / 32);
-    q.group_m = choose_group_m(p, tiles_m, tiles_n, q.ksplit);
-    if (q.ksplit > 1)
-        if (hipError_t e = launch_zero_fill(q, stream)) return e;
-    const dim3 grid((unsigned)(tiles_m * tiles_n * q.ksplit));
-    if (conv) hipLaunchKernelGGL((share_gemm_planes_kernel<T, true>), grid, dim3(T::NT), 0, stream, q);
-    else hipLaunchKernelGGL((share_gemm_planes_kernel<T, false>), grid, dim3(T::NT), 0, stream, q);
     return hipGetLastError();
 }
 
@@ -1549,6 +1404,8 @@ hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStrea
     CG_CASE(A_CONV_GEN, B_FLIP_GEN);
     CG_CASE(A_CONV_DIL, B_FLIP_GEN);
     CG_CASE(A_TRANS, B_PATCH_T);
+    CG_CASE(A_PLANES, B_PLANES);
+    CG_CASE(A_PLANES_CONV, B_PLANES);
 #undef CG_CASE
     return hipErrorInvalidValue;
 }

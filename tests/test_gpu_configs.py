@@ -53,6 +53,29 @@ def test_config_every_layer_bit_exact(env, cfg):
         check_layer(cg, ro, wl, cfg, li, L)
 
 
+def test_config4_backward_products_every_layer_bit_exact(env):
+    """Input and weight gradients of every convolution layer of the VGG16-shaped configuration at full size (the
+    shapes bench.py --extras times), one party, every element against the oracle."""
+    cg, ro, wl = env
+    for li, L in enumerate(wl.config_layers(4)):
+        if L.kind != "conv":
+            continue
+        say(f"config 4 backward, layer {li} {L.name}")
+        seed = wl.layer_seed(4, li) + 500
+        g = [wl.draw_ring(L.z_shape, seed), wl.draw_ring(L.z_shape, seed + 1)]
+        w = [wl.draw_ring(L.w_shape, seed + 2), wl.draw_ring(L.w_shape, seed + 3)]
+        x = [wl.draw_ring(L.x_shape, seed + 4), wl.draw_ring(L.x_shape, seed + 5)]
+        dg, dw, dx = ([cg.to_device(a) for a in t] for t in (g, w, x))
+        sp = ((L.stride, L.stride), (L.pad, L.pad))
+        got_dx = cg.cg_share_conv2d_dgrad(*dg, *dw, L.x_shape, stride=sp[0], pad=sp[1])
+        got_dw = cg.cg_share_conv2d_wgrad(*dg, *dx, L.w_shape, stride=sp[0], pad=sp[1])
+        torch.cuda.synchronize()
+        msg = first_mismatch(cg.to_host(got_dx), ro.party_conv2d_dgrad(*g, *w, L.x_shape, *sp))
+        assert not msg, f"{L.name} input gradient: {msg}"
+        msg = first_mismatch(cg.to_host(got_dw), ro.party_conv2d_wgrad(*g, *x, L.w_shape, *sp))
+        assert not msg, f"{L.name} weight gradient: {msg}"
+
+
 def test_config4_step_replayed_from_a_hip_graph_is_bit_exact(env):
     """A caller may capture the 16-layer step once and replay it (measured: no faster than host launches here,
     the GPU is never idle between them); every replay must give the oracle's outputs, also with eager work and

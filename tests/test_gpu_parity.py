@@ -330,6 +330,35 @@ def test_elementwise_ops(cg, ro, wl, n):
     assert np.array_equal(cg.to_host(ea), wa) and np.array_equal(cg.to_host(eb), wb)
 
 
+def test_elementwise_and_gates_beyond_one_grid_trip(cg, ro, wl):
+    """The element-wise kernels cap their grid (2^23 words per trip) and walk further with a grid stride: n just
+    above that cap plus 2^20 + 3 words reaches the second trip, its partial last chunk and the odd tail word,
+    with 16-byte-aligned pointers and with pointers offset by one word (the 8-byte path)."""
+    n = (1 << 23) + (1 << 20) + 3
+    say(f"element-wise ops and gates across a second grid trip, n={n}")
+    a, b, c, d = (wl.draw_ring((n + 1,), 700 + i) for i in range(4))
+    keys = PRF_KEYS
+    for off in (0, 1):
+        ha, hb, hc, hd = (v[off:off + n] for v in (a, b, c, d))
+        da, db, dc, dd = (cg.to_device(v)[off:off + n] for v in (a, b, c, d))
+        za, zb = cg.cg_share_add(da, db, dc, dd)
+        wa, wb = ro.share_add(ha, hb, hc, hd)
+        assert not first_mismatch(cg.to_host(za), wa) and not first_mismatch(cg.to_host(zb), wb)
+        out = cg.cg_reconstruct(da, db, dc)
+        assert not first_mismatch(cg.to_host(out), ro.reconstruct(ha, hb, hc))
+        g = cg.cg_bshare_and(da, db, dc, dd)
+        assert not first_mismatch(cg.to_host(g), ro.bshare_and(ha, hb, hc, hd))
+        r = cg.cg_reshare(da, keys[0], keys[2], 0x1234, 5)
+        assert not first_mismatch(cg.to_host(r), ro.reshare(ha, keys[0], keys[2], 0x1234, 5))
+        del da, db, dc, dd, za, zb, out, g, r
+    # column sums and the zero fill at a size beyond their grid caps: 2^19 + 1 columns, 17 rows
+    rows, cols = 17, (1 << 19) + 1
+    xa, xb = wl.draw_ring((rows, cols), 710), wl.draw_ring((rows, cols), 711)
+    sa, sb = cg.cg_share_col_sum(cg.to_device(xa), cg.to_device(xb))
+    wa, wb = ro.share_col_sum(xa, xb)
+    assert not first_mismatch(cg.to_host(sa), wa) and not first_mismatch(cg.to_host(sb), wb)
+
+
 def test_elementwise_unaligned(cg, ro, wl):
     n = 1001
     say("element-wise ops on 8-byte-aligned views")

@@ -251,6 +251,24 @@ def test_party_matmul_is_the_papers_three_terms():
         assert np.array_equal(z, ro.matmul(xi + xi1, yi + yi1) - ro.matmul(xi1, yi1))
 
 
+@pytest.mark.parametrize("trans_x,trans_y", [(False, True), (True, False), (True, True)])
+def test_party_matmul_on_transposed_storage(trans_x, trans_y):
+    """party_matmul_t takes operands stored [K, rows]: pinned, on a non-square case, against the big-integer
+    three-term formula applied to the operands transposed back by plain indexing (a wrong axis fails: M, N
+    and K all differ)."""
+    M, N, K = 5, 3, 7
+    xi, xi1, yi, yi1 = ring((M, K), 95), ring((M, K), 96), ring((N, K), 97), ring((N, K), 98)
+    want = bf_party(xi, xi1, yi, yi1)
+
+    def stored(a, t):   # [rows, K] -> what the caller keeps in memory
+        if not t:
+            return a
+        return np.array([[a[r, k] for r in range(a.shape[0])] for k in range(a.shape[1])], dtype=np.uint64)
+    got = ro.party_matmul_t(stored(xi, trans_x), stored(xi1, trans_x), stored(yi, trans_y), stored(yi1, trans_y),
+                            trans_x, trans_y)
+    assert got.shape == (M, N) and np.array_equal(got, want)
+
+
 @pytest.mark.parametrize("M,N,K", [(5, 4, 7), (16, 9, 33)])
 def test_three_parties_sum_to_the_plaintext_product(M, N, K):
     x, y = ring((M, K), 101), ring((N, K), 102)
