@@ -53,6 +53,8 @@ def parse_args():
     ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the register-only MFMA issue-rate measurement")
+    ap.add_argument("--plain", action="store_true",
+                    help="time the plain entry points only (no layer takes the route with scratch memory)")
     ap.add_argument("--no-rows", action="store_true",
                     help="skip the rows printed beside the step by default (largest share-GEMM shapes, totals of the "
                          "other configurations, streaming kernels, warm/cold fully connected layers)")
@@ -392,17 +394,42 @@ def main() -> int:
         outs.append(torch.empty(L.z_shape, dtype=torch.int64, device="cuda"))
     torch.cuda.synchronize()
 
-    def run_layer(li: int) -> None:
+    # Route per layer.  The library offers every product with and without caller-supplied scratch memory (the
+    # *_ws entry points: operands split into digit planes once, then a product kernel without split work); its
+    # own rule of thumb (cg_share_*_prefers_workspace) says which one to call for a shape.  The scratch buffer
+    # is allocated here, once, outside the timed region, like the operands; --plain times the plain calls only.
+    def prefers_ws(L) -> bool:
+        if args.plain:
+            return False
+        if L.kind == "conv":
+            return cg.cg_share_conv2d_prefers_workspace(L.x_shape, L.w_shape, (L.stride, L.stride), (L.pad, L.pad))
+        return cg.cg_share_matmul_prefers_workspace(*L.gemm)
+
+    def ws_bytes(L) -> int:
+        if L.kind == "conv":
+            return cg.cg_share_conv2d_workspace_bytes(L.x_shape, L.w_shape, (L.stride, L.stride), (L.pad, L.pad))
+        return cg.cg_share_matmul_workspace_bytes(*L.gemm)
+    use_ws = [prefers_ws(L) for L in layers]
+    scratch = torch.empty(max([ws_bytes(L) for L, u in zip(layers, use_ws) if u] + [16]), dtype=torch.uint8,
+                          device="cuda")
+
+    def run_layer(li: int, plain: bool = False) -> None:
         L = layers[li]
         for _ in range(L.repeat):
             if L.kind == "conv":
-                cg.cg_share_conv2d(*dev_ops[li], stride=(L.stride, L.stride), pad=(L.pad, L.pad), z_i=outs[li])
+                if use_ws[li] and not plain:
+                    cg.cg_share_conv2d_ws(*dev_ops[li], scratch, stride=(L.stride, L.stride), pad=(L.pad, L.pad),
+                                          z_i=outs[li])
+                else:
+                    cg.cg_share_conv2d(*dev_ops[li], stride=(L.stride, L.stride), pad=(L.pad, L.pad), z_i=outs[li])
+            elif use_ws[li] and not plain:
+                cg.cg_share_matmul_ws(*dev_ops[li], scratch, z_i=outs[li])
             else:
                 cg.cg_share_matmul(*dev_ops[li], z_i=outs[li])
 
-    def step() -> None:
+    def step(plain: bool = False) -> None:
         for li in range(len(layers)):
-            run_layer(li)
+            run_layer(li, plain)
 
     for _ in range(args.warmup):
         step()
@@ -430,6 +457,9 @@ def main() -> int:
     total_mnk = sum(L.mnk * L.repeat for L in layers)
     launches = sum(L.repeat for L in layers)
     value = 3.0 * total_mnk / (ms_per_step * 1e-3)
+    # the same step through the plain entry points only (no scratch memory anywhere)
+    plain_ms_per_step = ms_per_step if not any(use_ws) else _timed(torch, lambda: step(True), warm=3,
+                                                                    iters=max(10, args.steps // 4))
 
     # Per-layer durations of the share-product kernel, HIP events on the launch stream,
     # measured right after the timed region on the same buffers.
@@ -620,6 +650,10 @@ def main() -> int:
                                 4: "config 4: VGG16-shaped 13 conv + 3 FC on shares, batch 32, 64x64x3",
                                 5: "config 5: ResNet-50-shaped 53 conv + 1 FC on shares, batch 8, 224x224x3"}[args.config],
                    "layers": launches, "ring_macs_per_step": 3 * total_mnk,
+                   "layers_on_the_scratch_memory_route": [L.name for L, u in zip(layers, use_ws) if u],
+                   "scratch_bytes": int(scratch.numel()),
+                   "plain_entry_points_only": {"ms_per_step": plain_ms_per_step,
+                                               "ring_macs_per_s": 3.0 * total_mnk / (plain_ms_per_step * 1e-3)},
                    "parties_timed": 1, "fixed_point_bits": wl.FRAC_BITS},
         "roofline": roofline,
         "cpu_baseline": cpu,

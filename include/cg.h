@@ -115,6 +115,16 @@ CG_API cg_status cg_share_matmul_t(const uint64_t *x_i, const uint64_t *x_ip1,
  */
 CG_API size_t cg_share_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
+/*
+ * 1 when, for these sizes (16-byte-aligned operands assumed), the route with scratch
+ * memory is expected to be the faster one on MI355X, the conversion pass included; 0
+ * when the plain call is, or when the sizes are invalid.  A measured rule of thumb
+ * for callers that have scratch memory and want to pick per layer: large products
+ * whose operands are small against M*N*K gain (square products about 15 %), skinny
+ * or short ones lose.  Same for cg_share_conv2d_prefers_workspace below.
+ */
+CG_API int cg_share_matmul_prefers_workspace(int64_t M, int64_t N, int64_t K);
+
 CG_API cg_status cg_share_matmul_ws(const uint64_t *x_i, const uint64_t *x_ip1,
                              const uint64_t *y_i, const uint64_t *y_ip1,
                              uint64_t *z_i, int64_t M, int64_t N, int64_t K,
@@ -179,6 +189,7 @@ CG_API cg_status cg_share_conv2d(const uint64_t *x_i, const uint64_t *x_ip1,
  * 1x1, stride 1, unpadded with even Cin) and all pointers are 16-byte aligned.
  */
 CG_API size_t cg_share_conv2d_workspace_bytes(const cg_conv2d_desc *desc);
+CG_API int cg_share_conv2d_prefers_workspace(const cg_conv2d_desc *desc);
 
 CG_API cg_status cg_share_conv2d_ws(const uint64_t *x_i, const uint64_t *x_ip1,
                              const uint64_t *w_i, const uint64_t *w_ip1,

@@ -27,6 +27,7 @@ EXPORTS = ("cg_status_string", "cg_version", "cg_share_matmul", "cg_share_conv2d
            "cg_bzero_share", "cg_breshare", "cg_share_bias_add", "cg_share_col_sum",
            "cg_bit_transpose64", "cg_bshare_carry_level", "cg_bits_unpack", "cg_bshare_csa", "cg_bshare_half_adder",
            "cg_share_matmul_acc", "cg_share_conv2d_acc", "cg_share_matmul_f64limb", "cg_share_matmul_static",
+           "cg_share_matmul_prefers_workspace", "cg_share_conv2d_prefers_workspace",
            "cg_share_matmul_workspace_bytes", "cg_share_conv2d_workspace_bytes")
 SIZE_EXPORTS = 2      # the last entries return size_t, the first two a string and an int, the rest cg_status
 
@@ -80,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.cg_share_conv2d_ws.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), vp, sz, vp]
         L.cg_share_matmul_workspace_bytes.argtypes = [i64] * 3
         L.cg_share_conv2d_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+        L.cg_share_matmul_prefers_workspace.argtypes = [i64] * 3
+        L.cg_share_conv2d_prefers_workspace.argtypes = [ctypes.POINTER(ConvDesc)]
         key = ctypes.c_char_p
         L.cg_zero_share.argtypes = [key, key, u64, u64, vp, sz, vp]
         L.cg_reshare.argtypes = [vp, key, key, u64, u64, vp, sz, vp]
@@ -289,6 +292,17 @@ def cg_share_conv2d(x_i, x_ip1, w_i, w_ip1, stride=(1, 1), pad=(0, 0), z_i=None,
     _check(lib().cg_share_conv2d(_ptr(x_i), _ptr(x_ip1), _ptr(w_i), _ptr(w_ip1), _ptr(z_i),
                                  ctypes.byref(d), _stream(stream)), "cg_share_conv2d")
     return z_i
+
+
+def cg_share_matmul_prefers_workspace(M: int, N: int, K: int) -> bool:
+    return bool(lib().cg_share_matmul_prefers_workspace(M, N, K))
+
+
+def cg_share_conv2d_prefers_workspace(x_shape, w_shape, stride=(1, 1), pad=(0, 0)) -> bool:
+    B, H, W, Cin = x_shape
+    Cout, kh, kw, _ = w_shape
+    d = ConvDesc(B, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    return bool(lib().cg_share_conv2d_prefers_workspace(ctypes.byref(d)))
 
 
 def cg_share_conv2d_workspace_bytes(x_shape, w_shape, stride=(1, 1), pad=(0, 0)) -> int:

@@ -612,6 +612,18 @@ struct Plan {
 
 u64 round_up(u64 v, u64 a) { return (v + a - 1) / a * a; }
 
+// Does the digit route (one conversion launch, then a product kernel without split work) beat the plain
+// product for this plan?  Measured on MI355X: the plain kernel runs at about half the published int8 rate (144
+// int8 ops per (m, n, k) at 2.45e15 op/s), the product kernel of the digit route saves about 17 % of that time,
+// and the conversion moves 32 bytes per operand word at about 6.5 TB/s after a launch of about 5 microseconds.
+// The route must win by a margin to be preferred.
+bool planes_pay(const Plan& pl) {
+    if (!pl.planes_ok) return false;
+    const double mnk = (double)pl.p.M * (double)pl.p.N * (double)pl.p.K;
+    const double words = (double)pl.x_rows * (double)pl.x_k + (double)pl.p.N * (double)pl.p.K;
+    return 0.17 * 144.0 * mnk / 2.45e15 > 1.15 * (32.0 * words / 6.5e12 + 5.0e-6);
+}
+
 u64 plan_workspace_bytes(const Plan& pl) {
     return pl.planes_ok ? 2 * round_up(pl.xp_bytes, 256) + 2 * round_up(pl.wp_bytes, 256) : 0;
 }
@@ -961,14 +973,11 @@ cg_status run_planes(Plan& pl, void* workspace, size_t workspace_bytes, void* st
     char* wp_sum = xp_b + round_up(pl.xp_bytes, 256);
     char* wp_a = wp_sum + round_up(pl.wp_bytes, 256);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = cg::launch_to_planes(q.x_a, nullptr, xp_a, pl.x_rows, pl.x_k, s);
-    if (e == hipSuccess) e = cg::launch_to_planes(q.x_b, nullptr, xp_b, pl.x_rows, pl.x_k, s);
-    if (e == hipSuccess) e = cg::launch_to_planes(q.w_a, q.w_b, wp_sum, q.N, q.K, s);
-    if (e == hipSuccess) e = cg::launch_to_planes(q.w_a, nullptr, wp_a, q.N, q.K, s);
-    if (e != hipSuccess) return CG_ERR_DEVICE;
     pl.p.xp_a = xp_a; pl.p.xp_b = xp_b; pl.p.wp_sum = wp_sum; pl.p.wp_a = wp_a;
     pl.p.xp_bytes = pl.xp_bytes;
     pl.p.wp_bytes = pl.wp_bytes;
+    hipError_t e = cg::launch_to_planes(pl.p, pl.x_rows, pl.x_k, s);
+    if (e != hipSuccess) return CG_ERR_DEVICE;
     e = cg::launch_share_gemm(pl.p, pl.planes_conv ? cg::A_PLANES_CONV : cg::A_PLANES, cg::B_PLANES, s);
     return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;
 }
@@ -1084,6 +1093,18 @@ cg_status cg_share_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint
     Plan pl;
     if (cg_status st = plan_conv2d(x_i, x_ip1, w_i, w_ip1, z_i, d, true, &pl)) return st;
     return run_direct(pl, stream);
+}
+
+int cg_share_matmul_prefers_workspace(int64_t M, int64_t N, int64_t K) {
+    Plan pl;
+    if (plan_matmul(nullptr, nullptr, nullptr, nullptr, nullptr, M, N, K, false, &pl) != CG_OK) return 0;
+    return planes_pay(pl) ? 1 : 0;
+}
+
+int cg_share_conv2d_prefers_workspace(const cg_conv2d_desc* d) {
+    Plan pl;
+    if (plan_conv2d(nullptr, nullptr, nullptr, nullptr, nullptr, d, false, &pl) != CG_OK) return 0;
+    return planes_pay(pl) ? 1 : 0;
 }
 
 size_t cg_share_conv2d_workspace_bytes(const cg_conv2d_desc* d) {

@@ -97,12 +97,12 @@ hipError_t launch_share_gemm_f64limb(const uint64_t* x_a, const uint64_t* x_b, c
 // z[0..n) = 0 with a fill kernel (capturable).
 hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream);
 
-// Digit-plane route.  launch_to_planes converts a row-major [R, K] operand (K even,
-// 16-byte aligned), optionally summed with `add` first, into planes of
-// planes_bytes(R, K) bytes; launch_share_gemm with the modes A_PLANES / A_PLANES_CONV and
-// B_PLANES contracts four plane tensors.
-hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,
-                            hipStream_t stream);
+// Digit-plane route.  launch_to_planes converts, in one launch, the four operands of p into the
+// plane tensors p.xp_a, p.xp_b (left operand shares, seen as a row-major [x_rows, x_k] matrix),
+// p.wp_sum (w_a + w_b) and p.wp_a (right operand, [N, K]); rows of K even, 16-byte aligned.  A
+// row-major [R, K] operand takes planes_bytes(R, K) bytes.  launch_share_gemm with the modes
+// A_PLANES / A_PLANES_CONV and B_PLANES then contracts the four plane tensors.
+hipError_t launch_to_planes(const GemmParams& p, int64_t x_rows, int64_t x_k, hipStream_t stream);
 inline uint64_t planes_bytes(int64_t R, int64_t K) {
     return (uint64_t)((R + 15) / 16 * 16) * (uint64_t)((K + 31) / 32) * 256u;
 }

@@ -1173,12 +1173,31 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
 
 // One thread converts four consecutive words of a row; the 64 lanes of a wave take the four
 // 4-word quarters of one k-half of sixteen rows, so that each of their eight stores (one per
-// digit) writes 256 contiguous bytes.
-__global__ __launch_bounds__(256) void to_planes_kernel(const u64* __restrict__ src, const u64* __restrict__ add,
-                                                        char* __restrict__ dst, u32 R, u32 K, u32 KS) {
+// digit) writes 256 contiguous bytes.  One launch converts all four tensors of a product:
+// a block takes the job its index falls into.
+struct PlaneJob {
+    const u64 *src, *add;   // add: summed in before the split (w_a + w_b), or null
+    char* dst;
+    u32 R, K, KS;
+    u32 first_block;        // blocks [first_block, next job's first_block) work on this job
+};
+struct PlaneJobs {
+    PlaneJob job[4];
+    u32 total_blocks;
+};
+
+__global__ __launch_bounds__(256) void to_planes_kernel(const PlaneJobs jobs) {
+    int ji = 0;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        if (blockIdx.x >= jobs.job[i].first_block) ji = i;
+    const PlaneJob& jb = jobs.job[ji];
+    const u32 end_block = ji < 3 ? jobs.job[ji + 1].first_block : jobs.total_blocks;
+    const u64 nblocks = end_block - jb.first_block;
+    const u32 R = jb.R, K = jb.K, KS = jb.KS;
     const u64 rb_count = (R + 15) / 16;
     const u64 units = rb_count * KS * 2 * 64;  // per row block, slice and k-half: 16 rows x 4 quarters
-    for (u64 ui = (u64)blockIdx.x * 256 + threadIdx.x; ui < units; ui += (u64)gridDim.x * 256) {
+    for (u64 ui = (u64)(blockIdx.x - jb.first_block) * 256 + threadIdx.x; ui < units; ui += nblocks * 256) {
         const u32 lane = (u32)(ui & 63), q = lane & 3, r16 = lane >> 2;
         const u64 grp = ui >> 6;
         const u32 g = (u32)(grp & 1);
@@ -1189,8 +1208,8 @@ __global__ __launch_bounds__(256) void to_planes_kernel(const u64* __restrict__ 
         const u32 k0 = 32 * ks + 16 * g + 4 * q;  // first word of the unit
         u4 v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
         if (row < R) {
-            const u64* s_ = src + row * K + k0;
-            const u64* a = add ? add + row * K + k0 : nullptr;
+            const u64* s_ = jb.src + row * K + k0;
+            const u64* a = jb.add ? jb.add + row * K + k0 : nullptr;
             if (k0 < K) {  // K is even: words come in valid pairs
                 v0 = *reinterpret_cast<const u4*>(s_);
                 if (a) v0 = add64x2(v0, *reinterpret_cast<const u4*>(a));
@@ -1205,7 +1224,7 @@ __global__ __launch_bounds__(256) void to_planes_kernel(const u64* __restrict__ 
         u32 d[8];
         transpose4(v0.x, v0.z, v1.x, v1.z, d);
         transpose4(v0.y, v0.w, v1.y, v1.w, d + 4);
-        char* o = dst + ((bs * 16 + 8 * g) * 256) + r16 * 16 + q * 4;
+        char* o = jb.dst + ((bs * 16 + 8 * g) * 256) + r16 * 16 + q * 4;
 #pragma unroll
         for (int l = 0; l < 8; ++l) *reinterpret_cast<u32*>(o + l * 256) = d[l];
     }
@@ -1307,14 +1326,22 @@ static hipError_t launch_zero_fill(const GemmParams& p, hipStream_t stream) {
     return launch_zero_words(p.z, (size_t)p.M * (size_t)p.N, stream);
 }
 
-hipError_t launch_to_planes(const uint64_t* src, const uint64_t* add, void* dst, int64_t R, int64_t K,
-                            hipStream_t stream) {
-    const int64_t KS = (K + 31) / 32;
-    const int64_t units = (R + 15) / 16 * KS * 128;
-    int64_t blocks = (units + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    hipLaunchKernelGGL(to_planes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, add,
-                       static_cast<char*>(dst), (u32)R, (u32)K, (u32)KS);
+hipError_t launch_to_planes(const GemmParams& p, int64_t x_rows, int64_t x_k, hipStream_t stream) {
+    PlaneJobs jobs;
+    const struct { const u64 *src, *add; const char* dst; int64_t R, K; } in[4] = {
+        {p.x_a, nullptr, p.xp_a, x_rows, x_k}, {p.x_b, nullptr, p.xp_b, x_rows, x_k},
+        {p.w_a, p.w_b, p.wp_sum, p.N, p.K}, {p.w_a, nullptr, p.wp_a, p.N, p.K}};
+    u32 first = 0;
+    for (int i = 0; i < 4; ++i) {
+        const int64_t KS = (in[i].K + 31) / 32;
+        const int64_t units = (in[i].R + 15) / 16 * KS * 128;
+        int64_t blocks = (units + 255) / 256;
+        if (blocks > 256 * 16) blocks = 256 * 16;   // grid stride beyond that
+        jobs.job[i] = PlaneJob{in[i].src, in[i].add, const_cast<char*>(in[i].dst), (u32)in[i].R, (u32)in[i].K, (u32)KS, first};
+        first += (u32)blocks;
+    }
+    jobs.total_blocks = first;
+    hipLaunchKernelGGL(to_planes_kernel, dim3(first), dim3(256), 0, stream, jobs);
     return hipGetLastError();
 }
 
