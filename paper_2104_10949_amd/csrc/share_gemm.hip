@@ -1023,7 +1023,9 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     // split in XB0..XB1; W_LOAD then fetches the right operand of the slice after the next.
     constexpr int N1 = 40, N2 = 104;
     constexpr int W0 = 3, W1 = 39, XA_LOAD = 1, XA0 = 42, XA1 = 92, XB_LOAD = 41, XB0 = 94, XB1 = 142, W_LOAD = 93;
-    auto step = [&](int par) {
+    // LIVE = false is the step that computes the last slice of the block's range: nothing is left to prepare.
+    auto step = [&](int par, auto live_c) {
+        constexpr bool LIVE = decltype(live_c)::value;
         const int a_lo_rd = pin(par * T::A_HALF + a_frag), b_rd = pin(T::OFF_B + par * T::B_ALL + b_frag);
         const int a_lo_wr = pin((par ^ 1) * T::A_HALF + a_dst0), b_wr = pin(T::OFF_B + (par ^ 1) * T::B_ALL + b_dst0);
         auto read_a_hi = [&](int l) {   // digit l in 4..7 -> register set l - 4
@@ -1044,6 +1046,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         // what goes between the MFMAs of slot `slot` (0..143 over both phases)
         auto between = [&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
+            if constexpr (!LIVE) return;
             if constexpr (slot == XA_LOAD) load_xa();
             if constexpr (slot == XB_LOAD) load_xb();
             if constexpr (slot == W_LOAD) load_w();
@@ -1134,16 +1137,26 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         int tm, tn;
         logical_to_tile(p, tiles_m, tiles_n, wc.logical, tm, tn);
         const int fm0 = tm * T::BM + wm * 32, fn0 = tn * T::BN + wn * 32;   // the wave's sub-tile
+        const bool ends_here = !STREAM || wc.u >= u_end;   // the block's range ends with this tile
         // one pass per segment of at most SEG_KSTEPS slices (a single pass unless K > 32*SEG_KSTEPS)
         for (int ks0 = wc.ks; ks0 < wc.nk; ks0 += SEG_KSTEPS) {
             const int ke = ks0 + SEG_KSTEPS < wc.nk ? ks0 + SEG_KSTEPS : wc.nk;
+            // the very last slice of the range runs outside the loop, in a step that prepares nothing (classic
+            // distribution only: its blocks are short; the streamed kernel's long ranges gain little from it and
+            // the second copy of the step costs its loop registers)
+            const bool final_seg = !STREAM && ends_here && ke == wc.nk;
+            const int ke_live = final_seg ? ke - 1 : ke;
             clear_acc();
-            for (int ks = ks0; ks < ke; ++ks) {
-                step(par);
+            for (int ks = ks0; ks < ke_live; ++ks) {
+                step(par, std::true_type{});
                 // the loaders move on between two steps, where no fragment registers are alive (entering a
                 // new tile computes many addresses)
                 advance(wa_, setup_a);
                 advance(wb_, setup_b);
+                par ^= 1;
+            }
+            if (final_seg) {
+                step(par, std::false_type{});
                 par ^= 1;
             }
             fold_blocks<BMODE == B_FLIP_C32>(p, acc, fm0, fn0, lane, ks0 > wc.ks || p.z_add != 0);
