@@ -475,26 +475,28 @@ def main() -> int:
         per_layer_ms.append(a.elapsed_time(b) / (reps * L.repeat))
     kernel_ms_sum = sum(ms * L.repeat for ms, L in zip(per_layer_ms, layers))
 
-    def mfma_ceiling(random_bytes: bool) -> float:
-        """int8 TOP/s of a register-only MFMA loop on all compute units (2 waves per SIMD)."""
+    def mfma_ceiling(random_bytes: bool, k64: bool = True) -> float:
+        """int8 TOP/s of a register-only MFMA loop on all compute units (2 waves per SIMD): the 16x16x64 form the
+        share-product kernel issues (k64) or the 32x32x32 form."""
         import ctypes
         import numpy as np
         from paper_2104_10949_amd import build as hip_build
         probe = ctypes.CDLL(hip_build.PROBE_LIB)
-        probe.cg_probe_mfma_rate.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 3 + [ctypes.c_void_p]
-        probe.cg_probe_mfma_rate.restype = ctypes.c_int
+        fn = probe.cg_probe_mfma16_rate if k64 else probe.cg_probe_mfma_rate
+        fn.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 3 + [ctypes.c_void_p]
+        fn.restype = ctypes.c_int
         if random_bytes:
             ops = cg.to_device(wl.draw_ring((8192,), 12345))
         else:
             ops = cg.to_device(np.full((8192,), 0x0101010101010101, dtype=np.uint64))
         n_cu = torch.cuda.get_device_properties(0).multi_processor_count
         sink = torch.empty(n_cu * 512, dtype=torch.int32, device="cuda")
-        iters, stream = 20000, torch.cuda.current_stream().cuda_stream
+        iters, stream = 20000 if not k64 else 5000, torch.cuda.current_stream().cuda_stream
 
         def launch():
-            rc = probe.cg_probe_mfma_rate(ops.data_ptr(), sink.data_ptr(), n_cu, 2, iters, stream)
+            rc = fn(ops.data_ptr(), sink.data_ptr(), n_cu, 2, iters, stream)
             if rc != 0:
-                raise RuntimeError(f"cg_probe_mfma_rate returned {rc}")
+                raise RuntimeError(f"MFMA probe returned {rc}")
         launch()
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -502,7 +504,7 @@ def main() -> int:
         launch()
         b.record()
         torch.cuda.synchronize()
-        macs = n_cu * 8 * iters * 8 * 32768.0
+        macs = n_cu * 8 * iters * (32 * 16384.0 if k64 else 8 * 32768.0)
         return 2.0 * macs / (a.elapsed_time(b) * 1e-3) / 1e12
 
     def mfma_f64_ceiling() -> float:
@@ -576,7 +578,9 @@ def main() -> int:
         # register-only MFMA loop on the same box: what the matrix cores sustain at the power limit
         peak_const, peak_random = mfma_ceiling(False), mfma_ceiling(True)
         roofline["measured_mfma_loop"] = {
+            "instruction": "v_mfma_i32_16x16x64_i8",
             "constant_operands": round(peak_const, 1), "random_operands": round(peak_random, 1), "unit": "TOP/s",
+            "random_operands_32x32x32_form": round(mfma_ceiling(True, k64=False), 1),
             "frac_of_random_operand_loop": round(achieved_tops / peak_random, 4),
             "largest_layer_frac_of_random_operand_loop": round(big_tops / peak_random, 4)}
         # Limb-choice check: the paper's embedding (four 16-bit limbs in float64, 10 limb products per ring

@@ -1372,6 +1372,14 @@ struct CanStream {
                                   (AMODE == A_CONV_C32 && BMODE == B_FLIP_C32) || (AMODE == A_TRANS && BMODE == B_PATCH_T);
 };
 
+// The weight gradient's classic instantiation spills registers inside the loop (its streamed one does not,
+// and is 7 % faster on the same ranges over the VGG-shaped layers): only the streamed one is built.  The input
+// gradient keeps both: its unsplit tiles gain more from the classic order's neighbouring tiles per XCD.
+template <int AMODE, int BMODE>
+struct StreamOnly {
+    static constexpr bool value = AMODE == A_TRANS && BMODE == B_PATCH_T;
+};
+
 template <class T, int AMODE, int BMODE>
 static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     const int64_t tiles_m = (p.M + T::BM - 1) / T::BM, tiles_n = (p.N + T::BN - 1) / T::BN;
@@ -1409,6 +1417,12 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
         q.stream_per = tiles_per_block * nk;
         grid = (unsigned)((tiles + tiles_per_block - 1) / tiles_per_block);
     }
+    // The weight gradient runs the streamed kernel also where the classic distribution is the better one: a
+    // run of one split's slices is that distribution, tile after tile instead of split after split.
+    if (StreamOnly<AMODE, BMODE>::value && q.stream_per == 0) {
+        q.stream_per = (nk + q.ksplit - 1) / q.ksplit;
+        grid = (unsigned)((units + q.stream_per - 1) / q.stream_per);
+    }
     q.group_m = choose_group_m(p, tiles_m, tiles_n, q.stream_per > 0 ? 1 : q.ksplit);
     if (q.ksplit > 1)
         if (hipError_t e = launch_zero_fill(q, stream)) return e;
@@ -1418,7 +1432,8 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
             return hipGetLastError();
         }
     }
-    hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BMODE, false>), dim3(grid), dim3(T::NT), 0, stream, q);
+    if constexpr (!StreamOnly<AMODE, BMODE>::value)
+        hipLaunchKernelGGL((share_gemm_kernel<T, AMODE, BMODE, false>), dim3(grid), dim3(T::NT), 0, stream, q);
     return hipGetLastError();
 }
 
