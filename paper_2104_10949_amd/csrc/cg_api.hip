@@ -947,6 +947,19 @@ cg_status plan_conv2d_wgrad(const uint64_t* g_i, const uint64_t* g_ip1, const ui
     p.div_wo = cg::make_fast_div((uint32_t)cd.Wo);
     pl.amode = cg::A_TRANS; pl.bmode = cg::B_PATCH_T;
     pl.x_bytes = (u64)cd.z_el * 8; pl.w_bytes = (u64)cd.x_el * 8; pl.z_bytes = (u64)cd.w_el * 8;
+    // The three-term product is symmetric in its operands, so the patches may as well be the left operand
+    // and the gradient the right one, with DW written transposed.  Taken when that covers [Cout, kh*kw*Cin]
+    // with fewer 128 x 64 tiles: a layer of up to 64 output channels then fills its tiles.
+    const int64_t tiles_plain = ((d->Cout + 127) / 128) * ((cd.K + 63) / 64);
+    const int64_t tiles_swapped = ((cd.K + 127) / 128) * ((d->Cout + 63) / 64);
+    if (tiles_swapped < tiles_plain) {
+        p.x_a = x_i; p.x_b = x_ip1; p.w_a = g_i; p.w_b = g_ip1;
+        p.M = (int)cd.K; p.N = (int)d->Cout;
+        p.x_elems = (u64)cd.x_el;
+        p.w_elems = (u64)cd.z_el;
+        pl.amode = cg::A_PATCH_T; pl.bmode = cg::B_TRANS;
+        pl.x_bytes = (u64)cd.x_el * 8; pl.w_bytes = (u64)cd.z_el * 8;
+    }
     *out = pl;
     return CG_OK;
 }

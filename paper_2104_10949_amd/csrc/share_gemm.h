@@ -32,7 +32,11 @@ enum AMode {
     A_CONV_DIL = 5,       // NHWC patch gather from an image whose pixels sit dil_h, dil_w apart
                           // with zeros between them (input gradient of a strided convolution)
     A_PLANES = 6,         // row-major [M, K] kept as digit planes (xp_a, xp_b; see to_planes_kernel)
-    A_PLANES_CONV = 7     // NHWC patch gather, Cin % 32 == 0, from the digit planes of the [pixels, Cin] matrix
+    A_PLANES_CONV = 7,    // NHWC patch gather, Cin % 32 == 0, from the digit planes of the [pixels, Cin] matrix
+    // Weight gradient with the operands exchanged: the left operand is the layer input, A[(r, s, c), pixel] =
+    // patch entry (B_PATCH_T's generator), the right one the transposed gradient (B_TRANS), and z is written
+    // transposed, z[col * M + row]: few output channels then fill the 64-column side of the tile.
+    A_PATCH_T = 8
 };
 
 // How the right operand's words are addressed.

@@ -207,12 +207,16 @@ struct TransScalar {
     }
     __device__ __forceinline__ void load(const GemmParams&, __amdgpu_buffer_rsrc_t r, int ks, u32 K,
                                          u4 out[2]) const {
+        // The four offsets are one add away from off0.  Hidden from the optimiser, the pitch keeps them from
+        // being computed ahead of the loop and held in four registers per unit for its whole length.
+        u32 p8 = pitch8;
+        asm volatile("" : "+s"(p8));
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const u32 k = 32u * ks + kq + 8u * jj;
-            const u32 o = off0 + 8u * jj * pitch8;
+            const u32 o = off0 + 8u * jj * p8;
             const u2 e0 = __builtin_amdgcn_raw_buffer_load_b64(r, k < K ? o : OOB, 0, 0);
-            const u2 e1 = __builtin_amdgcn_raw_buffer_load_b64(r, k + 1 < K ? o + pitch8 : OOB, 0, 0);
+            const u2 e1 = __builtin_amdgcn_raw_buffer_load_b64(r, k + 1 < K ? o + p8 : OOB, 0, 0);
             out[jj].x = e0.x; out[jj].y = e0.y; out[jj].z = e1.x; out[jj].w = e1.y;
         }
     }
@@ -564,8 +568,8 @@ __device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int B
 // zero-filled z (split-K: integer sums mod 2^64 are exact in any order).  The lane index passes through an empty
 // asm so that none of the output addresses or bounds tests can be computed ahead of the K loop, where they would
 // sit in registers the loop needs.  REMAP: the rows are scattered over the pixels of a larger tensor (see
-// GemmParams::out_*).
-template <bool REMAP>
+// GemmParams::out_*).  ZT: z is stored transposed, [N, M].
+template <bool REMAP, bool ZT>
 __device__ __forceinline__ void fold_blocks(const GemmParams& p, v4i (&acc)[2][2][8], int row0, int col0, int lane,
                                             bool accumulate) {
     int lane_f = lane;
@@ -595,7 +599,7 @@ __device__ __forceinline__ void fold_blocks(const GemmParams& p, v4i (&acc)[2][2
                         zrow = ((u64)b * (u64)p.out_H + (u64)(p.out_h0 + p.out_sh * (int)i_)) * (u64)p.out_W +
                                (u64)(p.out_w0 + p.out_sw * (int)j_);
                     }
-                    u64* dst = p.z + zrow * (u64)p.N + (u64)col;
+                    u64* dst = ZT ? p.z + (u64)col * (u64)p.M + zrow : p.z + zrow * (u64)p.N + (u64)col;
                     if (p.ksplit > 1) {
                         atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
                     } else {
@@ -716,6 +720,8 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
 
     constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
     constexpr bool A_TR = AMODE == A_TRANS;
+    // left-operand modes whose memory is contiguous along m: consecutive lanes take consecutive rows
+    constexpr bool A_ROWS = A_TR || AMODE == A_PATCH_T;
     // digit-plane route: both operands arrive split; a thread moves the pieces of one row of each tile
     constexpr bool PLANES = AMODE == A_PLANES || AMODE == A_PLANES_CONV;
     static_assert(PLANES == (BMODE == B_PLANES), "plane operands come in pairs");
@@ -731,7 +737,8 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             typename std::conditional<AMODE == A_LINEAR_SCALAR, LinearScalar,
             typename std::conditional<AMODE == A_CONV_C32, ConvC32,
             typename std::conditional<AMODE == A_TRANS, TransScalar,
-            typename std::conditional<AMODE == A_CONV_DIL, ConvDil, ConvGen>::type>::type>::type>::type>::type AGen;
+            typename std::conditional<AMODE == A_PATCH_T, PatchTrans,
+            typename std::conditional<AMODE == A_CONV_DIL, ConvDil, ConvGen>::type>::type>::type>::type>::type>::type AGen;
     typedef typename std::conditional<BMODE == B_VEC, LinearVec,
             typename std::conditional<BMODE == B_SCALAR, LinearScalar,
             typename std::conditional<BMODE == B_FLIP_GEN, FlipGen,
@@ -755,7 +762,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     // LDS byte offset of unit 0 inside the slab set of digit 0, first share; where a thread's units go does
     // not depend on the tile, and unit i lies a compile-time distance from unit 0 (see unit_delta)
     // (plane route: row tid % BM, digit tid / BM of the low half; the k-half is the unit)
-    const int a_dst0 = PLANES ? (tid % T::BM) * 16 + (tid / T::BM) * T::A_DIG : unit_dst(tid, T::BM, A_TR);
+    const int a_dst0 = PLANES ? (tid % T::BM) * 16 + (tid / T::BM) * T::A_DIG : unit_dst(tid, T::BM, A_ROWS);
     auto setup_a = [&]() {
         // (the thread id passes through an empty asm so that nothing below is computed ahead of the K loop and
         // kept in registers across it: a new tile is entered rarely, the registers are needed all the time)
@@ -783,6 +790,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         }
         if (A_LINEAR) a_base_elems = (u64)m0 * (u64)p.lda;
         else if (A_TR) a_base_elems = (u64)m0;
+        else if (AMODE == A_PATCH_T) a_base_elems = 0;
         else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
         tap_a.reset();
         rs_xa = view(p.x_a, p.x_elems, a_base_elems);
@@ -790,9 +798,15 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
 #pragma unroll
         for (int i = 0; i < AU; ++i) {
             const int t = tid_s + i * T::NT;
-            const int q = A_TR ? (t / T::BM) & 3 : t & 3;
-            const int row = A_TR ? t % T::BM : (t >> 2) % T::BM;
-            const int jh = (t >> 2) / T::BM;
+            int q = A_ROWS ? (t / T::BM) & 3 : t & 3;
+            const int row = A_ROWS ? t % T::BM : (t >> 2) % T::BM;
+            int jh = (t >> 2) / T::BM;
+            // one wave's lanes share the quarter and the k-group when they take consecutive rows: said so, the
+            // arithmetic on a unit's k indices (bounds, pixel decomposition) runs on the scalar unit
+            if constexpr (A_ROWS && T::BM % 64 == 0) {
+                q = __builtin_amdgcn_readfirstlane(q);
+                jh = __builtin_amdgcn_readfirstlane(jh);
+            }
             ag[i].init(p, m0, row, rows_m, A_TR ? (u32)p.M : (u32)p.lda, q, jh);
         }
     };
@@ -827,9 +841,13 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
 #pragma unroll
         for (int i = 0; i < BU; ++i) {
             const int t = tid_s + i * T::NT;
-            const int q = B_TR ? (t / T::BN) & 3 : t & 3;
+            int q = B_TR ? (t / T::BN) & 3 : t & 3;
             const int row = B_TR ? t % T::BN : (t >> 2) % T::BN;
-            const int jh = (t >> 2) / T::BN;
+            int jh = (t >> 2) / T::BN;
+            if constexpr (B_TR && T::BN % 64 == 0) {  // see the left operand
+                q = __builtin_amdgcn_readfirstlane(q);
+                jh = __builtin_amdgcn_readfirstlane(jh);
+            }
             // pitch between consecutive k of one row: N for a transposed matrix, one output
             // channel of the filter (kh*kw*N words) for the flipped filter
             const u32 pitch = BMODE == B_FLIP_C32 ? (u32)(p.flt_kh * p.flt_kw) * (u32)p.N : (B_TR ? (u32)p.N : (u32)p.K);
@@ -858,6 +876,9 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     auto a_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
         if constexpr (A_TR) {
             const u64 base = a_base_elems + (u64)ks * 32u * (u64)p.M;
+            return base < p.x_elems ? view(ptr, p.x_elems, base) : make_rsrc(ptr, 0);
+        } else if constexpr (AMODE == A_PATCH_T) {
+            const u64 base = (u64)fast_div(32u * (u32)ks, p.div_howo) * p.img_elems;
             return base < p.x_elems ? view(ptr, p.x_elems, base) : make_rsrc(ptr, 0);
         } else {
             return fixed;
@@ -971,7 +992,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             if constexpr (op % 4 == 3) *reinterpret_cast<u4*>(lds + a_hi + poff) = x[unit][1];
             return;
         }
-        constexpr int off = decltype(share_c)::value * 2 * T::A_RS + unit_delta(unit, T::NT, T::BM, A_TR);
+        constexpr int off = decltype(share_c)::value * 2 * T::A_RS + unit_delta(unit, T::NT, T::BM, A_ROWS);
         unit_op(x[unit], nullptr, lds + a_lo + off, lds + a_hi + off, std::integral_constant<int, T::A_DIG>{},
                 std::integral_constant<int, op % 4>{});
     };
@@ -1159,7 +1180,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
                 step(par, std::false_type{});
                 par ^= 1;
             }
-            fold_blocks<BMODE == B_FLIP_C32>(p, acc, fm0, fn0, lane, ks0 > wc.ks || p.z_add != 0);
+            fold_blocks<BMODE == B_FLIP_C32, AMODE == A_PATCH_T>(p, acc, fm0, fn0, lane, ks0 > wc.ks || p.z_add != 0);
         }
         if (!STREAM || wc.u >= u_end) break;
     }
@@ -1369,7 +1390,8 @@ static double classic_cost(int64_t tiles, int nk, int ks) {
 template <int AMODE, int BMODE>
 struct CanStream {
     static constexpr bool value = (AMODE == A_LINEAR_VEC && BMODE == B_VEC) || (AMODE == A_CONV_C32 && BMODE == B_VEC) ||
-                                  (AMODE == A_CONV_C32 && BMODE == B_FLIP_C32) || (AMODE == A_TRANS && BMODE == B_PATCH_T);
+                                  (AMODE == A_CONV_C32 && BMODE == B_FLIP_C32) || (AMODE == A_TRANS && BMODE == B_PATCH_T) ||
+                                  (AMODE == A_PATCH_T && BMODE == B_TRANS);
 };
 
 // The weight gradient's classic instantiation spills registers inside the loop (its streamed one does not,
@@ -1377,7 +1399,7 @@ struct CanStream {
 // gradient keeps both: its unsplit tiles gain more from the classic order's neighbouring tiles per XCD.
 template <int AMODE, int BMODE>
 struct StreamOnly {
-    static constexpr bool value = AMODE == A_TRANS && BMODE == B_PATCH_T;
+    static constexpr bool value = (AMODE == A_TRANS && BMODE == B_PATCH_T) || (AMODE == A_PATCH_T && BMODE == B_TRANS);
 };
 
 template <class T, int AMODE, int BMODE>
@@ -1459,6 +1481,7 @@ hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStrea
     CG_CASE(A_CONV_GEN, B_FLIP_GEN);
     CG_CASE(A_CONV_DIL, B_FLIP_GEN);
     CG_CASE(A_TRANS, B_PATCH_T);
+    CG_CASE(A_PATCH_T, B_TRANS);
     CG_CASE(A_PLANES, B_PLANES);
     CG_CASE(A_PLANES_CONV, B_PLANES);
 #undef CG_CASE
