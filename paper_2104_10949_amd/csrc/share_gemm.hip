@@ -721,7 +721,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
     constexpr bool A_TR = AMODE == A_TRANS;
     // left-operand modes whose memory is contiguous along m: consecutive lanes take consecutive rows
-    constexpr bool A_ROWS = A_TR || AMODE == A_PATCH_T;
+    constexpr bool A_ROWS = A_TR || AMODE == A_PATCH_T || AMODE == A_CONV_GEN || AMODE == A_CONV_DIL;
     // digit-plane route: both operands arrive split; a thread moves the pieces of one row of each tile
     constexpr bool PLANES = AMODE == A_PLANES || AMODE == A_PLANES_CONV;
     static_assert(PLANES == (BMODE == B_PLANES), "plane operands come in pairs");

@@ -171,6 +171,18 @@ def test_wgrad_contraction_longer_than_a_plain_product_allows(cg, ro, wl):
     assert not first_mismatch(got, want), first_mismatch(got, want)
 
 
+def test_wgrad_exchanged_operands_very_long_contraction(cg, ro, wl):
+    # [Cout, kh*kw*Cin] = [4, 144] takes fewer tiles with the patches as the left operand (2 x 1 against 1 x 3), so
+    # the library exchanges the operands and writes DW transposed; 2^20 + 2^17 output pixels, ragged on both sides
+    case = (18, 256, 256, 16, 4, 3, 3, (1, 1), (1, 1))
+    say(f"cg_share_conv2d_wgrad exchanged operands, very long contraction {case}")
+    xs, ws, gs = shapes(case)
+    ops = (wl.draw_ring(gs, 521), wl.draw_ring(gs, 522), wl.draw_ring(xs, 523), wl.draw_ring(xs, 524))
+    got = run_wgrad(cg, *ops, ws, (1, 1), (1, 1))
+    want = ro.party_conv2d_wgrad(*ops, ws, (1, 1), (1, 1))
+    assert not first_mismatch(got, want), first_mismatch(got, want)
+
+
 def test_backward_of_every_layer_of_the_vgg_shaped_config(cg, ro, wl):
     for idx, layer in enumerate(wl.config_layers(4)):
         if layer.kind != "conv":
