@@ -72,6 +72,19 @@ CG_API int cg_version(void);
  *   M, N, K    : >= 1
  *
  * CG_ERR_UNSUPPORTED if K exceeds 2^20 or M or N exceeds 2^31-1.
+ *
+ * Why K stops at 2^20: the kernel reads its operands through buffer
+ * descriptors, whose 32-bit byte offsets and hardware range check are what
+ * return zeros for ragged tiles without a branch.  A block addresses the up to
+ * 256 rows of its tile relative to the tile's first row, so 256 * K * 8 bytes
+ * must stay below 2^31.  Lifting the limit would mean 64-bit addresses and
+ * explicit bounds tests on every load of every product; the longest
+ * contraction among the networks the paper evaluates (Sec. IV-A: LeNet,
+ * AlexNet, VGG-16, ResNet-50/101/152) is the 7*7*512 = 25088 inputs of
+ * ImageNet VGG-16's first fully connected layer, forty times below it.
+ * The one product whose contraction does grow with the batch, the weight
+ * gradient (contraction over B*Ho*Wo output pixels), rebases its descriptors
+ * slice by slice and accepts 2^30 (see cg_share_conv2d_wgrad).
  */
 CG_API cg_status cg_share_matmul(const uint64_t *x_i, const uint64_t *x_ip1,
                           const uint64_t *y_i, const uint64_t *y_ip1,

@@ -739,7 +739,7 @@ cg_status plan_conv2d(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
         const int64_t span_imgs = (cg::MAX_TILE_ROWS - 1) / howo + 2;
         const int64_t view = (span_imgs < d->B ? span_imgs : d->B) * img * 8;
         if (view > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;
-        amode = (a16 && d->Cin % 32 == 0) ? cg::A_CONV_C32 : cg::A_CONV_GEN;
+        amode = (a16 && d->Cin % 32 == 0 && d->kh * d->kw <= cg::MAX_MASK_TAPS) ? cg::A_CONV_C32 : cg::A_CONV_GEN;
     }
     pl.amode = amode;
     pl.bmode = bvec ? cg::B_VEC : cg::B_SCALAR;
@@ -812,7 +812,8 @@ cg_status plan_conv2d_dgrad(const uint64_t* g_i, const uint64_t* g_ip1, const ui
 
     const void* in[4] = {g_i, g_ip1, w_i, w_ip1};
     const bool strided = d->stride_h != 1 || d->stride_w != 1;
-    const bool c32 = !strided && all_aligned16(in, 4) && d->Cout % 32 == 0 && taps * d->Cin <= ((int64_t)1 << 22);
+    const bool c32 = !strided && all_aligned16(in, 4) && d->Cout % 32 == 0 && taps * d->Cin <= ((int64_t)1 << 22) &&
+                     taps <= cg::MAX_MASK_TAPS;
     if (c32) {
         pl.amode = cg::A_CONV_C32; pl.bmode = cg::B_FLIP_C32;
         // the window covers every tap of the filter and the rows are the pixels in order
@@ -874,7 +875,7 @@ cg_status plan_conv2d_dgrad_phase(const uint64_t* g_i, const uint64_t* g_ip1, co
     const int64_t g_img = cd.howo * d->Cout;
     if (Mg > MAX_DIM || d->Cin > MAX_DIM || Kg > MAX_ROW_WORDS || g_img > ((int64_t)1 << 27) ||
         fh.pad > 32767 || fw.pad > 32767 || fh.pad < -32767 || fw.pad < -32767 || d->kh > 32767 || d->kw > 32767 ||
-        d->kh * d->kw * d->Cin > ((int64_t)1 << 22) || d->B * d->H * d->W > MAX_DIM)
+        d->kh * d->kw * d->Cin > ((int64_t)1 << 22) || d->B * d->H * d->W > MAX_DIM || fh.t * fw.t > cg::MAX_MASK_TAPS)
         return CG_ERR_UNSUPPORTED;
     const int64_t span_imgs = (cg::MAX_TILE_ROWS - 1) / hw + 2;
     if ((span_imgs < d->B ? span_imgs : d->B) * g_img * 8 > MAX_VIEW_BYTES) return CG_ERR_UNSUPPORTED;

@@ -22,11 +22,14 @@ inline FastDiv make_fast_div(uint32_t d) {
     return f;
 }
 
+// The 32-channel patch gathers keep one bit per filter tap (inside the image or not) in a 32-bit register.
+constexpr int MAX_MASK_TAPS = 32;
+
 // How the left operand's words are addressed.
 enum AMode {
     A_LINEAR_VEC = 0,     // row-major [M, lda], 16-byte loads (lda even, 16-byte aligned base)
     A_LINEAR_SCALAR = 1,  // row-major [M, lda], 8-byte loads
-    A_CONV_C32 = 2,       // NHWC patch gather, Cin % 32 == 0, 16-byte loads
+    A_CONV_C32 = 2,       // NHWC patch gather, Cin % 32 == 0, at most MAX_MASK_TAPS taps, 16-byte loads
     A_CONV_GEN = 3,       // NHWC patch gather, any Cin, 8-byte loads
     A_TRANS = 4,          // stored transposed, [K, M] with M contiguous, 8-byte loads
     A_CONV_DIL = 5,       // NHWC patch gather from an image whose pixels sit dil_h, dil_w apart

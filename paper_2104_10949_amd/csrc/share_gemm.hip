@@ -272,34 +272,28 @@ struct TapCursor {
     }
 };
 
-// Patch gather with Cin % 32 == 0, 16-byte loads.  Which filter taps fall inside
-// the image for this unit's output pixel is decided once, as a bit mask over the
-// (up to 64) taps; windows with more taps test the bounds per load.
+// Patch gather with Cin % 32 == 0, 16-byte loads.  Which filter taps fall inside the image for this unit's
+// output pixel is decided once, as a bit mask over the taps; the host sends windows of more than
+// MAX_MASK_TAPS taps to the general gather.  Two registers per unit stay alive across the K loop.
 struct ConvC32 {
-    PatchRow pr;
-    u32 base_kq;  // pr.base + (16*jh + 2*q) * 8 bytes
-    u64 inside;   // bit t: tap t = r*kw + s reads a pixel inside the image
+    u32 base_kq;  // byte offset of word 16*jh + 2*q of pixel (hi0, wi0), relative to the view (mod 2^32)
+    u32 inside;   // bit t: tap t = r*kw + s reads a pixel inside the image
     __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, u32,
                                          int q, int jh) {
+        PatchRow pr;
         pr.init(p, m0, row_local, rows_left);
         base_kq = pr.base + (u32)(16 * jh + 2 * q) * 8u;
         inside = 0;
-        const int taps = p.kh * p.kw;
-        if (pr.ok && taps <= 64) {
+        if (pr.ok) {
             int t = 0;
             for (int r = 0; r < p.kh; ++r)
                 for (int s_ = 0; s_ < p.kw; ++s_, ++t)
-                    if ((u32)(pr.hi0 + r) < (u32)p.H && (u32)(pr.wi0 + s_) < (u32)p.W) inside |= 1ull << t;
+                    if ((u32)(pr.hi0 + r) < (u32)p.H && (u32)(pr.wi0 + s_) < (u32)p.W) inside |= 1u << t;
         }
     }
     __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, const TapCursor& t,
                                          u4 out[2]) const {
-        bool v;
-        if (p.kh * p.kw <= 64) {  // uniform
-            v = t.c0 < p.Cin && ((inside >> t.tap(p)) & 1);
-        } else {
-            v = pr.ok && t.c0 < p.Cin && (u32)(pr.hi0 + t.r) < (u32)p.H && (u32)(pr.wi0 + t.s) < (u32)p.W;
-        }
+        const bool v = t.c0 < p.Cin && ((inside >> t.tap(p)) & 1);
         const u32 off = v ? base_kq + t.off(p) : OOB;
         out[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off, 0, 0);
         out[1] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off + 64u, 0, 0);
@@ -465,39 +459,34 @@ struct PlanesRow {
     }
 };
 
-// Patch gather from the digit planes of the activations seen as a [pixels, Cin] matrix, Cin % 32 == 0.
+// Patch gather from the digit planes of the activations seen as a [pixels, Cin] matrix, Cin % 32 == 0, at most
+// MAX_MASK_TAPS taps.
 struct PlanesPatch {
     u32 pix0;     // pixel index of (hi0, wi0) relative to the view's first 16-pixel block (mod 2^32)
-    int hi0, wi0;
-    bool ok;
-    u64 inside;   // bit t: tap t = r*kw + s reads a pixel inside the image
+    u32 inside;   // bit t: tap t = r*kw + s reads a pixel inside the image
     u32 cq256;
     __device__ __forceinline__ void init(const GemmParams& p, int m0, int row_local, int rows_left, int cq) {
-        ok = row_local < rows_left;
+        const bool ok = row_local < rows_left;
         const u32 m = (u32)(m0 + (ok ? row_local : 0));
         const u32 HoWo = (u32)(p.Ho * p.Wo), HW = (u32)(p.H * p.W);
         const u32 b = m / HoWo, b0 = (u32)m0 / HoWo;
         const u32 rem = m - b * HoWo;
         const u32 ho = rem / (u32)p.Wo, wo = rem - ho * (u32)p.Wo;
-        hi0 = (int)ho * p.sh - p.ph;
-        wi0 = (int)wo * p.sw - p.pw;
+        const int hi0 = (int)ho * p.sh - p.ph, wi0 = (int)wo * p.sw - p.pw;
         // the view starts at the 16-pixel block that holds the first pixel of image b0
         pix0 = ((b0 * HW) & 15u) + (b - b0) * HW + (u32)hi0 * (u32)p.W + (u32)wi0;
         cq256 = (u32)cq * 256u;
         inside = 0;
-        const int taps = p.kh * p.kw;
-        if (ok && taps <= 64) {
+        if (ok) {
             int t = 0;
             for (int r = 0; r < p.kh; ++r)
                 for (int s_ = 0; s_ < p.kw; ++s_, ++t)
-                    if ((u32)(hi0 + r) < (u32)p.H && (u32)(wi0 + s_) < (u32)p.W) inside |= 1ull << t;
+                    if ((u32)(hi0 + r) < (u32)p.H && (u32)(wi0 + s_) < (u32)p.W) inside |= 1u << t;
         }
     }
     // byte offset of piece cq of the slice the cursor points at, or OOB
     __device__ __forceinline__ u32 offset(const GemmParams& p, const TapCursor& t) const {
-        bool v;
-        if (p.kh * p.kw <= 64) v = t.c0 < p.Cin && ((inside >> t.tap(p)) & 1);
-        else v = ok && t.c0 < p.Cin && (u32)(hi0 + t.r) < (u32)p.H && (u32)(wi0 + t.s) < (u32)p.W;
+        const bool v = t.c0 < p.Cin && ((inside >> t.tap(p)) & 1);
         const u32 pix = pix0 + (u32)t.r * (u32)p.W + (u32)t.s;
         const u32 KS = (u32)p.Cin >> 5;
         return v ? ((pix >> 4) * KS + ((u32)t.c0 >> 5)) * 4096u + cq256 + (pix & 15u) * 16u : OOB;

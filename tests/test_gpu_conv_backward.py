@@ -54,8 +54,11 @@ CASES = [
     (200, 1, 1, 32, 16, 3, 3, (1, 1), (1, 1)),         # many images per K slice and per row block
     (40, 2, 2, 8, 24, 2, 2, (1, 1), (1, 1)),
     (2, 20, 20, 200, 64, 3, 3, (1, 1), (1, 1)),        # ragged tails in every dimension
-    (1, 12, 12, 8, 32, 9, 9, (1, 1), (4, 4)),          # 81 taps: beyond the 64-bit tap mask of the gather
+    (1, 12, 12, 8, 32, 9, 9, (1, 1), (4, 4)),          # 81 taps: more than the tap mask of the 32-channel gather holds
     (2, 10, 11, 40, 64, 9, 8, (1, 1), (4, 3)),
+    (2, 11, 12, 24, 32, 4, 8, (1, 1), (1, 3)),         # 32 taps: the largest window of the 32-channel gather
+    (2, 11, 12, 24, 32, 5, 7, (1, 1), (2, 3)),         # 35 taps
+    (2, 23, 25, 24, 32, 9, 13, (2, 2), (4, 6)),        # strided, classes of up to 5 x 7 = 35 taps: zero-interleaved gather
     (8, 14, 14, 256, 256, 3, 3, (1, 1), (1, 1)),       # tile counts that take the streamed distribution
     (3, 21, 21, 96, 224, 3, 3, (1, 1), (1, 1)),
     # strided with Cout % 32 == 0: one unit-stride product per residue class of the input pixels

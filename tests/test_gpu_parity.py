@@ -191,8 +191,10 @@ CONV_CASES = [
     (2, 7, 7, 6, 10, 1, 1, (1, 1), (0, 0)),
     (4, 5, 5, 7, 9, 1, 1, (1, 1), (0, 0)),
     (200, 1, 1, 32, 16, 3, 3, (1, 1), (1, 1)),
-    (1, 12, 12, 32, 40, 9, 9, (1, 1), (4, 4)),       # 81 taps: beyond the 64-bit tap mask, bounds tested per load
+    (1, 12, 12, 32, 40, 9, 9, (1, 1), (4, 4)),       # 81 taps: more than the tap mask of the 32-channel gather holds, general gather
     (2, 10, 11, 64, 70, 9, 8, (2, 1), (4, 3)),
+    (2, 11, 12, 32, 40, 4, 8, (1, 1), (1, 3)),       # 32 taps: the largest window of the 32-channel gather
+    (2, 11, 12, 32, 40, 5, 7, (1, 1), (2, 3)),       # 35 taps
     (8, 14, 14, 256, 256, 3, 3, (1, 1), (1, 1)),     # 13 x 4 tiles, 72 slices: streamed distribution
     (3, 21, 21, 96, 200, 3, 3, (1, 1), (1, 1)),
 ]
