@@ -4,14 +4,19 @@
 One "step" is one pass of the hot path over one batch: every layer of the
 VGG16-shaped configuration (batch 32, 64x64x3 input, thirteen 3x3 convolutions
 and three fully connected layers), each computed by one party from its four
-share tensors with cg_share_conv2d / cg_share_matmul.  Inputs are uniform
-64-bit words (the distribution of any two of the three shares), seeded,
-resident in HBM before the timed region.
+share tensors with cg_share_conv2d / cg_share_matmul, or with their *_ws
+variants (caller-supplied scratch memory, allocated once outside the timed
+region) for the layers where the library's own rule says that route is faster;
+--plain times the plain calls only, and the default line reports both.  Inputs
+are uniform 64-bit words (the distribution of any two of the three shares),
+seeded, resident in HBM before the timed region.
 
 Prints ONE JSON line: effective 64-bit ring MAC/s (three ring products per
 party and output element, as the protocol states them), the int8-MFMA roofline
-fraction of the share-product kernel measured over the same timed region, and
-the CPU oracle timed on the host cores for the same workload.
+fraction of the share-product kernel measured over the same timed region, the
+CPU oracle timed on the host cores for the same workload, and (object "rows")
+the largest GEMM shapes, the other convolution configurations, the streaming
+kernels against the HBM peak and the small fully connected layers warm and cold.
 """
 from __future__ import annotations
 
@@ -33,8 +38,9 @@ DIGIT_MACS_PER_RING_MAC_TRIPLE = 72  # 2 ring products x 36 signed-byte digit pa
 WORKLOAD_CONFIG = 4
 # HBM bytes per share_gemm_kernel launch on the config-4 step, from the two rocprofv3 --pmc runs summarised in
 # profiles/share_gemm_config4_hbm_traffic.txt (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000 by the 1 GiB copy calibration).
-PROFILED_TRAFFIC_CONFIG4 = {"read_bytes_per_launch": 67.8e6, "write_bytes_per_launch": 23.9e6,
+PROFILED_TRAFFIC_CONFIG4 = {"read_bytes_per_launch": 65.8e6, "write_bytes_per_launch": 24.3e6,
                             "algorithmic_bytes_per_launch": 61.0e6,
+                            "conversion_pass_per_scratch_route_layer": {"read_bytes": 47.8e6, "write_bytes": 43.5e6},
                             "source": "profiles/share_gemm_config4_hbm_traffic.txt"}
 
 
@@ -505,7 +511,8 @@ def main() -> int:
             ops = cg.to_device(np.full((8192,), 0x0101010101010101, dtype=np.uint64))
         n_cu = torch.cuda.get_device_properties(0).multi_processor_count
         sink = torch.empty(n_cu * 512, dtype=torch.int32, device="cuda")
-        iters, stream = 20000 if not k64 else 5000, torch.cuda.current_stream().cuda_stream
+        # (long enough that the kernel's start-up, about 0.4 ms for the 16x16x64 loop, is under 5 % of the run)
+        iters, stream = 20000, torch.cuda.current_stream().cuda_stream
 
         def launch():
             rc = fn(ops.data_ptr(), sink.data_ptr(), n_cu, 2, iters, stream)
