@@ -8,8 +8,8 @@
 // By distributivity this is x_a*(w_a + w_b) + x_b*w_a: two ring products, i.e.
 // one matrix product over the doubled contraction length
 //     [x_a | x_b] * [w_a + w_b | w_a]^T.
-// Each 32-wide slice of K therefore yields two "half-steps": an even one
-// (x_a against w_a + w_b) and an odd one (x_b against w_a).
+// A matrix instruction contracts 64 bytes; here these are one digit of a 32-word
+// slice of K for BOTH terms at once: [x_a | x_b] against [w_a + w_b | w_a].
 //
 // How a ring product runs on the matrix cores.  A 64-bit word a is rewritten
 // as eight SIGNED byte digits d_0..d_7 in [-128,127] with
@@ -21,8 +21,8 @@
 // 36 digit pairs; pairs with l+m >= 8 vanish mod 2^64 (Sec. II-B: only block
 // products with w(i+j-2) < 64 are needed).  All pairs with the same s = l+m
 // share one i32 accumulator P_s, so a 32x32 output tile keeps eight of them.
-// |d d'| <= 2^14, and P_s receives (s+1)*32 products per half-step, so P_0..P_3
-// stay exact in i32 for 1023 half-steps; P_4..P_7 only matter mod 2^(64-8s) <=
+// |d d'| <= 2^14, and P_s receives (s+1)*64 products per slice, so P_0..P_3
+// stay exact in i32 for 511 slices; P_4..P_7 only matter mod 2^(64-8s) <=
 // 2^32, where i32 wraparound (verified on hardware) is harmless.  After at most
 // SEG_KSTEPS slices of K the accumulators are folded into the 64-bit result
 // z += sum_s sext(P_s) << 8s and cleared.
@@ -31,8 +31,8 @@
 // uint64 (coalesced 16-byte buffer loads, out-of-range lanes return 0, which
 // is exact padding in the ring), split into digit planes in registers
 // (4 integer ops + 4 byte permutes per word), written to LDS as
-// [digit][k-half][row][16 bytes] so that every MFMA operand is one conflict-free
-// ds_read_b128, and consumed by v_mfma_i32_32x32x32_i8.  Convolution and the
+// [digit][k-group][row][16 bytes] so that every MFMA operand is one conflict-free
+// ds_read_b128, and consumed by v_mfma_i32_16x16x64_i8.  Convolution and the
 // backward products of both layer kinds (Sec. III-C) use the same kernel: only the
 // address generators of the operands differ (patch gather from NHWC with zero
 // fill, operands stored transposed, the filter read with its taps reversed, patch
@@ -1277,7 +1277,7 @@ static constexpr double STREAM_MARGIN = 0.88;
 static constexpr int PERSIST_MAX_SLICES = 32;
 
 static int choose_ksplit(int64_t tiles, int nk) {
-    // A block's 96 KB of LDS leaves room for one block per compute unit, so a grid runs
+    // A block's 160 KB of LDS leaves room for one block per compute unit, so a grid runs
     // in rounds of 256 blocks and the last round costs as much as a full one.  Splitting
     // K makes the blocks shorter, which fills the chip when the tiles alone cannot and
     // shrinks the idle part of the last round otherwise.  The split count with the least
