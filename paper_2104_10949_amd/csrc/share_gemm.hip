@@ -542,15 +542,6 @@ __device__ __forceinline__ void logical_to_tile(const GemmParams& p, int tiles_m
     tn = in_g / gsz;
 }
 
-// classic distribution only: block -> (K split, output tile)
-__device__ __forceinline__ void block_to_tile(const GemmParams& p, int BM, int BN, int& split, int& tm, int& tn) {
-    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const int nb = tiles_m * tiles_n;
-    const int run = run_index(nb * p.ksplit);
-    split = run / nb;
-    logical_to_tile(p, tiles_m, tiles_n, run - split * nb, tm, tn);
-}
-
 // fold: z (+)= sum_s sext(P_s) << 8s for the wave's 32 x 32 sub-tile, which is 2 x 2 blocks of 16 x 16; lane i
 // holds rows 4*(i/16) .. +3 of column i%16 of each block.  P_4..P_7 only reach bits 32..63.  Modes: plain store
 // (one fold, one split), read-add-write by the owning lane (later folds of a single split), atomic add into a
