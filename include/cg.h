@@ -71,20 +71,21 @@ CG_API int cg_version(void);
  *   z_i        : [M,N] row-major, written in full
  *   M, N, K    : >= 1
  *
- * CG_ERR_UNSUPPORTED if K exceeds 2^20 or M or N exceeds 2^31-1.
+ * CG_ERR_UNSUPPORTED if K exceeds 2^30 or M or N exceeds 2^31-1.
  *
- * Why K stops at 2^20: the kernel reads its operands through buffer
- * descriptors, whose 32-bit byte offsets and hardware range check are what
- * return zeros for ragged tiles without a branch.  A block addresses the up to
- * 256 rows of its tile relative to the tile's first row, so 256 * K * 8 bytes
- * must stay below 2^31.  Lifting the limit would mean 64-bit addresses and
- * explicit bounds tests on every load of every product; the longest
- * contraction among the networks the paper evaluates (Sec. IV-A: LeNet,
- * AlexNet, VGG-16, ResNet-50/101/152) is the 7*7*512 = 25088 inputs of
- * ImageNet VGG-16's first fully connected layer, forty times below it.
- * The one product whose contraction does grow with the batch, the weight
- * gradient (contraction over B*Ho*Wo output pixels), rebases its descriptors
- * slice by slice and accepts 2^30 (see cg_share_conv2d_wgrad).
+ * K and the two ways of addressing a row.  Up to K = 2^20 the kernel reads its
+ * operands through buffer descriptors, whose 32-bit byte offsets and hardware
+ * range check return zeros for ragged tiles without a branch (a block addresses
+ * the up to 256 rows of its tile relative to the tile's first row, so
+ * 256 * K * 8 bytes must stay below 2^31).  Longer rows take generators with
+ * 64-bit addresses, 8-byte loads and explicit bounds: same result, bit for
+ * bit, at a lower rate, and without the scratch-memory route (the *_ws and
+ * *_static calls then compute as this call).  The longest contraction among
+ * the networks the paper evaluates (Sec. IV-A: LeNet, AlexNet, VGG-16,
+ * ResNet-50/101/152) is the 7*7*512 = 25088 inputs of ImageNet VGG-16's first
+ * fully connected layer.  The convolution calls keep kh*kw*Cin <= 2^20; the
+ * weight gradient, whose contraction runs over B*Ho*Wo output pixels, rebases
+ * its descriptors slice by slice and accepts 2^30 (see cg_share_conv2d_wgrad).
  */
 CG_API cg_status cg_share_matmul(const uint64_t *x_i, const uint64_t *x_ip1,
                           const uint64_t *y_i, const uint64_t *y_ip1,
@@ -232,8 +233,8 @@ CG_API cg_status cg_share_conv2d_acc(const uint64_t *x_i, const uint64_t *x_ip1,
  * (Sec. II-B): every word as four unsigned 16-bit blocks held in float64, the ten
  * block products whose weight stays below 2^64, on the float64 matrix instruction,
  * accumulators folded into the 64-bit result before they leave the exact range.
- * Same arguments, validation, errors and result (bit for bit) as cg_share_matmul;
- * several times slower.  A comparator: it exists so that the choice of 8-bit digits
+ * Same arguments, validation, errors and result (bit for bit) as cg_share_matmul,
+ * except that K stops at 2^20 (CG_ERR_UNSUPPORTED beyond); several times slower.  A comparator: it exists so that the choice of 8-bit digits
  * on the integer matrix instruction is backed by a measurement, not to be called by
  * applications.
  */

@@ -16,6 +16,7 @@ typedef uint64_t u64;
 
 const int64_t MAX_DIM = 0x7FFFFFFF;      // M, N as 32-bit ints in the kernel
 const int64_t MAX_ROW_WORDS = 1 << 20;   // K: MAX_TILE_ROWS rows of K words stay below 2^31 bytes
+const int64_t MAX_LONG_ROW_WORDS = (int64_t)1 << 30;   // K of the matrix products: slice indices stay 32-bit
 const int64_t MAX_VIEW_BYTES = 0x7FFFFFFF;
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -640,7 +641,7 @@ cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     if (check_ptrs_too)
         if (cg_status st = check_product_ptrs(x_i, x_ip1, y_i, y_ip1, z_i, (u64)mk * 8, (u64)nk * 8, (u64)mn * 8))
             return st;
-    if (M > MAX_DIM || N > MAX_DIM || K > MAX_ROW_WORDS) return CG_ERR_UNSUPPORTED;
+    if (M > MAX_DIM || N > MAX_DIM || K > MAX_LONG_ROW_WORDS) return CG_ERR_UNSUPPORTED;
 
     Plan pl = {};
     cg::GemmParams& p = pl.p;
@@ -657,7 +658,13 @@ cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
     if (!trans_x && trans_y) pl.amode = vec ? cg::A_LINEAR_VEC : cg::A_LINEAR_SCALAR;
     // a transposed operand is addressed slice by slice: 32 rows of its pitch must fit a 2^31-byte view
     if ((trans_x && M > (1 << 22)) || (trans_y && N > (1 << 22))) return CG_ERR_UNSUPPORTED;
-    pl.planes_ok = vec && !trans_x && !trans_y;
+    // rows beyond what a buffer view addresses: the row-major operands take the 64-bit generators
+    const bool long_rows = K > MAX_ROW_WORDS;
+    if (long_rows) {
+        if (!trans_x) pl.amode = cg::A_LINEAR_WIDE;
+        if (!trans_y) pl.bmode = cg::B_WIDE;
+    }
+    pl.planes_ok = vec && !trans_x && !trans_y && !long_rows;
     pl.planes_conv = false;
     pl.x_rows = M; pl.x_k = K;
     pl.xp_bytes = cg::planes_bytes(M, K); pl.wp_bytes = cg::planes_bytes(N, K);
@@ -1028,8 +1035,9 @@ cg_status cg_share_conv2d_acc(const uint64_t* x_i, const uint64_t* x_ip1, const 
 cg_status cg_share_matmul_f64limb(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t* y_i,
                                   const uint64_t* y_ip1, uint64_t* z_i, int64_t M, int64_t N, int64_t K,
                                   void* stream) {
-    Plan pl;  // validation and limits of the plain product
+    Plan pl;  // validation and limits of the plain product with rows a buffer view addresses
     if (cg_status st = plan_matmul(x_i, x_ip1, y_i, y_ip1, z_i, M, N, K, true, &pl)) return st;
+    if (K > MAX_ROW_WORDS) return CG_ERR_UNSUPPORTED;
     const hipError_t e = cg::launch_share_gemm_f64limb(x_i, x_ip1, y_i, y_ip1, z_i, (int)M, (int)N, (int)K,
                                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CG_OK : CG_ERR_DEVICE;

@@ -39,7 +39,9 @@ enum AMode {
     // Weight gradient with the operands exchanged: the left operand is the layer input, A[(r, s, c), pixel] =
     // patch entry (B_PATCH_T's generator), the right one the transposed gradient (B_TRANS), and z is written
     // transposed, z[col * M + row]: few output channels then fill the 64-column side of the tile.
-    A_PATCH_T = 8
+    A_PATCH_T = 8,
+    A_LINEAR_WIDE = 9     // row-major [M, lda] with rows too long for 32-bit offsets (256 rows of more than 2^31
+                          // bytes): 64-bit addresses, 8-byte loads, explicit bounds
 };
 
 // How the right operand's words are addressed.
@@ -55,7 +57,8 @@ enum BMode {
     B_FLIP_GEN = 4,  // ... any Cout: every word finds its own tap
     // Weight gradient: the right operand is the layer input, B[(r, s, c), pixel] = patch entry
     B_PATCH_T = 5,
-    B_PLANES = 6     // row-major [N, K] kept as digit planes (wp_sum, wp_a)
+    B_PLANES = 6,    // row-major [N, K] kept as digit planes (wp_sum, wp_a)
+    B_WIDE = 7       // row-major [N, K] with rows too long for 32-bit offsets (see A_LINEAR_WIDE)
 };
 
 struct GemmParams {

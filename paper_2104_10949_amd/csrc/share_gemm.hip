@@ -37,12 +37,27 @@
 // address generators of the operands differ (patch gather from NHWC with zero
 // fill, operands stored transposed, the filter read with its taps reversed, patch
 // entries gathered as the right operand).  Nothing but z is written to HBM.
+//
+// build.py compiles the file three times, with -DCG_INST_GROUP=0, 1, 2: every group instantiates the kernel for a
+// third of the address-generator pairs (see launch_share_gemm at the end), so that the three compile side by side;
+// group 0 also holds the conversion and clearing kernels and the entry point itself.  Without the macro the file
+// compiles to one object with everything.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include <type_traits>
 
 #include "share_gemm.h"
+
+#ifdef CG_INST_GROUP
+#define CG_G0 (CG_INST_GROUP == 0)
+#define CG_G1 (CG_INST_GROUP == 1)
+#define CG_G2 (CG_INST_GROUP == 2)
+#else   // compiled on its own: everything in one object
+#define CG_G0 1
+#define CG_G1 1
+#define CG_G2 1
+#endif
 
 namespace cg {
 
@@ -187,6 +202,36 @@ struct LinearScalar {
             const u32 k = 32u * ks + kq + 8u * jj;
             const u2 e0 = __builtin_amdgcn_raw_buffer_load_b64(r, k < K ? off + 64u * jj : OOB, 0, 0);
             const u2 e1 = __builtin_amdgcn_raw_buffer_load_b64(r, k + 1 < K ? off + 64u * jj + 8u : OOB, 0, 0);
+            out[jj].x = e0.x; out[jj].y = e0.y; out[jj].z = e1.x; out[jj].w = e1.y;
+        }
+    }
+};
+
+// Row-major operand whose rows are too long for the 32-bit offsets of a buffer view (a tile's 256 rows must
+// stay below 2^31 bytes, i.e. ld <= 2^20 words): 64-bit addresses and 8-byte loads.  Nothing checks a range in
+// hardware here, so a word outside the operand (rows past the end, the K tail, a loader past the block's range)
+// is read from a word of zeros instead.
+static __device__ u64 wide_zero_word[2];   // zero-initialised, never written (one copy per compiled group)
+
+struct LinearWide {
+    u64 row_w;  // word offset of word k = 16*jh + 2*q of the row, relative to the tile's first row
+    u32 kq;
+    bool ok;
+    __device__ __forceinline__ void init(const GemmParams&, int, int row_local, int rows_left, u32 ld,
+                                         int q, int jh) {
+        kq = 16 * jh + 2 * q;
+        ok = row_local < rows_left;
+        row_w = (u64)row_local * (u64)ld + kq;
+    }
+    // `tile`: first word of the tile's first row in this share tensor; null for a loader past its range
+    __device__ __forceinline__ void load_wide(const u64* tile, int ks, u32 K, u4 out[2]) const {
+        const u64* src = tile + row_w + 32u * (u32)ks;
+        const bool live = ok && tile != nullptr;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const u32 k = 32u * ks + kq + 8u * jj;
+            const u2 e0 = *reinterpret_cast<const u2*>(live && k < K ? src + 8 * jj : wide_zero_word);
+            const u2 e1 = *reinterpret_cast<const u2*>(live && k + 1 < K ? src + 8 * jj + 1 : wide_zero_word);
             out[jj].x = e0.x; out[jj].y = e0.y; out[jj].z = e1.x; out[jj].w = e1.y;
         }
     }
@@ -698,7 +743,8 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
         w.u += w.nk - w.ks;
     };
 
-    constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR;
+    constexpr bool A_WIDE = AMODE == A_LINEAR_WIDE, B_WIDEROWS = BMODE == B_WIDE;
+    constexpr bool A_LINEAR = AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR || A_WIDE;
     constexpr bool A_TR = AMODE == A_TRANS;
     // left-operand modes whose memory is contiguous along m: consecutive lanes take consecutive rows
     constexpr bool A_ROWS = A_TR || AMODE == A_PATCH_T || AMODE == A_CONV_GEN || AMODE == A_CONV_DIL;
@@ -714,15 +760,17 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     // ---- per-thread units.  Row-major operands put the four 16-byte quarters of a
     // 64-byte run on consecutive lanes; transposed operands put consecutive rows there.
     typedef typename std::conditional<AMODE == A_LINEAR_VEC, LinearVec,
+            typename std::conditional<AMODE == A_LINEAR_WIDE, LinearWide,
             typename std::conditional<AMODE == A_LINEAR_SCALAR, LinearScalar,
             typename std::conditional<AMODE == A_CONV_C32, ConvC32,
             typename std::conditional<AMODE == A_TRANS, TransScalar,
             typename std::conditional<AMODE == A_PATCH_T, PatchTrans,
-            typename std::conditional<AMODE == A_CONV_DIL, ConvDil, ConvGen>::type>::type>::type>::type>::type>::type AGen;
+            typename std::conditional<AMODE == A_CONV_DIL, ConvDil, ConvGen>::type>::type>::type>::type>::type>::type>::type AGen;
     typedef typename std::conditional<BMODE == B_VEC, LinearVec,
+            typename std::conditional<BMODE == B_WIDE, LinearWide,
             typename std::conditional<BMODE == B_SCALAR, LinearScalar,
             typename std::conditional<BMODE == B_FLIP_GEN, FlipGen,
-            typename std::conditional<BMODE == B_PATCH_T, PatchTrans, TransScalar>::type>::type>::type>::type BGen;
+            typename std::conditional<BMODE == B_PATCH_T, PatchTrans, TransScalar>::type>::type>::type>::type>::type BGen;
     PlanesRow pa_row, pb_row;   // plane route: this thread's row of the left and of the right tile
     PlanesPatch pa_patch;
     const u64 w_elems = p.w_elems;
@@ -906,6 +954,8 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
             tap_a.advance_to(p, ks);
 #pragma unroll
             for (int i = 0; i < AU; ++i) ag[i].load(p, rs, tap_a, dst[i]);
+        } else if constexpr (A_WIDE) {
+            (void)rs;   // see load_xa / load_xb
         } else {
 #pragma unroll
             for (int i = 0; i < AU; ++i) ag[i].load(p, rs, ks, (u32)p.K, dst[i]);
@@ -915,8 +965,22 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
     // out of range there, so the loads return zeros without touching memory (no branch around them: a branch
     // would make the compiler wait for all outstanding loads where the paths join).
     auto dead_view = [&](__amdgpu_buffer_rsrc_t r, const u64* ptr, bool live) { return live ? r : make_rsrc(ptr, 0); };
-    auto load_xa = [&]() { load_a(dead_view(a_view(p.x_a, rs_xa, wa_.ks), p.x_a, wa_.ks < wa_.nk), wa_.ks, xa); };
-    auto load_xb = [&]() { load_a(dead_view(a_view(p.x_b, rs_xb, wa_.ks), p.x_b, wa_.ks < wa_.nk), wa_.ks, xb); };
+    // (long rows: plain pointers instead of views, null past the range)
+    auto load_a_wide = [&](const u64* ptr, u4 (*dst)[2]) {
+        if constexpr (A_WIDE) {
+            const u64* tile = wa_.ks < wa_.nk ? ptr + a_base_elems : nullptr;
+#pragma unroll
+            for (int i = 0; i < AU; ++i) ag[i].load_wide(tile, wa_.ks, (u32)p.K, dst[i]);
+        }
+    };
+    auto load_xa = [&]() {
+        if constexpr (A_WIDE) load_a_wide(p.x_a, xa);
+        else load_a(dead_view(a_view(p.x_a, rs_xa, wa_.ks), p.x_a, wa_.ks < wa_.nk), wa_.ks, xa);
+    };
+    auto load_xb = [&]() {
+        if constexpr (A_WIDE) load_a_wide(p.x_b, xb);
+        else load_a(dead_view(a_view(p.x_b, rs_xb, wa_.ks), p.x_b, wa_.ks < wa_.nk), wa_.ks, xb);
+    };
     auto load_w = [&]() {
         const int ks = wb_.ks;
         int kb = ks;
@@ -935,6 +999,13 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
                 wa[0][g] = __builtin_amdgcn_raw_buffer_load_b128(ra, off + 2048u * g, 0, 0);
                 wb[0][g] = __builtin_amdgcn_raw_buffer_load_b128(rb, off + 2048u * g, 0, 0);
             }
+        } else if constexpr (B_WIDEROWS) {
+            (void)ra; (void)rb;
+            const u64 *ta = live ? p.w_a + b_base_elems : nullptr, *tb = live ? p.w_b + b_base_elems : nullptr;
+#pragma unroll
+            for (int i = 0; i < BU; ++i) bg[i].load_wide(ta, kb, (u32)p.K, wa[i]);
+#pragma unroll
+            for (int i = 0; i < BU; ++i) bg[i].load_wide(tb, kb, (u32)p.K, wb[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < BU; ++i) bg[i].load(p, ra, kb, (u32)p.K, wa[i]);
@@ -1185,6 +1256,7 @@ __global__ __launch_bounds__(T::NT, 1) void share_gemm_kernel(const GemmParams p
 // multiple of 16, K to whole slices).
 // ===========================================================================
 
+#if CG_G0
 // One thread converts four consecutive words of a row; the 64 lanes of a wave take the four
 // 4-word quarters of one k-half of sixteen rows, so that each of their eight stores (one per
 // digit) writes 256 contiguous bytes.  One launch converts all four tensors of a product:
@@ -1250,6 +1322,8 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(u64* z, size_t n) {
     const size_t stride = (size_t)gridDim.x * 256;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) z[i] = 0;
 }
+
+#endif  // CG_G0
 
 template <class T, int AMODE, int BMODE>
 static hipError_t launch(const GemmParams& p, hipStream_t stream);
@@ -1324,6 +1398,7 @@ static int choose_group_m(const GemmParams& p, int64_t tiles_m, int64_t tiles_n,
     return best;
 }
 
+#if CG_G0
 hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     size_t blocks = (n + 255) / 256;
@@ -1331,6 +1406,7 @@ hipError_t launch_zero_words(uint64_t* z, size_t n, hipStream_t stream) {
     hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, z, n);
     return hipGetLastError();
 }
+#endif
 
 // z = 0 ahead of a launch whose blocks add into it (unless the caller has done so: a
 // scattered output is cleared by the caller, who knows its extent; or z holds a value
@@ -1340,6 +1416,7 @@ static hipError_t launch_zero_fill(const GemmParams& p, hipStream_t stream) {
     return launch_zero_words(p.z, (size_t)p.M * (size_t)p.N, stream);
 }
 
+#if CG_G0
 hipError_t launch_to_planes(const GemmParams& p, int64_t x_rows, int64_t x_k, hipStream_t stream) {
     PlaneJobs jobs;
     const struct { const u64 *src, *add; const char* dst; int64_t R, K; } in[4] = {
@@ -1358,6 +1435,7 @@ hipError_t launch_to_planes(const GemmParams& p, int64_t x_rows, int64_t x_k, hi
     hipLaunchKernelGGL(to_planes_kernel, dim3(first), dim3(256), 0, stream, jobs);
     return hipGetLastError();
 }
+#endif
 
 // Modelled time of the classic distribution with `ks` splits, in K slices (see choose_ksplit).
 static double classic_cost(int64_t tiles, int nk, int ks) {
@@ -1439,33 +1517,72 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream) {
+// The address-generator pairs of one compiled group; *found says whether (amode, bmode) is one of them.
+#define CG_CASE(A, B) if (amode == A && bmode == B) return launch<T, A, B>(p, stream)
+#if CG_G0
+hipError_t launch_share_gemm_group0(const GemmParams& p, int amode, int bmode, hipStream_t stream, bool* found) {
     typedef DefaultStepTile T;  // 4 waves along M, 2 along N
+    *found = true;
     // Fully connected layers at small batch: one 32-row wave tile holds all of M, so a
     // 32 x 128 tile of four waves does a quarter of the matrix work of the 128-row tile
     // (measured: pays from K of a few thousand on; shorter products are launch-bound either way).
     if (amode == A_LINEAR_VEC && bmode == B_VEC && p.M <= 32 && p.N >= 128 && p.K >= 2048)
         return launch<StepTile<1, 4>, A_LINEAR_VEC, B_VEC>(p, stream);
-#define CG_CASE(A, B) if (amode == A && bmode == B) return launch<T, A, B>(p, stream)
     CG_CASE(A_LINEAR_VEC, B_VEC);
     CG_CASE(A_LINEAR_SCALAR, B_SCALAR);
+    CG_CASE(A_PLANES, B_PLANES);
+    CG_CASE(A_PLANES_CONV, B_PLANES);
+    CG_CASE(A_LINEAR_WIDE, B_WIDE);
+    *found = false;
+    return hipSuccess;
+}
+#endif
+#if CG_G1
+hipError_t launch_share_gemm_group1(const GemmParams& p, int amode, int bmode, hipStream_t stream, bool* found) {
+    typedef DefaultStepTile T;
+    *found = true;
     CG_CASE(A_CONV_C32, B_VEC);
     CG_CASE(A_CONV_GEN, B_VEC);
     CG_CASE(A_CONV_GEN, B_SCALAR);
+    CG_CASE(A_CONV_C32, B_FLIP_C32);
+    CG_CASE(A_CONV_GEN, B_FLIP_GEN);
+    CG_CASE(A_CONV_DIL, B_FLIP_GEN);
+    *found = false;
+    return hipSuccess;
+}
+#endif
+#if CG_G2
+hipError_t launch_share_gemm_group2(const GemmParams& p, int amode, int bmode, hipStream_t stream, bool* found) {
+    typedef DefaultStepTile T;
+    *found = true;
     CG_CASE(A_LINEAR_VEC, B_TRANS);
     CG_CASE(A_LINEAR_SCALAR, B_TRANS);
     CG_CASE(A_TRANS, B_VEC);
     CG_CASE(A_TRANS, B_SCALAR);
     CG_CASE(A_TRANS, B_TRANS);
-    CG_CASE(A_CONV_C32, B_FLIP_C32);
-    CG_CASE(A_CONV_GEN, B_FLIP_GEN);
-    CG_CASE(A_CONV_DIL, B_FLIP_GEN);
     CG_CASE(A_TRANS, B_PATCH_T);
     CG_CASE(A_PATCH_T, B_TRANS);
-    CG_CASE(A_PLANES, B_PLANES);
-    CG_CASE(A_PLANES_CONV, B_PLANES);
-#undef CG_CASE
-    return hipErrorInvalidValue;
+    CG_CASE(A_LINEAR_WIDE, B_TRANS);
+    CG_CASE(A_TRANS, B_WIDE);
+    *found = false;
+    return hipSuccess;
 }
+#endif
+#undef CG_CASE
+
+#if CG_G0
+hipError_t launch_share_gemm_group1(const GemmParams& p, int amode, int bmode, hipStream_t stream, bool* found);
+hipError_t launch_share_gemm_group2(const GemmParams& p, int amode, int bmode, hipStream_t stream, bool* found);
+
+hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream) {
+    bool found = false;
+    hipError_t e = launch_share_gemm_group0(p, amode, bmode, stream, &found);
+    if (found) return e;
+    e = launch_share_gemm_group1(p, amode, bmode, stream, &found);
+    if (found) return e;
+    e = launch_share_gemm_group2(p, amode, bmode, stream, &found);
+    return found ? e : hipErrorInvalidValue;
+}
+#endif
 
 }  // namespace cg

@@ -62,7 +62,7 @@ def test_matmul_validation_happens_before_any_device_work(L):
     assert f(*ok[:4], P + 8, 4, 4, 4, None) == b.CG_ERR_ALIAS              # z inside x_i
     assert f(*ok[:4], 4 * P + 64, 4, 4, 4, None) == b.CG_ERR_ALIAS         # z inside y_ip1
     big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
-    assert f(*big, 4, 4, (1 << 20) + 1, None) == b.CG_ERR_UNSUPPORTED
+    assert f(*big, 4, 4, (1 << 30) + 1, None) == b.CG_ERR_UNSUPPORTED     # rows of up to 2^30 words are addressed
     assert f(*big, 1 << 31, 1, 1, None) == b.CG_ERR_UNSUPPORTED
 
 
@@ -76,7 +76,7 @@ def test_accumulating_entry_points_validate_like_the_plain_ones(L):
     assert f(*ok[:4], 5 * P + 4, 4, 4, 4, None) == b.CG_ERR_ALIGN
     assert f(*ok[:4], P + 8, 4, 4, 4, None) == b.CG_ERR_ALIAS              # z inside x_i
     big = [1 << 40, 2 << 40, 3 << 40, 4 << 40, 5 << 40]
-    assert f(*big, 4, 4, (1 << 20) + 1, None) == b.CG_ERR_UNSUPPORTED
+    assert f(*big, 4, 4, (1 << 30) + 1, None) == b.CG_ERR_UNSUPPORTED
     h = L.cg_share_matmul_f64limb                                          # the float64 comparator: same checks
     assert h(0, *ok[1:], 4, 4, 4, None) == b.CG_ERR_NULL
     assert h(*ok, 4, 4, 0, None) == b.CG_ERR_SHAPE
