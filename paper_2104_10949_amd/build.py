@@ -17,6 +17,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hi
 
 # share_gemm.hip is compiled once per group of kernel instantiations (-DCG_INST_GROUP): the groups compile side by side.
 UNITS = [("cg_api.hip", "cg_api.o", []), ("share_gemm_f64.hip", "share_gemm_f64.o", []), ("prf.hip", "prf.o", []),
+         ("share_gemm_small.hip", "share_gemm_small.o", []),
          ("share_gemm.hip", "share_gemm_g0.o", ["-DCG_INST_GROUP=0"]),
          ("share_gemm.hip", "share_gemm_g1.o", ["-DCG_INST_GROUP=1"]),
          ("share_gemm.hip", "share_gemm_g2.o", ["-DCG_INST_GROUP=2"])]

@@ -98,6 +98,11 @@ static const int MAX_TILE_ROWS = 256;
 
 hipError_t launch_share_gemm(const GemmParams& p, int amode, int bmode, hipStream_t stream);
 
+// Products with few rows on the left (share_gemm_small.hip): row-major operands that A_LINEAR_VEC / B_VEC
+// address (K even, 16-byte aligned bases, lda == K).  `applies` says whether the launcher takes p.
+bool share_gemm_small_applies(const GemmParams& p);
+hipError_t launch_share_gemm_small(const GemmParams& p, hipStream_t stream);
+
 // The same product of row-major x [M, K] and w [N, K] on the float64 matrix instruction with
 // four 16-bit blocks per word (share_gemm_f64.hip); K below 2^31 / 8 words per row is the
 // caller's business, the kernel indexes with 64-bit offsets.

@@ -149,6 +149,49 @@ def test_matmul_long_k_without_split_k_folds_in_place(cg, ro, wl, route):
         assert not first_mismatch(got[r0:r0 + 8], want), f"rows {r0}.."
 
 
+# Left operands of few rows take a kernel of their own (one 16 x 16 block of z per thread block, the slices of K
+# shared out over its waves, K split over blocks as well when z has few blocks).
+FEW_ROWS_SHAPES = [
+    (16, 16, 32), (1, 1, 2), (32, 512, 512), (32, 200, 512), (8, 1000, 2048),    # the fully connected layers of the configs
+    (17, 33, 70), (33, 47, 1026), (64, 64, 1024), (49, 300, 512),                # ragged in every dimension, 2-4 row blocks
+    (5, 7, 20000), (16, 40, 4100),                                               # K split over blocks, ragged last range
+    (2, 3, 130816), (2, 3, 130818),                                              # the longest K it takes; just beyond
+    (16, 5000, 64), (3, 70001, 2),                                               # many column blocks
+    (32, 4608, 256), (32, 4609, 256),                                            # either side of its work limit
+]
+
+
+@pytest.mark.parametrize("route", ["plain", "acc"])
+@pytest.mark.parametrize("M,N,K", FEW_ROWS_SHAPES)
+def test_matmul_few_rows(cg, ro, wl, M, N, K, route):
+    say(f"cg_share_matmul few rows M={M} N={N} K={K} route={route}")
+    ops = (wl.draw_ring((M, K), 91), wl.draw_ring((M, K), 92), wl.draw_ring((N, K), 93), wl.draw_ring((N, K), 94))
+    dev = [cg.to_device(a) for a in ops]
+    want = ro.party_matmul(*ops)
+    if route == "plain":
+        got = cg.cg_share_matmul(*dev)
+    else:
+        base = wl.draw_ring((M, N), 95)
+        got = cg.to_device(base)
+        cg.cg_share_matmul_acc(*dev, got)
+        with np.errstate(over="ignore"):
+            want = want + base
+    torch.cuda.synchronize()
+    assert not first_mismatch(cg.to_host(got), want), first_mismatch(cg.to_host(got), want)
+
+
+@pytest.mark.parametrize("word", [0x8080808080808080, 0xFFFFFFFFFFFFFFFF, 0x7F7F7F7F7F7F7F7F, 0x80FF7F0080FF7F00])
+def test_matmul_few_rows_worst_case_digits_over_the_longest_wave_range(cg, ro, word):
+    """Every digit product at its extreme through as many slices as one wave ever accumulates before its fold."""
+    M, N, K = 16, 4096, 130816      # 256 blocks of z: K is not split, each of a block's 8 waves takes 511 slices
+    say(f"cg_share_matmul few rows constant word 0x{word:016x} M={M} N={N} K={K}")
+    x = torch.full((M, K), word - (1 << 64) if word >> 63 else word, dtype=torch.int64, device="cuda")
+    y = torch.full((N, K), word - (1 << 64) if word >> 63 else word, dtype=torch.int64, device="cuda")
+    got = cg.cg_share_matmul(x, x, y, y)
+    torch.cuda.synchronize()
+    assert np.all(cg.to_host(got) == np.uint64((3 * K * word * word) % (1 << 64)))
+
+
 @pytest.mark.parametrize("shape", [(3, 2, (1 << 20) + (1 << 17) + 6),      # even K, one ragged tile
                                    (5, 70, (1 << 20) + 33),                # odd K, two column tiles
                                    (130, 3, (1 << 20) + 2)])               # two row tiles: row offsets beyond 2^31 bytes
