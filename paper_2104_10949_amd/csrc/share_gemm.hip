@@ -1338,12 +1338,25 @@ static int choose_ksplit(int64_t tiles, int nk) {
 // minimises the bytes wins (ties go to the smaller group, which keeps the tiles that
 // run at the same time closer together).  For a convolution the left tensor is the
 // image, not the (kh*kw times larger) patch matrix: the taps of a tile hit in L2.
-static int choose_group_m(const GemmParams& p, int64_t tiles_m, int64_t tiles_n, int ksplit) {
+//
+// Two row-major matrices (matmul, either route) do not follow the byte count: measured on products of 1024 to
+// 16384 rows and columns, K = 1024 .. 8192, the best group is 2 tile-rows when the left operand has 32 tile-rows
+// or more and 4 below that, whatever the byte count prefers (8 and 16 for 4096^3 and 8192 x 8192 x 2048, which
+// run 3 % and 10 % slower that way: the left operand's slices are requested one step ahead of their use, the
+// right operand's two, so a miss on the left operand is the one that stalls a block, and a low group lets sixteen
+// blocks of an XCD share each slice of it).  When a block walks through whole tiles (`whole_tiles`), tall
+// products (four times as many tile-rows as tile columns) run best with the highest group, the others with 2.
+static int choose_group_m(const GemmParams& p, int64_t tiles_m, int64_t tiles_n, int ksplit, bool matrix_pair,
+                          bool whole_tiles) {
     const double a_row = (double)p.x_elems / (double)tiles_m, b_col = (double)p.w_elems / (double)tiles_n;
     const int64_t nb = tiles_m * tiles_n;
     int64_t run = nb * ksplit / 8;
     if (run < 1) run = 1;
     if (run >= nb) return tiles_n >= 8 ? 4 : (tiles_n >= 2 ? 8 : 32);  // whole splits per XCD: shape is irrelevant
+    if (matrix_pair) {
+        if (whole_tiles) return tiles_m >= 4 * tiles_n ? 32 : 2;
+        return tiles_m >= 32 ? 2 : 4;
+    }
     int best = 1;
     double best_cost = -1;
     for (int64_t g = 1; g <= tiles_m; g *= 2) {
@@ -1469,7 +1482,11 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
         q.stream_per = (nk + q.ksplit - 1) / q.ksplit;
         grid = (unsigned)((units + q.stream_per - 1) / q.stream_per);
     }
-    q.group_m = choose_group_m(p, tiles_m, tiles_n, q.stream_per > 0 ? 1 : q.ksplit);
+    constexpr bool MATRIX_PAIR =
+        (AMODE == A_LINEAR_VEC || AMODE == A_LINEAR_SCALAR || AMODE == A_LINEAR_WIDE || AMODE == A_PLANES) &&
+        (BMODE == B_VEC || BMODE == B_SCALAR || BMODE == B_WIDE || BMODE == B_PLANES);
+    q.group_m = choose_group_m(p, tiles_m, tiles_n, q.stream_per > 0 ? 1 : q.ksplit, MATRIX_PAIR,
+                               q.stream_per > 0 && q.ksplit == 1);
     if (q.ksplit > 1)
         if (hipError_t e = launch_zero_fill(q, stream)) return e;
     if constexpr (CanStream<AMODE, BMODE>::value) {
