@@ -121,7 +121,9 @@ CG_API cg_status cg_share_matmul_t(const uint64_t *x_i, const uint64_t *x_ip1,
  * kernel; the product kernel then only moves bytes.  Result and argument rules
  * are those of cg_share_matmul, bit for bit.  The scratch contents are
  * undefined afterwards and carry no state between calls.  When the digit route
- * does not apply (odd K, or a pointer that is only 8-byte aligned) the call
+ * does not apply (odd K, a pointer that is only 8-byte aligned, K above 2^20,
+ * or a left operand of so few rows, at most 64, that the plain call's kernel for
+ * such products is the faster one) the call
  * computes exactly as cg_share_matmul and does not touch the scratch memory;
  * cg_share_matmul_workspace_bytes then returns 0 (as it does for invalid sizes).
  * CG_ERR_WORKSPACE if workspace_bytes is too small, CG_ERR_NULL / CG_ERR_ALIGN /

@@ -664,7 +664,9 @@ cg_status plan_matmul(const uint64_t* x_i, const uint64_t* x_ip1, const uint64_t
         if (!trans_x) pl.amode = cg::A_LINEAR_WIDE;
         if (!trans_y) pl.bmode = cg::B_WIDE;
     }
-    pl.planes_ok = vec && !trans_x && !trans_y && !long_rows;
+    // (a product of few rows is a few microseconds on the kernel of its own: converting its operands first would
+    // cost more than the product)
+    pl.planes_ok = vec && !trans_x && !trans_y && !long_rows && !cg::share_gemm_small_applies(p);
     pl.planes_conv = false;
     pl.x_rows = M; pl.x_k = K;
     pl.xp_bytes = cg::planes_bytes(M, K); pl.wp_bytes = cg::planes_bytes(N, K);

@@ -97,13 +97,14 @@ def test_workspace_entry_points_validate_like_the_plain_ones(L):
     f = L.cg_share_matmul_ws
     assert f(0, *big[1:], 4, 4, 4, ws, 1 << 20, None) == b.CG_ERR_NULL
     assert f(*big, 4, 0, 4, ws, 1 << 20, None) == b.CG_ERR_SHAPE
-    assert f(*big, 64, 64, 64, 0, 1 << 20, None) == b.CG_ERR_NULL            # digit route needs scratch memory
-    assert f(*big, 64, 64, 64, ws + 8, 1 << 20, None) == b.CG_ERR_ALIGN
-    need = L.cg_share_matmul_workspace_bytes(64, 64, 64)
-    assert need == 4 * 64 * 2 * 256
-    assert f(*big, 64, 64, 64, ws, need - 1, None) == b.CG_ERR_WORKSPACE
-    assert f(*big, 64, 64, 64, big[0] + 256, need, None) == b.CG_ERR_ALIAS   # scratch inside x_i
-    assert L.cg_share_matmul_workspace_bytes(64, 64, 65) == 0                # odd K: no digit route
+    assert f(*big, 128, 64, 64, 0, 1 << 20, None) == b.CG_ERR_NULL            # digit route needs scratch memory
+    assert f(*big, 128, 64, 64, ws + 8, 1 << 20, None) == b.CG_ERR_ALIGN
+    need = L.cg_share_matmul_workspace_bytes(128, 64, 64)
+    assert need == (2 * 128 + 2 * 64) * 2 * 256
+    assert f(*big, 128, 64, 64, ws, need - 1, None) == b.CG_ERR_WORKSPACE
+    assert f(*big, 128, 64, 64, big[0] + 256, need, None) == b.CG_ERR_ALIAS   # scratch inside x_i
+    assert L.cg_share_matmul_workspace_bytes(128, 64, 65) == 0               # odd K: no digit route
+    assert L.cg_share_matmul_workspace_bytes(64, 64, 64) == 0                # few rows: computes as the plain call
     assert L.cg_share_matmul_workspace_bytes(-1, 64, 64) == 0
     d = b.ConvDesc(2, 8, 8, 32, 16, 3, 3, 1, 1, 1, 1)
     need = L.cg_share_conv2d_workspace_bytes(ctypes.byref(d))

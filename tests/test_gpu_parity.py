@@ -343,12 +343,13 @@ def test_conv_input_larger_than_2_gib(cg, ro, wl):
 
 def test_workspace_errors(cg):
     say("workspace argument errors")
-    x = torch.zeros((64, 64), dtype=torch.int64, device="cuda")
+    x = torch.zeros((128, 64), dtype=torch.int64, device="cuda")
     y = torch.zeros((64, 64), dtype=torch.int64, device="cuda")
-    need = cg.cg_share_matmul_workspace_bytes(64, 64, 64)
-    assert need == 4 * 64 * 2 * 256
-    assert cg.cg_share_matmul_workspace_bytes(64, 64, 63) == 0      # odd K: direct route only
+    need = cg.cg_share_matmul_workspace_bytes(128, 64, 64)
+    assert need == (2 * 128 + 2 * 64) * 2 * 256
+    assert cg.cg_share_matmul_workspace_bytes(128, 64, 63) == 0     # odd K: direct route only
     assert cg.cg_share_matmul_workspace_bytes(0, 64, 64) == 0
+    assert cg.cg_share_matmul_workspace_bytes(64, 64, 64) == 0      # few rows: the plain call's kernel is the fast one
     small = torch.zeros(need // 8 - 1, dtype=torch.int64, device="cuda")
     with pytest.raises(cg.CgError) as e:
         cg.cg_share_matmul_ws(x, x, y, y, small)
