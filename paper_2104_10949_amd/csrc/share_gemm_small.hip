@@ -69,8 +69,9 @@ __device__ __forceinline__ u4 add64x2(u4 a, u4 b) {
 // instruction wants lane (r, g) to hold words of row r only, so the raw words cross a wave-private LDS
 // buffer: four regions (x_a, x_b, w_a + w_b, w_a) of 16 rows x 256 bytes.  Loads and LDS writes run with sixteen
 // lanes along the sixteen 16-byte pieces of a row's slice (four rows per instruction); the read-back has lane
-// (r, g) take the eight pieces of half g & 1 of row r in region g >> 1.  Piece p of row r sits at piece p ^ r:
-// both patterns are then free of bank conflicts.  No barrier is involved: a wave reads what it wrote itself.
+// (r, g) take the eight pieces of half g & 1 of row r in region g >> 1.  Piece p of row r sits at piece p ^ r, so
+// that neither the sixteen pieces of a row nor one piece of sixteen rows fall on the same banks.  No barrier is
+// involved: a wave reads what it wrote itself.
 __global__ __launch_bounds__(SMALL_WAVES * 64) void share_gemm_small_kernel(const GemmParams p) {
     __shared__ __attribute__((aligned(16))) char stage[SMALL_WAVES][4][16 * 256];
     __shared__ unsigned long long red[256];
