@@ -53,15 +53,17 @@ def test_config_every_layer_bit_exact(env, cfg):
         check_layer(cg, ro, wl, cfg, li, L)
 
 
-def test_config4_backward_products_every_layer_bit_exact(env):
-    """Input and weight gradients of every convolution layer of the VGG16-shaped configuration at full size (the
-    shapes bench.py --extras times), one party, every element against the oracle."""
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_config_backward_products_every_layer_bit_exact(env, cfg):
+    """Input and weight gradients of every convolution layer of the VGG16-shaped and the ResNet-50-shaped
+    configuration at full size (the shapes bench.py --extras times; the second brings the strided 3x3 layers, the
+    strided 1x1 projections and the 7x7 stem), one party, every element against the oracle."""
     cg, ro, wl = env
-    for li, L in enumerate(wl.config_layers(4)):
+    for li, L in enumerate(wl.config_layers(cfg)):
         if L.kind != "conv":
             continue
-        say(f"config 4 backward, layer {li} {L.name}")
-        seed = wl.layer_seed(4, li) + 500
+        say(f"config {cfg} backward, layer {li} {L.name}")
+        seed = wl.layer_seed(cfg, li) + 500
         g = [wl.draw_ring(L.z_shape, seed), wl.draw_ring(L.z_shape, seed + 1)]
         w = [wl.draw_ring(L.w_shape, seed + 2), wl.draw_ring(L.w_shape, seed + 3)]
         x = [wl.draw_ring(L.x_shape, seed + 4), wl.draw_ring(L.x_shape, seed + 5)]
