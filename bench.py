@@ -119,6 +119,19 @@ def measure_rows(torch, cg, wl, headline_config):
                      "frac_of_peak": round(ops_per / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4),
                      "cg_share_matmul_ws_ms": round(ms_ws, 4),
                      "ws_frac_of_peak": round(ops_per / (ms_ws * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4)})
+        if (M, N, K) == (4096, 4096, 4096):
+            # the same launches on all-zero shares: control flow and memory traffic do not depend on the data,
+            # the power the matrix cores draw does (share words are uniformly random, the worst case), so the gap
+            # to the rows above is what the chip's power limit costs and these are what the schedule itself reaches
+            for t in ops:
+                t.zero_()
+            ms0 = _timed(torch, lambda: cg.cg_share_matmul(*ops, z_i=z), warm=2, iters=8)
+            ms0_ws = _timed(torch, lambda: cg.cg_share_matmul_ws(*ops, ws, z_i=z), warm=2, iters=8)
+            rows[-1]["all_zero_operands"] = {
+                "cg_share_matmul_ms": round(ms0, 4),
+                "frac_of_peak": round(ops_per / (ms0 * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4),
+                "cg_share_matmul_ws_ms": round(ms0_ws, 4),
+                "ws_frac_of_peak": round(ops_per / (ms0_ws * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4)}
         del ops, z, ws
     out["largest_gemm_shapes"] = rows
     # ---- the other convolution configurations: one step = all their layers, same method as the headline step
