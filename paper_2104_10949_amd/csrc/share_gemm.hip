@@ -140,14 +140,9 @@ struct LinearVec {
     __device__ __forceinline__ void load(const GemmParams&, __amdgpu_buffer_rsrc_t r, int ks, u32 K,
                                          u4 out[2]) const {
         const u32 off = off0 + 256u * ks;
-        if (32u * ks + 32u <= K) {  // uniform: whole slice inside K
-            out[0] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
-            out[1] = __builtin_amdgcn_raw_buffer_load_b128(r, off + 64u, 0, 0);
-        } else {
-            const u32 k = 32u * ks + kq;
-            out[0] = __builtin_amdgcn_raw_buffer_load_b128(r, k < K ? off : OOB, 0, 0);
-            out[1] = __builtin_amdgcn_raw_buffer_load_b128(r, k + 8u < K ? off + 64u : OOB, 0, 0);
-        }
+        const u32 k = 32u * ks + kq;
+        out[0] = __builtin_amdgcn_raw_buffer_load_b128(r, k < K ? off : OOB, 0, 0);
+        out[1] = __builtin_amdgcn_raw_buffer_load_b128(r, k + 8u < K ? off + 64u : OOB, 0, 0);
     }
 };
 
@@ -266,13 +261,25 @@ struct PatchRow {
 // increments.
 struct TapCursor {
     int ks, r, s, c0;   // the cursor proper; everything else is derived on use, to keep few values alive
-    __device__ __forceinline__ void reset() { ks = 0; r = 0; s = 0; c0 = 0; }
+    // put the cursor on slice `at` (once per tile: two divisions)
+    __device__ __forceinline__ void set(const GemmParams& p, int at) {
+        const int taps = p.kh * p.kw;
+        const int cb = at / taps, t = at - cb * taps;
+        ks = at; c0 = 32 * cb; r = t / p.kw; s = t - r * p.kw;
+    }
+    // `want` is the cursor's slice or the next one (the loaders move one slice at a time).  Written as selects:
+    // branches here end up inside the K loop, where each costs the wave an instruction-fetch bubble and the
+    // compiler a conservative wait at the join.
     __device__ __forceinline__ void advance_to(const GemmParams& p, int want) {
-        while (ks < want) {  // zero or one step per call in the kernel's load order
-            ++ks;
-            if (++s == p.kw) { s = 0; ++r; }
-            if (r == p.kh) { r = 0; c0 += 32; }  // past the end of K: c0 == Cin
-        }
+        const int d = want - ks;   // 0 or 1
+        ks = want;
+        s += d;
+        const bool row_done = s == p.kw;
+        s = row_done ? 0 : s;
+        r += row_done ? 1 : 0;
+        const bool block_done = r == p.kh;
+        r = block_done ? 0 : r;
+        c0 += block_done ? 32 : 0;   // past the end of K: c0 >= Cin
     }
     __device__ __forceinline__ int tap(const GemmParams& p) const { return r * p.kw + s; }
     // slice index in the filter's own (tap, channel) order
@@ -304,7 +311,7 @@ struct ConvC32 {
     }
     __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, const TapCursor& t,
                                          u4 out[2]) const {
-        const bool v = t.c0 < p.Cin && ((inside >> t.tap(p)) & 1);
+        const bool v = (t.c0 < p.Cin) & (((inside >> t.tap(p)) & 1) != 0);   // (no short circuit: no branch)
         const u32 off = v ? base_kq + t.off(p) : OOB;
         out[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off, 0, 0);
         out[1] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off + 64u, 0, 0);
@@ -497,7 +504,7 @@ struct PlanesPatch {
     }
     // byte offset of piece cq of the slice the cursor points at, or OOB
     __device__ __forceinline__ u32 offset(const GemmParams& p, const TapCursor& t) const {
-        const bool v = t.c0 < p.Cin && ((inside >> t.tap(p)) & 1);
+        const bool v = (t.c0 < p.Cin) & (((inside >> t.tap(p)) & 1) != 0);   // (no short circuit: no branch)
         const u32 pix = pix0 + (u32)t.r * (u32)p.W + (u32)t.s;
         const u32 KS = (u32)p.Cin >> 5;
         return v ? ((pix >> 4) * KS + ((u32)t.c0 >> 5)) * 4096u + cq256 + (pix & 15u) * 16u : OOB;
@@ -778,7 +785,7 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
                 base = (((u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)(p.H * p.W)) >> 4) * KS * 4096u;
                 pa_patch.init(p, m0, tid_s % T::BM, rows_m, tid_s / T::BM);
             }
-            tap_a.reset();
+            tap_a.set(p, wa_.ks);
             const u64 left = p.xp_bytes - base;
             const u32 bytes = left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left;
             rs_xa = make_rsrc(p.xp_a + base, bytes);
@@ -789,7 +796,7 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
         else if (A_TR) a_base_elems = (u64)m0;
         else if (AMODE == A_PATCH_T) a_base_elems = 0;
         else a_base_elems = (u64)((u32)m0 / (u32)(p.Ho * p.Wo)) * (u64)p.img_elems;
-        tap_a.reset();
+        tap_a.set(p, wa_.ks);
         rs_xa = view(p.x_a, p.x_elems, a_base_elems);
         rs_xb = view(p.x_b, p.x_elems, a_base_elems);
 #pragma unroll
@@ -824,7 +831,7 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
             const u32 KS = (u32)(p.K + 31) >> 5;
             const u64 base = (u64)(n0 >> 4) * KS * 4096u;
             pb_row.init(tid_s % T::BN, rows_n, KS, tid_s / T::BN);
-            tap_b.reset();
+            tap_b.set(p, wb_.ks);
             const u64 left = p.wp_bytes - base;
             const u32 bytes = left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left;
             rs_wa = make_rsrc(p.wp_a + base, bytes);
@@ -832,7 +839,7 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
             return;
         }
         b_base_elems = BMODE == B_PATCH_T ? 0 : (B_TR ? (u64)n0 : (u64)n0 * (u64)p.K);
-        tap_b.reset();
+        tap_b.set(p, wb_.ks);
         rs_wa = view(p.w_a, w_elems, b_base_elems);
         rs_wb = view(p.w_b, w_elems, b_base_elems);
 #pragma unroll
