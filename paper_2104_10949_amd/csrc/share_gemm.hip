@@ -312,7 +312,9 @@ struct ConvC32 {
     __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, const TapCursor& t,
                                          u4 out[2]) const {
         const bool v = (t.c0 < p.Cin) & (((inside >> t.tap(p)) & 1) != 0);   // (no short circuit: no branch)
-        const u32 off = v ? base_kq + t.off(p) : OOB;
+        u32 in_off = base_kq + t.off(p);
+        asm volatile("" : "+v"(in_off));   // computed by every lane, then selected: no masked-off region in the K loop
+        const u32 off = v ? in_off : OOB;
         out[0] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off, 0, 0);
         out[1] = __builtin_amdgcn_raw_buffer_load_b128(rs_, off + 64u, 0, 0);
     }
@@ -507,7 +509,9 @@ struct PlanesPatch {
         const bool v = (t.c0 < p.Cin) & (((inside >> t.tap(p)) & 1) != 0);   // (no short circuit: no branch)
         const u32 pix = pix0 + (u32)t.r * (u32)p.W + (u32)t.s;
         const u32 KS = (u32)p.Cin >> 5;
-        return v ? ((pix >> 4) * KS + ((u32)t.c0 >> 5)) * 4096u + cq256 + (pix & 15u) * 16u : OOB;
+        u32 in_off = ((pix >> 4) * KS + ((u32)t.c0 >> 5)) * 4096u + cq256 + (pix & 15u) * 16u;
+        asm volatile("" : "+v"(in_off));   // computed by every lane, then selected: no masked-off region in the K loop
+        return v ? in_off : OOB;
     }
 };
 
@@ -755,6 +759,15 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
         const u64 left = (elems_total - base) * 8u;
         return make_rsrc(ptr + base, left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left);
     };
+    // the same, or an empty view (every offset out of range) when `base` lies past the operand or `ok` is false;
+    // written as selects on pointer and size: the views of transposed operands are rebuilt in the K loop, where a
+    // branch costs the wave an instruction-fetch bubble
+    auto view_if = [&](const u64* ptr, u64 elems_total, u64 base, bool ok) {
+        const bool in = ok & (base < elems_total);
+        const u64 b = in ? base : 0;
+        const u64 left = in ? (elems_total - b) * 8u : 0;
+        return make_rsrc(ptr + b, left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)left);
+    };
 
     // ---- loader of the left operand: walker, views rebased per tile so that 32-bit offsets suffice,
     // address generators, tap cursor of the patch gather
@@ -880,10 +893,10 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
     auto a_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
         if constexpr (A_TR) {
             const u64 base = a_base_elems + (u64)ks * 32u * (u64)p.M;
-            return base < p.x_elems ? view(ptr, p.x_elems, base) : make_rsrc(ptr, 0);
+            return view_if(ptr, p.x_elems, base, true);
         } else if constexpr (AMODE == A_PATCH_T) {
             const u64 base = (u64)fast_div(32u * (u32)ks, p.div_howo) * p.img_elems;
-            return base < p.x_elems ? view(ptr, p.x_elems, base) : make_rsrc(ptr, 0);
+            return view_if(ptr, p.x_elems, base, true);
         } else {
             return fixed;
         }
@@ -892,15 +905,14 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
     auto b_view = [&](const u64* ptr, __amdgpu_buffer_rsrc_t fixed, int ks) {
         if constexpr (BMODE == B_TRANS) {
             const u64 base = b_base_elems + (u64)ks * 32u * (u64)p.N;
-            return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
+            return view_if(ptr, w_elems, base, true);
         } else if constexpr (BMODE == B_FLIP_C32) {
-            if (tap_b.c0 >= p.Cin) return make_rsrc(ptr, 0);  // past the end of K
             const int ftap = (p.flt_r0 + p.flt_sh * (p.kh - 1 - tap_b.r)) * p.flt_kw + p.flt_s0 + p.flt_sw * (p.kw - 1 - tap_b.s);
             const u64 base = b_base_elems + ((u64)tap_b.c0 * (u64)(p.flt_kh * p.flt_kw) + (u64)ftap) * (u64)p.N;
-            return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
+            return view_if(ptr, w_elems, base, tap_b.c0 < p.Cin);   // (c0 >= Cin: past the end of K)
         } else if constexpr (BMODE == B_PATCH_T) {
             const u64 base = (u64)fast_div(32u * (u32)ks, p.div_howo) * p.img_elems;
-            return base < w_elems ? view(ptr, w_elems, base) : make_rsrc(ptr, 0);
+            return view_if(ptr, w_elems, base, true);
         } else {
             return fixed;
         }
