@@ -597,6 +597,12 @@ def main() -> int:
                             "frac": round(2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * L.mnk / (ms * 1e-3) / 1e12
                                           / INT8_PEAK_TOPS, 4)}
                            for L, ms in zip(layers, per_layer_ms) if L.mnk == layers[big].mnk],
+        # the same layers as one figure: their int8 ops over their summed time
+        "largest_layers_together": (lambda ties: {
+            "layers": len(ties), "ms": round(sum(ms for _, ms in ties), 5),
+            "frac": round(sum(2.0 * DIGIT_MACS_PER_RING_MAC_TRIPLE * L.mnk for L, _ in ties)
+                          / (sum(ms for _, ms in ties) * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4)})(
+            [(L, ms) for L, ms in zip(layers, per_layer_ms) if L.mnk == layers[big].mnk]),
         "traffic": PROFILED_TRAFFIC_CONFIG4 if args.config == WORKLOAD_CONFIG else None,
     }
     # Per layer: measured time against t_roof = max(int8 ops / peak, algorithmic bytes / HBM peak) and the larger term.
