@@ -693,7 +693,15 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
     __shared__ __attribute__((aligned(16))) char lds[T::LDS_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % T::WM, wn = wave / T::WM;
+    // The streamed instantiation needs the thread id again whenever it enters a tile, i.e. across the K loop, whose
+    // registers are all taken: the wave's number waits in a scalar register and the lane is counted anew (a
+    // thread id kept in a vector register was spilled, and its reload at the top of every step came with a wait
+    // for ALL outstanding loads).
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto thread_id_again = [&]() {
+        return wave_u * 64 + (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    };
+    const int wm = wave_u % T::WM, wn = wave_u / T::WM;   // uniform over the wave: scalar registers
     const int r16 = lane & 15, kg = lane >> 4;
 
     // ---- this block's range [u0, u_end) of (tile, slice) units
@@ -784,7 +792,10 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
         // (the thread id passes through an empty asm so that nothing below is computed ahead of the K loop and
         // kept in registers across it: a new tile is entered rarely, the registers are needed all the time)
         int tid_s = tid;
-        if constexpr (STREAM) asm volatile("" : "+v"(tid_s));
+        if constexpr (STREAM) {
+            tid_s = thread_id_again();
+            asm volatile("" : "+v"(tid_s));
+        }
         int tm, tn;
         logical_to_tile(p, tiles_m, tiles_n, wa_.logical, tm, tn);
         const int m0 = tm * T::BM, rows_m = p.M - m0;
@@ -836,7 +847,10 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
     const int b_dst0 = PLANES ? (tid % T::BN) * 16 + (tid / T::BN) * T::B_DIG : unit_dst(tid, T::BN, B_TR);
     auto setup_b = [&]() {
         int tid_s = tid;
-        if constexpr (STREAM) asm volatile("" : "+v"(tid_s));
+        if constexpr (STREAM) {
+            tid_s = thread_id_again();
+            asm volatile("" : "+v"(tid_s));
+        }
         int tm, tn;
         logical_to_tile(p, tiles_m, tiles_n, wb_.logical, tm, tn);
         const int n0 = tn * T::BN, rows_n = p.N - n0;
@@ -1219,7 +1233,8 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
                 step(par, std::false_type{});
                 par ^= 1;
             }
-            fold_blocks<BMODE == B_FLIP_C32, AMODE == A_PATCH_T>(p, acc, fm0, fn0, lane, ks0 > wc.ks || p.z_add != 0);
+            fold_blocks<BMODE == B_FLIP_C32, AMODE == A_PATCH_T>(p, acc, fm0, fn0, STREAM ? thread_id_again() & 63 : lane,
+                                                                 ks0 > wc.ks || p.z_add != 0);
         }
         if (!STREAM || wc.u >= u_end) break;
     }
