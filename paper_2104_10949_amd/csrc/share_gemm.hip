@@ -577,6 +577,8 @@ __device__ __forceinline__ void fold_blocks(const GemmParams& p, v4i (&acc)[2][2
     int lane_f = lane;
     asm volatile("" : "+v"(lane_f));
     const int c16 = lane_f & 15, g4 = lane_f >> 4;
+    int w8 = 1 << 8, w16 = 1 << 16, w24 = 1 << 24;
+    asm volatile("" : "+s"(w8), "+s"(w16), "+s"(w24));
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -585,13 +587,15 @@ __device__ __forceinline__ void fold_blocks(const GemmParams& p, v4i (&acc)[2][2
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int row = row0 + rb * 16 + 4 * g4 + i;
-                u64 v = (u64)(int64_t)acc[rb][cb][0][i];
-                v += (u64)(int64_t)acc[rb][cb][1][i] << 8;
-                v += (u64)(int64_t)acc[rb][cb][2][i] << 16;
-                v += (u64)(int64_t)acc[rb][cb][3][i] << 24;
+                // three signed 32 x 32 -> 64 multiply-adds (the weights 2^8, 2^16, 2^24 sit in scalar registers the
+                // compiler cannot see through: as shifts this is seven 64-bit shifts and adds per element)
+                int64_t lo = (int64_t)acc[rb][cb][0][i];
+                lo += (int64_t)acc[rb][cb][1][i] * (int64_t)w8;
+                lo += (int64_t)acc[rb][cb][2][i] * (int64_t)w16;
+                lo += (int64_t)acc[rb][cb][3][i] * (int64_t)w24;
                 const u32 hi = (u32)acc[rb][cb][4][i] + ((u32)acc[rb][cb][5][i] << 8) +
                                ((u32)acc[rb][cb][6][i] << 16) + ((u32)acc[rb][cb][7][i] << 24);
-                v += (u64)hi << 32;
+                u64 v = (u64)lo + ((u64)hi << 32);
                 if (row < p.M && col < p.N) {
                     u64 zrow = (u64)row;
                     if constexpr (REMAP) {
