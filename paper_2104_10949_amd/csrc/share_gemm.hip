@@ -579,42 +579,50 @@ __device__ __forceinline__ void fold_blocks(const GemmParams& p, v4i (&acc)[2][2
     const int c16 = lane_f & 15, g4 = lane_f >> 4;
     int w8 = 1 << 8, w16 = 1 << 16, w24 = 1 << 24;
     asm volatile("" : "+s"(w8), "+s"(w16), "+s"(w24));
+    // MODE 0: plain store, 1: read-add-write, 2: atomic add.  The mode is uniform over the launch: one copy of the
+    // element loop per mode instead of two branches per element.
+    auto all_elements = [&](auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            const int col = col0 + cb * 16 + c16;
+            for (int cb = 0; cb < 2; ++cb) {
+                const int col = col0 + cb * 16 + c16;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = row0 + rb * 16 + 4 * g4 + i;
-                // three signed 32 x 32 -> 64 multiply-adds (the weights 2^8, 2^16, 2^24 sit in scalar registers the
-                // compiler cannot see through: as shifts this is seven 64-bit shifts and adds per element)
-                int64_t lo = (int64_t)acc[rb][cb][0][i];
-                lo += (int64_t)acc[rb][cb][1][i] * (int64_t)w8;
-                lo += (int64_t)acc[rb][cb][2][i] * (int64_t)w16;
-                lo += (int64_t)acc[rb][cb][3][i] * (int64_t)w24;
-                const u32 hi = (u32)acc[rb][cb][4][i] + ((u32)acc[rb][cb][5][i] << 8) +
-                               ((u32)acc[rb][cb][6][i] << 16) + ((u32)acc[rb][cb][7][i] << 24);
-                u64 v = (u64)lo + ((u64)hi << 32);
-                if (row < p.M && col < p.N) {
-                    u64 zrow = (u64)row;
-                    if constexpr (REMAP) {
-                        const u32 b = fast_div((u32)row, p.div_howo);
-                        const u32 rem = (u32)row - b * (u32)(p.Ho * p.Wo);
-                        const u32 i_ = fast_div(rem, p.div_wo), j_ = rem - i_ * (u32)p.Wo;
-                        zrow = ((u64)b * (u64)p.out_H + (u64)(p.out_h0 + p.out_sh * (int)i_)) * (u64)p.out_W +
-                               (u64)(p.out_w0 + p.out_sw * (int)j_);
-                    }
-                    u64* dst = ZT ? p.z + (u64)col * (u64)p.M + zrow : p.z + zrow * (u64)p.N + (u64)col;
-                    if (p.ksplit > 1) {
-                        atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
-                    } else {
-                        if (accumulate) v += *dst;
-                        *dst = v;
+                for (int i = 0; i < 4; ++i) {
+                    const int row = row0 + rb * 16 + 4 * g4 + i;
+                    // three signed 32 x 32 -> 64 multiply-adds (the weights 2^8, 2^16, 2^24 sit in scalar registers
+                    // the compiler cannot see through: as shifts this is seven 64-bit shifts and adds per element)
+                    int64_t lo = (int64_t)acc[rb][cb][0][i];
+                    lo += (int64_t)acc[rb][cb][1][i] * (int64_t)w8;
+                    lo += (int64_t)acc[rb][cb][2][i] * (int64_t)w16;
+                    lo += (int64_t)acc[rb][cb][3][i] * (int64_t)w24;
+                    const u32 hi = (u32)acc[rb][cb][4][i] + ((u32)acc[rb][cb][5][i] << 8) +
+                                   ((u32)acc[rb][cb][6][i] << 16) + ((u32)acc[rb][cb][7][i] << 24);
+                    u64 v = (u64)lo + ((u64)hi << 32);
+                    if (row < p.M && col < p.N) {
+                        u64 zrow = (u64)row;
+                        if constexpr (REMAP) {
+                            const u32 b = fast_div((u32)row, p.div_howo);
+                            const u32 rem = (u32)row - b * (u32)(p.Ho * p.Wo);
+                            const u32 i_ = fast_div(rem, p.div_wo), j_ = rem - i_ * (u32)p.Wo;
+                            zrow = ((u64)b * (u64)p.out_H + (u64)(p.out_h0 + p.out_sh * (int)i_)) * (u64)p.out_W +
+                                   (u64)(p.out_w0 + p.out_sw * (int)j_);
+                        }
+                        u64* dst = ZT ? p.z + (u64)col * (u64)p.M + zrow : p.z + zrow * (u64)p.N + (u64)col;
+                        if constexpr (MODE == 2) {
+                            atomicAdd(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)v);
+                        } else {
+                            if constexpr (MODE == 1) v += *dst;
+                            *dst = v;
+                        }
                     }
                 }
             }
-        }
+    };
+    if (p.ksplit > 1) all_elements(std::integral_constant<int, 2>{});
+    else if (accumulate) all_elements(std::integral_constant<int, 1>{});
+    else all_elements(std::integral_constant<int, 0>{});
 }
 
 // The digit pairs (l, m), l + m <= 7, of one step in issue order, in two phases.
