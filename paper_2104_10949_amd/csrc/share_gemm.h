@@ -90,6 +90,15 @@ struct GemmParams {
     int group_m;                // tile-rows per launch-order group (set by the launcher)
     int ksplit;                 // number of K ranges the grid is replicated over (set by the launcher)
     int64_t stream_per;         // > 0: (tile, slice) units per block of the streamed distribution (set by the launcher)
+    // Divisors of the block's index arithmetic as multiply-shift pairs (set by the launcher from the tile shape
+    // and the fields above): a block's first load waits for this arithmetic, and a division by a value known
+    // only at run time is some thirty dependent instructions.
+    FastDiv div_tiles;          // tiles of the launch (classic distribution: block -> (split, tile))
+    int per_split;              // slices per K range of the classic distribution
+    FastDiv div_per_group;      // group_m * tile columns
+    FastDiv div_group, div_last_group;   // tile-rows of a full group / of the last, shorter one (or of a full one)
+    FastDiv div_taps, div_tap_kw;        // kh * kw and kw, for the tap cursor
+    FastDiv div_row_howo, div_row_wo;    // Ho * Wo and Wo, for the pixel of an output row
 };
 
 // Largest block-tile height any instantiation uses; the host checks 32-bit

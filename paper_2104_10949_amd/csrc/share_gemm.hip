@@ -239,9 +239,9 @@ struct PatchRow {
         ok = row_local < rows_left;
         const u32 m = (u32)(m0 + (ok ? row_local : 0));
         const u32 HoWo = (u32)(p.Ho * p.Wo);
-        const u32 b = m / HoWo, b0 = (u32)m0 / HoWo;
+        const u32 b = fast_div(m, p.div_row_howo), b0 = fast_div((u32)m0, p.div_row_howo);
         const u32 rem = m - b * HoWo;
-        const u32 ho = rem / (u32)p.Wo, wo = rem - ho * (u32)p.Wo;
+        const u32 ho = fast_div(rem, p.div_row_wo), wo = rem - ho * (u32)p.Wo;
         hi0 = (int)ho * p.sh - p.ph;
         wi0 = (int)wo * p.sw - p.pw;
         base = (b - b0) * (u32)p.H * (u32)p.W * (u32)p.Cin * 8u +
@@ -261,11 +261,11 @@ struct PatchRow {
 // increments.
 struct TapCursor {
     int ks, r, s, c0;   // the cursor proper; everything else is derived on use, to keep few values alive
-    // put the cursor on slice `at` (once per tile: two divisions)
+    // put the cursor on slice `at` (once per tile)
     __device__ __forceinline__ void set(const GemmParams& p, int at) {
         const int taps = p.kh * p.kw;
-        const int cb = at / taps, t = at - cb * taps;
-        ks = at; c0 = 32 * cb; r = t / p.kw; s = t - r * p.kw;
+        const int cb = (int)fast_div((u32)at, p.div_taps), t = at - cb * taps;
+        ks = at; c0 = 32 * cb; r = (int)fast_div((u32)t, p.div_tap_kw); s = t - r * p.kw;
     }
     // `want` is the cursor's slice or the next one (the loaders move one slice at a time).  Written as selects:
     // branches here end up inside the K loop, where each costs the wave an instruction-fetch bubble and the
@@ -365,9 +365,9 @@ struct ConvDil {
         ok = row_local < rows_left;
         const u32 m = (u32)(m0 + (ok ? row_local : 0));
         const u32 HoWo = (u32)(p.Ho * p.Wo);
-        const u32 b = m / HoWo, b0 = (u32)m0 / HoWo;
+        const u32 b = fast_div(m, p.div_row_howo), b0 = fast_div((u32)m0, p.div_row_howo);
         const u32 rem = m - b * HoWo;
-        const u32 ho = rem / (u32)p.Wo, wo = rem - ho * (u32)p.Wo;
+        const u32 ho = fast_div(rem, p.div_row_wo), wo = rem - ho * (u32)p.Wo;
         hi0 = (int)ho * p.sh - p.ph;
         wi0 = (int)wo * p.sw - p.pw;
         img_off = (b - b0) * (u32)p.H * (u32)p.W * (u32)p.Cin * 8u;
@@ -489,9 +489,9 @@ struct PlanesPatch {
         const bool ok = row_local < rows_left;
         const u32 m = (u32)(m0 + (ok ? row_local : 0));
         const u32 HoWo = (u32)(p.Ho * p.Wo), HW = (u32)(p.H * p.W);
-        const u32 b = m / HoWo, b0 = (u32)m0 / HoWo;
+        const u32 b = fast_div(m, p.div_row_howo), b0 = fast_div((u32)m0, p.div_row_howo);
         const u32 rem = m - b * HoWo;
-        const u32 ho = rem / (u32)p.Wo, wo = rem - ho * (u32)p.Wo;
+        const u32 ho = fast_div(rem, p.div_row_wo), wo = rem - ho * (u32)p.Wo;
         const int hi0 = (int)ho * p.sh - p.ph, wi0 = (int)wo * p.sw - p.pw;
         // the view starts at the 16-pixel block that holds the first pixel of image b0
         pix0 = ((b0 * HW) & 15u) + (b - b0) * HW + (u32)hi0 * (u32)p.W + (u32)wi0;
@@ -557,11 +557,15 @@ __device__ __forceinline__ void logical_to_tile(const GemmParams& p, int tiles_m
                                                 int& tn) {
     const int GM = p.group_m;
     const int per_group = GM * tiles_n;
-    const int g = logical / per_group, in_g = logical - g * per_group;
+    const int g = (int)fast_div((u32)logical, p.div_per_group), in_g = logical - g * per_group;
     const int first = g * GM;
-    const int gsz = tiles_m - first < GM ? tiles_m - first : GM;
-    tm = first + in_g % gsz;
-    tn = in_g / gsz;
+    const bool last = tiles_m - first < GM;   // the last group may hold fewer tile-rows
+    const int gsz = last ? tiles_m - first : GM;
+    FastDiv d;
+    d.mul = last ? p.div_last_group.mul : p.div_group.mul;
+    d.shift = last ? p.div_last_group.shift : p.div_group.shift;
+    tn = (int)fast_div((u32)in_g, d);
+    tm = first + in_g - tn * gsz;
 }
 
 // fold: z (+)= sum_s sext(P_s) << 8s for the wave's 32 x 32 sub-tile, which is 2 x 2 blocks of 16 x 16; lane i
@@ -721,24 +725,32 @@ __device__ __forceinline__ void share_gemm_body(const GemmParams p) {
     const int nb = tiles_m * tiles_n;
     const int nk_all = (int)((p.K + 31) / 32);
     int64_t u0, u_end;
+    int logical0 = 0, ks0 = 0;   // classic distribution: the block's tile and first slice, known without a division
     if constexpr (STREAM) {
         const int64_t units = (int64_t)nb * nk_all;
         u0 = (int64_t)run_index((int)gridDim.x) * p.stream_per;
         u_end = u0 + p.stream_per < units ? u0 + p.stream_per : units;
     } else {
         const int run = run_index(nb * p.ksplit);
-        const int split = run / nb, logical = run - split * nb;
-        const int per_split = (nk_all + p.ksplit - 1) / p.ksplit;
+        const int split = (int)fast_div((u32)run, p.div_tiles), logical = run - split * nb;
+        const int per_split = p.per_split;
         const int kb = split * per_split;
         u0 = (int64_t)logical * nk_all + kb;
         u_end = (int64_t)logical * nk_all + (kb + per_split < nk_all ? kb + per_split : nk_all);
+        logical0 = logical;
+        ks0 = kb;
     }
     if (u0 >= u_end) return;  // uniform over the block
 
     // take the tile that starts at unit w.u: its slices [w.ks, w.nk)
     auto enter_tile = [&](Walker& w) {
-        w.logical = (int)(w.u / nk_all);
-        w.ks = (int)(w.u - (int64_t)w.logical * nk_all);
+        if constexpr (STREAM) {
+            w.logical = (int)(w.u / nk_all);
+            w.ks = (int)(w.u - (int64_t)w.logical * nk_all);
+        } else {   // one tile per block
+            w.logical = logical0;
+            w.ks = ks0;
+        }
         w.nk = (int64_t)w.ks + (u_end - w.u) < nk_all ? w.ks + (int)(u_end - w.u) : nk_all;
         w.u += w.nk - w.ks;
     };
@@ -1541,6 +1553,18 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
         (BMODE == B_VEC || BMODE == B_SCALAR || BMODE == B_WIDE || BMODE == B_PLANES);
     q.group_m = choose_group_m(p, tiles_m, tiles_n, q.stream_per > 0 ? 1 : q.ksplit, MATRIX_PAIR,
                                q.stream_per > 0 && q.ksplit == 1);
+    {   // divisors of the blocks' index arithmetic (every divisor is at least 1)
+        auto fd = [](int64_t d) { return make_fast_div((uint32_t)(d < 1 ? 1 : d)); };
+        q.div_tiles = fd(tiles);
+        q.per_split = (nk + q.ksplit - 1) / q.ksplit;
+        q.div_per_group = fd((int64_t)q.group_m * tiles_n);
+        q.div_group = fd(q.group_m);
+        q.div_last_group = fd(tiles_m % q.group_m ? tiles_m % q.group_m : q.group_m);
+        q.div_taps = fd((int64_t)q.kh * q.kw);
+        q.div_tap_kw = fd(q.kw);
+        q.div_row_howo = fd((int64_t)q.Ho * q.Wo);
+        q.div_row_wo = fd(q.Wo);
+    }
     if (q.ksplit > 1)
         if (hipError_t e = launch_zero_fill(q, stream)) return e;
     if constexpr (CanStream<AMODE, BMODE>::value) {
