@@ -99,6 +99,7 @@ struct GemmParams {
     FastDiv div_group, div_last_group;   // tile-rows of a full group / of the last, shorter one (or of a full one)
     FastDiv div_taps, div_tap_kw;        // kh * kw and kw, for the tap cursor
     FastDiv div_row_howo, div_row_wo;    // Ho * Wo and Wo, for the pixel of an output row
+    uint32_t tap_rows;          // bit r*kw for every row r of the kh x kw tap grid (tap masks of the patch gathers)
 };
 
 // Largest block-tile height any instantiation uses; the host checks 32-bit

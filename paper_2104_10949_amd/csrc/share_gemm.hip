@@ -290,6 +290,24 @@ struct TapCursor {
     }
 };
 
+// Bits [lo, hi) of a 32-bit word, 0 <= lo, hi <= 32 (empty when hi <= lo).
+__device__ __forceinline__ u32 bit_range(int lo, int hi) {
+    const u32 below_hi = hi >= 32 ? 0xFFFFFFFFu : (1u << hi) - 1u;
+    const u32 below_lo = lo >= 32 ? 0xFFFFFFFFu : (1u << lo) - 1u;
+    return hi > lo ? below_hi & ~below_lo : 0u;
+}
+// Which taps t = r*kw + s of a kh x kw window (at most 32 taps) whose corner sits on pixel (hi0, wi0) read a pixel
+// inside the H x W image: rows r with 0 <= hi0 + r < H times columns s with 0 <= wi0 + s < W.  The valid columns
+// are one run of bits, the valid rows select every kw-th bit of p.tap_rows: their product is the mask (the runs
+// do not overlap), without a loop over the taps.
+__device__ __forceinline__ u32 taps_inside(const GemmParams& p, int hi0, int wi0) {
+    const int r_lo = hi0 < 0 ? -hi0 : 0, r_hi = p.H - hi0 < p.kh ? p.H - hi0 : p.kh;
+    const int s_lo = wi0 < 0 ? -wi0 : 0, s_hi = p.W - wi0 < p.kw ? p.W - wi0 : p.kw;
+    if (r_hi <= r_lo || s_hi <= s_lo) return 0u;   // (a select: both sides are a few instructions)
+    const u32 rows = p.tap_rows & bit_range(r_lo * p.kw, r_hi * p.kw);
+    return rows * bit_range(s_lo, s_hi);
+}
+
 // Patch gather with Cin % 32 == 0, 16-byte loads.  Which filter taps fall inside the image for this unit's
 // output pixel is decided once, as a bit mask over the taps; the host sends windows of more than
 // MAX_MASK_TAPS taps to the general gather.  Two registers per unit stay alive across the K loop.
@@ -301,13 +319,7 @@ struct ConvC32 {
         PatchRow pr;
         pr.init(p, m0, row_local, rows_left);
         base_kq = pr.base + (u32)(16 * jh + 2 * q) * 8u;
-        inside = 0;
-        if (pr.ok) {
-            int t = 0;
-            for (int r = 0; r < p.kh; ++r)
-                for (int s_ = 0; s_ < p.kw; ++s_, ++t)
-                    if ((u32)(pr.hi0 + r) < (u32)p.H && (u32)(pr.wi0 + s_) < (u32)p.W) inside |= 1u << t;
-        }
+        inside = pr.ok ? taps_inside(p, pr.hi0, pr.wi0) : 0u;
     }
     __device__ __forceinline__ void load(const GemmParams& p, __amdgpu_buffer_rsrc_t rs_, const TapCursor& t,
                                          u4 out[2]) const {
@@ -496,13 +508,7 @@ struct PlanesPatch {
         // the view starts at the 16-pixel block that holds the first pixel of image b0
         pix0 = ((b0 * HW) & 15u) + (b - b0) * HW + (u32)hi0 * (u32)p.W + (u32)wi0;
         cq256 = (u32)cq * 256u;
-        inside = 0;
-        if (ok) {
-            int t = 0;
-            for (int r = 0; r < p.kh; ++r)
-                for (int s_ = 0; s_ < p.kw; ++s_, ++t)
-                    if ((u32)(hi0 + r) < (u32)p.H && (u32)(wi0 + s_) < (u32)p.W) inside |= 1u << t;
-        }
+        inside = ok ? taps_inside(p, hi0, wi0) : 0u;
     }
     // byte offset of piece cq of the slice the cursor points at, or OOB
     __device__ __forceinline__ u32 offset(const GemmParams& p, const TapCursor& t) const {
@@ -1564,6 +1570,9 @@ static hipError_t launch(const GemmParams& p, hipStream_t stream) {
         q.div_tap_kw = fd(q.kw);
         q.div_row_howo = fd((int64_t)q.Ho * q.Wo);
         q.div_row_wo = fd(q.Wo);
+        q.tap_rows = 0;   // bit r*kw for every row r of the tap grid (patch gathers with a tap mask: at most 32 taps)
+        if (q.kh >= 1 && q.kw >= 1 && (int64_t)q.kh * q.kw <= 32)
+            for (int r = 0; r < q.kh; ++r) q.tap_rows |= 1u << (r * q.kw);
     }
     if (q.ksplit > 1)
         if (hipError_t e = launch_zero_fill(q, stream)) return e;
