@@ -279,6 +279,13 @@ CONV_CASES = [
     (2, 10, 11, 64, 70, 9, 8, (2, 1), (4, 3)),
     (2, 11, 12, 32, 40, 4, 8, (1, 1), (1, 3)),       # 32 taps: the largest window of the 32-channel gather
     (2, 11, 12, 32, 40, 5, 7, (1, 1), (2, 3)),       # 35 taps
+    # 32-tap windows of other shapes, padded up to the window's own size: every bit of the tap mask, the mask's last
+    # bit included, is set for some pixel and clear for another
+    (1, 3, 40, 32, 8, 1, 32, (1, 1), (0, 31)),
+    (1, 40, 3, 32, 8, 32, 1, (1, 1), (31, 0)),
+    (2, 9, 9, 32, 16, 8, 4, (1, 2), (7, 3)),
+    (1, 6, 20, 32, 8, 2, 16, (1, 1), (1, 15)),
+    (1, 5, 5, 32, 8, 6, 5, (1, 1), (5, 4)),          # 30 taps, windows larger than the image
     (8, 14, 14, 256, 256, 3, 3, (1, 1), (1, 1)),     # 13 x 4 tiles, 72 slices: streamed distribution
     (3, 21, 21, 96, 200, 3, 3, (1, 1), (1, 1)),
 ]
