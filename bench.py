@@ -38,7 +38,7 @@ DIGIT_MACS_PER_RING_MAC_TRIPLE = 72  # 2 ring products x 36 signed-byte digit pa
 WORKLOAD_CONFIG = 4
 # HBM bytes per share_gemm_kernel launch on the config-4 step, from the two rocprofv3 --pmc runs summarised in
 # profiles/share_gemm_config4_hbm_traffic.txt (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000 by the 1 GiB copy calibration).
-PROFILED_TRAFFIC_CONFIG4 = {"read_bytes_per_launch": 65.9e6, "write_bytes_per_launch": 22.6e6,
+PROFILED_TRAFFIC_CONFIG4 = {"read_bytes_per_launch": 65.8e6, "write_bytes_per_launch": 22.6e6,
                             "algorithmic_bytes_per_launch": 61.0e6,
                             "conversion_pass_per_scratch_route_layer": {"read_bytes": 47.8e6, "write_bytes": 43.5e6},
                             "source": "profiles/share_gemm_config4_hbm_traffic.txt"}

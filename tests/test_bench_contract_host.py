@@ -41,3 +41,23 @@ def test_more_than_one_gpu_is_refused_before_anything_touches_a_device():
     assert r.returncode == 2
     assert r.stdout.strip() == ""
     assert "ONE GPU" in r.stderr
+
+
+def test_traffic_constants_are_the_ones_the_committed_counter_summary_holds():
+    """bench.py quotes the HBM bytes per launch from the rocprofv3 counter summary: both must say the same."""
+    import re
+    sys.path.insert(0, ROOT)
+    import bench
+    t = bench.PROFILED_TRAFFIC_CONFIG4
+    text = open(os.path.join(ROOT, t["source"])).read()
+    m = re.search(r"scaled bytes per dispatch:\s*([\d.]+) MB read,\s*([\d.]+) MB written", text)
+    assert m, "summary line of the product kernels not found"
+    assert abs(float(m.group(1)) * 1e6 - t["read_bytes_per_launch"]) < 0.05e6
+    assert abs(float(m.group(2)) * 1e6 - t["write_bytes_per_launch"]) < 0.05e6
+    m = re.search(r"([\d.]+) MB per dispatch", text)
+    assert m and abs(float(m.group(1)) * 1e6 - t["algorithmic_bytes_per_launch"]) < 0.05e6
+    # the conversion pass: the to_planes_kernel line holds FETCH_SIZE and WRITE_SIZE in KiB per dispatch (x 2.000, x 1.000)
+    m = re.search(r"to_planes_kernel\S*\s+\d+\s+([\d.]+)\s+([\d.]+)", text)
+    conv = t["conversion_pass_per_scratch_route_layer"]
+    assert m and abs(float(m.group(1)) * 1024 * 2.0 - conv["read_bytes"]) < 0.05e6
+    assert abs(float(m.group(2)) * 1024 * 1.0 - conv["write_bytes"]) < 0.05e6
